@@ -1,0 +1,273 @@
+"""ctypes access to the CPU oracle (oracle/sf_oracle.c).
+
+Test infrastructure only: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg, never by the product package.  Holds no arithmetic
+of its own: every function here marshals numpy arrays into the C routines.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libsf_oracle.so")
+_SRC = os.path.join(_HERE, "sf_oracle.c")
+
+MAX_CONV, MAX_STAGE, MAX_HEADS, MAX_CONV_TENSORS = 4, 4, 16, 20
+
+
+def build(force=True):
+    """Compile the oracle with gcc (no fast-math, no contraction)."""
+    if not force and os.path.exists(_SO) and os.path.getmtime(_SO) >= max(
+            os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "sf_oracle.h"))):
+        return _SO
+    cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC",
+           "-shared", "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _SO
+
+
+class RefNet(C.Structure):
+    _fields_ = [
+        ("obs_c", C.c_int32), ("obs_h", C.c_int32), ("obs_w", C.c_int32),
+        ("encoder", C.c_int32),
+        ("n_conv", C.c_int32),
+        ("conv_cout", C.c_int32 * MAX_CONV), ("conv_k", C.c_int32 * MAX_CONV),
+        ("conv_stride", C.c_int32 * MAX_CONV), ("conv_pad", C.c_int32 * MAX_CONV),
+        ("n_stage", C.c_int32), ("stage_ch", C.c_int32 * MAX_STAGE),
+        ("blocks_per_stage", C.c_int32),
+        ("fc_dim", C.c_int32), ("rnn_dim", C.c_int32),
+        ("n_heads", C.c_int32), ("head_sizes", C.c_int32 * MAX_HEADS),
+        ("obs_sub", C.c_float), ("obs_mul", C.c_float),
+    ]
+
+
+_FP = C.POINTER(C.c_float)
+
+
+class RefParams(C.Structure):
+    _fields_ = [
+        ("conv_w", _FP * MAX_CONV_TENSORS), ("conv_b", _FP * MAX_CONV_TENSORS),
+        ("fc_w", _FP), ("fc_b", _FP),
+        ("gru_w_ih", _FP), ("gru_w_hh", _FP), ("gru_b_ih", _FP), ("gru_b_hh", _FP),
+        ("pi_w", _FP), ("pi_b", _FP), ("v_w", _FP), ("v_b", _FP),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_SO):
+            build()
+        L = C.CDLL(_SO)
+        L.ref_conv2d.restype = C.c_int
+        L.ref_flat_size.restype = C.c_int64
+        L.ref_policy_step.restype = C.c_int
+        L.ref_num_threads.restype = C.c_int
+        L.ref_bits_to_uniform.restype = C.c_float
+        L.ref_bits_to_uniform.argtypes = [C.c_uint32]
+        L.ref_gumbel.restype = C.c_float
+        L.ref_gumbel.argtypes = [C.c_float]
+        _lib = L
+    return _lib
+
+
+def _p(a, t=C.c_void_p):
+    return a.ctypes.data_as(t)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def make_net(net):
+    """net: dict as produced by workloads.network()."""
+    r = RefNet()
+    r.obs_c, r.obs_h, r.obs_w = net["obs"]
+    r.encoder = 1 if net["encoder"] == "resnet" else 0
+    if r.encoder == 0:
+        r.n_conv = len(net["convs"])
+        for i, (co, k, s, p) in enumerate(net["convs"]):
+            r.conv_cout[i], r.conv_k[i], r.conv_stride[i], r.conv_pad[i] = co, k, s, p
+    else:
+        r.n_stage = len(net["stages"])
+        for i, ch in enumerate(net["stages"]):
+            r.stage_ch[i] = ch
+        r.blocks_per_stage = net["blocks_per_stage"]
+    r.fc_dim, r.rnn_dim = net["fc"], net["rnn"]
+    r.n_heads = len(net["heads"])
+    for i, a in enumerate(net["heads"]):
+        r.head_sizes[i] = a
+    r.obs_sub, r.obs_mul = net["obs_sub"], net["obs_mul"]
+    return r
+
+
+def make_params(w):
+    """w: dict of fp32 numpy arrays as produced by workloads.weights().
+    Returns (RefParams, keepalive list)."""
+    p = RefParams()
+    keep = []
+
+    def fp(a):
+        a = _f32(a)
+        keep.append(a)
+        return _p(a, _FP)
+
+    for i, (cw, cb) in enumerate(zip(w["conv_w"], w["conv_b"])):
+        p.conv_w[i] = fp(cw)
+        p.conv_b[i] = fp(cb)
+    for name in ("fc_w", "fc_b", "gru_w_ih", "gru_w_hh", "gru_b_ih", "gru_b_hh", "pi_w", "pi_b",
+                 "v_w", "v_b"):
+        setattr(p, name, fp(w[name]))
+    return p, keep
+
+
+def flat_size(net):
+    return int(lib().ref_flat_size(C.byref(make_net(net))))
+
+
+def num_threads():
+    return int(lib().ref_num_threads())
+
+
+def policy_step(net, w, obs, h_in, done, seed, step, want_logits=True, want_margin=True):
+    """Run one step on host arrays; returns a dict of numpy outputs."""
+    L = lib()
+    rn = make_net(net)
+    rp, keep = make_params(w)
+    B = int(obs.shape[0])
+    obs = np.ascontiguousarray(obs, dtype=np.uint8)
+    h_in = _f32(h_in)
+    done = np.ascontiguousarray(done, dtype=np.uint8)
+    nh, sumA, H = len(net["heads"]), int(sum(net["heads"])), net["rnn"]
+    out = {
+        "actions": np.zeros((B, nh), np.int32), "logp": np.zeros(B, np.float32),
+        "value": np.zeros(B, np.float32), "h_out": np.zeros((B, H), np.float32),
+        "logits": np.zeros((B, sumA), np.float32) if want_logits else None,
+        "margin": np.zeros((B, nh), np.float32) if want_margin else None,
+    }
+    rc = L.ref_policy_step(
+        C.byref(rn), C.byref(rp), C.c_int32(B), _p(obs), _p(h_in), _p(done),
+        C.c_uint64(seed), C.c_uint64(step), _p(out["actions"]), _p(out["logp"]),
+        _p(out["value"]), _p(out["h_out"]),
+        _p(out["logits"]) if want_logits else None, _p(out["margin"]) if want_margin else None)
+    if rc != 0:
+        raise ValueError("ref_policy_step rejected the network description")
+    del keep
+    return out
+
+
+# ---- building blocks ---------------------------------------------------------
+
+def conv2d(x, w, b, stride, pad, relu):
+    x = _f64(x)
+    w = _f32(w)
+    b = _f32(b)
+    Cc, H, W = x.shape
+    O, _, k, _ = w.shape
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    out = np.zeros((O, max(Ho, 0), max(Wo, 0)), np.float64)
+    rc = lib().ref_conv2d(_p(x), Cc, H, W, _p(w), _p(b), O, k, stride, pad, int(relu), _p(out))
+    if rc != 0:
+        raise ValueError("empty convolution output")
+    return out
+
+
+def maxpool3x3s2p1(x):
+    x = _f64(x)
+    Cc, H, W = x.shape
+    out = np.zeros((Cc, (H - 1) // 2 + 1, (W - 1) // 2 + 1), np.float64)
+    lib().ref_maxpool3x3s2p1(_p(x), Cc, H, W, _p(out))
+    return out
+
+
+def linear(x, w, b, relu):
+    x = _f64(x)
+    w = _f32(w)
+    b = _f32(b)
+    out = np.zeros(w.shape[0], np.float64)
+    lib().ref_linear(_p(x), x.shape[0], _p(w), _p(b), w.shape[0], int(relu), _p(out))
+    return out
+
+
+def gru_cell(x, h, w_ih, w_hh, b_ih, b_hh):
+    x = _f64(x)
+    h = _f64(h)
+    out = np.zeros_like(h)
+    lib().ref_gru_cell(_p(x), x.shape[0], _p(h), h.shape[0], _p(_f32(w_ih)), _p(_f32(w_hh)),
+                       _p(_f32(b_ih)), _p(_f32(b_hh)), _p(out))
+    return out
+
+
+def resnet_encoder(net, w, x):
+    rn = make_net(net)
+    rp, keep = make_params(w)
+    x = _f64(x)
+    out = np.zeros(flat_size(net), np.float64)
+    hf, wf = C.c_int(), C.c_int()
+    lib().ref_resnet_encoder(C.byref(rn), C.byref(rp), _p(x), _p(out), C.byref(hf), C.byref(wf))
+    del keep
+    return out.reshape(net["stages"][-1], hf.value, wf.value)
+
+
+def philox4x32_10(ctr, key):
+    ctr = np.ascontiguousarray(ctr, np.uint32)
+    key = np.ascontiguousarray(key, np.uint32)
+    out = np.zeros(4, np.uint32)
+    lib().ref_philox4x32_10(_p(ctr), _p(key), _p(out))
+    return out
+
+
+def sampler_words(seed, env, step, head, block):
+    out = np.zeros(4, np.uint32)
+    lib().ref_sampler_words(C.c_uint64(seed), C.c_uint32(env), C.c_uint64(step), C.c_uint32(head),
+                            C.c_uint32(block), _p(out))
+    return out
+
+
+def bits_to_uniform(w):
+    return float(lib().ref_bits_to_uniform(int(w)))
+
+
+def bits_to_uniform_many(words):
+    words = np.ascontiguousarray(words, np.uint32)
+    out = np.zeros(words.shape, np.float32)
+    lib().ref_bits_to_uniform_many(_p(words), C.c_int64(words.size), _p(out))
+    return out
+
+
+def gumbel(u):
+    return float(lib().ref_gumbel(C.c_float(u)))
+
+
+def head_sample(logits, seed, env, step, head, g_override=None):
+    logits = _f32(logits)
+    a, lp, mg = C.c_int32(), C.c_double(), C.c_float()
+    g = _f32(g_override) if g_override is not None else None
+    lib().ref_head_sample(_p(logits), logits.shape[0], C.c_uint64(seed), C.c_uint32(env),
+                          C.c_uint64(step), C.c_uint32(head), _p(g) if g is not None else None,
+                          C.byref(a), C.byref(lp), C.byref(mg))
+    return a.value, lp.value, mg.value
+
+
+def head_histogram(logits, seed, head, n, n_env, step0=0):
+    logits = _f32(logits)
+    counts = np.zeros(logits.shape[0], np.int64)
+    lib().ref_head_histogram(_p(logits), logits.shape[0], C.c_uint64(seed), C.c_uint32(head),
+                             C.c_int64(n), C.c_uint32(n_env), C.c_uint64(step0), _p(counts))
+    return counts
+
+
+def log_softmax(logits):
+    logits = _f32(logits)
+    out = np.zeros(logits.shape[0], np.float64)
+    lib().ref_log_softmax(_p(logits), logits.shape[0], _p(out))
+    return out

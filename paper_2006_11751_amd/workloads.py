@@ -1,0 +1,133 @@
+"""Seeded synthetic workloads: network shapes and input generators.
+
+Serves both the HIP library's callers and the CPU oracle's tests.  Holds none of
+the method's arithmetic: only shapes, random draws and the bf16 rounding of the
+weight *inputs*.  numpy only.
+
+The observations stand in for the paper's VizDoom frames (128x72 RGB bytes,
+paper Sec. 4.1): the step's cost does not depend on pixel content, and the paper
+itself benchmarks one domain with random actions for the same reason (paper,
+App. "Benchmarking details").
+"""
+import numpy as np
+
+OBS_MUL = float(np.float32(1.0) / np.float32(255.0))  # the fp32 value nearest 1/255
+
+_STD_CONVS = [(32, 8, 4, 0), (64, 4, 2, 0), (128, 3, 2, 0)]  # (cout, k, stride, pad)
+
+# One entry per benchmark configuration: 0 tiny, 1 standard (the headline one),
+# 2 bf16 standard at B=4096, 3 multi-discrete over 16 chained steps, 4 ResNet bf16.
+CONFIGS = [
+    dict(name="tiny", B=8, obs=(3, 36, 64), encoder="conv", convs=[(16, 8, 4, 0), (32, 4, 2, 0)],
+         fc=128, rnn=128, heads=[6], dtype="fp32", p_done=0.1, steps=4),
+    dict(name="standard", B=1024, obs=(3, 72, 128), encoder="conv", convs=_STD_CONVS,
+         fc=512, rnn=512, heads=[7], dtype="fp32", p_done=0.05, steps=1),
+    dict(name="standard_bf16", B=4096, obs=(3, 72, 128), encoder="conv", convs=_STD_CONVS,
+         fc=512, rnn=512, heads=[7], dtype="bf16", p_done=0.05, steps=1),
+    dict(name="multi_discrete", B=2048, obs=(3, 72, 128), encoder="conv", convs=_STD_CONVS,
+         fc=512, rnn=512, heads=[3, 3, 2, 2, 2, 11], dtype="fp32", p_done=0.1, steps=16),
+    dict(name="resnet_bf16", B=8192, obs=(3, 72, 128), encoder="resnet", stages=[16, 32, 32],
+         blocks_per_stage=2, fc=256, rnn=256, heads=[15], dtype="bf16", p_done=0.05, steps=1),
+]
+
+
+def network(index, **overrides):
+    """A copy of configuration `index` with normalisation defaults filled in."""
+    cfg = dict(CONFIGS[index])
+    cfg["index"] = index
+    cfg.setdefault("obs_sub", 0.0)
+    cfg.setdefault("obs_mul", OBS_MUL)
+    cfg.update(overrides)
+    return cfg
+
+
+def conv_out_hw(h, w, k, s, p):
+    return (h + 2 * p - k) // s + 1, (w + 2 * p - k) // s + 1
+
+
+def conv_tensor_shapes(net):
+    """[(cout, cin, k)] for every convolution, in parameter order."""
+    c = net["obs"][0]
+    shapes = []
+    if net["encoder"] == "conv":
+        for co, k, _, _ in net["convs"]:
+            shapes.append((co, c, k))
+            c = co
+    else:
+        for ch in net["stages"]:
+            shapes.append((ch, c, 3))
+            c = ch
+            for _ in range(net["blocks_per_stage"]):
+                shapes.append((ch, ch, 3))
+                shapes.append((ch, ch, 3))
+    return shapes
+
+
+def flat_size(net):
+    c, h, w = net["obs"]
+    if net["encoder"] == "conv":
+        for co, k, s, p in net["convs"]:
+            h, w = conv_out_hw(h, w, k, s, p)
+            c = co
+    else:
+        for ch in net["stages"]:
+            h, w = (h - 1) // 2 + 1, (w - 1) // 2 + 1
+            c = ch
+    return c * h * w
+
+
+def round_to_bf16(a):
+    """Round fp32 values to the nearest bf16 (ties to even), returned as fp32."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    bits = a.view(np.uint32).astype(np.uint64)
+    bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
+    return bits.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def weights(net, seed=None):
+    """Parameters ~ N(0, variance 1/fan_in), biases too (non-zero on purpose).
+    For bf16 configurations every tensor is rounded to bf16 once, so that both
+    the oracle and the library start from identical values."""
+    seed = 1000 + net.get("index", 0) if seed is None else seed
+    rng = np.random.default_rng(seed)
+
+    def draw(shape, fan_in):
+        a = (rng.standard_normal(shape) / np.sqrt(fan_in)).astype(np.float32)
+        return round_to_bf16(a) if net["dtype"] == "bf16" else a
+
+    w = {"conv_w": [], "conv_b": []}
+    for co, ci, k in conv_tensor_shapes(net):
+        fan = ci * k * k
+        w["conv_w"].append(draw((co, ci, k, k), fan))
+        w["conv_b"].append(draw((co,), fan))
+    flat, fc, H, sumA = flat_size(net), net["fc"], net["rnn"], sum(net["heads"])
+    w["fc_w"], w["fc_b"] = draw((fc, flat), flat), draw((fc,), flat)
+    w["gru_w_ih"], w["gru_b_ih"] = draw((3 * H, fc), fc), draw((3 * H,), fc)
+    w["gru_w_hh"], w["gru_b_hh"] = draw((3 * H, H), H), draw((3 * H,), H)
+    w["pi_w"], w["pi_b"] = draw((sumA, H), H), draw((sumA,), H)
+    w["v_w"], w["v_b"] = draw((H,), H), draw((1,), H)
+    return w
+
+
+def observations(net, t=0, B=None, seed=None):
+    B = net["B"] if B is None else B
+    seed = 2000 + 100 * net.get("index", 0) + t if seed is None else seed
+    rng = np.random.default_rng(seed)
+    return rng.integers(0, 256, size=(B,) + tuple(net["obs"]), dtype=np.uint8)
+
+
+def initial_state(net, B=None, seed=None):
+    B = net["B"] if B is None else B
+    seed = 3000 + net.get("index", 0) if seed is None else seed
+    rng = np.random.default_rng(seed)
+    return (0.1 * rng.standard_normal((B, net["rnn"]))).astype(np.float32)
+
+
+def done_mask(net, t=0, B=None, seed=None):
+    B = net["B"] if B is None else B
+    seed = 4000 + 100 * net.get("index", 0) + t if seed is None else seed
+    rng = np.random.default_rng(seed)
+    return (rng.random(B) < net["p_done"]).astype(np.uint8)
+
+
+PHILOX_SEED = 1
