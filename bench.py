@@ -1,0 +1,113 @@
+"""Benchmark of the policy-worker step (paper, Sec. 3.1) on one MI355X.
+
+One "step" = one sf_policy_step over a batch of synthetic observations already
+resident in HBM (the standard configuration: B=1024 frames of 3x72x128 bytes,
+conv encoder, FC-512, GRU-512, one 7-way head + value, fp32).  Prints one JSON
+line: env-frames/s, the roofline of the dominant kernel (live HIP-event timing of
+every launch) and the CPU oracle timed on the host cores on a bounded sample.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+MI355X_PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2500.0}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="workload index (1 = the headline one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (the step is data-parallel over rows "
+                 "with no exchange between GPUs); run with --gpus 1")
+
+    import torch
+    from paper_2006_11751_amd import binding, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    net = wl.network(args.config)
+    B = net["B"]
+    w = wl.weights(net)
+    pol = binding.Policy(net, w)
+    dev = pol.device
+    obs = torch.from_numpy(wl.observations(net)).to(dev)
+    done = torch.from_numpy(wl.done_mask(net)).to(dev)
+    h = [torch.from_numpy(wl.initial_state(net)).to(dev), torch.empty((B, net["rnn"]), device=dev)]
+    out = [pol.alloc_outputs(B, logits=False) for _ in range(2)]
+    out[0]["h_out"], out[1]["h_out"] = h[1], h[0]
+    stream = torch.cuda.current_stream(dev)
+
+    def run(n, t0):
+        for t in range(t0, t0 + n):
+            pol.step(obs, h[t & 1], done, wl.PHILOX_SEED, t, out=out[t & 1], stream=stream)
+
+    run(args.warmup, 0)
+    torch.cuda.synchronize()
+    tic = time.perf_counter()
+    run(args.steps, args.warmup)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - tic
+    ms_per_step = 1e3 * elapsed / args.steps
+    fps = B * args.steps / elapsed
+
+    # per-launch durations: the same steps again with a HIP event after every launch
+    ops = pol.ops()
+    pol.set_op_timing(True)
+    acc = np.zeros(len(ops))
+    n_timed = min(args.steps, 100)
+    for t in range(n_timed):
+        run(1, args.warmup + args.steps + t)
+        acc += np.array(pol.last_op_times_ms())
+    pol.set_op_timing(False)
+    op_ms = acc / n_timed
+    dtype = net["dtype"]
+    peak = MI355X_PEAK_TFLOPS[dtype]
+    i_dom = int(np.argmax(op_ms))
+    per_op = {name: {"ms": round(float(ms), 5),
+                     "tflops": round(fl * B / (ms * 1e-3) / 1e12, 3) if ms > 0 else None}
+              for (name, fl), ms in zip(ops, op_ms)}
+    dom_tflops = ops[i_dom][1] * B / (op_ms[i_dom] * 1e-3) / 1e12
+    whole_tflops = pol.flops_per_row() * B / (ms_per_step * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": ops[i_dom][0], "achieved": round(dom_tflops, 3), "peak": peak,
+                "unit": "TFLOP/s", "frac": round(dom_tflops / peak, 5), "traffic": None,
+                "avg_launch_ms": round(float(op_ms[i_dom]), 5),
+                "whole_step": {"achieved": round(whole_tflops, 3), "frac": round(whole_tflops / peak, 5)},
+                "per_kernel": per_op}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ref
+        n_rows = min(B, 1024)
+        o_obs, o_h, o_done = wl.observations(net, B=n_rows), wl.initial_state(net, B=n_rows), wl.done_mask(net, B=n_rows)
+        reps, spent = 0, 0.0
+        while spent < 10.0 and reps < 50:
+            tic = time.perf_counter()
+            ref.policy_step(net, w, o_obs, o_h, o_done, wl.PHILOX_SEED, reps, want_logits=False, want_margin=False)
+            spent += time.perf_counter() - tic
+            reps += 1
+        cpu = {"value": round(n_rows * reps / spent, 2), "unit": "env-frames/s", "cores": ref.num_threads(),
+               "kind": "oracle", "sample": "%d rows of the same workload x %d repeats (%.1f s)" % (n_rows, reps, spent)}
+
+    print(json.dumps({
+        "metric": "policy-step env-frames/sec at B=1024 3x72x128 GRU-512; % MFMA/HBM roofline",
+        "value": round(fps, 1), "unit": "env-frames/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32" if dtype == "fp32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s: B=%d obs u8 %dx%dx%d, %s encoder, FC%d, GRU%d, heads %s" % (
+            net["name"], B, *net["obs"], net["encoder"], net["fc"], net["rnn"], net["heads"]),
+            "paper_accounting_x4_frameskip_fps": round(4 * fps, 1),
+            "inputs": "device-resident; host-to-device transfer excluded"},
+        "roofline": roofline, "cpu_baseline": cpu}))
+    pol.close()
+
+
+if __name__ == "__main__":
+    main()

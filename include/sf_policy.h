@@ -1,0 +1,182 @@
+/*
+ * sf_policy -- the policy worker's batched actor-critic step on one MI355X (gfx950).
+ *
+ * The operation (paper, Sec. 3.1, "policy worker"): a batch of observations x_t
+ * and recurrent states h_t is run through the policy network, giving the action
+ * distributions mu(a_t | x_t, h_t) and the new states h_{t+1}; actions a_t are
+ * sampled from mu and returned together with h_{t+1}.  The network (paper, App.
+ * "Model architectures"): convolutional encoder -> fully connected layer -> RNN
+ * core (GRU, as in the paper's large-scale experiments) -> one linear head for
+ * the action distribution(s) and one for the baseline (value).  The full action
+ * space is a tuple of L independent categorical heads (paper, App. "VizDoom
+ * experiments", action-space table), so the joint log-probability is the sum of
+ * the per-head log-probabilities.
+ *
+ * The policy worker of the paper is stateless (Sec. 3.1 "Parallelism"): all
+ * per-environment state lives in tensors owned by someone else.  Accordingly
+ * sf_policy_step is a pure function of (weights, obs, h_in, done, seed, step):
+ * row b of every output depends on row b of the inputs and on b itself (the
+ * sampler's counter word) only, and is bitwise reproducible from call to call.
+ *
+ * Conventions
+ *   - every function returns an int status (SF_OK or a negative SF_ERR_*),
+ *     never throws and never aborts; sf_last_error() gives the text of the last
+ *     failure on the calling thread.
+ *   - "dev" pointers are device memory on the HIP device given at create time;
+ *     "host" pointers are ordinary host memory.
+ *   - the library copies and repacks the weights during sf_policy_create (the
+ *     caller may free them as soon as it returns) and allocates its workspace
+ *     there, sized for max_batch; sf_policy_step allocates nothing, does not
+ *     synchronise, and keeps no pointer past the completion of the stream work
+ *     it enqueues.  The caller owns every buffer passed to sf_policy_step.
+ *   - one sf_policy handle must not be stepped from two threads or on two
+ *     streams at the same time (its workspace is shared by its calls).
+ */
+#ifndef SF_POLICY_H
+#define SF_POLICY_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SF_ABI_VERSION 1u
+#define SF_MAX_CONV 4
+#define SF_MAX_STAGE 4
+#define SF_MAX_HEADS 16
+#define SF_MAX_CONV_TENSORS 20
+
+enum {
+  SF_OK = 0,
+  SF_ERR_ARG = -1,    /* null or misaligned pointer, bad struct_size / abi_version */
+  SF_ERR_SHAPE = -2,  /* inconsistent network description (empty layer output, ...) */
+  SF_ERR_BATCH = -3,  /* B < 0 or B > max_batch */
+  SF_ERR_ALIAS = -4,  /* h_out overlaps h_in */
+  SF_ERR_DEVICE = -5, /* a HIP call failed */
+  SF_ERR_OOM = -6,    /* device allocation failed at create */
+  SF_ERR_ARCH = -7    /* the device is not gfx950 */
+};
+
+enum { SF_ENCODER_CONV = 0, SF_ENCODER_RESNET = 1 };
+enum { SF_DTYPE_FP32 = 0, SF_DTYPE_BF16 = 1 };
+
+typedef struct sf_policy sf_policy; /* opaque */
+
+typedef struct {
+  int32_t cout, k, stride, pad; /* square kernel; out = floor((in + 2 pad - k) / stride) + 1 */
+} sf_conv;
+
+typedef struct {
+  uint32_t struct_size; /* sizeof(sf_policy_config) */
+  uint32_t abi_version; /* SF_ABI_VERSION */
+  int32_t max_batch;    /* largest B that sf_policy_step will be given */
+  int32_t obs_c, obs_h, obs_w;
+  int32_t encoder; /* SF_ENCODER_CONV: n_conv convolutions, each followed by ReLU.
+                      SF_ENCODER_RESNET: n_stage stages of conv3x3/s1/pad1 ->
+                      maxpool 3x3/s2/pad1 (padding never wins the maximum) ->
+                      blocks_per_stage residual blocks x + conv(relu(conv(relu(x))));
+                      ReLU after the last stage. */
+  int32_t n_conv;
+  sf_conv conv[SF_MAX_CONV];
+  int32_t n_stage;
+  int32_t stage_ch[SF_MAX_STAGE];
+  int32_t blocks_per_stage;
+  int32_t fc_dim;  /* fully connected layer after the encoder, followed by ReLU */
+  int32_t rnn_dim; /* GRU hidden size H */
+  int32_t n_heads; /* independent categorical heads */
+  int32_t head_sizes[SF_MAX_HEADS];
+  int32_t dtype; /* SF_DTYPE_FP32, or SF_DTYPE_BF16: weights and encoder/FC activations
+                    in bf16 with fp32 accumulation; the GRU state, the gate arithmetic,
+                    the heads and the sampler stay fp32 */
+  float obs_sub, obs_mul; /* normalisation: x = ((float)byte - obs_sub) * obs_mul */
+} sf_policy_config;
+
+/* HOST pointers to fp32 parameters in canonical layouts; read during create only.
+ *   conv_w[i]: [cout][cin][k][k], conv_b[i]: [cout].  Residual encoder: per stage
+ *              the stage convolution, then each block's two convolutions in order.
+ *   fc_w: [fc_dim][flat], flat index = c*(Hf*Wf) + y*Wf + x of the encoder output.
+ *   GRU:  w_ih [3H][fc_dim], w_hh [3H][H], b_ih [3H], b_hh [3H]; gate rows r, z, n:
+ *           r = sigmoid(W_ir x + b_ir + W_hr h + b_hr)
+ *           z = sigmoid(W_iz x + b_iz + W_hz h + b_hz)
+ *           n = tanh   (W_in x + b_in + r * (W_hn h + b_hn))
+ *           h_out = (1 - z) * n + z * h,   h = done ? 0 : h_in
+ *   pi_w: [sum(head_sizes)][H], pi_b: [sum(head_sizes)] (heads concatenated in order)
+ *   v_w:  [H], v_b: [1] */
+typedef struct {
+  const float* conv_w[SF_MAX_CONV_TENSORS];
+  const float* conv_b[SF_MAX_CONV_TENSORS];
+  const float* fc_w;
+  const float* fc_b;
+  const float* gru_w_ih;
+  const float* gru_w_hh;
+  const float* gru_b_ih;
+  const float* gru_b_hh;
+  const float* pi_w;
+  const float* pi_b;
+  const float* v_w;
+  const float* v_b;
+} sf_policy_weights;
+
+/* Build a policy on HIP device `hip_device`: validates the description, packs the
+ * weights into device layouts and allocates the workspace for max_batch rows.
+ * On success *out receives the handle.  Errors: SF_ERR_ARG, SF_ERR_SHAPE,
+ * SF_ERR_ARCH, SF_ERR_OOM, SF_ERR_DEVICE; *out is then NULL. */
+int sf_policy_create(const sf_policy_config* cfg, const sf_policy_weights* weights,
+                     int hip_device, sf_policy** out);
+
+/* One step of the policy worker (paper, Sec. 3.1) on B rows, enqueued
+ * asynchronously on `hip_stream` (a hipStream_t; NULL = the default stream).
+ *   obs        dev  [B][obs_c][obs_h][obs_w] bytes (planar frames)
+ *   h_in       dev  [B][rnn_dim] fp32, 4-byte aligned
+ *   done       dev  [B] bytes; non-zero = this observation is the first of a new
+ *                   episode: the incoming state is zeroed before the GRU cell
+ *   seed, step      sampler key and time step.  Category i of head k in row b is
+ *                   perturbed with Gumbel noise from word (i mod 4) of
+ *                   Philox4x32-10(key = (seed lo, seed hi),
+ *                                 counter = (b, step lo, step hi, k << 16 | i / 4)),
+ *                   u = ((word >> 9) + 0.5) * 2^-23, g = -log(-log(u)) in fp32;
+ *                   the action is the lowest index maximising logit + g.
+ *   actions    dev  [B][n_heads] int32
+ *   logp       dev  [B] fp32, log-probability of the sampled joint action
+ *   value      dev  [B] fp32
+ *   h_out      dev  [B][rnn_dim] fp32; must not overlap h_in
+ *   logits_opt dev  [B][sum(head_sizes)] fp32, or NULL if not wanted
+ * B == 0 is accepted and does nothing.  Errors: SF_ERR_ARG (null handle or
+ * pointer, misaligned fp32/int32 pointer), SF_ERR_BATCH, SF_ERR_ALIAS,
+ * SF_ERR_DEVICE (a launch failed).  Nothing is enqueued when an error is
+ * returned for the arguments. */
+int sf_policy_step(sf_policy* p, int32_t B, const uint8_t* obs, const float* h_in,
+                   const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions,
+                   float* logp, float* value, float* h_out, float* logits_opt,
+                   void* hip_stream);
+
+/* Free the workspace and the packed weights.  The caller must have synchronised
+ * every stream the handle was stepped on.  NULL is accepted. */
+int sf_policy_destroy(sf_policy* p);
+
+/* Text of the last error on this thread (static storage; empty if none). */
+const char* sf_last_error(void);
+
+/* Number of floating point operations (2 per multiply-add) of one row of the
+ * step for this policy's network, as used by the benchmark's roofline figures. */
+int64_t sf_policy_flops_per_row(const sf_policy* p);
+
+/* ---- measurement aids (used by the benchmark; not part of the step) ----------
+ * The step is a fixed sequence of kernel launches ("ops": the convolutions, the
+ * FC layer, the GRU cell, the heads).  With timing enabled sf_policy_step records
+ * a HIP event on its stream before the first and after every launch;
+ * sf_policy_last_op_times waits for the last recorded step and writes the
+ * duration of each launch in milliseconds to ms_out[0..op_count).  Errors:
+ * SF_ERR_ARG (null handle or buffer, n < op_count), SF_ERR_DEVICE (nothing
+ * recorded yet). */
+int sf_policy_op_count(const sf_policy* p);
+const char* sf_policy_op_name(const sf_policy* p, int i); /* static per handle; "" if out of range */
+int64_t sf_policy_op_flops_per_row(const sf_policy* p, int i);
+int sf_policy_set_op_timing(sf_policy* p, int enable);
+int sf_policy_last_op_times(sf_policy* p, float* ms_out /* host */, int n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,286 @@
+"""Thin ctypes binding of libsf_policy.so (C ABI in include/sf_policy.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  There is no fallback: if the library has not been built, loading it
+raises.  PyTorch appears only as the owner of device memory and streams.
+"""
+import ctypes as C
+import glob
+import os
+import subprocess
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_PKG)
+_CSRC = os.path.join(_PKG, "csrc")
+_SO = os.path.join(_PKG, "libsf_policy.so")
+
+SF_ABI_VERSION = 1
+SF_MAX_CONV, SF_MAX_STAGE, SF_MAX_HEADS, SF_MAX_CONV_TENSORS = 4, 4, 16, 20
+SF_OK, SF_ERR_ARG, SF_ERR_SHAPE, SF_ERR_BATCH, SF_ERR_ALIAS = 0, -1, -2, -3, -4
+SF_ERR_DEVICE, SF_ERR_OOM, SF_ERR_ARCH = -5, -6, -7
+
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-fast-math",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall"]
+
+
+def library_path():
+    return _SO
+
+
+def build_library(verbose=False):
+    """Compile every .hip source for gfx950 and link libsf_policy.so in-tree."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    srcs = sorted(glob.glob(os.path.join(_CSRC, "*.hip")))
+    objdir = os.path.join(_PKG, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    inc = ["-I", os.path.join(_ROOT, "include"), "-I", _CSRC]
+    procs = []
+    for s in srcs:
+        o = os.path.join(objdir, os.path.basename(s) + ".o")
+        cmd = [hipcc] + HIPCC_FLAGS + inc + ["-c", s, "-o", o]
+        if verbose:
+            print(" ".join(cmd))
+        procs.append((s, o, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
+    objs = []
+    for s, o, pr in procs:
+        out, _ = pr.communicate()
+        text = "\n".join(l for l in out.decode().splitlines()
+                         if "packed-fp32-ops" not in l)  # the host pass does not know the feature
+        if pr.returncode != 0:
+            raise RuntimeError("hipcc failed on %s:\n%s" % (s, text))
+        if verbose and text.strip():
+            print(text)
+        objs.append(o)
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", _SO] + objs
+    subprocess.run(cmd, check=True)
+    return _SO
+
+
+class SfConv(C.Structure):
+    _fields_ = [("cout", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32)]
+
+
+class SfPolicyConfig(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("abi_version", C.c_uint32),
+        ("max_batch", C.c_int32), ("obs_c", C.c_int32), ("obs_h", C.c_int32), ("obs_w", C.c_int32),
+        ("encoder", C.c_int32), ("n_conv", C.c_int32), ("conv", SfConv * SF_MAX_CONV),
+        ("n_stage", C.c_int32), ("stage_ch", C.c_int32 * SF_MAX_STAGE),
+        ("blocks_per_stage", C.c_int32),
+        ("fc_dim", C.c_int32), ("rnn_dim", C.c_int32), ("n_heads", C.c_int32),
+        ("head_sizes", C.c_int32 * SF_MAX_HEADS), ("dtype", C.c_int32),
+        ("obs_sub", C.c_float), ("obs_mul", C.c_float),
+    ]
+
+
+_FP = C.POINTER(C.c_float)
+
+
+class SfPolicyWeights(C.Structure):
+    _fields_ = [
+        ("conv_w", _FP * SF_MAX_CONV_TENSORS), ("conv_b", _FP * SF_MAX_CONV_TENSORS),
+        ("fc_w", _FP), ("fc_b", _FP),
+        ("gru_w_ih", _FP), ("gru_w_hh", _FP), ("gru_b_ih", _FP), ("gru_b_hh", _FP),
+        ("pi_w", _FP), ("pi_b", _FP), ("v_w", _FP), ("v_b", _FP),
+    ]
+
+
+EXPORTS = ("sf_policy_create", "sf_policy_step", "sf_policy_destroy", "sf_last_error",
+           "sf_policy_flops_per_row", "sf_policy_op_count", "sf_policy_op_name",
+           "sf_policy_op_flops_per_row", "sf_policy_set_op_timing", "sf_policy_last_op_times")
+
+_lib = None
+
+
+class SfError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("sf_policy error %d: %s" % (code, text))
+        self.code = code
+
+
+def load_library():
+    """Load libsf_policy.so; raises if it has not been built (no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_SO):
+            raise FileNotFoundError(
+                "%s is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                "(hipcc, gfx950) first" % _SO)
+        # PyTorch ships its own copy of the HIP runtime.  Import it first so that this
+        # library binds to that same copy: two HIP runtimes in one process do not
+        # both see the GPU, and the device pointers handed in come from torch's.
+        import torch  # noqa: F401
+        L = C.CDLL(_SO)
+        L.sf_policy_create.restype = C.c_int
+        L.sf_policy_create.argtypes = [C.POINTER(SfPolicyConfig), C.POINTER(SfPolicyWeights),
+                                       C.c_int, C.POINTER(C.c_void_p)]
+        L.sf_policy_step.restype = C.c_int
+        L.sf_policy_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sf_policy_destroy.restype = C.c_int
+        L.sf_policy_destroy.argtypes = [C.c_void_p]
+        L.sf_last_error.restype = C.c_char_p
+        L.sf_policy_flops_per_row.restype = C.c_int64
+        L.sf_policy_flops_per_row.argtypes = [C.c_void_p]
+        L.sf_policy_op_count.restype = C.c_int
+        L.sf_policy_op_count.argtypes = [C.c_void_p]
+        L.sf_policy_op_name.restype = C.c_char_p
+        L.sf_policy_op_name.argtypes = [C.c_void_p, C.c_int]
+        L.sf_policy_op_flops_per_row.restype = C.c_int64
+        L.sf_policy_op_flops_per_row.argtypes = [C.c_void_p, C.c_int]
+        L.sf_policy_set_op_timing.restype = C.c_int
+        L.sf_policy_set_op_timing.argtypes = [C.c_void_p, C.c_int]
+        L.sf_policy_last_op_times.restype = C.c_int
+        L.sf_policy_last_op_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int]
+        _lib = L
+    return _lib
+
+
+def sf_last_error():
+    return load_library().sf_last_error().decode()
+
+
+def make_config(net, max_batch):
+    """net: dict as produced by workloads.network()."""
+    c = SfPolicyConfig()
+    c.struct_size, c.abi_version = C.sizeof(SfPolicyConfig), SF_ABI_VERSION
+    c.max_batch = max_batch
+    c.obs_c, c.obs_h, c.obs_w = net["obs"]
+    if net["encoder"] == "resnet":
+        c.encoder = 1
+        c.n_stage = len(net["stages"])
+        for i, ch in enumerate(net["stages"]):
+            c.stage_ch[i] = ch
+        c.blocks_per_stage = net["blocks_per_stage"]
+    else:
+        c.encoder = 0
+        c.n_conv = len(net["convs"])
+        for i, (co, k, s, p) in enumerate(net["convs"]):
+            c.conv[i] = SfConv(co, k, s, p)
+    c.fc_dim, c.rnn_dim, c.n_heads = net["fc"], net["rnn"], len(net["heads"])
+    for i, a in enumerate(net["heads"]):
+        c.head_sizes[i] = a
+    c.dtype = 1 if net["dtype"] == "bf16" else 0
+    c.obs_sub, c.obs_mul = net["obs_sub"], net["obs_mul"]
+    return c
+
+
+def make_weights(w):
+    """w: dict of fp32 numpy arrays (workloads.weights()).  Returns (struct, keepalive)."""
+    s = SfPolicyWeights()
+    keep = []
+
+    def fp(a):
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        keep.append(a)
+        return a.ctypes.data_as(_FP)
+
+    for i, (cw, cb) in enumerate(zip(w["conv_w"], w["conv_b"])):
+        s.conv_w[i], s.conv_b[i] = fp(cw), fp(cb)
+    for name in ("fc_w", "fc_b", "gru_w_ih", "gru_w_hh", "gru_b_ih", "gru_b_hh", "pi_w", "pi_b",
+                 "v_w", "v_b"):
+        setattr(s, name, fp(w[name]))
+    return s, keep
+
+
+def sf_policy_create(cfg, weights, hip_device=0):
+    """cfg: SfPolicyConfig, weights: SfPolicyWeights -> opaque handle (int)."""
+    h = C.c_void_p()
+    rc = load_library().sf_policy_create(C.byref(cfg), C.byref(weights), hip_device, C.byref(h))
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+    return h.value
+
+
+def sf_policy_step(handle, B, obs, h_in, done, seed, step, actions, logp, value, h_out,
+                   logits_opt=None, hip_stream=None):
+    """All buffers are device addresses (ints), e.g. torch.Tensor.data_ptr()."""
+    rc = load_library().sf_policy_step(handle, B, obs, h_in, done, seed, step, actions, logp,
+                                       value, h_out, logits_opt, hip_stream)
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+
+
+def sf_policy_destroy(handle):
+    load_library().sf_policy_destroy(handle)
+
+
+class Policy:
+    """Convenience owner of one handle; torch tensors in, torch tensors out."""
+
+    def __init__(self, net, weights, max_batch=None, device=0):
+        import torch
+        self._torch = torch
+        self.net = net
+        self.device = torch.device("cuda", device)
+        self.max_batch = max_batch or net["B"]
+        cfg = make_config(net, self.max_batch)
+        ws, keep = make_weights(weights)
+        self.handle = sf_policy_create(cfg, ws, device)
+        del keep
+        self.n_heads, self.sumA, self.H = len(net["heads"]), sum(net["heads"]), net["rnn"]
+
+    def flops_per_row(self):
+        return int(load_library().sf_policy_flops_per_row(self.handle))
+
+    def ops(self):
+        """[(name, flops_per_row)] for each kernel launch of the step."""
+        L = load_library()
+        return [(L.sf_policy_op_name(self.handle, i).decode(),
+                 int(L.sf_policy_op_flops_per_row(self.handle, i)))
+                for i in range(L.sf_policy_op_count(self.handle))]
+
+    def set_op_timing(self, enable):
+        rc = load_library().sf_policy_set_op_timing(self.handle, int(bool(enable)))
+        if rc != SF_OK:
+            raise SfError(rc, sf_last_error())
+
+    def last_op_times_ms(self):
+        L = load_library()
+        n = L.sf_policy_op_count(self.handle)
+        buf = (C.c_float * n)()
+        rc = L.sf_policy_last_op_times(self.handle, buf, n)
+        if rc != SF_OK:
+            raise SfError(rc, sf_last_error())
+        return list(buf)
+
+    def alloc_outputs(self, B, logits=True):
+        t = self._torch
+        d = self.device
+        return dict(actions=t.empty((B, self.n_heads), dtype=t.int32, device=d),
+                    logp=t.empty(B, dtype=t.float32, device=d),
+                    value=t.empty(B, dtype=t.float32, device=d),
+                    h_out=t.empty((B, self.H), dtype=t.float32, device=d),
+                    logits=t.empty((B, self.sumA), dtype=t.float32, device=d) if logits else None)
+
+    def step(self, obs, h_in, done, seed, step, out=None, stream=None):
+        """obs u8 [B,C,H,W], h_in f32 [B,H], done u8 [B]: contiguous CUDA tensors."""
+        t = self._torch
+        B = obs.shape[0]
+        assert obs.dtype == t.uint8 and h_in.dtype == t.float32 and done.dtype == t.uint8
+        assert obs.is_contiguous() and h_in.is_contiguous() and done.is_contiguous()
+        assert tuple(obs.shape[1:]) == tuple(self.net["obs"]) and tuple(h_in.shape) == (B, self.H)
+        assert done.shape == (B,)
+        if out is None:
+            out = self.alloc_outputs(B)
+        s = stream if stream is not None else t.cuda.current_stream(self.device)
+        sf_policy_step(self.handle, B, obs.data_ptr(), h_in.data_ptr(), done.data_ptr(), seed, step,
+                       out["actions"].data_ptr(), out["logp"].data_ptr(), out["value"].data_ptr(),
+                       out["h_out"].data_ptr(),
+                       out["logits"].data_ptr() if out.get("logits") is not None else None,
+                       s.cuda_stream)
+        return out
+
+    def close(self):
+        if self.handle:
+            sf_policy_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,183 @@
+// Shape-agnostic kernels: one thread per output element, fp32 FMA in a fixed
+// order.  They serve every network description the boundary accepts; the
+// MFMA kernels replace them for the shapes they are specialised for.
+#include "sf_internal.h"
+
+namespace sf {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// Convolution (paper, App. "Model architectures": convolutional encoder).
+// in: planar bytes [B][C][H][W] (normalised on the fly) or channels-last fp32.
+// out: channels-last fp32 [B][Ho][Wo][Cout].  w: [k][k][Cin][Cout].
+template <bool kU8Planar>
+__global__ __launch_bounds__(kThreads) void conv_generic_kernel(
+    const void* __restrict__ in_v, float* __restrict__ out, const float* __restrict__ w,
+    const float* __restrict__ bias, const float* __restrict__ residual, long long total, int Cin,
+    int H, int W, int Cout, int k, int s, int pad, int Ho, int Wo, int relu_in, int relu_out,
+    float obs_sub, float obs_mul) {
+  long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
+  int o = (int)(idx % Cout);
+  long long t = idx / Cout;
+  int ox = (int)(t % Wo);
+  t /= Wo;
+  int oy = (int)(t % Ho);
+  long long b = t / Ho;
+  float acc = bias[o];
+  for (int p = 0; p < k; ++p) {
+    int y = oy * s + p - pad;
+    if (y < 0 || y >= H) continue;
+    for (int q = 0; q < k; ++q) {
+      int x = ox * s + q - pad;
+      if (x < 0 || x >= W) continue;
+      const float* wp = w + ((size_t)(p * k + q) * Cin) * Cout + o;
+      if (kU8Planar) {
+        const uint8_t* ip = (const uint8_t*)in_v + ((size_t)b * Cin * H + y) * W + x;
+        for (int c = 0; c < Cin; ++c) {
+          float v = ((float)ip[(size_t)c * H * W] - obs_sub) * obs_mul;
+          acc = fmaf(v, wp[(size_t)c * Cout], acc);
+        }
+      } else {
+        const float* ip = (const float*)in_v + (((size_t)b * H + y) * W + x) * Cin;
+        for (int c = 0; c < Cin; ++c) {
+          float v = ip[c];
+          if (relu_in) v = fmaxf(v, 0.0f);
+          acc = fmaf(v, wp[(size_t)c * Cout], acc);
+        }
+      }
+    }
+  }
+  if (residual) acc += residual[idx];
+  if (relu_out) acc = fmaxf(acc, 0.0f);
+  out[idx] = acc;
+}
+
+// 3x3/s2 max pooling whose padding ring never wins (channels-last).
+__global__ __launch_bounds__(kThreads) void maxpool_kernel(const float* __restrict__ in,
+                                                           float* __restrict__ out,
+                                                           long long total, int C, int H, int W,
+                                                           int Ho, int Wo) {
+  long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
+  int c = (int)(idx % C);
+  long long t = idx / C;
+  int ox = (int)(t % Wo);
+  t /= Wo;
+  int oy = (int)(t % Ho);
+  long long b = t / Ho;
+  float m = -INFINITY;
+  for (int y = 2 * oy - 1; y <= 2 * oy + 1; ++y) {
+    if (y < 0 || y >= H) continue;
+    for (int x = 2 * ox - 1; x <= 2 * ox + 1; ++x) {
+      if (x < 0 || x >= W) continue;
+      m = fmaxf(m, in[(((size_t)b * H + y) * W + x) * C + c]);
+    }
+  }
+  out[idx] = m;
+}
+
+// out[b][o] = act(bias[o] + sum_i in[b][i] * w_t[i][o])
+__global__ __launch_bounds__(kThreads) void linear_generic_kernel(
+    const float* __restrict__ in, const float* __restrict__ w_t, const float* __restrict__ bias,
+    float* __restrict__ out, int n_in, int n_out, int relu) {
+  int o = blockIdx.x * kThreads + threadIdx.x;
+  int b = blockIdx.y;
+  if (o >= n_out) return;
+  const float* ip = in + (size_t)b * n_in;
+  float acc = bias[o];
+  for (int i = 0; i < n_in; ++i) acc = fmaf(ip[i], w_t[(size_t)i * n_out + o], acc);
+  if (relu) acc = fmaxf(acc, 0.0f);
+  out[(size_t)b * n_out + o] = acc;
+}
+
+__device__ inline float sigmoidf_acc(float a) { return 1.0f / (1.0f + expf(-a)); }
+
+// GRU cell with the episode-boundary reset applied to the incoming state.
+// Gate columns of the transposed weights: [0,H) r, [H,2H) z, [2H,3H) n.
+__global__ __launch_bounds__(kThreads) void gru_generic_kernel(
+    const float* __restrict__ x, const float* __restrict__ h_in, const uint8_t* __restrict__ done,
+    const float* __restrict__ wih_t, const float* __restrict__ whh_t,
+    const float* __restrict__ bih, const float* __restrict__ bhh, float* __restrict__ h_out,
+    int n_in, int H) {
+  int j = blockIdx.x * kThreads + threadIdx.x;
+  int b = blockIdx.y;
+  if (j >= H) return;
+  const bool reset = done[b] != 0;
+  const float* xp = x + (size_t)b * n_in;
+  const float* hp = h_in + (size_t)b * H;
+  float ir = bih[j], iz = bih[H + j], in_ = bih[2 * H + j];
+  for (int i = 0; i < n_in; ++i) {
+    float v = xp[i];
+    const float* wp = wih_t + (size_t)i * 3 * H + j;
+    ir = fmaf(v, wp[0], ir);
+    iz = fmaf(v, wp[H], iz);
+    in_ = fmaf(v, wp[2 * H], in_);
+  }
+  float hr = bhh[j], hz = bhh[H + j], hn = bhh[2 * H + j];
+  if (!reset) {
+    for (int i = 0; i < H; ++i) {
+      float v = hp[i];
+      const float* wp = whh_t + (size_t)i * 3 * H + j;
+      hr = fmaf(v, wp[0], hr);
+      hz = fmaf(v, wp[H], hz);
+      hn = fmaf(v, wp[2 * H], hn);
+    }
+  }
+  float hprev = reset ? 0.0f : hp[j];
+  float r = sigmoidf_acc(ir + hr);
+  float z = sigmoidf_acc(iz + hz);
+  float n = tanhf(in_ + r * hn);
+  h_out[(size_t)b * H + j] = (1.0f - z) * n + z * hprev;
+}
+
+inline unsigned blocks_for(long long total) { return (unsigned)((total + kThreads - 1) / kThreads); }
+
+}  // namespace
+
+hipError_t launch_conv_generic(const ConvLayer& L, int B, const void* in, bool in_is_u8_planar,
+                               float obs_sub, float obs_mul, const float* residual, float* out,
+                               hipStream_t st) {
+  long long total = (long long)B * L.Ho * L.Wo * L.cout;
+  if (total == 0) return hipSuccess;
+  if (in_is_u8_planar)
+    conv_generic_kernel<true><<<blocks_for(total), kThreads, 0, st>>>(
+        in, out, L.w_khwc_o, L.bias, residual, total, L.cin, L.H, L.W, L.cout, L.k, L.s, L.pad,
+        L.Ho, L.Wo, L.relu_in, L.relu_out, obs_sub, obs_mul);
+  else
+    conv_generic_kernel<false><<<blocks_for(total), kThreads, 0, st>>>(
+        in, out, L.w_khwc_o, L.bias, residual, total, L.cin, L.H, L.W, L.cout, L.k, L.s, L.pad,
+        L.Ho, L.Wo, L.relu_in, L.relu_out, obs_sub, obs_mul);
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool3x3s2p1(int B, int C, int H, int W, const float* in, float* out,
+                                 hipStream_t st) {
+  int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
+  long long total = (long long)B * Ho * Wo * C;
+  if (total == 0) return hipSuccess;
+  maxpool_kernel<<<blocks_for(total), kThreads, 0, st>>>(in, out, total, C, H, W, Ho, Wo);
+  return hipGetLastError();
+}
+
+hipError_t launch_linear_generic(int B, int n_in, int n_out, const float* in, const float* w_t,
+                                 const float* bias, int relu, float* out, hipStream_t st) {
+  if (B == 0) return hipSuccess;
+  dim3 grid((n_out + kThreads - 1) / kThreads, B);
+  linear_generic_kernel<<<grid, kThreads, 0, st>>>(in, w_t, bias, out, n_in, n_out, relu);
+  return hipGetLastError();
+}
+
+hipError_t launch_gru_generic(int B, int n_in, int H, const float* x, const float* h_in,
+                              const uint8_t* done, const float* wih_t, const float* whh_t,
+                              const float* bih, const float* bhh, float* h_out, hipStream_t st) {
+  if (B == 0) return hipSuccess;
+  dim3 grid((H + kThreads - 1) / kThreads, B);
+  gru_generic_kernel<<<grid, kThreads, 0, st>>>(x, h_in, done, wih_t, whh_t, bih, bhh, h_out,
+                                                n_in, H);
+  return hipGetLastError();
+}
+
+}  // namespace sf

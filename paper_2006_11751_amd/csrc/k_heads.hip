@@ -1,0 +1,141 @@
+// Action heads, value head, log-probability and sampling: one 64-lane wavefront
+// per batch row.
+//
+// The linear heads (paper, App. "Model architectures": a pair of fully connected
+// layers giving the action distribution and the baseline) are thin dot products
+// over h_out.  Each categorical head is then sampled with the Gumbel-max rule:
+// category i is perturbed with g_i = -log(-log(u_i)), u_i from a counter-based
+// Philox4x32-10 stream keyed by (seed; row, step, head, i/4), and the lowest index
+// attaining the maximum is the action.  Heads are independent (paper, App.
+// "VizDoom experiments"), so the joint log-probability is the sum over heads.
+#include "sf_internal.h"
+
+namespace sf {
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kRowsPerBlock = 4;
+constexpr int kMaxLogits = 1024;  // per row, value included (LDS staging)
+
+__device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                     uint32_t k0, uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t m0 = 0xD2511F53u, m1 = 0xCD9E8D57u;
+    uint32_t hi0 = __umulhi(m0, c0), lo0 = m0 * c0;
+    uint32_t hi1 = __umulhi(m1, c2), lo1 = m1 * c2;
+    uint32_t n0 = hi1 ^ c1 ^ k0;
+    uint32_t n2 = hi0 ^ c3 ^ k1;
+    c0 = n0;
+    c1 = lo1;
+    c2 = n2;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0;
+  out[1] = c1;
+  out[2] = c2;
+  out[3] = c3;
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
+  return v;
+}
+
+__global__ __launch_bounds__(kWave* kRowsPerBlock) void heads_kernel(
+    const float* __restrict__ h, const float* __restrict__ head_w,
+    const float* __restrict__ head_b, const int32_t* __restrict__ head_off, int B, int H,
+    int n_heads, int sumA, uint32_t seed_lo, uint32_t seed_hi, uint32_t step_lo,
+    uint32_t step_hi, int32_t* __restrict__ actions, float* __restrict__ logp,
+    float* __restrict__ value, float* __restrict__ logits_opt) {
+  __shared__ float s_logits[kRowsPerBlock][kMaxLogits];
+  const int lane = threadIdx.x % kWave;
+  const int wave = threadIdx.x / kWave;
+  const int b = blockIdx.x * kRowsPerBlock + wave;
+  if (b >= B) return;  // whole wave leaves together; no block-level barrier below
+  float* lg = s_logits[wave];
+  const float* hp = h + (size_t)b * H;
+
+  // logits and value: lane-strided dot products, butterfly reduction (fixed order)
+  for (int a = 0; a <= sumA; ++a) {
+    const float* wp = head_w + (size_t)a * H;
+    float acc = 0.0f;
+    for (int i = lane; i < H; i += kWave) acc = fmaf(hp[i], wp[i], acc);
+    acc = wave_sum(acc) + head_b[a];
+    if (lane == 0) lg[a] = acc;
+  }
+  __builtin_amdgcn_wave_barrier();
+  __threadfence_block();
+  if (lane == 0) value[b] = lg[sumA];
+  if (logits_opt)
+    for (int a = lane; a < sumA; a += kWave) logits_opt[(size_t)b * sumA + a] = lg[a];
+
+  float lp_total = 0.0f;
+  for (int k = 0; k < n_heads; ++k) {
+    const int off = head_off[k];
+    const int A = head_off[k + 1] - off;
+    float best = -INFINITY, lmax = -INFINITY;
+    int arg = 0x7FFFFFFF;
+    for (int i = lane; i < A; i += kWave) {
+      uint32_t wd[4];
+      philox4x32_10((uint32_t)b, step_lo, step_hi, ((uint32_t)k << 16) | (uint32_t)(i >> 2),
+                    seed_lo, seed_hi, wd);
+      uint32_t word = wd[i & 3];
+      float u = ((float)(word >> 9) + 0.5f) * 0x1.0p-23f;
+      float g = -logf(-logf(u));
+      float l = lg[off + i];
+      float pert = l + g;
+      if (arg == 0x7FFFFFFF || pert > best) {
+        best = pert;
+        arg = i;
+      }
+      lmax = fmaxf(lmax, l);
+    }
+    // wave argmax, ties to the lowest index
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+      float ob = __shfl_xor(best, m, kWave);
+      int oa = __shfl_xor(arg, m, kWave);
+      bool take = (oa != 0x7FFFFFFF) && (arg == 0x7FFFFFFF || ob > best || (ob == best && oa < arg));
+      if (take) {
+        best = ob;
+        arg = oa;
+      }
+    }
+    lmax = wave_max(lmax);
+    float se = 0.0f;
+    for (int i = lane; i < A; i += kWave) se += expf(lg[off + i] - lmax);
+    se = wave_sum(se);
+    float lse = lmax + logf(se);
+    lp_total += lg[off + arg] - lse;
+    if (lane == 0) actions[(size_t)b * n_heads + k] = arg;
+  }
+  if (lane == 0) logp[b] = lp_total;
+}
+
+}  // namespace
+
+hipError_t launch_heads(int B, int H, int n_heads, int sumA, const int32_t* head_off,
+                        const float* h, const float* head_w, const float* head_b, uint64_t seed,
+                        uint64_t step, int32_t* actions, float* logp, float* value,
+                        float* logits_opt, hipStream_t st) {
+  if (B == 0) return hipSuccess;
+  if (sumA + 1 > kMaxLogits) return hipErrorInvalidValue;
+  unsigned blocks = (unsigned)((B + kRowsPerBlock - 1) / kRowsPerBlock);
+  heads_kernel<<<blocks, kWave * kRowsPerBlock, 0, st>>>(
+      h, head_w, head_b, head_off, B, H, n_heads, sumA, (uint32_t)seed, (uint32_t)(seed >> 32),
+      (uint32_t)step, (uint32_t)(step >> 32), actions, logp, value, logits_opt);
+  return hipGetLastError();
+}
+
+}  // namespace sf

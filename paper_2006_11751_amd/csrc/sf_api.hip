@@ -1,0 +1,512 @@
+// C ABI of the sf_policy library: validation, weight packing, workspace and the
+// launch sequence of one policy step (see include/sf_policy.h for the contract).
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "sf_internal.h"
+
+namespace sf {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+namespace {
+
+// Round to the nearest bf16 (ties to even) and widen again.
+float bf16_round(float v) {
+  uint32_t u;
+  memcpy(&u, &v, 4);
+  if ((u & 0x7F800000u) != 0x7F800000u) u = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
+  memcpy(&v, &u, 4);
+  return v;
+}
+
+struct Builder {
+  Policy* p;
+  bool bf16;
+  int status = SF_OK;
+
+  void* dev_alloc(size_t bytes) {
+    void* d = nullptr;
+    if (bytes == 0) bytes = 4;
+    hipError_t e = hipMalloc(&d, bytes);
+    if (e != hipSuccess) {
+      set_error("hipMalloc(%zu bytes) failed: %s", bytes, hipGetErrorString(e));
+      status = SF_ERR_OOM;
+      return nullptr;
+    }
+    p->allocations.push_back(d);
+    return d;
+  }
+
+  template <typename T>
+  T* upload(const std::vector<T>& host) {
+    T* d = (T*)dev_alloc(host.size() * sizeof(T));
+    if (!d) return nullptr;
+    hipError_t e = hipMemcpy(d, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      set_error("hipMemcpy to device failed: %s", hipGetErrorString(e));
+      status = SF_ERR_DEVICE;
+      return nullptr;
+    }
+    return d;
+  }
+
+  float q(float v) const { return bf16 ? bf16_round(v) : v; }
+
+  // [cout][cin][k][k] -> [k][k][cin][cout]
+  float* pack_conv(const float* w, int cout, int cin, int k) {
+    std::vector<float> t((size_t)cout * cin * k * k);
+    for (int o = 0; o < cout; ++o)
+      for (int c = 0; c < cin; ++c)
+        for (int a = 0; a < k; ++a)
+          for (int b = 0; b < k; ++b)
+            t[(((size_t)a * k + b) * cin + c) * cout + o] =
+                q(w[(((size_t)o * cin + c) * k + a) * k + b]);
+    return upload(t);
+  }
+
+  float* pack_vec(const float* v, size_t n) {
+    std::vector<float> t(n);
+    for (size_t i = 0; i < n; ++i) t[i] = q(v[i]);
+    return upload(t);
+  }
+
+  // [n_out][n_in] -> [n_in][n_out]
+  float* pack_transposed(const float* w, int n_out, int n_in) {
+    std::vector<float> t((size_t)n_out * n_in);
+    for (int o = 0; o < n_out; ++o)
+      for (int i = 0; i < n_in; ++i) t[(size_t)i * n_out + o] = q(w[(size_t)o * n_in + i]);
+    return upload(t);
+  }
+};
+
+int check_config(const sf_policy_config* c, int* Cf, int* Hf, int* Wf) {
+  if (c->max_batch < 1 || c->max_batch > 65535) {
+    set_error("max_batch %d outside [1, 65535]", c->max_batch);
+    return SF_ERR_SHAPE;
+  }
+  if (c->obs_c < 1 || c->obs_h < 1 || c->obs_w < 1) {
+    set_error("empty observation shape");
+    return SF_ERR_SHAPE;
+  }
+  int C = c->obs_c, H = c->obs_h, W = c->obs_w;
+  if (c->encoder == SF_ENCODER_CONV) {
+    if (c->n_conv < 1 || c->n_conv > SF_MAX_CONV) {
+      set_error("n_conv %d outside [1, %d]", c->n_conv, SF_MAX_CONV);
+      return SF_ERR_SHAPE;
+    }
+    for (int l = 0; l < c->n_conv; ++l) {
+      const sf_conv& v = c->conv[l];
+      if (v.cout < 1 || v.k < 1 || v.stride < 1 || v.pad < 0 || H + 2 * v.pad < v.k ||
+          W + 2 * v.pad < v.k) {
+        set_error("convolution %d has an empty output or bad parameters", l);
+        return SF_ERR_SHAPE;
+      }
+      H = (H + 2 * v.pad - v.k) / v.stride + 1;
+      W = (W + 2 * v.pad - v.k) / v.stride + 1;
+      C = v.cout;
+    }
+  } else if (c->encoder == SF_ENCODER_RESNET) {
+    if (c->n_stage < 1 || c->n_stage > SF_MAX_STAGE || c->blocks_per_stage < 0 ||
+        c->n_stage * (1 + 2 * c->blocks_per_stage) > SF_MAX_CONV_TENSORS) {
+      set_error("bad residual encoder description");
+      return SF_ERR_SHAPE;
+    }
+    for (int s = 0; s < c->n_stage; ++s) {
+      if (c->stage_ch[s] < 1) {
+        set_error("stage %d has no channels", s);
+        return SF_ERR_SHAPE;
+      }
+      C = c->stage_ch[s];
+      H = (H - 1) / 2 + 1;
+      W = (W - 1) / 2 + 1;
+    }
+  } else {
+    set_error("unknown encoder %d", c->encoder);
+    return SF_ERR_SHAPE;
+  }
+  if (c->fc_dim < 1 || c->rnn_dim < 1) {
+    set_error("fc_dim and rnn_dim must be positive");
+    return SF_ERR_SHAPE;
+  }
+  if (c->n_heads < 1 || c->n_heads > SF_MAX_HEADS) {
+    set_error("n_heads %d outside [1, %d]", c->n_heads, SF_MAX_HEADS);
+    return SF_ERR_SHAPE;
+  }
+  int sumA = 0;
+  for (int k = 0; k < c->n_heads; ++k) {
+    if (c->head_sizes[k] < 1 || c->head_sizes[k] > 65535) {
+      set_error("head %d has size %d", k, c->head_sizes[k]);
+      return SF_ERR_SHAPE;
+    }
+    sumA += c->head_sizes[k];
+  }
+  if (sumA + 1 > 1024) {
+    set_error("more than 1023 logits per row");
+    return SF_ERR_SHAPE;
+  }
+  if (c->dtype != SF_DTYPE_FP32 && c->dtype != SF_DTYPE_BF16) {
+    set_error("unknown dtype %d", c->dtype);
+    return SF_ERR_SHAPE;
+  }
+  *Cf = C;
+  *Hf = H;
+  *Wf = W;
+  return SF_OK;
+}
+
+void free_policy(Policy* p) {
+  if (!p) return;
+  for (void* d : p->allocations) (void)hipFree(d);
+  for (hipEvent_t ev : p->events)
+    if (ev) (void)hipEventDestroy(ev);
+  delete p;
+}
+
+}  // namespace
+}  // namespace sf
+
+using namespace sf;
+
+extern "C" const char* sf_last_error(void) { return g_err; }
+
+extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_weights* w,
+                                int hip_device, sf_policy** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !w || !out) {
+    set_error("sf_policy_create: null argument");
+    return SF_ERR_ARG;
+  }
+  if (cfg->struct_size != sizeof(sf_policy_config) || cfg->abi_version != SF_ABI_VERSION) {
+    set_error("sf_policy_create: struct_size %u / abi_version %u do not match this library (%zu / %u)",
+              cfg->struct_size, cfg->abi_version, sizeof(sf_policy_config), SF_ABI_VERSION);
+    return SF_ERR_ARG;
+  }
+  int Cf, Hf, Wf;
+  int rc = check_config(cfg, &Cf, &Hf, &Wf);
+  if (rc != SF_OK) return rc;
+
+  // every parameter tensor the description needs must be present
+  int n_tensors = cfg->encoder == SF_ENCODER_CONV ? cfg->n_conv
+                                                  : cfg->n_stage * (1 + 2 * cfg->blocks_per_stage);
+  for (int i = 0; i < n_tensors; ++i)
+    if (!w->conv_w[i] || !w->conv_b[i]) {
+      set_error("sf_policy_create: conv tensor %d is null", i);
+      return SF_ERR_ARG;
+    }
+  if (!w->fc_w || !w->fc_b || !w->gru_w_ih || !w->gru_w_hh || !w->gru_b_ih || !w->gru_b_hh ||
+      !w->pi_w || !w->pi_b || !w->v_w || !w->v_b) {
+    set_error("sf_policy_create: a weight pointer is null");
+    return SF_ERR_ARG;
+  }
+
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || hip_device < 0 || hip_device >= n_dev) {
+    set_error("sf_policy_create: HIP device %d not available (%d devices)", hip_device, n_dev);
+    return SF_ERR_DEVICE;
+  }
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, hip_device) != hipSuccess) {
+    set_error("sf_policy_create: hipGetDeviceProperties failed");
+    return SF_ERR_DEVICE;
+  }
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+    set_error("sf_policy_create: device %d is %s; this library is built for gfx950 only",
+              hip_device, prop.gcnArchName);
+    return SF_ERR_ARCH;
+  }
+  if (hipSetDevice(hip_device) != hipSuccess) {
+    set_error("sf_policy_create: hipSetDevice(%d) failed", hip_device);
+    return SF_ERR_DEVICE;
+  }
+
+  Policy* p = new (std::nothrow) Policy();
+  if (!p) {
+    set_error("sf_policy_create: out of host memory");
+    return SF_ERR_OOM;
+  }
+  p->cfg = *cfg;
+  p->device = hip_device;
+  p->flat = Cf * Hf * Wf;
+  Builder bld{p, cfg->dtype == SF_DTYPE_BF16};
+
+  // ---- encoder plan ----
+  size_t act_elems = 0;
+  int64_t macs = 0;
+  {
+    int C = cfg->obs_c, H = cfg->obs_h, W = cfg->obs_w;
+    int ti = 0;
+    auto add_conv = [&](const char* name, int cout, int k, int s, int pad, int relu_in,
+                        int relu_out, int in_buf, int out_buf, int resid_buf) {
+      ConvLayer L{};
+      L.cin = C; L.H = H; L.W = W;
+      L.cout = cout; L.k = k; L.s = s; L.pad = pad;
+      L.Ho = (H + 2 * pad - k) / s + 1;
+      L.Wo = (W + 2 * pad - k) / s + 1;
+      L.w_khwc_o = bld.pack_conv(w->conv_w[ti], cout, C, k);
+      L.bias = bld.pack_vec(w->conv_b[ti], cout);
+      L.relu_in = relu_in; L.relu_out = relu_out; L.add_residual = resid_buf >= 0;
+      ++ti;
+      int64_t m = (int64_t)L.Ho * L.Wo * cout * C * k * k;
+      Op op{OP_CONV, name, 2 * m, (int)p->convs.size(), in_buf, out_buf, resid_buf, 0, 0, 0};
+      p->convs.push_back(L);
+      p->ops.push_back(op);
+      macs += m;
+      size_t e = (size_t)L.Ho * L.Wo * cout;
+      if (e > act_elems) act_elems = e;
+      C = cout; H = L.Ho; W = L.Wo;
+    };
+    char name[64];
+    if (cfg->encoder == SF_ENCODER_CONV) {
+      int in_buf = -1, out_buf = 0;
+      for (int l = 0; l < cfg->n_conv; ++l) {
+        snprintf(name, sizeof(name), "conv%d", l + 1);
+        add_conv(name, cfg->conv[l].cout, cfg->conv[l].k, cfg->conv[l].stride, cfg->conv[l].pad,
+                 0, 1, in_buf, out_buf, -1);
+        in_buf = out_buf;
+        out_buf ^= 1;
+      }
+      p->enc_buf = in_buf;
+    } else {
+      // buffer roles rotate: x holds the stage state, t and u are scratch
+      int x = 0, t = 1, u = 2;
+      int in_buf = -1;
+      for (int s = 0; s < cfg->n_stage; ++s) {
+        snprintf(name, sizeof(name), "stage%d.conv", s + 1);
+        add_conv(name, cfg->stage_ch[s], 3, 1, 1, 0, 0, in_buf, t, -1);
+        snprintf(name, sizeof(name), "stage%d.pool", s + 1);
+        p->ops.push_back(Op{OP_POOL, name, 0, -1, t, x, -1, C, H, W});
+        H = (H - 1) / 2 + 1;
+        W = (W - 1) / 2 + 1;
+        for (int b = 0; b < cfg->blocks_per_stage; ++b) {
+          bool last = (s == cfg->n_stage - 1) && (b == cfg->blocks_per_stage - 1);
+          snprintf(name, sizeof(name), "stage%d.block%d.conv_a", s + 1, b + 1);
+          add_conv(name, cfg->stage_ch[s], 3, 1, 1, 1, 1, x, t, -1);
+          snprintf(name, sizeof(name), "stage%d.block%d.conv_b", s + 1, b + 1);
+          add_conv(name, cfg->stage_ch[s], 3, 1, 1, 0, last ? 1 : 0, t, u, x);
+          int tmp = x;
+          x = u;
+          u = tmp;
+        }
+        in_buf = x;
+      }
+      p->enc_buf = x;
+    }
+  }
+  p->act_elems = act_elems;
+
+  // ---- FC: columns permuted from (c, y, x) to the channels-last order (y, x, c), transposed ----
+  {
+    std::vector<float> t((size_t)p->flat * cfg->fc_dim);
+    for (int o = 0; o < cfg->fc_dim; ++o)
+      for (int c = 0; c < Cf; ++c)
+        for (int y = 0; y < Hf; ++y)
+          for (int x = 0; x < Wf; ++x) {
+            size_t src = (size_t)o * p->flat + ((size_t)c * Hf + y) * Wf + x;
+            size_t dst = ((size_t)(y * Wf + x) * Cf + c) * cfg->fc_dim + o;
+            t[dst] = bld.q(w->fc_w[src]);
+          }
+    p->fc_w_t = bld.upload(t);
+    p->fc_b = bld.pack_vec(w->fc_b, cfg->fc_dim);
+    macs += (int64_t)p->flat * cfg->fc_dim;
+    p->ops.push_back(Op{OP_FC, "fc", 2 * (int64_t)p->flat * cfg->fc_dim, -1, p->enc_buf, -1, -1, 0, 0, 0});
+  }
+  // ---- GRU ----
+  const int H3 = 3 * cfg->rnn_dim;
+  p->gru_wih_t = bld.pack_transposed(w->gru_w_ih, H3, cfg->fc_dim);
+  p->gru_whh_t = bld.pack_transposed(w->gru_w_hh, H3, cfg->rnn_dim);
+  p->gru_bih = bld.pack_vec(w->gru_b_ih, H3);
+  p->gru_bhh = bld.pack_vec(w->gru_b_hh, H3);
+  macs += (int64_t)H3 * (cfg->fc_dim + cfg->rnn_dim);
+  p->ops.push_back(Op{OP_GRU, "gru", 2 * (int64_t)H3 * (cfg->fc_dim + cfg->rnn_dim), -1, -1, -1, -1, 0, 0, 0});
+  // ---- heads: action logits then the value row ----
+  {
+    int sumA = 0;
+    std::vector<int32_t> off(cfg->n_heads + 1, 0);
+    for (int k = 0; k < cfg->n_heads; ++k) {
+      sumA += cfg->head_sizes[k];
+      off[k + 1] = sumA;
+    }
+    p->sumA = sumA;
+    const int Hd = cfg->rnn_dim;
+    std::vector<float> hw((size_t)(sumA + 1) * Hd), hb(sumA + 1);
+    for (size_t i = 0; i < (size_t)sumA * Hd; ++i) hw[i] = bld.q(w->pi_w[i]);
+    for (int i = 0; i < Hd; ++i) hw[(size_t)sumA * Hd + i] = bld.q(w->v_w[i]);
+    for (int i = 0; i < sumA; ++i) hb[i] = bld.q(w->pi_b[i]);
+    hb[sumA] = bld.q(w->v_b[0]);
+    p->head_w = bld.upload(hw);
+    p->head_b = bld.upload(hb);
+    p->head_off = bld.upload(off);
+    macs += (int64_t)(sumA + 1) * Hd;
+    p->ops.push_back(Op{OP_HEADS, "heads", 2 * (int64_t)(sumA + 1) * Hd, -1, -1, -1, -1, 0, 0, 0});
+  }
+  p->flops_per_row = 2 * macs;
+
+  // ---- workspace ----
+  int n_act = cfg->encoder == SF_ENCODER_RESNET ? 3 : 2;
+  for (int i = 0; i < 3; ++i)
+    p->act[i] = i < n_act ? (float*)bld.dev_alloc(sizeof(float) * act_elems * cfg->max_batch)
+                          : nullptr;
+  p->fc_out = (float*)bld.dev_alloc(sizeof(float) * (size_t)cfg->fc_dim * cfg->max_batch);
+
+  p->events.resize(p->ops.size() + 1, nullptr);
+  for (auto& ev : p->events)
+    if (bld.status == SF_OK && hipEventCreate(&ev) != hipSuccess) {
+      set_error("sf_policy_create: hipEventCreate failed");
+      bld.status = SF_ERR_DEVICE;
+    }
+  if (bld.status != SF_OK) {
+    int st = bld.status;
+    free_policy(p);
+    return st;
+  }
+  if (hipDeviceSynchronize() != hipSuccess) {
+    set_error("sf_policy_create: device synchronisation failed");
+    free_policy(p);
+    return SF_ERR_DEVICE;
+  }
+  *out = reinterpret_cast<sf_policy*>(p);
+  return SF_OK;
+}
+
+extern "C" int sf_policy_destroy(sf_policy* handle) {
+  free_policy(reinterpret_cast<Policy*>(handle));
+  return SF_OK;
+}
+
+extern "C" int64_t sf_policy_flops_per_row(const sf_policy* handle) {
+  return handle ? reinterpret_cast<const Policy*>(handle)->flops_per_row : 0;
+}
+
+#define SF_LAUNCH(expr)                                                         \
+  do {                                                                          \
+    hipError_t e_ = (expr);                                                     \
+    if (e_ != hipSuccess) {                                                     \
+      set_error("sf_policy_step: %s failed: %s", #expr, hipGetErrorString(e_)); \
+      return SF_ERR_DEVICE;                                                     \
+    }                                                                           \
+  } while (0)
+
+extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, const float* h_in,
+                              const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions,
+                              float* logp, float* value, float* h_out, float* logits_opt,
+                              void* hip_stream) {
+  Policy* p = reinterpret_cast<Policy*>(handle);
+  if (!p) {
+    set_error("sf_policy_step: null handle");
+    return SF_ERR_ARG;
+  }
+  const sf_policy_config& c = p->cfg;
+  if (B < 0 || B > c.max_batch) {
+    set_error("sf_policy_step: B = %d outside [0, max_batch = %d]", B, c.max_batch);
+    return SF_ERR_BATCH;
+  }
+  if (B == 0) return SF_OK;
+  if (!obs || !h_in || !done || !actions || !logp || !value || !h_out) {
+    set_error("sf_policy_step: null buffer");
+    return SF_ERR_ARG;
+  }
+  auto misaligned = [](const void* q, uintptr_t a) { return (reinterpret_cast<uintptr_t>(q) & (a - 1)) != 0; };
+  if (misaligned(h_in, 4) || misaligned(h_out, 4) || misaligned(actions, 4) ||
+      misaligned(logp, 4) || misaligned(value, 4) || (logits_opt && misaligned(logits_opt, 4))) {
+    set_error("sf_policy_step: fp32/int32 buffer not 4-byte aligned");
+    return SF_ERR_ARG;
+  }
+  {
+    uintptr_t a0 = (uintptr_t)h_in, b0 = (uintptr_t)h_out;
+    uintptr_t n = sizeof(float) * (uintptr_t)B * c.rnn_dim;
+    if (a0 < b0 + n && b0 < a0 + n) {
+      set_error("sf_policy_step: h_out overlaps h_in");
+      return SF_ERR_ALIAS;
+    }
+  }
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+
+  auto buf = [&](int i) -> float* { return i < 0 ? nullptr : p->act[i]; };
+  if (p->timing) SF_LAUNCH(hipEventRecord(p->events[0], st));
+  for (size_t i = 0; i < p->ops.size(); ++i) {
+    const Op& op = p->ops[i];
+    switch (op.kind) {
+      case OP_CONV: {
+        const ConvLayer& L = p->convs[op.conv];
+        const void* in = op.in_buf < 0 ? (const void*)obs : (const void*)buf(op.in_buf);
+        SF_LAUNCH(launch_conv_generic(L, B, in, op.in_buf < 0, c.obs_sub, c.obs_mul,
+                                      buf(op.resid_buf), buf(op.out_buf), st));
+        break;
+      }
+      case OP_POOL:
+        SF_LAUNCH(launch_maxpool3x3s2p1(B, op.C, op.H, op.W, buf(op.in_buf), buf(op.out_buf), st));
+        break;
+      case OP_FC:
+        SF_LAUNCH(launch_linear_generic(B, p->flat, c.fc_dim, buf(op.in_buf), p->fc_w_t, p->fc_b, 1,
+                                        p->fc_out, st));
+        break;
+      case OP_GRU:
+        SF_LAUNCH(launch_gru_generic(B, c.fc_dim, c.rnn_dim, p->fc_out, h_in, done, p->gru_wih_t,
+                                     p->gru_whh_t, p->gru_bih, p->gru_bhh, h_out, st));
+        break;
+      case OP_HEADS:
+        SF_LAUNCH(launch_heads(B, c.rnn_dim, c.n_heads, p->sumA, p->head_off, h_out, p->head_w,
+                               p->head_b, seed, step, actions, logp, value, logits_opt, st));
+        break;
+    }
+    if (p->timing) SF_LAUNCH(hipEventRecord(p->events[i + 1], st));
+  }
+  return SF_OK;
+}
+
+// ---- measurement aids ------------------------------------------------------
+
+extern "C" int sf_policy_op_count(const sf_policy* handle) {
+  return handle ? (int)reinterpret_cast<const Policy*>(handle)->ops.size() : 0;
+}
+
+extern "C" const char* sf_policy_op_name(const sf_policy* handle, int i) {
+  const Policy* p = reinterpret_cast<const Policy*>(handle);
+  if (!p || i < 0 || i >= (int)p->ops.size()) return "";
+  return p->ops[i].name.c_str();
+}
+
+extern "C" int64_t sf_policy_op_flops_per_row(const sf_policy* handle, int i) {
+  const Policy* p = reinterpret_cast<const Policy*>(handle);
+  if (!p || i < 0 || i >= (int)p->ops.size()) return 0;
+  return p->ops[i].flops_per_row;
+}
+
+extern "C" int sf_policy_set_op_timing(sf_policy* handle, int enable) {
+  Policy* p = reinterpret_cast<Policy*>(handle);
+  if (!p) {
+    set_error("sf_policy_set_op_timing: null handle");
+    return SF_ERR_ARG;
+  }
+  p->timing = enable != 0;
+  return SF_OK;
+}
+
+extern "C" int sf_policy_last_op_times(sf_policy* handle, float* ms_out, int n) {
+  Policy* p = reinterpret_cast<Policy*>(handle);
+  if (!p || !ms_out || n < (int)p->ops.size()) {
+    set_error("sf_policy_last_op_times: bad argument");
+    return SF_ERR_ARG;
+  }
+  if (hipEventSynchronize(p->events.back()) != hipSuccess) {
+    set_error("sf_policy_last_op_times: no timed step has been recorded");
+    return SF_ERR_DEVICE;
+  }
+  for (size_t i = 0; i < p->ops.size(); ++i)
+    if (hipEventElapsedTime(&ms_out[i], p->events[i], p->events[i + 1]) != hipSuccess) {
+      set_error("sf_policy_last_op_times: hipEventElapsedTime failed");
+      return SF_ERR_DEVICE;
+    }
+  return SF_OK;
+}

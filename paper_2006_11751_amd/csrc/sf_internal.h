@@ -1,0 +1,85 @@
+// Internal declarations of the sf_policy library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "sf_policy.h"
+
+namespace sf {
+
+// One convolution as executed.  Activations between layers are channels-last
+// fp32 ([B][H][W][C]); only the observation is planar bytes.
+struct ConvLayer {
+  int cin, H, W;          // input
+  int cout, k, s, pad;    // filter
+  int Ho, Wo;             // output
+  float* w_khwc_o;        // dev [k][k][cin][cout]
+  float* bias;            // dev [cout]
+  int relu_in, relu_out;  // ReLU applied to the input as it is read / to the result
+  int add_residual;       // result += residual buffer before relu_out
+};
+
+// One kernel launch of the step, fixed at create time.
+enum OpKind { OP_CONV, OP_POOL, OP_FC, OP_GRU, OP_HEADS };
+struct Op {
+  OpKind kind;
+  std::string name;
+  int64_t flops_per_row;  // 2 per multiply-add
+  int conv;               // index into Policy::convs (OP_CONV), else -1
+  int in_buf, out_buf;    // activation buffer indices; in_buf -1 = the observation
+  int resid_buf;          // buffer added to the result, or -1
+  int C, H, W;            // OP_POOL: input shape
+};
+
+struct Policy {
+  sf_policy_config cfg;
+  int device;
+  int flat;   // encoder output elements per row
+  int sumA;   // total logits per row
+  std::vector<ConvLayer> convs;  // in execution order
+  // packed weights
+  float* fc_w_t;      // dev [flat (channels-last order)][fc_dim]
+  float* fc_b;        // dev [fc_dim]
+  float* gru_wih_t;   // dev [fc_dim][3H]
+  float* gru_whh_t;   // dev [H][3H]
+  float* gru_bih;     // dev [3H]
+  float* gru_bhh;     // dev [3H]
+  float* head_w;      // dev [sumA + 1][H]   (last row: value head)
+  float* head_b;      // dev [sumA + 1]
+  int32_t* head_off;  // dev [n_heads + 1]   prefix sums of head_sizes
+  // workspace, sized for max_batch
+  float* act[3];      // three activation buffers of act_elems floats per row
+  size_t act_elems;
+  float* fc_out;      // dev [max_batch][fc_dim]
+  std::vector<void*> allocations;
+  int64_t flops_per_row;
+  std::vector<Op> ops;    // the launch sequence
+  int enc_buf;            // buffer holding the encoder output
+  // optional per-launch timing (measurement aid)
+  bool timing = false;
+  std::vector<hipEvent_t> events;  // ops.size() + 1
+};
+
+void set_error(const char* fmt, ...);
+
+// ---- generic kernels (any shape) ----
+hipError_t launch_conv_generic(const ConvLayer& L, int B, const void* in, bool in_is_u8_planar,
+                               float obs_sub, float obs_mul, const float* residual, float* out,
+                               hipStream_t st);
+hipError_t launch_maxpool3x3s2p1(int B, int C, int H, int W, const float* in, float* out,
+                                 hipStream_t st);
+hipError_t launch_linear_generic(int B, int n_in, int n_out, const float* in, const float* w_t,
+                                 const float* bias, int relu, float* out, hipStream_t st);
+hipError_t launch_gru_generic(int B, int n_in, int H, const float* x, const float* h_in,
+                              const uint8_t* done, const float* wih_t, const float* whh_t,
+                              const float* bih, const float* bhh, float* h_out, hipStream_t st);
+hipError_t launch_heads(int B, int H, int n_heads, int sumA, const int32_t* head_off,
+                        const float* h, const float* head_w, const float* head_b, uint64_t seed,
+                        uint64_t step, int32_t* actions, float* logp, float* value,
+                        float* logits_opt, hipStream_t st);
+
+}  // namespace sf

@@ -1,0 +1,274 @@
+"""GPU parity: sf_policy_step (through the C ABI) against the CPU oracle on the
+same seeded inputs, element by element; plus edge cases and the purity /
+prefix properties (paper, Sec. 3.1 "Parallelism": stateless policy workers).
+"""
+import numpy as np
+import pytest
+
+from paper_2006_11751_amd import workloads as wl
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def _to_np(out):
+    return {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
+
+
+def _gpu_step(torch, pol, obs, h_in, done, seed, step):
+    d = pol.device
+    out = pol.step(torch.from_numpy(obs).to(d), torch.from_numpy(h_in).to(d),
+                   torch.from_numpy(done).to(d), seed, step)
+    torch.cuda.synchronize()
+    return _to_np(out)
+
+
+def _make(torch, net, max_batch=None):
+    from paper_2006_11751_amd import binding
+    w = wl.weights(net)
+    return binding.Policy(net, w, max_batch=max_batch or net["B"]), w
+
+
+SMALL_RESNET = dict(name="resnet_small", B=5, obs=(3, 18, 24), encoder="resnet", stages=[4, 6, 6],
+                    blocks_per_stage=2, fc=16, rnn=12, heads=[5], dtype="fp32", p_done=0.3, steps=1,
+                    obs_sub=0.0, obs_mul=wl.OBS_MUL, index=4)
+ODD_NET = dict(name="odd", B=37, obs=(2, 23, 29), encoder="conv", convs=[(5, 5, 2, 1), (7, 3, 1, 0)],
+               fc=19, rnn=33, heads=[1, 2, 70, 5], dtype="fp32", p_done=0.5, steps=1,
+               obs_sub=127.5, obs_mul=1.0 / 64, index=0)
+
+
+def test_tiny_four_steps_free_running(torch_cuda, ref):
+    """Configuration 0: every element, 4 steps, each side carrying its own state."""
+    torch = torch_cuda
+    net = wl.network(0)
+    pol, w = _make(torch, net)
+    h_gpu = wl.initial_state(net)
+    h_ref = h_gpu.copy()
+    for t in range(net["steps"]):
+        obs, done = wl.observations(net, t), wl.done_mask(net, t)
+        g = _gpu_step(torch, pol, obs, h_gpu, done, wl.PHILOX_SEED, t)
+        o = ref.policy_step(net, w, obs, h_ref, done, wl.PHILOX_SEED, t)
+        parity.check_against_oracle(net, g, o, ref, wl.PHILOX_SEED, t)
+        h_gpu, h_ref = g["h_out"], o["h_out"]
+    pol.close()
+
+
+@pytest.mark.parametrize("net", [SMALL_RESNET, ODD_NET], ids=lambda n: n["name"])
+def test_small_networks_all_elements(torch_cuda, ref, net):
+    torch = torch_cuda
+    pol, w = _make(torch, net)
+    B = net["B"]
+    obs, h_in, done = wl.observations(net, 0, B), wl.initial_state(net, B), wl.done_mask(net, 0, B)
+    g = _gpu_step(torch, pol, obs, h_in, done, 7, 11)
+    o = ref.policy_step(net, w, obs, h_in, done, 7, 11)
+    parity.check_against_oracle(net, g, o, ref, 7, 11)
+    pol.close()
+
+
+def test_standard_full_batch(torch_cuda, ref):
+    """Configuration 1 at its full size (B=1024): every row against the oracle."""
+    torch = torch_cuda
+    net = wl.network(1)
+    pol, w = _make(torch, net)
+    obs, h_in, done = wl.observations(net), wl.initial_state(net), wl.done_mask(net)
+    g = _gpu_step(torch, pol, obs, h_in, done, wl.PHILOX_SEED, 0)
+    o = ref.policy_step(net, w, obs, h_in, done, wl.PHILOX_SEED, 0)
+    stats = parity.check_against_oracle(net, g, o, ref, wl.PHILOX_SEED, 0)
+    print("standard parity:", stats)
+    # ragged batch on the same handle: B = 1000 + tail, and the prefix property
+    g2 = _gpu_step(torch, pol, obs[:999], h_in[:999], done[:999], wl.PHILOX_SEED, 0)
+    for k in ("h_out", "logits", "value", "logp", "actions"):
+        assert np.array_equal(g2[k], g[k][:999]), k
+    pol.close()
+
+
+def _sampled_rows_check(torch, ref, net, n_rows, n_steps=1, full_steps=1):
+    """Full-size batch on the GPU; the oracle computes a sample of rows one by one."""
+    pol, w = _make(torch, net)
+    B = net["B"]
+    rng = np.random.default_rng(99)
+    rows = np.unique(np.concatenate([[0, 1, B - 1, B - 2, B // 2], rng.integers(0, B, n_rows)]))
+    h_gpu = wl.initial_state(net)
+    for t in range(n_steps):
+        obs, done = wl.observations(net, t), wl.done_mask(net, t)
+        g = _gpu_step(torch, pol, obs, h_gpu, done, wl.PHILOX_SEED, t)
+        if t < full_steps or t == n_steps - 1:
+            # teacher-forced on the GPU's incoming state for the sampled rows
+            o = ref.policy_step(net, w, obs[rows], h_gpu[rows], done[rows], wl.PHILOX_SEED, t)
+            # the oracle numbered these rows 0..n-1: redo its sampling with the true row index
+            off = 0
+            for k, A in enumerate(net["heads"]):
+                for i, r in enumerate(rows):
+                    a, lp_k, mg = ref.head_sample(o["logits"][i, off:off + A], wl.PHILOX_SEED, int(r), t, k)
+                    o["actions"][i, k], o["margin"][i, k] = a, mg
+                off += A
+            o["logp"] = np.array([
+                sum(ref.log_softmax(o["logits"][i, s:s + A])[o["actions"][i, k]]
+                    for k, (s, A) in enumerate(zip(np.cumsum([0] + net["heads"][:-1]), net["heads"])))
+                for i in range(len(rows))], np.float32)
+            gs = {k: v[rows] for k, v in g.items()}
+            stats = parity.check_against_oracle(net, gs, o, ref, wl.PHILOX_SEED, t, rows=rows)
+            print(net["name"], "step", t, stats)
+        # properties that hold at any size
+        assert np.all(np.isfinite(g["h_out"])) and np.all(np.abs(g["h_out"]) <= 1.0 + 1e-6)
+        assert np.all(g["logp"] <= 1e-6)
+        h_gpu = g["h_out"]
+    pol.close()
+
+
+def test_standard_bf16_full_size_sampled_rows(torch_cuda, ref):
+    """Configuration 2 (B=4096, bf16 weights/activations)."""
+    _sampled_rows_check(torch_cuda, ref, wl.network(2), 200)
+
+
+def test_multi_discrete_16_steps(torch_cuda, ref):
+    """Configuration 3 (B=2048, six heads, 16 chained steps), sampled rows."""
+    _sampled_rows_check(torch_cuda, ref, wl.network(3), 120, n_steps=16, full_steps=2)
+
+
+def test_multi_discrete_small_free_running(torch_cuda, ref):
+    """Configuration 3's network at B=70, all rows, 16 free-running steps."""
+    torch = torch_cuda
+    net = wl.network(3, B=70)
+    pol, w = _make(torch, net)
+    h_gpu = wl.initial_state(net)
+    h_ref = h_gpu.copy()
+    for t in range(16):
+        obs, done = wl.observations(net, t), wl.done_mask(net, t)
+        g = _gpu_step(torch, pol, obs, h_gpu, done, wl.PHILOX_SEED, t)
+        o = ref.policy_step(net, w, obs, h_ref, done, wl.PHILOX_SEED, t)
+        parity.check_against_oracle(net, g, o, ref, wl.PHILOX_SEED, t)
+        h_gpu, h_ref = g["h_out"], o["h_out"]
+    pol.close()
+
+
+def test_resnet_bf16_full_size_sampled_rows(torch_cuda, ref):
+    """Configuration 4 (B=8192, residual encoder, bf16)."""
+    _sampled_rows_check(torch_cuda, ref, wl.network(4), 40)
+
+
+def test_purity_done_reset_and_edges(torch_cuda, ref):
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    net = wl.network(0)
+    pol, w = _make(torch, net, max_batch=16)
+    obs, h_in = wl.observations(net), wl.initial_state(net)
+    done = np.array([1, 0, 1, 0, 255, 0, 0, 1], np.uint8)
+    a = _gpu_step(torch, pol, obs, h_in, done, 3, 5)
+    b = _gpu_step(torch, pol, obs, h_in, done, 3, 5)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    # reset rows ignore h_in and equal the zero-state result bit for bit
+    h2 = h_in.copy()
+    h2[done != 0] = 55.0
+    c = _gpu_step(torch, pol, obs, h2, done, 3, 5)
+    h0 = h_in.copy()
+    h0[done != 0] = 0.0
+    d = _gpu_step(torch, pol, obs, h0, np.zeros(8, np.uint8), 3, 5)
+    for k in a:
+        assert np.array_equal(a[k], c[k]) and np.array_equal(a[k], d[k]), k
+    # single row and prefix
+    one = _gpu_step(torch, pol, obs[:1], h_in[:1], done[:1], 3, 5)
+    for k in a:
+        assert np.array_equal(one[k], a[k][:1]), k
+    # seed / step reach the sampler only
+    e = _gpu_step(torch, pol, obs, h_in, done, 3, 6)
+    assert np.array_equal(e["logits"], a["logits"]) and np.array_equal(e["h_out"], a["h_out"])
+    # logits are optional
+    dev = pol.device
+    out = pol.alloc_outputs(8, logits=False)
+    pol.step(torch.from_numpy(obs).to(dev), torch.from_numpy(h_in).to(dev), torch.from_numpy(done).to(dev),
+             3, 5, out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out["actions"].cpu().numpy(), a["actions"])
+    assert np.array_equal(out["logp"].cpu().numpy(), a["logp"])
+
+    # argument errors: nothing is enqueued, a status and a message come back
+    t_obs, t_h, t_d = (torch.from_numpy(x).to(dev) for x in (obs, h_in, done))
+    o8 = pol.alloc_outputs(8)
+
+    def call(B=8, obs_p=None, h_p=None, hout_p=None, act_p=None):
+        binding.sf_policy_step(pol.handle, B, t_obs.data_ptr() if obs_p is None else obs_p,
+                               t_h.data_ptr() if h_p is None else h_p, t_d.data_ptr(), 1, 0,
+                               o8["actions"].data_ptr() if act_p is None else act_p,
+                               o8["logp"].data_ptr(), o8["value"].data_ptr(),
+                               o8["h_out"].data_ptr() if hout_p is None else hout_p,
+                               o8["logits"].data_ptr(), None)
+
+    call(B=0)  # accepted, does nothing
+    for kwargs, code in [(dict(B=17), binding.SF_ERR_BATCH), (dict(B=-1), binding.SF_ERR_BATCH),
+                         (dict(hout_p=t_h.data_ptr()), binding.SF_ERR_ALIAS),
+                         (dict(hout_p=t_h.data_ptr() + 64), binding.SF_ERR_ALIAS),
+                         (dict(act_p=o8["actions"].data_ptr() + 2), binding.SF_ERR_ARG)]:
+        with pytest.raises(binding.SfError) as ei:
+            call(**kwargs)
+        assert ei.value.code == code and binding.sf_last_error()
+    with pytest.raises(binding.SfError) as ei:
+        binding.sf_policy_step(pol.handle, 8, None, t_h.data_ptr(), t_d.data_ptr(), 1, 0,
+                               o8["actions"].data_ptr(), o8["logp"].data_ptr(), o8["value"].data_ptr(),
+                               o8["h_out"].data_ptr(), None, None)
+    assert ei.value.code == binding.SF_ERR_ARG
+    torch.cuda.synchronize()
+    pol.close()
+
+
+def test_create_rejects_bad_descriptions(torch_cuda):
+    from paper_2006_11751_amd import binding
+    net = wl.network(0)
+    w = wl.weights(net)
+    ws, keep = binding.make_weights(w)
+    bad = binding.make_config(dict(net, convs=[(16, 8, 4, 0), (32, 40, 2, 0)]), 8)   # empty output
+    with pytest.raises(binding.SfError) as ei:
+        binding.sf_policy_create(bad, ws, 0)
+    assert ei.value.code == binding.SF_ERR_SHAPE
+    cfg = binding.make_config(net, 8)
+    cfg.abi_version = 99
+    with pytest.raises(binding.SfError) as ei:
+        binding.sf_policy_create(cfg, ws, 0)
+    assert ei.value.code == binding.SF_ERR_ARG
+    cfg = binding.make_config(net, 8)
+    ws.fc_w = None
+    with pytest.raises(binding.SfError) as ei:
+        binding.sf_policy_create(cfg, ws, 0)
+    assert ei.value.code == binding.SF_ERR_ARG
+    with pytest.raises(binding.SfError) as ei:
+        binding.sf_policy_create(binding.make_config(net, 8), binding.make_weights(w)[0], 99)
+    assert ei.value.code == binding.SF_ERR_DEVICE
+
+
+def test_sampler_distribution_on_gpu(torch_cuda, ref):
+    """Frequencies of GPU-sampled actions follow softmax(logits): a tiny net whose
+    logits do not depend on the row (zero head weights, fixed bias)."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    net = dict(name="bias_only", B=4096, obs=(1, 4, 4), encoder="conv", convs=[(2, 2, 2, 0)], fc=4, rnn=4,
+               heads=[7, 3], dtype="fp32", p_done=0.0, obs_sub=0.0, obs_mul=wl.OBS_MUL, index=0)
+    w = wl.weights(net)
+    w["pi_w"][:] = 0
+    w["pi_b"][:] = np.array([2.0, 0.5, -1.0, 0.0, 1.5, -3.0, 0.25, 0.0, 1.0, -1.0], np.float32)
+    pol = binding.Policy(net, w)
+    obs, h_in, done = wl.observations(net), wl.initial_state(net), wl.done_mask(net)
+    counts = [np.zeros(7), np.zeros(3)]
+    n_steps = 64
+    for t in range(n_steps):
+        g = _gpu_step(torch, pol, obs, h_in, done, 5, t)
+        for k in range(2):
+            counts[k] += np.bincount(g["actions"][:, k], minlength=len(counts[k]))
+        if t == 0:  # bit-identical to the oracle's draws for these logits
+            for bb in range(0, 4096, 97):
+                assert ref.head_sample(w["pi_b"][:7], 5, bb, 0, 0)[0] == g["actions"][bb, 0]
+                assert ref.head_sample(w["pi_b"][7:], 5, bb, 0, 1)[0] == g["actions"][bb, 1]
+    n = 4096 * n_steps
+    for k, sl in enumerate([slice(0, 7), slice(7, 10)]):
+        p = np.exp(ref.log_softmax(w["pi_b"][sl]))
+        chi2 = float(((counts[k] - n * p) ** 2 / (n * p)).sum())
+        dof = len(p) - 1
+        assert chi2 < dof + 5 * np.sqrt(2 * dof) + 5
+    pol.close()
