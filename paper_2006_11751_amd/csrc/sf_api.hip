@@ -2,6 +2,7 @@
 // launch sequence of one policy step (see include/sf_policy.h for the contract).
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -238,6 +239,7 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
   p->cfg = *cfg;
   p->device = hip_device;
   p->flat = Cf * Hf * Wf;
+  p->conv1_waves = getenv("SF_CONV1_WAVES") ? atoi(getenv("SF_CONV1_WAVES")) : 0;
   Builder bld{p, cfg->dtype == SF_DTYPE_BF16};
 
   // ---- encoder plan ----
@@ -256,6 +258,14 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
       L.w_khwc_o = bld.pack_conv(w->conv_w[ti], cout, C, k);
       L.bias = bld.pack_vec(w->conv_b[ti], cout);
       L.relu_in = relu_in; L.relu_out = relu_out; L.add_residual = resid_buf >= 0;
+      L.impl = CONV_GENERIC;
+      if (in_buf < 0 && !bld.bf16 && conv1_mfma_supported(L) && !getenv("SF_FORCE_GENERIC")) {
+        std::vector<float> wpk, bpk;
+        conv1_mfma_pack(w->conv_w[ti], w->conv_b[ti], C, cfg->obs_sub, cfg->obs_mul, wpk, bpk);
+        L.wpk = bld.upload(wpk);
+        L.bpk = bld.upload(bpk);
+        L.impl = CONV1_U8_MFMA;
+      }
       ++ti;
       int64_t m = (int64_t)L.Ho * L.Wo * cout * C * k * k;
       Op op{OP_CONV, name, 2 * m, (int)p->convs.size(), in_buf, out_buf, resid_buf, 0, 0, 0};
@@ -440,8 +450,11 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
       case OP_CONV: {
         const ConvLayer& L = p->convs[op.conv];
         const void* in = op.in_buf < 0 ? (const void*)obs : (const void*)buf(op.in_buf);
-        SF_LAUNCH(launch_conv_generic(L, B, in, op.in_buf < 0, c.obs_sub, c.obs_mul,
-                                      buf(op.resid_buf), buf(op.out_buf), st));
+        if (L.impl == CONV1_U8_MFMA && !misaligned(obs, 4))
+          SF_LAUNCH(launch_conv1_mfma(L, B, obs, L.wpk, L.bpk, buf(op.out_buf), p->conv1_waves, st));
+        else
+          SF_LAUNCH(launch_conv_generic(L, B, in, op.in_buf < 0, c.obs_sub, c.obs_mul,
+                                        buf(op.resid_buf), buf(op.out_buf), st));
         break;
       }
       case OP_POOL:

@@ -21,7 +21,11 @@ struct ConvLayer {
   float* bias;            // dev [cout]
   int relu_in, relu_out;  // ReLU applied to the input as it is read / to the result
   int add_residual;       // result += residual buffer before relu_out
+  int impl;               // kernel choice, see ConvImpl
+  float* wpk;             // dev, layout of the chosen MFMA kernel (or null)
+  float* bpk;             // dev, bias as the chosen MFMA kernel wants it (or null)
 };
+enum ConvImpl { CONV_GENERIC = 0, CONV1_U8_MFMA = 1 };
 
 // One kernel launch of the step, fixed at create time.
 enum OpKind { OP_CONV, OP_POOL, OP_FC, OP_GRU, OP_HEADS };
@@ -59,6 +63,7 @@ struct Policy {
   int64_t flops_per_row;
   std::vector<Op> ops;    // the launch sequence
   int enc_buf;            // buffer holding the encoder output
+  int conv1_waves = 0;    // wavefronts for the first-convolution kernel (0 = default)
   // optional per-launch timing (measurement aid)
   bool timing = false;
   std::vector<hipEvent_t> events;  // ops.size() + 1
@@ -81,5 +86,12 @@ hipError_t launch_heads(int B, int H, int n_heads, int sumA, const int32_t* head
                         const float* h, const float* head_w, const float* head_b, uint64_t seed,
                         uint64_t step, int32_t* actions, float* logp, float* value,
                         float* logits_opt, hipStream_t st);
+
+// ---- MFMA kernels (specialised shapes) ----
+bool conv1_mfma_supported(const ConvLayer& L);
+void conv1_mfma_pack(const float* w, const float* bias, int cin, float obs_sub, float obs_mul,
+                     std::vector<float>& wpk, std::vector<float>& bpk);
+hipError_t launch_conv1_mfma(const ConvLayer& L, int B, const uint8_t* obs, const float* wpk,
+                             const float* bpk, float* out, int waves_hint, hipStream_t st);
 
 }  // namespace sf
