@@ -30,10 +30,10 @@ constexpr int kS = 4;       // stride
 constexpr int kWaves = 4;   // per workgroup
 
 template <int CIN>
-__global__ __launch_bounds__(64 * kWaves) void conv1_u8_mfma_kernel(
+__global__ __launch_bounds__(64 * kWaves, 2) void conv1_u8_mfma_kernel(
     const uint8_t* __restrict__ obs, const float* __restrict__ wpk, const float* __restrict__ bias,
-    float* __restrict__ out, int H, int W, int Ho, int Wo, int n_xchunks, long long n_items,
-    int n_waves_total) {
+    float* __restrict__ out, float* __restrict__ trash, int H, int W, int Ho, int Wo,
+    int n_xchunks, long long n_items, int n_waves_total) {
   constexpr int NG = CIN * kK;  // (channel, filter row) groups; 4 MFMAs each
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWaves + (threadIdx.x >> 6);
@@ -88,32 +88,50 @@ __global__ __launch_bounds__(64 * kWaves) void conv1_u8_mfma_kernel(
         nxt[g] = *(const uint32_t*)(src + ((size_t)c * H + p) * W);
       }
     }
-    // two independent accumulation chains (even / odd groups)
-    f32x16 acc0, acc1;
+    // One accumulation chain of 4*NG MFMAs.  The byte->float conversions of the next
+    // pair of groups are placed ahead of the eight MFMAs of the current pair
+    // (sched_group_barrier: 8 VALU, then 8 MFMA), so that the matrix pipe gets
+    // uninterrupted runs: every other instruction issued between two MFMAs of a wave
+    // delays the second one.
+    f32x16 acc;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      acc0[v] = bias_n;
-      acc1[v] = 0.0f;
+    for (int v = 0; v < 16; ++v) acc[v] = bias_n;
+    float a_cur[8], a_nxt[8];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      a_cur[t] = (float)((cur[0] >> (8 * t)) & 0xFFu);
+      a_cur[4 + t] = (float)((cur[1] >> (8 * t)) & 0xFFu);
     }
 #pragma unroll
     for (int g = 0; g < NG; g += 2) {
-      const uint32_t w0 = cur[g], w1 = cur[g + 1];
+      if (g + 2 < NG) {
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        float a0 = (float)((w0 >> (8 * t)) & 0xFFu);
-        float a1 = (float)((w1 >> (8 * t)) & 0xFFu);
-        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, wreg[g][t], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, wreg[g + 1][t], acc1, 0, 0, 0);
+        for (int t = 0; t < 4; ++t) {
+          a_nxt[t] = (float)((cur[g + 2] >> (8 * t)) & 0xFFu);
+          a_nxt[4 + t] = (float)((cur[g + 3] >> (8 * t)) & 0xFFu);
+        }
       }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[t], wreg[g][t], acc, 0, 0, 0);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[4 + t], wreg[g + 1][t], acc, 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);  // VALU: the conversions
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);  // MFMA
+#pragma unroll
+      for (int t = 0; t < 8; ++t) a_cur[t] = a_nxt[t];
     }
-    // epilogue: ReLU, channels-last store.  D[i][j]: j = n, i = (v%4) + 4h + 8(v/4)
+    // epilogue: ReLU, channels-last store.  D[i][j]: j = n, i = (v%4) + 4h + 8(v/4).
+    // Lanes past the row end loaded the last pixel's bytes, so their result rows are
+    // bitwise copies of that pixel's: storing them to its address is harmless and
+    // keeps the stores unconditional.
     const long long b = it / items_per_frame;
     float* dst = out + (((size_t)b * Ho + oy) * Wo) * kCout + n;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int ox = xc * 32 + (v & 3) + 4 * h + 8 * (v >> 2);
-      float r = fmaxf(acc0[v] + acc1[v], 0.0f);
-      if (ox < Wo) dst[(size_t)ox * kCout] = r;
+      int ox = xc * 32 + (v & 3) + 4 * h + 8 * (v >> 2);
+      ox = ox < Wo ? ox : Wo - 1;
+      dst[ox * kCout] = fmaxf(acc[v], 0.0f);
     }
     if (more) {
 #pragma unroll
@@ -154,26 +172,27 @@ void conv1_mfma_pack(const float* w, const float* bias, int cin, float obs_sub, 
 }
 
 hipError_t launch_conv1_mfma(const ConvLayer& L, int B, const uint8_t* obs, const float* wpk,
-                             const float* bpk, float* out, int waves_hint, hipStream_t st) {
+                             const float* bpk, float* out, float* trash, int waves_hint,
+                             hipStream_t st) {
   if (B == 0) return hipSuccess;
   const int n_xchunks = (L.Wo + 31) / 32;
   const long long n_items = (long long)B * L.Ho * n_xchunks;
-  long long waves = waves_hint > 0 ? waves_hint : 1024;
+  long long waves = waves_hint > 0 ? waves_hint : 2048;  // two wavefronts per SIMD on 256 CUs
   if (waves > n_items) waves = n_items;
   const int blocks = (int)((waves + kWaves - 1) / kWaves);
   const int n_waves_total = blocks * kWaves;
   switch (L.cin) {
     case 1:
-      conv1_u8_mfma_kernel<1><<<blocks, 64 * kWaves, 0, st>>>(obs, wpk, bpk, out, L.H, L.W, L.Ho, L.Wo,
-                                                             n_xchunks, n_items, n_waves_total);
+      conv1_u8_mfma_kernel<1><<<blocks, 64 * kWaves, 0, st>>>(obs, wpk, bpk, out, trash, L.H, L.W, L.Ho,
+                                                             L.Wo, n_xchunks, n_items, n_waves_total);
       break;
     case 3:
-      conv1_u8_mfma_kernel<3><<<blocks, 64 * kWaves, 0, st>>>(obs, wpk, bpk, out, L.H, L.W, L.Ho, L.Wo,
-                                                             n_xchunks, n_items, n_waves_total);
+      conv1_u8_mfma_kernel<3><<<blocks, 64 * kWaves, 0, st>>>(obs, wpk, bpk, out, trash, L.H, L.W, L.Ho,
+                                                             L.Wo, n_xchunks, n_items, n_waves_total);
       break;
     case 4:
-      conv1_u8_mfma_kernel<4><<<blocks, 64 * kWaves, 0, st>>>(obs, wpk, bpk, out, L.H, L.W, L.Ho, L.Wo,
-                                                             n_xchunks, n_items, n_waves_total);
+      conv1_u8_mfma_kernel<4><<<blocks, 64 * kWaves, 0, st>>>(obs, wpk, bpk, out, trash, L.H, L.W, L.Ho,
+                                                             L.Wo, n_xchunks, n_items, n_waves_total);
       break;
     default:
       return hipErrorInvalidValue;

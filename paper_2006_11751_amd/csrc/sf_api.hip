@@ -367,6 +367,7 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
   for (int i = 0; i < 3; ++i)
     p->act[i] = i < n_act ? (float*)bld.dev_alloc(sizeof(float) * act_elems * cfg->max_batch)
                           : nullptr;
+  p->trash = (float*)bld.dev_alloc(256);
   p->fc_out = (float*)bld.dev_alloc(sizeof(float) * (size_t)cfg->fc_dim * cfg->max_batch);
 
   p->events.resize(p->ops.size() + 1, nullptr);
@@ -451,7 +452,8 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
         const ConvLayer& L = p->convs[op.conv];
         const void* in = op.in_buf < 0 ? (const void*)obs : (const void*)buf(op.in_buf);
         if (L.impl == CONV1_U8_MFMA && !misaligned(obs, 4))
-          SF_LAUNCH(launch_conv1_mfma(L, B, obs, L.wpk, L.bpk, buf(op.out_buf), p->conv1_waves, st));
+          SF_LAUNCH(launch_conv1_mfma(L, B, obs, L.wpk, L.bpk, buf(op.out_buf), p->trash,
+                                      p->conv1_waves, st));
         else
           SF_LAUNCH(launch_conv_generic(L, B, in, op.in_buf < 0, c.obs_sub, c.obs_mul,
                                         buf(op.resid_buf), buf(op.out_buf), st));

@@ -59,6 +59,7 @@ struct Policy {
   float* act[3];      // three activation buffers of act_elems floats per row
   size_t act_elems;
   float* fc_out;      // dev [max_batch][fc_dim]
+  float* trash;       // dev, 64 floats: target of stores that fall outside a tensor
   std::vector<void*> allocations;
   int64_t flops_per_row;
   std::vector<Op> ops;    // the launch sequence
@@ -92,6 +93,7 @@ bool conv1_mfma_supported(const ConvLayer& L);
 void conv1_mfma_pack(const float* w, const float* bias, int cin, float obs_sub, float obs_mul,
                      std::vector<float>& wpk, std::vector<float>& bpk);
 hipError_t launch_conv1_mfma(const ConvLayer& L, int B, const uint8_t* obs, const float* wpk,
-                             const float* bpk, float* out, int waves_hint, hipStream_t st);
+                             const float* bpk, float* out, float* trash, int waves_hint,
+                             hipStream_t st);
 
 }  // namespace sf
