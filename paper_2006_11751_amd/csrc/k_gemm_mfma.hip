@@ -1,0 +1,237 @@
+// Implicit-GEMM convolution and fully connected layer on the fp32 MFMA
+// (paper, App. "Model architectures": conv layers 2..n and the FC layer).
+//
+//   out[m][n] = act(bias[n] + sum_k A[m][k] * Wt[n][k])
+//
+// A is never materialised: row m = (frame b, output pixel oy, ox) of a channels-last
+// activation [B][H][W][Cin]; with K ordered (filter row p, filter column q, channel c)
+// the K axis of a row is `ksize` contiguous segments of ksize*Cin floats, one per
+// filter row (no padding).  The FC layer is the case H = W = ksize = 1.  Wt is
+// [N][K] with K contiguous in the same order.
+//
+// Tiling: a 256-thread workgroup owns a BM x BN output tile, K is walked in chunks
+// of 32 staged through LDS (double buffered, one barrier per chunk, the next
+// chunk's global loads in flight during the MFMAs).  LDS rows have a pitch of 36
+// floats so that both the 16-byte tile stores and the 16-byte fragment loads are
+// bank-conflict free.  v_mfma_f32_32x32x2_f32 takes its K index from the lane half
+// h = lane/32; a lane loads four consecutive k (one ds_read_b128) at 8g + 4h, and
+// instruction t of the group's four uses element t, for both operands alike.
+// The four wavefronts are arranged WM x WN x WK: WK > 1 splits the K groups of
+// every chunk between waves (for GEMMs with few output tiles) and the partial
+// tiles are summed through LDS in a fixed order.
+#include "sf_internal.h"
+
+namespace sf {
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBK = 32;
+constexpr int kPitch = 36;
+
+struct GemmArgs {
+  const float* A;
+  const float* Wt;
+  const float* bias;
+  float* out;
+  int M, N, K;
+  // row gather
+  int rows_per_img, Wo, stride, Wpix, Cin;
+  long long img_elems;
+  int seg_len, seg_stride;
+  int relu;
+};
+
+template <int BM, int BN, int WM, int WN, int WK>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
+  static_assert(WM * WN * WK == 4, "four wavefronts");
+  constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
+  constexpr int RA = BM / 32, RB = BN / 32;  // 16-byte loads per thread per chunk
+  constexpr int GPW = 4 / WK;                // K groups per wave per chunk
+  extern __shared__ float smem[];
+  float* As = smem;                      // [2][BM][kPitch]
+  float* Bs = smem + 2 * BM * kPitch;    // [2][BN][kPitch]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WM, wn = (wave / WM) % WN, wk = wave / (WM * WN);
+  const int li = lane & 31, lh = lane >> 5;
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const int lrow = tid >> 3, lk4 = (tid & 7) * 4;
+
+  const float* a_ptr[RA];
+#pragma unroll
+  for (int r = 0; r < RA; ++r) {
+    int m = m0 + lrow + 32 * r;
+    m = m < g.M ? m : g.M - 1;  // rows past the end re-read the last row; never stored
+    int b = m / g.rows_per_img;
+    int rem = m - b * g.rows_per_img;
+    int oy = rem / g.Wo, ox = rem - oy * g.Wo;
+    a_ptr[r] = g.A + (size_t)b * g.img_elems +
+               ((size_t)(oy * g.stride) * g.Wpix + (size_t)ox * g.stride) * g.Cin + lk4;
+  }
+  const float* b_ptr[RB];
+#pragma unroll
+  for (int r = 0; r < RB; ++r) b_ptr[r] = g.Wt + (size_t)(n0 + lrow + 32 * r) * g.K + lk4;
+
+  f32x4 ra[RA], rb[RB];
+  auto gload = [&](int kk) {
+    const int seg = kk / g.seg_len;
+    const int off = kk - seg * g.seg_len + seg * g.seg_stride;
+#pragma unroll
+    for (int r = 0; r < RA; ++r) ra[r] = *(const f32x4*)(a_ptr[r] + off);
+#pragma unroll
+    for (int r = 0; r < RB; ++r) rb[r] = *(const f32x4*)(b_ptr[r] + kk);
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int r = 0; r < RA; ++r)
+      *(f32x4*)&As[((buf * BM) + lrow + 32 * r) * kPitch + lk4] = ra[r];
+#pragma unroll
+    for (int r = 0; r < RB; ++r)
+      *(f32x4*)&Bs[((buf * BN) + lrow + 32 * r) * kPitch + lk4] = rb[r];
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  const int nchunks = g.K / kBK;
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  for (int c = 0; c < nchunks; ++c) {
+    const int buf = c & 1;
+    if (c + 1 < nchunks) gload((c + 1) * kBK);
+    const float* Ab = As + (buf * BM + wm * TM * 32 + li) * kPitch + 4 * lh;
+    const float* Bb = Bs + (buf * BN + wn * TN * 32 + li) * kPitch + 4 * lh;
+#pragma unroll
+    for (int gi = 0; gi < GPW; ++gi) {
+      const int kg = (gi * WK + wk) * 8;
+      f32x4 af[TM], bf[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[i] = *(const f32x4*)(Ab + i * 32 * kPitch + kg);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bf[j] = *(const f32x4*)(Bb + j * 32 * kPitch + kg);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
+    }
+    if (c + 1 < nchunks) sstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // sum the K-split partial tiles in a fixed order (wk = 1, 2, 3 into wk = 0)
+  if (WK > 1) {
+    float* red = smem;  // [WM*WN][TM*TN][16][64] floats, reused per source wave
+    for (int src = 1; src < WK; ++src) {
+      if (wk == src) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              red[(((wm + WM * wn) * TM * TN + i * TN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+      }
+      __syncthreads();
+      if (wk == 0) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              acc[i][j][v] += red[(((wm + WM * wn) * TM * TN + i * TN + j) * 16 + v) * 64 + lane];
+      }
+      __syncthreads();
+    }
+    if (wk != 0) return;
+  }
+
+  // epilogue: D[i][j] of a 32x32 tile: j = lane%32, i = (v%4) + 4*(lane/32) + 8*(v/4)
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int col = n0 + (wn * TN + j) * 32 + li;
+    const float bj = g.bias[col];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + (wm * TM + i) * 32 + (v & 3) + 4 * lh + 8 * (v >> 2);
+        float r = acc[i][j][v] + bj;
+        if (g.relu) r = fmaxf(r, 0.0f);
+        if (m < g.M) g.out[(size_t)m * g.N + col] = r;
+      }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int WK>
+hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
+  constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
+  size_t lds = sizeof(float) * 2 * (BM + BN) * kPitch;
+  size_t red = WK > 1 ? sizeof(float) * WM * WN * TM * TN * 16 * 64 : 0;
+  if (red > lds) lds = red;
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, WK>;
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  dim3 grid((g.M + BM - 1) / BM, g.N / BN);
+  kern<<<grid, 256, lds, st>>>(g);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Shapes the kernel accepts: no padding, channel count and row segment multiples of
+// 32 / 4, N a multiple of 32.
+bool gemm_mfma_supported(int Cin, int ksize, int pad, int N) {
+  return pad == 0 && (Cin % 4) == 0 && ((ksize * Cin) % kBK) == 0 && (N % 32) == 0;
+}
+
+// Tile configuration for an M x N problem: fill 256 CUs with at least two workgroups
+// each where the shape allows.  Callers fix the choice once (from the largest batch)
+// so that results do not depend on the batch size of a call.
+int gemm_mfma_pick_tile(long long M, int N) {
+  long long t128 = ((M + 127) / 128) * (N / 64);
+  long long t64 = ((M + 63) / 64) * (N / 64);
+  if (N % 64 == 0 && t128 >= 512) return 1;
+  if (N % 64 == 0 && t64 >= 512) return 2;
+  return 3;
+}
+
+hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,
+                            int H, int W, int Cin, int ksize, int stride, int Ho, int Wo, int N,
+                            int relu, int tile_hint, hipStream_t st) {
+  GemmArgs g;
+  g.A = A; g.Wt = Wt; g.bias = bias; g.out = out;
+  g.M = B * Ho * Wo; g.N = N; g.K = ksize * ksize * Cin;
+  g.rows_per_img = Ho * Wo; g.Wo = Wo; g.stride = stride; g.Wpix = W; g.Cin = Cin;
+  g.img_elems = (long long)H * W * Cin;
+  g.seg_len = ksize * Cin; g.seg_stride = W * Cin;
+  g.relu = relu;
+  if (g.M == 0) return hipSuccess;
+  const int tile = tile_hint > 0 ? tile_hint : gemm_mfma_pick_tile(g.M, N);
+  switch (tile) {
+    case 1: return (N % 64) ? hipErrorInvalidValue : launch_cfg<128, 64, 4, 1, 1>(g, st);
+    case 2: return (N % 64) ? hipErrorInvalidValue : launch_cfg<64, 64, 2, 2, 1>(g, st);
+    case 3: return launch_cfg<64, 32, 2, 1, 2>(g, st);
+    case 4: return launch_cfg<32, 32, 1, 1, 4>(g, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace sf

@@ -259,7 +259,24 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
       L.bias = bld.pack_vec(w->conv_b[ti], cout);
       L.relu_in = relu_in; L.relu_out = relu_out; L.add_residual = resid_buf >= 0;
       L.impl = CONV_GENERIC;
-      if (in_buf < 0 && !bld.bf16 && conv1_mfma_supported(L) && !getenv("SF_FORCE_GENERIC")) {
+      const bool allow_mfma = !getenv("SF_FORCE_GENERIC");
+      if (in_buf >= 0 && allow_mfma && !relu_in && resid_buf < 0 &&
+          gemm_mfma_supported(C, k, pad, cout)) {
+        // [cout][cin][k][k] -> [cout][k][k][cin]: K ordered (filter row, filter column, channel)
+        std::vector<float> t((size_t)cout * C * k * k);
+        for (int o = 0; o < cout; ++o)
+          for (int c2 = 0; c2 < C; ++c2)
+            for (int a = 0; a < k; ++a)
+              for (int b2 = 0; b2 < k; ++b2)
+                t[(((size_t)o * k + a) * k + b2) * C + c2] =
+                    bld.q(w->conv_w[ti][(((size_t)o * C + c2) * k + a) * k + b2]);
+        L.wpk = bld.upload(t);
+        L.bpk = L.bias;
+        L.impl = CONV_GEMM_MFMA;
+        const char* th = getenv("SF_GEMM_TILE");
+        L.tile = th ? atoi(th) : gemm_mfma_pick_tile((long long)cfg->max_batch * L.Ho * L.Wo, cout);
+      }
+      if (in_buf < 0 && allow_mfma && conv1_mfma_supported(L)) {
         std::vector<float> wpk, bpk;
         conv1_mfma_pack(w->conv_w[ti], w->conv_b[ti], C, cfg->obs_sub, cfg->obs_mul, wpk, bpk);
         L.wpk = bld.upload(wpk);
@@ -328,6 +345,15 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
           }
     p->fc_w_t = bld.upload(t);
     p->fc_b = bld.pack_vec(w->fc_b, cfg->fc_dim);
+    p->fc_wt = nullptr;
+    if (!getenv("SF_FORCE_GENERIC") && gemm_mfma_supported(p->flat, 1, 0, cfg->fc_dim)) {
+      std::vector<float> u((size_t)p->flat * cfg->fc_dim);  // [fc][flat in channels-last order]
+      for (int o = 0; o < cfg->fc_dim; ++o)
+        for (int i = 0; i < p->flat; ++i) u[(size_t)o * p->flat + i] = t[(size_t)i * cfg->fc_dim + o];
+      p->fc_wt = bld.upload(u);
+      const char* th = getenv("SF_FC_TILE");
+      p->fc_tile = th ? atoi(th) : gemm_mfma_pick_tile(cfg->max_batch, cfg->fc_dim);
+    }
     macs += (int64_t)p->flat * cfg->fc_dim;
     p->ops.push_back(Op{OP_FC, "fc", 2 * (int64_t)p->flat * cfg->fc_dim, -1, p->enc_buf, -1, -1, 0, 0, 0});
   }
@@ -454,6 +480,9 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
         if (L.impl == CONV1_U8_MFMA && !misaligned(obs, 4))
           SF_LAUNCH(launch_conv1_mfma(L, B, obs, L.wpk, L.bpk, buf(op.out_buf), p->trash,
                                       p->conv1_waves, st));
+        else if (L.impl == CONV_GEMM_MFMA)
+          SF_LAUNCH(launch_gemm_mfma((const float*)in, L.wpk, L.bpk, buf(op.out_buf), B, L.H, L.W,
+                                     L.cin, L.k, L.s, L.Ho, L.Wo, L.cout, L.relu_out, L.tile, st));
         else
           SF_LAUNCH(launch_conv_generic(L, B, in, op.in_buf < 0, c.obs_sub, c.obs_mul,
                                         buf(op.resid_buf), buf(op.out_buf), st));
@@ -463,8 +492,12 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
         SF_LAUNCH(launch_maxpool3x3s2p1(B, op.C, op.H, op.W, buf(op.in_buf), buf(op.out_buf), st));
         break;
       case OP_FC:
-        SF_LAUNCH(launch_linear_generic(B, p->flat, c.fc_dim, buf(op.in_buf), p->fc_w_t, p->fc_b, 1,
-                                        p->fc_out, st));
+        if (p->fc_wt)
+          SF_LAUNCH(launch_gemm_mfma(buf(op.in_buf), p->fc_wt, p->fc_b, p->fc_out, B, 1, 1, p->flat, 1,
+                                     1, 1, 1, c.fc_dim, 1, p->fc_tile, st));
+        else
+          SF_LAUNCH(launch_linear_generic(B, p->flat, c.fc_dim, buf(op.in_buf), p->fc_w_t, p->fc_b,
+                                          1, p->fc_out, st));
         break;
       case OP_GRU:
         SF_LAUNCH(launch_gru_generic(B, c.fc_dim, c.rnn_dim, p->fc_out, h_in, done, p->gru_wih_t,

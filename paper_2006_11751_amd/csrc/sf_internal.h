@@ -22,10 +22,11 @@ struct ConvLayer {
   int relu_in, relu_out;  // ReLU applied to the input as it is read / to the result
   int add_residual;       // result += residual buffer before relu_out
   int impl;               // kernel choice, see ConvImpl
+  int tile;               // tile configuration of the GEMM kernel, fixed at create
   float* wpk;             // dev, layout of the chosen MFMA kernel (or null)
   float* bpk;             // dev, bias as the chosen MFMA kernel wants it (or null)
 };
-enum ConvImpl { CONV_GENERIC = 0, CONV1_U8_MFMA = 1 };
+enum ConvImpl { CONV_GENERIC = 0, CONV1_U8_MFMA = 1, CONV_GEMM_MFMA = 2 };
 
 // One kernel launch of the step, fixed at create time.
 enum OpKind { OP_CONV, OP_POOL, OP_FC, OP_GRU, OP_HEADS };
@@ -48,6 +49,8 @@ struct Policy {
   // packed weights
   float* fc_w_t;      // dev [flat (channels-last order)][fc_dim]
   float* fc_b;        // dev [fc_dim]
+  float* fc_wt;       // dev [fc_dim][flat (channels-last order)] for the MFMA GEMM, or null
+  int fc_tile;
   float* gru_wih_t;   // dev [fc_dim][3H]
   float* gru_whh_t;   // dev [H][3H]
   float* gru_bih;     // dev [3H]
@@ -95,5 +98,11 @@ void conv1_mfma_pack(const float* w, const float* bias, int cin, float obs_sub, 
 hipError_t launch_conv1_mfma(const ConvLayer& L, int B, const uint8_t* obs, const float* wpk,
                              const float* bpk, float* out, float* trash, int waves_hint,
                              hipStream_t st);
+
+bool gemm_mfma_supported(int Cin, int ksize, int pad, int N);
+int gemm_mfma_pick_tile(long long M, int N);
+hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,
+                            int H, int W, int Cin, int ksize, int stride, int Ho, int Wo, int N,
+                            int relu, int tile, hipStream_t st);
 
 }  // namespace sf
