@@ -53,6 +53,8 @@ struct Policy {
   int fc_tile;
   float* gru_wih_t;   // dev [fc_dim][3H]
   float* gru_whh_t;   // dev [H][3H]
+  float* gru_wih;     // dev [3H][fc_dim] (canonical) for the MFMA kernel, or null
+  float* gru_whh;     // dev [3H][H]
   float* gru_bih;     // dev [3H]
   float* gru_bhh;     // dev [3H]
   float* head_w;      // dev [sumA + 1][H]   (last row: value head)
@@ -99,6 +101,10 @@ hipError_t launch_conv1_mfma(const ConvLayer& L, int B, const uint8_t* obs, cons
                              const float* bpk, float* out, float* trash, int waves_hint,
                              hipStream_t st);
 
+bool gru_mfma_supported(int I, int H);
+hipError_t launch_gru_mfma(int B, int I, int H, const float* x, const float* h_in,
+                           const uint8_t* done, const float* w_ih, const float* w_hh,
+                           const float* b_ih, const float* b_hh, float* h_out, hipStream_t st);
 bool gemm_mfma_supported(int Cin, int ksize, int pad, int N);
 int gemm_mfma_pick_tile(long long M, int N);
 hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,
