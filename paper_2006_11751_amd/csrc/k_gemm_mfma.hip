@@ -19,6 +19,8 @@
 // The four wavefronts are arranged WM x WN x WK: WK > 1 splits the K groups of
 // every chunk between waves (for GEMMs with few output tiles) and the partial
 // tiles are summed through LDS in a fixed order.
+#include <type_traits>
+
 #include "sf_internal.h"
 
 namespace sf {
@@ -28,8 +30,7 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBK = 32;
-constexpr int kPitch = 36;
+constexpr int kBK = 32;  // smallest K chunk: shapes must be multiples of it
 
 struct GemmArgs {
   const float* A;
@@ -44,26 +45,31 @@ struct GemmArgs {
   int relu;
 };
 
-template <int BM, int BN, int WM, int WN, int WK>
+template <int BM, int BN, int BK, int WM, int WN, int WK>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   static_assert(WM * WN * WK == 4, "four wavefronts");
+  constexpr int P = BK + 4;                  // LDS row pitch in floats
   constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
-  constexpr int RA = BM / 32, RB = BN / 32;  // 16-byte loads per thread per chunk
-  constexpr int GPW = 4 / WK;                // K groups per wave per chunk
+  constexpr int TPR = BK / 4;                // threads (16-byte loads) per tile row
+  constexpr int RPP = 256 / TPR;             // tile rows covered by one pass of the workgroup
+  constexpr int RA = BM / RPP, RB = BN / RPP;
+  constexpr int NG = BK / 8;                 // K groups per chunk
+  constexpr int GPW = NG / WK;               // K groups per wave per chunk
+  static_assert(RA >= 1 && RB >= 1 && GPW >= 1, "tile too small for this BK");
   extern __shared__ float smem[];
-  float* As = smem;                      // [2][BM][kPitch]
-  float* Bs = smem + 2 * BM * kPitch;    // [2][BN][kPitch]
+  float* As = smem;                 // [2][BM][P]
+  float* Bs = smem + 2 * BM * P;    // [2][BN][P]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = (wave / WM) % WN, wk = wave / (WM * WN);
   const int li = lane & 31, lh = lane >> 5;
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-  const int lrow = tid >> 3, lk4 = (tid & 7) * 4;
+  const int lrow = tid / TPR, lk4 = (tid % TPR) * 4;
 
   const float* a_ptr[RA];
 #pragma unroll
   for (int r = 0; r < RA; ++r) {
-    int m = m0 + lrow + 32 * r;
+    int m = m0 + lrow + RPP * r;
     m = m < g.M ? m : g.M - 1;  // rows past the end re-read the last row; never stored
     int b = m / g.rows_per_img;
     int rem = m - b * g.rows_per_img;
@@ -73,24 +79,27 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   }
   const float* b_ptr[RB];
 #pragma unroll
-  for (int r = 0; r < RB; ++r) b_ptr[r] = g.Wt + (size_t)(n0 + lrow + 32 * r) * g.K + lk4;
+  for (int r = 0; r < RB; ++r) b_ptr[r] = g.Wt + (size_t)(n0 + lrow + RPP * r) * g.K + lk4;
 
-  f32x4 ra[RA], rb[RB];
-  auto gload = [&](int kk) {
+  // Two register sets: global loads run two chunks ahead of the MFMAs (one chunk of
+  // compute does not cover the latency of a load that misses the L2).
+  f32x4 ra[2][RA], rb[2][RB];
+  auto gload = [&](auto set, int c) {
+    constexpr int S = decltype(set)::value;
+    const int kk = c * BK;
     const int seg = kk / g.seg_len;
     const int off = kk - seg * g.seg_len + seg * g.seg_stride;
 #pragma unroll
-    for (int r = 0; r < RA; ++r) ra[r] = *(const f32x4*)(a_ptr[r] + off);
+    for (int r = 0; r < RA; ++r) ra[S][r] = *(const f32x4*)(a_ptr[r] + off);
 #pragma unroll
-    for (int r = 0; r < RB; ++r) rb[r] = *(const f32x4*)(b_ptr[r] + kk);
+    for (int r = 0; r < RB; ++r) rb[S][r] = *(const f32x4*)(b_ptr[r] + kk);
   };
-  auto sstore = [&](int buf) {
+  auto sstore = [&](auto set, int buf) {
+    constexpr int S = decltype(set)::value;
 #pragma unroll
-    for (int r = 0; r < RA; ++r)
-      *(f32x4*)&As[((buf * BM) + lrow + 32 * r) * kPitch + lk4] = ra[r];
+    for (int r = 0; r < RA; ++r) *(f32x4*)&As[((buf * BM) + lrow + RPP * r) * P + lk4] = ra[S][r];
 #pragma unroll
-    for (int r = 0; r < RB; ++r)
-      *(f32x4*)&Bs[((buf * BN) + lrow + 32 * r) * kPitch + lk4] = rb[r];
+    for (int r = 0; r < RB; ++r) *(f32x4*)&Bs[((buf * BN) + lrow + RPP * r) * P + lk4] = rb[S][r];
   };
 
   f32x16 acc[TM][TN];
@@ -101,23 +110,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  const int nchunks = g.K / kBK;
-  gload(0);
-  sstore(0);
-  __syncthreads();
-  for (int c = 0; c < nchunks; ++c) {
-    const int buf = c & 1;
-    if (c + 1 < nchunks) gload((c + 1) * kBK);
-    const float* Ab = As + (buf * BM + wm * TM * 32 + li) * kPitch + 4 * lh;
-    const float* Bb = Bs + (buf * BN + wn * TN * 32 + li) * kPitch + 4 * lh;
+  const int nchunks = g.K / BK;
+  auto compute = [&](int buf) {
+    const float* Ab = As + (buf * BM + wm * TM * 32 + li) * P + 4 * lh;
+    const float* Bb = Bs + (buf * BN + wn * TN * 32 + li) * P + 4 * lh;
 #pragma unroll
     for (int gi = 0; gi < GPW; ++gi) {
       const int kg = (gi * WK + wk) * 8;
       f32x4 af[TM], bf[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *(const f32x4*)(Ab + i * 32 * kPitch + kg);
+      for (int i = 0; i < TM; ++i) af[i] = *(const f32x4*)(Ab + i * 32 * P + kg);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bf[j] = *(const f32x4*)(Bb + j * 32 * kPitch + kg);
+      for (int j = 0; j < TN; ++j) bf[j] = *(const f32x4*)(Bb + j * 32 * P + kg);
 #pragma unroll
       for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -126,8 +130,26 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
           for (int j = 0; j < TN; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
     }
-    if (c + 1 < nchunks) sstore(buf ^ 1);
+  };
+  // iteration c: start the loads of chunk c+2 into set S, run the MFMAs of chunk c from
+  // LDS buffer c&1, then move chunk c+1 (set S^1, loaded one iteration ago) into the
+  // other LDS buffer; one barrier per chunk.
+  auto step = [&](auto set, int c) {
+    constexpr int S = decltype(set)::value;
+    if (c + 2 < nchunks) gload(set, c + 2);
+    compute(c & 1);
+    if (c + 1 < nchunks) sstore(std::integral_constant<int, S ^ 1>{}, (c + 1) & 1);
     __syncthreads();
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  gload(I0{}, 0);
+  sstore(I0{}, 0);
+  if (nchunks > 1) gload(I1{}, 1);
+  __syncthreads();
+  for (int c = 0; c < nchunks; c += 2) {
+    step(I0{}, c);
+    if (c + 1 < nchunks) step(I1{}, c + 1);
   }
 
   // sum the K-split partial tiles in a fixed order (wk = 1, 2, 3 into wk = 0)
@@ -175,13 +197,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, int WM, int WN, int WK>
+template <int BM, int BN, int BK, int WM, int WN, int WK>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
   constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
-  size_t lds = sizeof(float) * 2 * (BM + BN) * kPitch;
+  if (g.K % BK != 0 || g.seg_len % BK != 0) return hipErrorInvalidValue;
+  size_t lds = sizeof(float) * 2 * (BM + BN) * (BK + 4);
   size_t red = WK > 1 ? sizeof(float) * WM * WN * TM * TN * 16 * 64 : 0;
   if (red > lds) lds = red;
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, WK>;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, WM, WN, WK>;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -202,15 +225,16 @@ bool gemm_mfma_supported(int Cin, int ksize, int pad, int N) {
   return pad == 0 && (Cin % 4) == 0 && ((ksize * Cin) % kBK) == 0 && (N % 32) == 0;
 }
 
-// Tile configuration for an M x N problem: fill 256 CUs with at least two workgroups
-// each where the shape allows.  Callers fix the choice once (from the largest batch)
-// so that results do not depend on the batch size of a call.
-int gemm_mfma_pick_tile(long long M, int N) {
-  long long t128 = ((M + 127) / 128) * (N / 64);
-  long long t64 = ((M + 63) / 64) * (N / 64);
-  if (N % 64 == 0 && t128 >= 512) return 1;
-  if (N % 64 == 0 && t64 >= 512) return 2;
-  return 3;
+// Tile configuration for an M x N x K problem.  Measured on MI355X: these GEMMs are
+// bound by latency and occupancy rather than by operand traffic, so the small 64x32
+// tile with an in-workgroup K split wins whenever it yields enough workgroups, and
+// the 32x32 tile with a four-way K split (chunks of 64 where K allows) otherwise.
+// Callers fix the choice once (from the largest batch) so that results do not depend
+// on the batch size of a call.
+int gemm_mfma_pick_tile(long long M, int N, int K, int seg_len) {
+  long long wgs = ((M + 63) / 64) * (N / 32);
+  if (wgs >= 1024) return 3;
+  return (K % 64 == 0 && seg_len % 64 == 0) ? 7 : 4;
 }
 
 hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,
@@ -224,12 +248,16 @@ hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, 
   g.seg_len = ksize * Cin; g.seg_stride = W * Cin;
   g.relu = relu;
   if (g.M == 0) return hipSuccess;
-  const int tile = tile_hint > 0 ? tile_hint : gemm_mfma_pick_tile(g.M, N);
+  const int tile = tile_hint > 0 ? tile_hint : gemm_mfma_pick_tile(g.M, N, g.K, g.seg_len);
   switch (tile) {
-    case 1: return (N % 64) ? hipErrorInvalidValue : launch_cfg<128, 64, 4, 1, 1>(g, st);
-    case 2: return (N % 64) ? hipErrorInvalidValue : launch_cfg<64, 64, 2, 2, 1>(g, st);
-    case 3: return launch_cfg<64, 32, 2, 1, 2>(g, st);
-    case 4: return launch_cfg<32, 32, 1, 1, 4>(g, st);
+    case 1: return (N % 64) ? hipErrorInvalidValue : launch_cfg<128, 64, 32, 4, 1, 1>(g, st);
+    case 2: return (N % 64) ? hipErrorInvalidValue : launch_cfg<64, 64, 32, 2, 2, 1>(g, st);
+    case 3: return launch_cfg<64, 32, 32, 2, 1, 2>(g, st);
+    case 4: return launch_cfg<32, 32, 32, 1, 1, 4>(g, st);
+    case 5: return (N % 64) ? hipErrorInvalidValue : launch_cfg<64, 64, 64, 2, 2, 1>(g, st);
+    case 6: return launch_cfg<64, 32, 64, 2, 1, 2>(g, st);
+    case 7: return launch_cfg<32, 32, 64, 1, 1, 4>(g, st);
+    case 8: return (N % 64) ? hipErrorInvalidValue : launch_cfg<128, 64, 64, 4, 1, 1>(g, st);
     default: return hipErrorInvalidValue;
   }
 }

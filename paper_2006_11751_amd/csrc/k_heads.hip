@@ -66,13 +66,28 @@ __global__ __launch_bounds__(kWave* kRowsPerBlock) void heads_kernel(
   float* lg = s_logits[wave];
   const float* hp = h + (size_t)b * H;
 
-  // logits and value: lane-strided dot products, butterfly reduction (fixed order)
-  for (int a = 0; a <= sumA; ++a) {
-    const float* wp = head_w + (size_t)a * H;
-    float acc = 0.0f;
-    for (int i = lane; i < H; i += kWave) acc = fmaf(hp[i], wp[i], acc);
-    acc = wave_sum(acc) + head_b[a];
-    if (lane == 0) lg[a] = acc;
+  // logits and value: lane-strided dot products, butterfly reduction (fixed order).
+  // Outputs are processed eight at a time so that their loads are all in flight
+  // together instead of one dependent reduction after another.
+  constexpr int kGroup = 8;
+  for (int a0 = 0; a0 <= sumA; a0 += kGroup) {
+    float part[kGroup];
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u) part[u] = 0.0f;
+    for (int i = lane; i < H; i += kWave) {
+      const float hv = hp[i];
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u) {
+        const int a = a0 + u <= sumA ? a0 + u : sumA;  // clamp: duplicates are not stored
+        part[u] = fmaf(hv, head_w[(size_t)a * H + i], part[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u) {
+      float acc = wave_sum(part[u]);
+      const int a = a0 + u;
+      if (a <= sumA && lane == 0) lg[a] = acc + head_b[a];
+    }
   }
   __builtin_amdgcn_wave_barrier();
   __threadfence_block();

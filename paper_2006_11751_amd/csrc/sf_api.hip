@@ -274,7 +274,8 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
         L.bpk = L.bias;
         L.impl = CONV_GEMM_MFMA;
         const char* th = getenv("SF_GEMM_TILE");
-        L.tile = th ? atoi(th) : gemm_mfma_pick_tile((long long)cfg->max_batch * L.Ho * L.Wo, cout);
+        L.tile = th ? atoi(th) : gemm_mfma_pick_tile((long long)cfg->max_batch * L.Ho * L.Wo, cout,
+                                                         k * k * C, k * C);
       }
       if (in_buf < 0 && allow_mfma && conv1_mfma_supported(L)) {
         std::vector<float> wpk, bpk;
@@ -352,7 +353,7 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
         for (int i = 0; i < p->flat; ++i) u[(size_t)o * p->flat + i] = t[(size_t)i * cfg->fc_dim + o];
       p->fc_wt = bld.upload(u);
       const char* th = getenv("SF_FC_TILE");
-      p->fc_tile = th ? atoi(th) : gemm_mfma_pick_tile(cfg->max_batch, cfg->fc_dim);
+      p->fc_tile = th ? atoi(th) : gemm_mfma_pick_tile(cfg->max_batch, cfg->fc_dim, p->flat, p->flat);
     }
     macs += (int64_t)p->flat * cfg->fc_dim;
     p->ops.push_back(Op{OP_FC, "fc", 2 * (int64_t)p->flat * cfg->fc_dim, -1, p->enc_buf, -1, -1, 0, 0, 0});

@@ -106,7 +106,7 @@ hipError_t launch_gru_mfma(int B, int I, int H, const float* x, const float* h_i
                            const uint8_t* done, const float* w_ih, const float* w_hh,
                            const float* b_ih, const float* b_hh, float* h_out, hipStream_t st);
 bool gemm_mfma_supported(int Cin, int ksize, int pad, int N);
-int gemm_mfma_pick_tile(long long M, int N);
+int gemm_mfma_pick_tile(long long M, int N, int K, int seg_len);
 hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,
                             int H, int W, int Cin, int ksize, int stride, int Ho, int Wo, int N,
                             int relu, int tile, hipStream_t st);
