@@ -366,6 +366,7 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
   if (!getenv("SF_FORCE_GENERIC") && gru_mfma_supported(cfg->fc_dim, cfg->rnn_dim)) {
     p->gru_wih = bld.pack_vec(w->gru_w_ih, (size_t)H3 * cfg->fc_dim);
     p->gru_whh = bld.pack_vec(w->gru_w_hh, (size_t)H3 * cfg->rnn_dim);
+    p->gru_bm = getenv("SF_GRU_BM") ? atoi(getenv("SF_GRU_BM")) : gru_mfma_pick_bm(cfg->max_batch, cfg->rnn_dim);
   }
   p->gru_bih = bld.pack_vec(w->gru_b_ih, H3);
   p->gru_bhh = bld.pack_vec(w->gru_b_hh, H3);
@@ -508,7 +509,7 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
       case OP_GRU:
         if (p->gru_wih && !misaligned(h_in, 16))
           SF_LAUNCH(launch_gru_mfma(B, c.fc_dim, c.rnn_dim, p->fc_out, h_in, done, p->gru_wih,
-                                    p->gru_whh, p->gru_bih, p->gru_bhh, h_out, st));
+                                    p->gru_whh, p->gru_bih, p->gru_bhh, h_out, p->gru_bm, st));
         else
           SF_LAUNCH(launch_gru_generic(B, c.fc_dim, c.rnn_dim, p->fc_out, h_in, done, p->gru_wih_t,
                                        p->gru_whh_t, p->gru_bih, p->gru_bhh, h_out, st));

@@ -55,6 +55,7 @@ struct Policy {
   float* gru_whh_t;   // dev [H][3H]
   float* gru_wih;     // dev [3H][fc_dim] (canonical) for the MFMA kernel, or null
   float* gru_whh;     // dev [3H][H]
+  int gru_bm;         // rows per workgroup of the MFMA GRU kernel, fixed at create
   float* gru_bih;     // dev [3H]
   float* gru_bhh;     // dev [3H]
   float* head_w;      // dev [sumA + 1][H]   (last row: value head)
@@ -104,7 +105,9 @@ hipError_t launch_conv1_mfma(const ConvLayer& L, int B, const uint8_t* obs, cons
 bool gru_mfma_supported(int I, int H);
 hipError_t launch_gru_mfma(int B, int I, int H, const float* x, const float* h_in,
                            const uint8_t* done, const float* w_ih, const float* w_hh,
-                           const float* b_ih, const float* b_hh, float* h_out, hipStream_t st);
+                           const float* b_ih, const float* b_hh, float* h_out, int bm,
+                           hipStream_t st);
+int gru_mfma_pick_bm(int max_batch, int H);
 bool gemm_mfma_supported(int Cin, int ksize, int pad, int N);
 int gemm_mfma_pick_tile(long long M, int N, int K, int seg_len);
 hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,
