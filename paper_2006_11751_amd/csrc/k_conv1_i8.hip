@@ -1,0 +1,225 @@
+// First convolution of the plain encoder on the int8 MFMA, exact in the pixels
+// (paper, App. "Model architectures": the convolutional encoder reads the pixel
+// observation).  Same shape as the fp32 kernel: 8x8 filter, stride 4, no padding,
+// 32 output channels, planar byte frames.
+//
+// The observation is bytes, so the convolution is an integer contraction in the
+// pixels.  Per output channel n the (normalisation-folded) filter W'[.][n] is
+// written in three signed base-128 digits with one scale,
+//   W'[k][n] ~= s_n * (d1[k][n] + d2[k][n] / 128 + d3[k][n] / 16384),   |d| <= 127,
+// (error <= 2^-15 * s_n per weight, i.e. 2.4e-7 of the largest weight of the
+// channel: the size of an fp32 rounding).  With x_s = byte - 128 (one XOR per four
+// pixels) the three sums S_i = sum_k x_s[k] * d_i[k][n] are exact int32 values from
+// v_mfma_i32_32x32x32_i8, which runs at 32x the rate of the fp32 MFMA and takes the
+// loaded frame words as operands without any conversion:
+//   out = relu(s_n * (S1 + S2/128 + S3/16384) + b''_n),
+//   b''_n = b_n - sub*mul*sum_k W[k][n] + 128 * sum_k W'[k][n]   (exact W').
+//
+// v_mfma_i32_32x32x32_i8: lane l supplies 16 bytes A[i = l%32][k = 16*(l/32) + e] and
+// B[k = 16*(l/32) + e][j = l%32].  One instruction covers four (channel, filter row)
+// groups of 8 filter columns: lane half h holds groups 4s+2h and 4s+2h+1, i.e. two
+// 8-byte runs of the frame.  Work split and prefetch as in the fp32 kernel.
+#include <math.h>
+
+#include "sf_internal.h"
+
+namespace sf {
+
+namespace {
+
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kCout = 32;
+constexpr int kK = 8;
+constexpr int kS = 4;
+constexpr int kWaves = 4;
+
+struct __attribute__((packed, aligned(4))) U2 {
+  uint32_t x, y;
+};
+
+template <int CIN>
+__global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_kernel(
+    const uint8_t* __restrict__ obs, const int* __restrict__ wpk, const float* __restrict__ scale,
+    const float* __restrict__ bias, float* __restrict__ out, int H, int W, int Ho, int Wo,
+    int n_xchunks, long long n_items, int n_waves_total) {
+  constexpr int NSTEP = CIN * kK / 4;  // MFMA K steps (32 bytes each)
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const int n = lane & 31;
+  const int h = lane >> 5;
+
+  // digit planes of the filter bank: wd[s][digit] = 16 bytes of this lane's B operand
+  i32x4 wd[NSTEP][3];
+#pragma unroll
+  for (int s = 0; s < NSTEP; ++s)
+#pragma unroll
+    for (int d = 0; d < 3; ++d)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) wd[s][d][w] = wpk[((s * 3 + d) * 4 + w) * 64 + lane];
+  const float s_n = scale[n], b_n = bias[n];
+
+  const long long per = n_items / n_waves_total, rem = n_items % n_waves_total;
+  long long it = wave * per + (wave < rem ? wave : rem);
+  const long long it_end = it + per + (wave < rem ? 1 : 0);
+  if (it >= it_end) return;
+
+  const size_t frame_bytes = (size_t)CIN * H * W;
+  const int items_per_frame = Ho * n_xchunks;
+
+  auto item_src = [&](long long item, int& oy, int& xc) -> const uint8_t* {
+    long long b = item / items_per_frame;
+    int r = (int)(item - b * items_per_frame);
+    oy = r / n_xchunks;
+    xc = r - oy * n_xchunks;
+    int ox = xc * 32 + n;
+    if (ox > Wo - 1) ox = Wo - 1;  // lanes past the row end repeat the last pixel
+    return obs + (size_t)b * frame_bytes + (size_t)(oy * kS) * W + ox * kS;
+  };
+  auto load_item = [&](const uint8_t* src, U2 (&dst)[NSTEP][2]) {
+#pragma unroll
+    for (int s = 0; s < NSTEP; ++s)
+#pragma unroll
+      for (int pp = 0; pp < 2; ++pp) {
+        const int g = 4 * s + 2 * h + pp;  // (channel, filter row) group
+        const int c = g / kK, p = g % kK;
+        dst[s][pp] = *(const U2*)(src + ((size_t)c * H + p) * W);
+      }
+  };
+
+  U2 cur[NSTEP][2], nxt[NSTEP][2];
+  int oy, xc;
+  load_item(item_src(it, oy, xc), cur);
+  for (; it < it_end; ++it) {
+    int oy_n = 0, xc_n = 0;
+    const bool more = it + 1 < it_end;
+    if (more) load_item(item_src(it + 1, oy_n, xc_n), nxt);
+
+    i32x16 s1, s2, s3;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s1[v] = s2[v] = s3[v] = 0;
+#pragma unroll
+    for (int s = 0; s < NSTEP; ++s) {
+      i32x4 a;  // byte - 128 on all 16 pixels of the two runs
+      a[0] = (int)(cur[s][0].x ^ 0x80808080u);
+      a[1] = (int)(cur[s][0].y ^ 0x80808080u);
+      a[2] = (int)(cur[s][1].x ^ 0x80808080u);
+      a[3] = (int)(cur[s][1].y ^ 0x80808080u);
+      s1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, wd[s][0], s1, 0, 0, 0);
+      s2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, wd[s][1], s2, 0, 0, 0);
+      s3 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, wd[s][2], s3, 0, 0, 0);
+    }
+    // epilogue.  D[i][j]: j = n, i = (v%4) + 4h + 8(v/4).  S2*128 + S3 fits int32
+    // (|S2|, |S3| <= 192*128*64); its float image is exact to 6e-8 relative.
+    const long long b = it / items_per_frame;
+    float* dst = out + (((size_t)b * Ho + oy) * Wo) * kCout + n;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      int ox = xc * 32 + (v & 3) + 4 * h + 8 * (v >> 2);
+      ox = ox < Wo ? ox : Wo - 1;  // duplicate rows hold the last pixel's result bit for bit
+      const float lo = (float)(s2[v] * 128 + s3[v]);
+      const float q = fmaf(lo, 0x1.0p-14f, (float)s1[v]);
+      dst[ox * kCout] = fmaxf(fmaf(q, s_n, b_n), 0.0f);
+    }
+    if (more) {
+#pragma unroll
+      for (int s = 0; s < NSTEP; ++s) {
+        cur[s][0] = nxt[s][0];
+        cur[s][1] = nxt[s][1];
+      }
+      oy = oy_n;
+      xc = xc_n;
+    }
+  }
+}
+
+}  // namespace
+
+bool conv1_i8_supported(const ConvLayer& L) {
+  return L.k == kK && L.s == kS && L.pad == 0 && L.cout == kCout && (L.W % 4) == 0 &&
+         (L.cin == 3 || L.cin == 1 || L.cin == 4) && L.relu_out == 1 && !L.add_residual;
+}
+
+// Digit planes, scales and bias for the kernel above.
+// wpk[((s*3 + d)*4 + w)*64 + lane]: bytes e = 4w..4w+3 of the lane's operand for K step s
+// and digit d; byte e belongs to group g = 4s + 2*(lane/32) + e/8 = (channel g/8, filter
+// row g%8), filter column e%8, output channel lane%32.
+void conv1_i8_pack(const float* w, const float* bias, int cin, float obs_sub, float obs_mul,
+                   std::vector<int>& wpk, std::vector<float>& scale, std::vector<float>& bpk) {
+  const int K = cin * kK * kK;
+  const int nstep = cin * kK / 4;
+  wpk.assign((size_t)nstep * 3 * 4 * 64, 0);
+  scale.assign(kCout, 1.0f);
+  bpk.assign(kCout, 0.0f);
+  std::vector<signed char> dig((size_t)kCout * K * 3);
+  for (int n = 0; n < kCout; ++n) {
+    double mx = 0.0, sum_w = 0.0, sum_wm = 0.0;
+    for (int i = 0; i < K; ++i) {
+      double wm = (double)obs_mul * (double)w[(size_t)n * K + i];
+      mx = fmax(mx, fabs(wm));
+      sum_w += (double)w[(size_t)n * K + i];
+      sum_wm += wm;
+    }
+    const float sf = mx > 0.0 ? (float)(mx / 127.0) : 1.0f;  // the kernel multiplies by this fp32 value
+    const double s = (double)sf;
+    for (int i = 0; i < K; ++i) {
+      double q = (double)obs_mul * (double)w[(size_t)n * K + i] / s;
+      double d1 = nearbyint(q);
+      if (d1 > 127) d1 = 127;
+      if (d1 < -127) d1 = -127;
+      double r = (q - d1) * 128.0;
+      double d2 = nearbyint(r);
+      if (d2 > 127) d2 = 127;
+      if (d2 < -127) d2 = -127;
+      double d3 = nearbyint((r - d2) * 128.0);
+      if (d3 > 127) d3 = 127;
+      if (d3 < -127) d3 = -127;
+      dig[((size_t)n * K + i) * 3 + 0] = (signed char)d1;
+      dig[((size_t)n * K + i) * 3 + 1] = (signed char)d2;
+      dig[((size_t)n * K + i) * 3 + 2] = (signed char)d3;
+    }
+    scale[n] = sf;
+    bpk[n] = (float)((double)bias[n] - (double)obs_sub * (double)obs_mul * sum_w + 128.0 * sum_wm);
+  }
+  for (int s = 0; s < nstep; ++s)
+    for (int d = 0; d < 3; ++d)
+      for (int wq = 0; wq < 4; ++wq)
+        for (int lane = 0; lane < 64; ++lane) {
+          const int n = lane & 31, hh = lane >> 5;
+          uint32_t word = 0;
+          for (int e4 = 0; e4 < 4; ++e4) {
+            const int e = 4 * wq + e4;
+            const int g = 4 * s + 2 * hh + e / 8, q = e % 8;
+            const int c = g / kK, p = g % kK;
+            const signed char v = dig[((size_t)n * K + ((size_t)c * kK + p) * kK + q) * 3 + d];
+            word |= (uint32_t)(uint8_t)v << (8 * e4);
+          }
+          wpk[((size_t)(s * 3 + d) * 4 + wq) * 64 + lane] = (int)word;
+        }
+}
+
+hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const int* wpk,
+                           const float* scale, const float* bpk, float* out, int waves_hint,
+                           hipStream_t st) {
+  if (B == 0) return hipSuccess;
+  const int n_xchunks = (L.Wo + 31) / 32;
+  const long long n_items = (long long)B * L.Ho * n_xchunks;
+  long long waves = waves_hint > 0 ? waves_hint : 2048;  // two wavefronts per SIMD on 256 CUs
+  if (waves > n_items) waves = n_items;
+  const int blocks = (int)((waves + kWaves - 1) / kWaves);
+  const int n_waves_total = blocks * kWaves;
+#define SF_LAUNCH_CIN(C)                                                                       \
+  conv1_u8_i8_kernel<C><<<blocks, 64 * kWaves, 0, st>>>(obs, wpk, scale, bpk, out, L.H, L.W, L.Ho, \
+                                                        L.Wo, n_xchunks, n_items, n_waves_total)
+  switch (L.cin) {
+    case 1: SF_LAUNCH_CIN(1); break;
+    case 3: SF_LAUNCH_CIN(3); break;
+    case 4: SF_LAUNCH_CIN(4); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef SF_LAUNCH_CIN
+  return hipGetLastError();
+}
+
+}  // namespace sf

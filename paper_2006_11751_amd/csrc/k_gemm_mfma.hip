@@ -45,7 +45,9 @@ struct GemmArgs {
   int relu;
 };
 
-template <int BM, int BN, int BK, int WM, int WN, int WK>
+// TAG only gives each layer of a network its own kernel symbol, so that a profiler's
+// per-kernel statistics do not merge layers that share a tile configuration.
+template <int BM, int BN, int BK, int WM, int WN, int WK, int TAG>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   static_assert(WM * WN * WK == 4, "four wavefronts");
   constexpr int P = BK + 4;                  // LDS row pitch in floats
@@ -197,14 +199,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int WK>
+template <int BM, int BN, int BK, int WM, int WN, int WK, int TAG>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
   constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
   if (g.K % BK != 0 || g.seg_len % BK != 0) return hipErrorInvalidValue;
   size_t lds = sizeof(float) * 2 * (BM + BN) * (BK + 4);
   size_t red = WK > 1 ? sizeof(float) * WM * WN * TM * TN * 16 * 64 : 0;
   if (red > lds) lds = red;
-  auto kern = gemm_mfma_kernel<BM, BN, BK, WM, WN, WK>;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, WM, WN, WK, TAG>;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -215,6 +217,20 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
   dim3 grid((g.M + BM - 1) / BM, g.N / BN);
   kern<<<grid, 256, lds, st>>>(g);
   return hipGetLastError();
+}
+
+template <int TAG>
+hipError_t launch_tile(const GemmArgs& g, int tile, hipStream_t st) {
+  const bool n64 = (g.N % 64) == 0;
+  switch (tile) {
+    case 1: return n64 ? launch_cfg<128, 64, 32, 4, 1, 1, TAG>(g, st) : hipErrorInvalidValue;
+    case 2: return n64 ? launch_cfg<64, 64, 32, 2, 2, 1, TAG>(g, st) : hipErrorInvalidValue;
+    case 3: return launch_cfg<64, 32, 32, 2, 1, 2, TAG>(g, st);
+    case 4: return launch_cfg<32, 32, 32, 1, 1, 4, TAG>(g, st);
+    case 6: return launch_cfg<64, 32, 64, 2, 1, 2, TAG>(g, st);
+    case 7: return launch_cfg<32, 32, 64, 1, 1, 4, TAG>(g, st);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace
@@ -239,7 +255,7 @@ int gemm_mfma_pick_tile(long long M, int N, int K, int seg_len) {
 
 hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,
                             int H, int W, int Cin, int ksize, int stride, int Ho, int Wo, int N,
-                            int relu, int tile_hint, hipStream_t st) {
+                            int relu, int tile_hint, int tag, hipStream_t st) {
   GemmArgs g;
   g.A = A; g.Wt = Wt; g.bias = bias; g.out = out;
   g.M = B * Ho * Wo; g.N = N; g.K = ksize * ksize * Cin;
@@ -249,16 +265,11 @@ hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, 
   g.relu = relu;
   if (g.M == 0) return hipSuccess;
   const int tile = tile_hint > 0 ? tile_hint : gemm_mfma_pick_tile(g.M, N, g.K, g.seg_len);
-  switch (tile) {
-    case 1: return (N % 64) ? hipErrorInvalidValue : launch_cfg<128, 64, 32, 4, 1, 1>(g, st);
-    case 2: return (N % 64) ? hipErrorInvalidValue : launch_cfg<64, 64, 32, 2, 2, 1>(g, st);
-    case 3: return launch_cfg<64, 32, 32, 2, 1, 2>(g, st);
-    case 4: return launch_cfg<32, 32, 32, 1, 1, 4>(g, st);
-    case 5: return (N % 64) ? hipErrorInvalidValue : launch_cfg<64, 64, 64, 2, 2, 1>(g, st);
-    case 6: return launch_cfg<64, 32, 64, 2, 1, 2>(g, st);
-    case 7: return launch_cfg<32, 32, 64, 1, 1, 4>(g, st);
-    case 8: return (N % 64) ? hipErrorInvalidValue : launch_cfg<128, 64, 64, 4, 1, 1>(g, st);
-    default: return hipErrorInvalidValue;
+  switch (tag & 3) {
+    case 0: return launch_tile<0>(g, tile, st);
+    case 1: return launch_tile<1>(g, tile, st);
+    case 2: return launch_tile<2>(g, tile, st);
+    default: return launch_tile<3>(g, tile, st);
   }
 }
 

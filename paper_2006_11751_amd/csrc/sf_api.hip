@@ -277,7 +277,16 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
         L.tile = th ? atoi(th) : gemm_mfma_pick_tile((long long)cfg->max_batch * L.Ho * L.Wo, cout,
                                                          k * k * C, k * C);
       }
-      if (in_buf < 0 && allow_mfma && conv1_mfma_supported(L)) {
+      const char* c1 = getenv("SF_CONV1");  // "fp32": the fp32-MFMA variant of the first convolution
+      if (in_buf < 0 && allow_mfma && conv1_i8_supported(L) && !(c1 && !strcmp(c1, "fp32"))) {
+        std::vector<int> ipk;
+        std::vector<float> spk, bpk;
+        conv1_i8_pack(w->conv_w[ti], w->conv_b[ti], C, cfg->obs_sub, cfg->obs_mul, ipk, spk, bpk);
+        L.ipk = bld.upload(ipk);
+        L.spk = bld.upload(spk);
+        L.bpk = bld.upload(bpk);
+        L.impl = CONV1_U8_I8;
+      } else if (in_buf < 0 && allow_mfma && conv1_mfma_supported(L)) {
         std::vector<float> wpk, bpk;
         conv1_mfma_pack(w->conv_w[ti], w->conv_b[ti], C, cfg->obs_sub, cfg->obs_mul, wpk, bpk);
         L.wpk = bld.upload(wpk);
@@ -484,12 +493,15 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
       case OP_CONV: {
         const ConvLayer& L = p->convs[op.conv];
         const void* in = op.in_buf < 0 ? (const void*)obs : (const void*)buf(op.in_buf);
-        if (L.impl == CONV1_U8_MFMA && !misaligned(obs, 4))
+        if (L.impl == CONV1_U8_I8 && !misaligned(obs, 4))
+          SF_LAUNCH(launch_conv1_i8(L, B, obs, L.ipk, L.spk, L.bpk, buf(op.out_buf), p->conv1_waves, st));
+        else if (L.impl == CONV1_U8_MFMA && !misaligned(obs, 4))
           SF_LAUNCH(launch_conv1_mfma(L, B, obs, L.wpk, L.bpk, buf(op.out_buf), p->trash,
                                       p->conv1_waves, st));
         else if (L.impl == CONV_GEMM_MFMA)
           SF_LAUNCH(launch_gemm_mfma((const float*)in, L.wpk, L.bpk, buf(op.out_buf), B, L.H, L.W,
-                                     L.cin, L.k, L.s, L.Ho, L.Wo, L.cout, L.relu_out, L.tile, st));
+                                     L.cin, L.k, L.s, L.Ho, L.Wo, L.cout, L.relu_out, L.tile, op.conv + 1,
+                                     st));
         else
           SF_LAUNCH(launch_conv_generic(L, B, in, op.in_buf < 0, c.obs_sub, c.obs_mul,
                                         buf(op.resid_buf), buf(op.out_buf), st));
@@ -501,7 +513,7 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
       case OP_FC:
         if (p->fc_wt)
           SF_LAUNCH(launch_gemm_mfma(buf(op.in_buf), p->fc_wt, p->fc_b, p->fc_out, B, 1, 1, p->flat, 1,
-                                     1, 1, 1, c.fc_dim, 1, p->fc_tile, st));
+                                     1, 1, 1, c.fc_dim, 1, p->fc_tile, 0, st));
         else
           SF_LAUNCH(launch_linear_generic(B, p->flat, c.fc_dim, buf(op.in_buf), p->fc_w_t, p->fc_b,
                                           1, p->fc_out, st));

@@ -25,8 +25,10 @@ struct ConvLayer {
   int tile;               // tile configuration of the GEMM kernel, fixed at create
   float* wpk;             // dev, layout of the chosen MFMA kernel (or null)
   float* bpk;             // dev, bias as the chosen MFMA kernel wants it (or null)
+  int* ipk;               // dev, int8 digit planes of the int8 first-convolution kernel
+  float* spk;             // dev, per-channel scales of that kernel
 };
-enum ConvImpl { CONV_GENERIC = 0, CONV1_U8_MFMA = 1, CONV_GEMM_MFMA = 2 };
+enum ConvImpl { CONV_GENERIC = 0, CONV1_U8_MFMA = 1, CONV_GEMM_MFMA = 2, CONV1_U8_I8 = 3 };
 
 // One kernel launch of the step, fixed at create time.
 enum OpKind { OP_CONV, OP_POOL, OP_FC, OP_GRU, OP_HEADS };
@@ -102,6 +104,12 @@ hipError_t launch_conv1_mfma(const ConvLayer& L, int B, const uint8_t* obs, cons
                              const float* bpk, float* out, float* trash, int waves_hint,
                              hipStream_t st);
 
+bool conv1_i8_supported(const ConvLayer& L);
+void conv1_i8_pack(const float* w, const float* bias, int cin, float obs_sub, float obs_mul,
+                   std::vector<int>& wpk, std::vector<float>& scale, std::vector<float>& bpk);
+hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const int* wpk,
+                           const float* scale, const float* bpk, float* out, int waves_hint,
+                           hipStream_t st);
 bool gru_mfma_supported(int I, int H);
 hipError_t launch_gru_mfma(int B, int I, int H, const float* x, const float* h_in,
                            const uint8_t* done, const float* w_ih, const float* w_hh,
@@ -112,6 +120,6 @@ bool gemm_mfma_supported(int Cin, int ksize, int pad, int N);
 int gemm_mfma_pick_tile(long long M, int N, int K, int seg_len);
 hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,
                             int H, int W, int Cin, int ksize, int stride, int Ho, int Wo, int N,
-                            int relu, int tile, hipStream_t st);
+                            int relu, int tile, int tag, hipStream_t st);
 
 }  // namespace sf
