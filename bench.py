@@ -23,6 +23,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = the headline one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the step is data-parallel over rows "
@@ -47,6 +49,16 @@ def main():
     def run(n, t0):
         for t in range(t0, t0 + n):
             pol.step(obs, h[t & 1], done, wl.PHILOX_SEED, t, out=out[t & 1], stream=stream)
+
+    if args.calibrate_copy:
+        n = 256 << 20
+        src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 256)
+        dst = torch.empty(n, dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            binding.sf_copy_bytes(src.data_ptr(), dst.data_ptr(), n, stream.cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(src, dst)
+        del src, dst
 
     run(args.warmup, 0)
     torch.cuda.synchronize()

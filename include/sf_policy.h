@@ -176,6 +176,12 @@ int64_t sf_policy_op_flops_per_row(const sf_policy* p, int i);
 int sf_policy_set_op_timing(sf_policy* p, int enable);
 int sf_policy_last_op_times(sf_policy* p, float* ms_out /* host */, int n);
 
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16; both dev pointers
+ * 16-byte aligned), asynchronous on hip_stream.  It exists as the known-size
+ * reference kernel against which hardware byte counters are scaled when the
+ * step's HBM traffic is measured.  Errors: SF_ERR_ARG, SF_ERR_DEVICE. */
+int sf_copy_bytes(const void* src, void* dst, int64_t bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -89,7 +89,8 @@ class SfPolicyWeights(C.Structure):
 
 EXPORTS = ("sf_policy_create", "sf_policy_step", "sf_policy_destroy", "sf_last_error",
            "sf_policy_flops_per_row", "sf_policy_op_count", "sf_policy_op_name",
-           "sf_policy_op_flops_per_row", "sf_policy_set_op_timing", "sf_policy_last_op_times")
+           "sf_policy_op_flops_per_row", "sf_policy_set_op_timing", "sf_policy_last_op_times",
+           "sf_copy_bytes")
 
 _lib = None
 
@@ -135,6 +136,8 @@ def load_library():
         L.sf_policy_set_op_timing.argtypes = [C.c_void_p, C.c_int]
         L.sf_policy_last_op_times.restype = C.c_int
         L.sf_policy_last_op_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int]
+        L.sf_copy_bytes.restype = C.c_int
+        L.sf_copy_bytes.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         _lib = L
     return _lib
 
@@ -200,6 +203,12 @@ def sf_policy_step(handle, B, obs, h_in, done, seed, step, actions, logp, value,
     """All buffers are device addresses (ints), e.g. torch.Tensor.data_ptr()."""
     rc = load_library().sf_policy_step(handle, B, obs, h_in, done, seed, step, actions, logp,
                                        value, h_out, logits_opt, hip_stream)
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+
+
+def sf_copy_bytes(src, dst, nbytes, hip_stream=None):
+    rc = load_library().sf_copy_bytes(src, dst, nbytes, hip_stream)
     if rc != SF_OK:
         raise SfError(rc, sf_last_error())
 

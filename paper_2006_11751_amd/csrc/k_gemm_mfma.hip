@@ -65,7 +65,16 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = (wave / WM) % WN, wk = wave / (WM * WN);
   const int li = lane & 31, lh = lane >> 5;
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Give
+  // every XCD one contiguous run of tiles (N tiles of an M tile adjacent, then the
+  // next M tile), so that the rows shared by overlapping filter windows and by the
+  // N tiles are re-read from that XCD's L2 instead of from memory.
+  const int n_ntiles = g.N / BN;
+  const int n_tiles = ((g.M + BM - 1) / BM) * n_ntiles;
+  const int per_xcd = (n_tiles + 7) / 8;
+  const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (tile_id >= n_tiles) return;
+  const int m0 = (tile_id / n_ntiles) * BM, n0 = (tile_id % n_ntiles) * BN;
   const int lrow = tid / TPR, lk4 = (tid % TPR) * 4;
 
   const float* a_ptr[RA];
@@ -214,8 +223,9 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid((g.M + BM - 1) / BM, g.N / BN);
-  kern<<<grid, 256, lds, st>>>(g);
+  const int n_tiles = ((g.M + BM - 1) / BM) * (g.N / BN);
+  const int per_xcd = (n_tiles + 7) / 8;
+  kern<<<per_xcd * 8, 256, lds, st>>>(g);
   return hipGetLastError();
 }
 

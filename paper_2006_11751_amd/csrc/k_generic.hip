@@ -133,6 +133,14 @@ __global__ __launch_bounds__(kThreads) void gru_generic_kernel(
   h_out[(size_t)b * H + j] = (1.0f - z) * n + z * hprev;
 }
 
+// Plain copy of 16-byte words: the known-size reference for scaling HBM byte counters.
+__global__ __launch_bounds__(kThreads) void copy16_kernel(const uint4* __restrict__ src,
+                                                          uint4* __restrict__ dst, long long n16) {
+  long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const long long stride = (long long)gridDim.x * kThreads;
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
 inline unsigned blocks_for(long long total) { return (unsigned)((total + kThreads - 1) / kThreads); }
 
 }  // namespace
@@ -177,6 +185,15 @@ hipError_t launch_gru_generic(int B, int n_in, int H, const float* x, const floa
   dim3 grid((H + kThreads - 1) / kThreads, B);
   gru_generic_kernel<<<grid, kThreads, 0, st>>>(x, h_in, done, wih_t, whh_t, bih, bhh, h_out,
                                                 n_in, H);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy16(const void* src, void* dst, long long bytes, hipStream_t st) {
+  long long n16 = bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  long long blocks = (n16 + kThreads - 1) / kThreads;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  copy16_kernel<<<(unsigned)blocks, kThreads, 0, st>>>((const uint4*)src, (uint4*)dst, n16);
   return hipGetLastError();
 }
 

@@ -581,3 +581,16 @@ extern "C" int sf_policy_last_op_times(sf_policy* handle, float* ms_out, int n) 
     }
   return SF_OK;
 }
+
+extern "C" int sf_copy_bytes(const void* src, void* dst, int64_t bytes, void* hip_stream) {
+  if (!src || !dst || bytes < 0 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) {
+    set_error("sf_copy_bytes: null or misaligned argument");
+    return SF_ERR_ARG;
+  }
+  hipError_t e = launch_copy16(src, dst, bytes, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) {
+    set_error("sf_copy_bytes: launch failed: %s", hipGetErrorString(e));
+    return SF_ERR_DEVICE;
+  }
+  return SF_OK;
+}

@@ -96,6 +96,8 @@ hipError_t launch_heads(int B, int H, int n_heads, int sumA, const int32_t* head
                         uint64_t step, int32_t* actions, float* logp, float* value,
                         float* logits_opt, hipStream_t st);
 
+hipError_t launch_copy16(const void* src, void* dst, long long bytes, hipStream_t st);
+
 // ---- MFMA kernels (specialised shapes) ----
 bool conv1_mfma_supported(const ConvLayer& L);
 void conv1_mfma_pack(const float* w, const float* bias, int cin, float obs_sub, float obs_mul,
