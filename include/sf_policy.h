@@ -127,8 +127,8 @@ int sf_policy_create(const sf_policy_config* cfg, const sf_policy_weights* weigh
 
 /* One step of the policy worker (paper, Sec. 3.1) on B rows, enqueued
  * asynchronously on `hip_stream` (a hipStream_t; NULL = the default stream).
- *   obs        dev  [B][obs_c][obs_h][obs_w] bytes (planar frames)
- *   h_in       dev  [B][rnn_dim] fp32, 4-byte aligned
+ *   obs        dev  [B][obs_c][obs_h][obs_w] bytes (planar frames), 4-byte aligned
+ *   h_in       dev  [B][rnn_dim] fp32, 16-byte aligned
  *   done       dev  [B] bytes; non-zero = this observation is the first of a new
  *                   episode: the incoming state is zeroed before the GRU cell
  *   seed, step      sampler key and time step.  Category i of head k in row b is
@@ -140,10 +140,10 @@ int sf_policy_create(const sf_policy_config* cfg, const sf_policy_weights* weigh
  *   actions    dev  [B][n_heads] int32
  *   logp       dev  [B] fp32, log-probability of the sampled joint action
  *   value      dev  [B] fp32
- *   h_out      dev  [B][rnn_dim] fp32; must not overlap h_in
+ *   h_out      dev  [B][rnn_dim] fp32, 16-byte aligned; must not overlap h_in
  *   logits_opt dev  [B][sum(head_sizes)] fp32, or NULL if not wanted
  * B == 0 is accepted and does nothing.  Errors: SF_ERR_ARG (null handle or
- * pointer, misaligned fp32/int32 pointer), SF_ERR_BATCH, SF_ERR_ALIAS,
+ * pointer, misaligned pointer), SF_ERR_BATCH, SF_ERR_ALIAS,
  * SF_ERR_DEVICE (a launch failed).  Nothing is enqueued when an error is
  * returned for the arguments. */
 int sf_policy_step(sf_policy* p, int32_t B, const uint8_t* obs, const float* h_in,

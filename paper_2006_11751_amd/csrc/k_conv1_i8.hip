@@ -39,10 +39,10 @@ struct __attribute__((packed, aligned(4))) U2 {
   uint32_t x, y;
 };
 
-template <int CIN>
+template <int CIN, bool OUT_BF16>
 __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_kernel(
     const uint8_t* __restrict__ obs, const int* __restrict__ wpk, const float* __restrict__ scale,
-    const float* __restrict__ bias, float* __restrict__ out, int H, int W, int Ho, int Wo,
+    const float* __restrict__ bias, void* __restrict__ out_v, int H, int W, int Ho, int Wo,
     int n_xchunks, long long n_items, int n_waves_total) {
   constexpr int NSTEP = CIN * kK / 4;  // MFMA K steps (32 bytes each)
   const int lane = threadIdx.x & 63;
@@ -113,14 +113,20 @@ __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_k
     // epilogue.  D[i][j]: j = n, i = (v%4) + 4h + 8(v/4).  S2*128 + S3 fits int32
     // (|S2|, |S3| <= 192*128*64); its float image is exact to 6e-8 relative.
     const long long b = it / items_per_frame;
-    float* dst = out + (((size_t)b * Ho + oy) * Wo) * kCout + n;
+    const size_t dst0 = (((size_t)b * Ho + oy) * Wo) * kCout + n;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       int ox = xc * 32 + (v & 3) + 4 * h + 8 * (v >> 2);
       ox = ox < Wo ? ox : Wo - 1;  // duplicate rows hold the last pixel's result bit for bit
       const float lo = (float)(s2[v] * 128 + s3[v]);
       const float q = fmaf(lo, 0x1.0p-14f, (float)s1[v]);
-      dst[ox * kCout] = fmaxf(fmaf(q, s_n, b_n), 0.0f);
+      const float r = fmaxf(fmaf(q, s_n, b_n), 0.0f);
+      if (OUT_BF16) {
+        const unsigned u = __float_as_uint(r);
+        ((uint16_t*)out_v)[dst0 + ox * kCout] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+      } else {
+        ((float*)out_v)[dst0 + ox * kCout] = r;
+      }
     }
     if (more) {
 #pragma unroll
@@ -200,8 +206,8 @@ void conv1_i8_pack(const float* w, const float* bias, int cin, float obs_sub, fl
 }
 
 hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const int* wpk,
-                           const float* scale, const float* bpk, float* out, int waves_hint,
-                           hipStream_t st) {
+                           const float* scale, const float* bpk, void* out, int out_bf16,
+                           int waves_hint, hipStream_t st) {
   if (B == 0) return hipSuccess;
   const int n_xchunks = (L.Wo + 31) / 32;
   const long long n_items = (long long)B * L.Ho * n_xchunks;
@@ -209,9 +215,15 @@ hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const 
   if (waves > n_items) waves = n_items;
   const int blocks = (int)((waves + kWaves - 1) / kWaves);
   const int n_waves_total = blocks * kWaves;
-#define SF_LAUNCH_CIN(C)                                                                       \
-  conv1_u8_i8_kernel<C><<<blocks, 64 * kWaves, 0, st>>>(obs, wpk, scale, bpk, out, L.H, L.W, L.Ho, \
-                                                        L.Wo, n_xchunks, n_items, n_waves_total)
+#define SF_LAUNCH_CIN(C)                                                                         \
+  do {                                                                                           \
+    if (out_bf16)                                                                                \
+      conv1_u8_i8_kernel<C, true><<<blocks, 64 * kWaves, 0, st>>>(                               \
+          obs, wpk, scale, bpk, out, L.H, L.W, L.Ho, L.Wo, n_xchunks, n_items, n_waves_total);   \
+    else                                                                                         \
+      conv1_u8_i8_kernel<C, false><<<blocks, 64 * kWaves, 0, st>>>(                              \
+          obs, wpk, scale, bpk, out, L.H, L.W, L.Ho, L.Wo, n_xchunks, n_items, n_waves_total);   \
+  } while (0)
   switch (L.cin) {
     case 1: SF_LAUNCH_CIN(1); break;
     case 3: SF_LAUNCH_CIN(3); break;

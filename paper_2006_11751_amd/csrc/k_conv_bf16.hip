@@ -1,0 +1,444 @@
+// bf16 path of the encoder: implicit-GEMM convolution / FC on the bf16 MFMA with fp32
+// accumulation, bf16 activations between layers (paper, App. "Model architectures":
+// convolutional encoder and FC layer; the residual encoder follows IMPALA).
+//
+//   out[m][n] = act(bias[n] + sum_k A[m][k] * Wt[n][k] (+ residual[m][n]))
+//
+// A row m = (frame, output pixel) of a channels-last bf16 activation
+// [B][H][W][Cin]; K is ordered (filter row p, filter column q, channel c), any filter
+// size, stride and zero padding; Cin is a multiple of 8, so every 16-byte load (8
+// channels) lies inside one input pixel and is either wholly valid or wholly padding.
+// K is padded to a multiple of 64 with zero weights.  ReLU on the input (residual
+// blocks), the residual add and the output ReLU are fused.
+//
+// v_mfma_f32_32x32x16_bf16: lane l supplies A[i = l%32][k = 8*(l/32) + e] and
+// B[k = 8*(l/32) + e][j = l%32], e = 0..7 (one 16-byte LDS read per operand).  The
+// weights take the A role and the pixels the B role, so that in the result tile
+// D[i = channel][j = pixel] a lane holds 4 consecutive channels of one pixel per
+// register quad: the epilogue writes 8-byte (bf16) or 16-byte (fp32) pieces.
+// Workgroup tile: 128 pixels x 32 channels, one 32x32 tile per wave, K in chunks of
+// 64 through double-buffered LDS (pitch 144 bytes: conflict-free 16-byte accesses),
+// global loads two chunks ahead, XCD-contiguous tile order.
+#include <type_traits>
+
+#include <string.h>
+
+#include "sf_internal.h"
+
+namespace sf {
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kBK = 64;          // K elements per chunk
+constexpr int kPitchB = 144;     // LDS row pitch in bytes (128 + 16)
+constexpr int kBP = 128;         // pixels per workgroup
+constexpr int kBC = 32;          // channels per workgroup
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// 16-bit element type of the activations: bf16, or fp16 (kF16) where eight bits of
+// significand are not enough (deep residual encoder); weights are bf16 values either way.
+template <bool kF16>
+__device__ inline unsigned f32_to_h(float f) {
+  if (kF16) {
+    _Float16 h = (_Float16)f;  // round to nearest even
+    return (unsigned)__builtin_bit_cast(unsigned short, h);
+  }
+  unsigned u = __float_as_uint(f);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;  // round to nearest even (finite inputs)
+}
+template <bool kF16>
+__device__ inline float h_to_f32(unsigned h) {
+  if (kF16) return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+  return __uint_as_float(h << 16);
+}
+__device__ inline unsigned relu_bf16x2(unsigned w) {
+  unsigned neg = (w >> 15) & 0x00010001u;  // sign bits of the two halves
+  return w & ~(neg * 0xFFFFu);
+}
+
+struct ConvBf16Args {
+  const void* in;         // bf16 or fp32 [B][H][W][Cin]
+  const uint16_t* Wt;     // bf16 [Npad][Kpad]
+  const float* bias;      // [Npad]
+  const void* resid;      // bf16 or fp32 [M][N], or null
+  void* out;              // bf16 or fp32 [M][N]
+  int M, N, K, Kpad;
+  int rows_per_img, Wo, H, W, Cin, ks, stride, pad;
+  long long img_elems;
+  int relu_in, relu_out, out_f32, in_f32, resid_f32;
+};
+
+template <int TAG, bool kF16>
+__global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (kBP + kBC) * kPitchB];
+  unsigned char* Ps = smem;                        // [2][128][pitch] pixels
+  unsigned char* Cs = smem + 2 * kBP * kPitchB;    // [2][32][pitch] channels (weights)
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 31, lh = lane >> 5;
+  const int n_ctiles = (g.N + kBC - 1) / kBC;
+  const int n_tiles = ((g.M + kBP - 1) / kBP) * n_ctiles;
+  const int per_xcd = (n_tiles + 7) / 8;
+  const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (tile_id >= n_tiles) return;
+  const int m0 = (tile_id / n_ctiles) * kBP, n0 = (tile_id % n_ctiles) * kBC;
+  const int lrow = tid >> 3, lk8 = (tid & 7) * 8;  // 8 threads x 16 bytes per tile row
+
+  // pixel rows handled by this thread when staging (4 rows, 32 apart)
+  long long pbase[4];
+  int iy0[4], ix0[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    int m = m0 + lrow + 32 * r;
+    m = m < g.M ? m : g.M - 1;  // rows past the end repeat the last row; never stored
+    int b = m / g.rows_per_img;
+    int rem = m - b * g.rows_per_img;
+    int oy = rem / g.Wo, ox = rem - oy * g.Wo;
+    pbase[r] = (long long)b * g.img_elems;
+    iy0[r] = oy * g.stride - g.pad;
+    ix0[r] = ox * g.stride - g.pad;
+  }
+  const uint16_t* wrow = g.Wt + (size_t)(n0 + lrow) * g.Kpad + lk8;  // 32 rows x 8 pieces = 256 threads
+
+  u32x4 rp[2][4], rw[2];
+  const int nchunks = g.Kpad / kBK;
+  auto gload = [&](auto set, int c) {
+    constexpr int S = decltype(set)::value;
+    const int k0 = c * kBK + lk8;
+    const int pq = k0 / g.Cin;
+    const int c0 = k0 - pq * g.Cin;
+    const int p = pq / g.ks, q = pq - p * g.ks;
+    const bool kvalid = k0 < g.K;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int y = iy0[r] + p, x = ix0[r] + q;
+      const bool ok = kvalid && y >= 0 && y < g.H && x >= 0 && x < g.W;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (ok) {
+        const long long e = pbase[r] + ((long long)y * g.W + x) * g.Cin + c0;
+        if (g.in_f32) {  // fp32 activations are rounded to bf16 on their way to the matrix core
+          const f32x4 lo = *(const f32x4*)((const float*)g.in + e);
+          const f32x4 hi = *(const f32x4*)((const float*)g.in + e + 4);
+          v[0] = f32_to_h<kF16>(lo[0]) | (f32_to_h<kF16>(lo[1]) << 16);
+          v[1] = f32_to_h<kF16>(lo[2]) | (f32_to_h<kF16>(lo[3]) << 16);
+          v[2] = f32_to_h<kF16>(hi[0]) | (f32_to_h<kF16>(hi[1]) << 16);
+          v[3] = f32_to_h<kF16>(hi[2]) | (f32_to_h<kF16>(hi[3]) << 16);
+        } else {
+          v = *(const u32x4*)((const uint16_t*)g.in + e);
+        }
+      }
+      if (g.relu_in) {
+        v[0] = relu_bf16x2(v[0]);
+        v[1] = relu_bf16x2(v[1]);
+        v[2] = relu_bf16x2(v[2]);
+        v[3] = relu_bf16x2(v[3]);
+      }
+      rp[S][r] = v;
+    }
+    rw[S] = *(const u32x4*)(wrow + c * kBK);
+  };
+  auto sstore = [&](auto set, int buf) {
+    constexpr int S = decltype(set)::value;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      *(u32x4*)(Ps + ((size_t)(buf * kBP + lrow + 32 * r)) * kPitchB + lk8 * 2) = rp[S][r];
+    *(u32x4*)(Cs + ((size_t)(buf * kBC + lrow)) * kPitchB + lk8 * 2) = rw[S];
+  };
+
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+
+  auto compute = [&](int buf) {
+    const unsigned char* Pb = Ps + ((size_t)(buf * kBP + wave * 32 + li)) * kPitchB + lh * 16;
+    const unsigned char* Cb = Cs + ((size_t)(buf * kBC + li)) * kPitchB + lh * 16;
+#pragma unroll
+    for (int s = 0; s < kBK / 16; ++s) {
+      if (kF16) {
+        const f16x8 wf = *(const f16x8*)(Cb + s * 32);
+        const f16x8 pf = *(const f16x8*)(Pb + s * 32);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf, pf, acc, 0, 0, 0);
+      } else {
+        const bf16x8 wf = *(const bf16x8*)(Cb + s * 32);
+        const bf16x8 pf = *(const bf16x8*)(Pb + s * 32);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, pf, acc, 0, 0, 0);
+      }
+    }
+  };
+  auto step = [&](auto set, int c) {
+    constexpr int S = decltype(set)::value;
+    if (c + 2 < nchunks) gload(set, c + 2);
+    compute(c & 1);
+    if (c + 1 < nchunks) sstore(std::integral_constant<int, S ^ 1>{}, (c + 1) & 1);
+    __syncthreads();
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  gload(I0{}, 0);
+  sstore(I0{}, 0);
+  if (nchunks > 1) gload(I1{}, 1);
+  __syncthreads();
+  for (int c = 0; c < nchunks; c += 2) {
+    step(I0{}, c);
+    if (c + 1 < nchunks) step(I1{}, c + 1);
+  }
+
+  // epilogue: D[i][j], i = channel = (v%4) + 4*lh + 8*(v/4), j = pixel = li
+  const int m = m0 + wave * 32 + li;
+  if (m >= g.M) return;
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4) {
+    const int ch = n0 + 8 * q4 + 4 * lh;
+    if (ch >= g.N) continue;  // N is a multiple of 4
+    float r[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) r[t] = acc[4 * q4 + t] + g.bias[ch + t];
+    if (g.resid) {
+      if (g.resid_f32) {
+        const f32x4 rv = *(const f32x4*)((const float*)g.resid + (size_t)m * g.N + ch);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) r[t] += rv[t];
+      } else {
+        const u32x2 rv = *(const u32x2*)((const uint16_t*)g.resid + (size_t)m * g.N + ch);
+        r[0] += h_to_f32<kF16>(rv[0] & 0xFFFFu);
+        r[1] += h_to_f32<kF16>(rv[0] >> 16);
+        r[2] += h_to_f32<kF16>(rv[1] & 0xFFFFu);
+        r[3] += h_to_f32<kF16>(rv[1] >> 16);
+      }
+    }
+    if (g.relu_out) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) r[t] = fmaxf(r[t], 0.0f);
+    }
+    if (g.out_f32) {
+      f32x4 o = {r[0], r[1], r[2], r[3]};
+      *(f32x4*)((float*)g.out + (size_t)m * g.N + ch) = o;
+    } else {
+      u32x2 o;
+      o[0] = f32_to_h<kF16>(r[0]) | (f32_to_h<kF16>(r[1]) << 16);
+      o[1] = f32_to_h<kF16>(r[2]) | (f32_to_h<kF16>(r[3]) << 16);
+      *(u32x2*)((uint16_t*)g.out + (size_t)m * g.N + ch) = o;
+    }
+  }
+}
+
+// 3x3/s2 max pooling whose padding ring never wins; bf16 channels-last, 8 channels
+// (16 bytes) per thread.  Comparing bf16 values as floats is exact; the result can be
+// written as fp32 (the residual stream is kept in fp32).
+template <bool OUT_F32, bool kF16>
+__global__ __launch_bounds__(256) void maxpool_bf16_kernel(const uint16_t* __restrict__ in,
+                                                           void* __restrict__ out,
+                                                           long long total8, int C8, int H, int W,
+                                                           int Ho, int Wo) {
+  long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total8) return;
+  int c8 = (int)(idx % C8);
+  long long t = idx / C8;
+  int ox = (int)(t % Wo);
+  t /= Wo;
+  int oy = (int)(t % Ho);
+  long long b = t / Ho;
+  float m[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) m[e] = -INFINITY;
+  for (int y = 2 * oy - 1; y <= 2 * oy + 1; ++y) {
+    if (y < 0 || y >= H) continue;
+    for (int x = 2 * ox - 1; x <= 2 * ox + 1; ++x) {
+      if (x < 0 || x >= W) continue;
+      const u32x4 v = *(const u32x4*)(in + ((((size_t)b * H + y) * W + x) * C8 + c8) * 8);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        m[2 * e] = fmaxf(m[2 * e], h_to_f32<kF16>(v[e] & 0xFFFFu));
+        m[2 * e + 1] = fmaxf(m[2 * e + 1], h_to_f32<kF16>(v[e] >> 16));
+      }
+    }
+  }
+  if (OUT_F32) {
+    f32x4 o0 = {m[0], m[1], m[2], m[3]}, o1 = {m[4], m[5], m[6], m[7]};
+    *(f32x4*)((float*)out + (size_t)idx * 8) = o0;
+    *(f32x4*)((float*)out + (size_t)idx * 8 + 4) = o1;
+  } else {
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      o[e] = f32_to_h<kF16>(m[2 * e]) | (f32_to_h<kF16>(m[2 * e + 1]) << 16);
+    *(u32x4*)((uint16_t*)out + (size_t)idx * 8) = o;
+  }
+}
+
+// First convolution of a residual stage on planar byte frames: 3x3, stride 1, one ring
+// of zero padding (of the NORMALISED image: a padded tap contributes nothing), COUT
+// output channels, no activation; bf16 channels-last output.  One thread per output
+// pixel, fp32 FMAs; the 27*COUT weights are wave-uniform.
+template <int COUT, bool kF16>
+__global__ __launch_bounds__(256) void conv3x3_u8_bf16_kernel(
+    const uint8_t* __restrict__ obs, const float* __restrict__ w /* [c][p][q][COUT] */,
+    const float* __restrict__ bias, uint16_t* __restrict__ out, long long total, int Cin, int H,
+    int W, float obs_sub, float obs_mul) {
+  long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int x = (int)(idx % W);
+  long long t = idx / W;
+  const int y = (int)(t % H);
+  const long long b = t / H;
+  float acc[COUT];
+#pragma unroll
+  for (int o = 0; o < COUT; ++o) acc[o] = bias[o];
+  for (int c = 0; c < Cin; ++c) {
+    const uint8_t* plane = obs + ((size_t)b * Cin + c) * H * W;
+#pragma unroll
+    for (int p = 0; p < 3; ++p) {
+      const int yy = y + p - 1;
+#pragma unroll
+      for (int q = 0; q < 3; ++q) {
+        const int xx = x + q - 1;
+        const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
+        const float v = ok ? ((float)plane[(size_t)yy * W + xx] - obs_sub) * obs_mul : 0.0f;
+        const float* wp = w + ((c * 3 + p) * 3 + q) * COUT;
+#pragma unroll
+        for (int o = 0; o < COUT; ++o) acc[o] = fmaf(v, wp[o], acc[o]);
+      }
+    }
+  }
+  uint32_t* dst = (uint32_t*)(out + (size_t)idx * COUT);
+#pragma unroll
+  for (int o = 0; o < COUT; o += 2)
+    dst[o / 2] = f32_to_h<kF16>(acc[o]) | (f32_to_h<kF16>(acc[o + 1]) << 16);
+}
+
+template <int TAG>
+hipError_t launch_tagged(const ConvBf16Args& g, bool f16, hipStream_t st) {
+  const int n_tiles = ((g.M + kBP - 1) / kBP) * ((g.N + kBC - 1) / kBC);
+  const int per_xcd = (n_tiles + 7) / 8;
+  if (f16)
+    conv_bf16_kernel<TAG, true><<<per_xcd * 8, 256, 0, st>>>(g);
+  else
+    conv_bf16_kernel<TAG, false><<<per_xcd * 8, 256, 0, st>>>(g);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool conv_bf16_supported(int Cin, int N) { return (Cin % 8) == 0 && (N % 4) == 0; }
+
+// Weights [cout][cin][k][k] fp32 -> bf16 [Npad32][Kpad64], K ordered (p, q, c).
+namespace {
+// fp32 -> fp16 bits, round to nearest even, subnormals kept.
+uint16_t host_f32_to_f16(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  const uint32_t sign = (u >> 16) & 0x8000u;
+  const int32_t exp = (int32_t)((u >> 23) & 0xFF) - 127 + 15;
+  uint32_t man = u & 0x7FFFFFu;
+  if (((u >> 23) & 0xFF) == 0xFF) return (uint16_t)(sign | 0x7C00u | (man ? 0x200u : 0));
+  if (exp >= 31) return (uint16_t)(sign | 0x7C00u);
+  if (exp <= 0) {
+    if (exp < -10) return (uint16_t)sign;
+    man |= 0x800000u;
+    const int shift = 14 - exp;  // 14..24
+    uint32_t h = man >> shift;
+    const uint32_t remb = man & ((1u << shift) - 1), half = 1u << (shift - 1);
+    if (remb > half || (remb == half && (h & 1))) ++h;
+    return (uint16_t)(sign | h);
+  }
+  uint32_t h = ((uint32_t)exp << 10) | (man >> 13);
+  const uint32_t remb = man & 0x1FFFu;
+  if (remb > 0x1000u || (remb == 0x1000u && (h & 1))) ++h;
+  return (uint16_t)(sign | h);
+}
+}  // namespace
+
+void conv_bf16_pack(const float* w, const float* bias, int cout, int cin, int k, bool f16,
+                    std::vector<uint16_t>& wt, std::vector<float>& b, int* Kpad) {
+  const int K = k * k * cin;
+  const int kp = (K + kBK - 1) / kBK * kBK;
+  const int np = (cout + kBC - 1) / kBC * kBC;
+  wt.assign((size_t)np * kp, 0);
+  b.assign(np, 0.0f);
+  for (int o = 0; o < cout; ++o) {
+    b[o] = bias[o];
+    for (int c = 0; c < cin; ++c)
+      for (int p = 0; p < k; ++p)
+        for (int q = 0; q < k; ++q) {
+          float v = w[(((size_t)o * cin + c) * k + p) * k + q];
+          uint32_t u;
+          memcpy(&u, &v, 4);
+          u = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;  // the bf16 value of the weight
+          uint16_t hbits = (uint16_t)(u >> 16);
+          if (f16) {  // the same bf16 value, held in fp16
+            float bv;
+            memcpy(&bv, &u, 4);
+            hbits = host_f32_to_f16(bv);
+          }
+          wt[(size_t)o * kp + (size_t)(p * k + q) * cin + c] = hbits;
+        }
+  }
+  *Kpad = kp;
+}
+
+hipError_t launch_conv_bf16(const void* in, const uint16_t* wt, const float* bias,
+                            const void* resid, void* out, int B, int H, int W, int Cin, int ks,
+                            int stride, int pad, int Ho, int Wo, int N, int Kpad, int relu_in,
+                            int relu_out, int in_f32, int resid_f32, int out_f32, int f16,
+                            int tag, hipStream_t st) {
+  ConvBf16Args g;
+  g.in = in; g.Wt = wt; g.bias = bias; g.resid = resid; g.out = out;
+  g.in_f32 = in_f32; g.resid_f32 = resid_f32;
+  g.M = B * Ho * Wo; g.N = N; g.K = ks * ks * Cin; g.Kpad = Kpad;
+  g.rows_per_img = Ho * Wo; g.Wo = Wo; g.H = H; g.W = W; g.Cin = Cin; g.ks = ks;
+  g.stride = stride; g.pad = pad; g.img_elems = (long long)H * W * Cin;
+  g.relu_in = relu_in; g.relu_out = relu_out; g.out_f32 = out_f32;
+  if (g.M == 0) return hipSuccess;
+  switch (tag & 15) {
+#define SF_TAG_CASE(T) case T: return launch_tagged<T>(g, f16 != 0, st);
+    SF_TAG_CASE(0) SF_TAG_CASE(1) SF_TAG_CASE(2) SF_TAG_CASE(3) SF_TAG_CASE(4) SF_TAG_CASE(5)
+    SF_TAG_CASE(6) SF_TAG_CASE(7) SF_TAG_CASE(8) SF_TAG_CASE(9) SF_TAG_CASE(10) SF_TAG_CASE(11)
+    SF_TAG_CASE(12) SF_TAG_CASE(13) SF_TAG_CASE(14)
+#undef SF_TAG_CASE
+    default: return launch_tagged<15>(g, f16 != 0, st);
+  }
+}
+
+hipError_t launch_maxpool_bf16(int B, int C, int H, int W, const void* in, void* out, int out_f32,
+                               int f16, hipStream_t st) {
+  const int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
+  const long long total8 = (long long)B * Ho * Wo * (C / 8);
+  if (total8 == 0) return hipSuccess;
+  const unsigned blocks = (unsigned)((total8 + 255) / 256);
+#define SF_POOL(O, F) \
+  maxpool_bf16_kernel<O, F><<<blocks, 256, 0, st>>>((const uint16_t*)in, out, total8, C / 8, H, W, Ho, Wo)
+  if (out_f32 && f16) SF_POOL(true, true);
+  else if (out_f32) SF_POOL(true, false);
+  else if (f16) SF_POOL(false, true);
+  else SF_POOL(false, false);
+#undef SF_POOL
+  return hipGetLastError();
+}
+
+bool conv3x3_u8_bf16_supported(int cout) { return cout == 16 || cout == 32; }
+
+hipError_t launch_conv3x3_u8_bf16(int B, int Cin, int H, int W, int cout, const uint8_t* obs,
+                                  const float* w_cpqo, const float* bias, void* out, float obs_sub,
+                                  float obs_mul, int f16, hipStream_t st) {
+  const long long total = (long long)B * H * W;
+  if (total == 0) return hipSuccess;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+#define SF_C3(C, F) \
+  conv3x3_u8_bf16_kernel<C, F><<<blocks, 256, 0, st>>>(obs, w_cpqo, bias, (uint16_t*)out, total, Cin, H, W, obs_sub, obs_mul)
+  if (cout == 16 && f16) SF_C3(16, true);
+  else if (cout == 16) SF_C3(16, false);
+  else if (cout == 32 && f16) SF_C3(32, true);
+  else if (cout == 32) SF_C3(32, false);
+  else return hipErrorInvalidValue;
+#undef SF_C3
+  return hipGetLastError();
+}
+
+}  // namespace sf

@@ -242,6 +242,33 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
   p->conv1_waves = getenv("SF_CONV1_WAVES") ? atoi(getenv("SF_CONV1_WAVES")) : 0;
   Builder bld{p, cfg->dtype == SF_DTYPE_BF16};
 
+  // bf16 configurations run the encoder and the FC layer on the bf16 kernels with bf16
+  // activations, provided every layer has a shape those kernels take; otherwise the
+  // fp32 kernels run on the (bf16-rounded) weights.
+  p->bf16_path = false;
+  if (cfg->dtype == SF_DTYPE_BF16 && !getenv("SF_FORCE_GENERIC") && !getenv("SF_NO_BF16_PATH")) {
+    bool ok = (p->flat % 8) == 0 && (cfg->fc_dim % 4) == 0;
+    if (cfg->encoder == SF_ENCODER_CONV) {
+      ConvLayer L0{};
+      L0.cin = cfg->obs_c; L0.W = cfg->obs_w; L0.k = cfg->conv[0].k; L0.s = cfg->conv[0].stride;
+      L0.pad = cfg->conv[0].pad; L0.cout = cfg->conv[0].cout; L0.relu_out = 1;
+      ok = ok && conv1_i8_supported(L0);
+      for (int l = 1; l < cfg->n_conv; ++l)
+        ok = ok && conv_bf16_supported(cfg->conv[l - 1].cout, cfg->conv[l].cout);
+    } else {
+      ok = ok && conv3x3_u8_bf16_supported(cfg->stage_ch[0]);
+      for (int s = 0; s < cfg->n_stage; ++s) {
+        ok = ok && (cfg->stage_ch[s] % 8) == 0;
+        if (s > 0) ok = ok && conv_bf16_supported(cfg->stage_ch[s - 1], cfg->stage_ch[s]);
+      }
+    }
+    p->bf16_path = ok;
+  }
+  // The residual encoder is 15 convolutions deep: with 8-bit significands the rounding of
+  // the activations alone exceeds the 2e-2 tolerance in the tails, so its 16-bit
+  // activations are fp16 (the weights stay bf16 values, exactly representable in fp16).
+  p->act_f16 = p->bf16_path && cfg->encoder == SF_ENCODER_RESNET && !getenv("SF_ACT_BF16");
+
   // ---- encoder plan ----
   size_t act_elems = 0;
   int64_t macs = 0;
@@ -259,7 +286,41 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
       L.bias = bld.pack_vec(w->conv_b[ti], cout);
       L.relu_in = relu_in; L.relu_out = relu_out; L.add_residual = resid_buf >= 0;
       L.impl = CONV_GENERIC;
-      const bool allow_mfma = !getenv("SF_FORCE_GENERIC");
+      const bool allow_mfma = !getenv("SF_FORCE_GENERIC") && !p->bf16_path;
+      if (p->bf16_path) {
+        if (in_buf >= 0) {
+          std::vector<uint16_t> wt;
+          std::vector<float> bb;
+          conv_bf16_pack(w->conv_w[ti], w->conv_b[ti], cout, C, k, p->act_f16, wt, bb, &L.Kpad);
+          L.wbf = bld.upload(wt);
+          L.bbf = bld.upload(bb);
+          L.impl = CONV_BF16;
+          // Residual encoder: the stream x (pool outputs, block outputs) stays fp32 so that
+          // its rounding does not accumulate over the blocks; branch intermediates and
+          // stage-convolution outputs are bf16.  Plain stack: everything bf16.
+          const bool resnet = cfg->encoder == SF_ENCODER_RESNET;
+          L.in_f32 = resnet && !(relu_in == 0 && resid_buf >= 0);  // conv_b reads the bf16 branch
+          L.out_f32 = resnet && resid_buf >= 0;
+        } else if (cfg->encoder == SF_ENCODER_CONV) {
+          std::vector<int> ipk;
+          std::vector<float> spk, bpk;
+          conv1_i8_pack(w->conv_w[ti], w->conv_b[ti], C, cfg->obs_sub, cfg->obs_mul, ipk, spk, bpk);
+          L.ipk = bld.upload(ipk);
+          L.spk = bld.upload(spk);
+          L.bpk = bld.upload(bpk);
+          L.impl = CONV1_U8_I8;
+        } else {
+          std::vector<float> t((size_t)C * 9 * cout);  // [c][p][q][cout]
+          for (int o = 0; o < cout; ++o)
+            for (int c2 = 0; c2 < C; ++c2)
+              for (int a = 0; a < 3; ++a)
+                for (int b2 = 0; b2 < 3; ++b2)
+                  t[(((size_t)c2 * 3 + a) * 3 + b2) * cout + o] =
+                      bld.q(w->conv_w[ti][(((size_t)o * C + c2) * 3 + a) * 3 + b2]);
+          L.w_cpqo = bld.upload(t);
+          L.impl = CONV3X3_U8_BF16;
+        }
+      }
       if (in_buf >= 0 && allow_mfma && !relu_in && resid_buf < 0 &&
           gemm_mfma_supported(C, k, pad, cout)) {
         // [cout][cin][k][k] -> [cout][k][k][cin]: K ordered (filter row, filter column, channel)
@@ -356,13 +417,27 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
     p->fc_w_t = bld.upload(t);
     p->fc_b = bld.pack_vec(w->fc_b, cfg->fc_dim);
     p->fc_wt = nullptr;
-    if (!getenv("SF_FORCE_GENERIC") && gemm_mfma_supported(p->flat, 1, 0, cfg->fc_dim)) {
+    if (!getenv("SF_FORCE_GENERIC") && !p->bf16_path && gemm_mfma_supported(p->flat, 1, 0, cfg->fc_dim)) {
       std::vector<float> u((size_t)p->flat * cfg->fc_dim);  // [fc][flat in channels-last order]
       for (int o = 0; o < cfg->fc_dim; ++o)
         for (int i = 0; i < p->flat; ++i) u[(size_t)o * p->flat + i] = t[(size_t)i * cfg->fc_dim + o];
       p->fc_wt = bld.upload(u);
       const char* th = getenv("SF_FC_TILE");
       p->fc_tile = th ? atoi(th) : gemm_mfma_pick_tile(cfg->max_batch, cfg->fc_dim, p->flat, p->flat);
+    }
+    p->fc_wbf = nullptr;
+    if (p->bf16_path) {
+      // the FC is a 1x1 "convolution" over a 1x1 image with flat channels; t is [flat][fc]
+      std::vector<float> u((size_t)cfg->fc_dim * p->flat);  // [fc][flat][1][1]
+      for (int o = 0; o < cfg->fc_dim; ++o)
+        for (int i = 0; i < p->flat; ++i) u[(size_t)o * p->flat + i] = t[(size_t)i * cfg->fc_dim + o];
+      std::vector<uint16_t> wt;
+      std::vector<float> bb;
+      std::vector<float> fb(cfg->fc_dim);
+      for (int o = 0; o < cfg->fc_dim; ++o) fb[o] = bld.q(w->fc_b[o]);
+      conv_bf16_pack(u.data(), fb.data(), cfg->fc_dim, p->flat, 1, p->act_f16, wt, bb, &p->fc_Kpad);
+      p->fc_wbf = bld.upload(wt);
+      p->fc_bbf = bld.upload(bb);
     }
     macs += (int64_t)p->flat * cfg->fc_dim;
     p->ops.push_back(Op{OP_FC, "fc", 2 * (int64_t)p->flat * cfg->fc_dim, -1, p->enc_buf, -1, -1, 0, 0, 0});
@@ -470,9 +545,10 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
     return SF_ERR_ARG;
   }
   auto misaligned = [](const void* q, uintptr_t a) { return (reinterpret_cast<uintptr_t>(q) & (a - 1)) != 0; };
-  if (misaligned(h_in, 4) || misaligned(h_out, 4) || misaligned(actions, 4) ||
+  if (misaligned(obs, 4) || misaligned(h_in, 16) || misaligned(h_out, 16) || misaligned(actions, 4) ||
       misaligned(logp, 4) || misaligned(value, 4) || (logits_opt && misaligned(logits_opt, 4))) {
-    set_error("sf_policy_step: fp32/int32 buffer not 4-byte aligned");
+    set_error("sf_policy_step: misaligned buffer (obs, actions, logp, value, logits: 4 bytes; "
+              "h_in, h_out: 16 bytes)");
     return SF_ERR_ARG;
   }
   {
@@ -493,25 +569,49 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
       case OP_CONV: {
         const ConvLayer& L = p->convs[op.conv];
         const void* in = op.in_buf < 0 ? (const void*)obs : (const void*)buf(op.in_buf);
-        if (L.impl == CONV1_U8_I8 && !misaligned(obs, 4))
-          SF_LAUNCH(launch_conv1_i8(L, B, obs, L.ipk, L.spk, L.bpk, buf(op.out_buf), p->conv1_waves, st));
-        else if (L.impl == CONV1_U8_MFMA && !misaligned(obs, 4))
-          SF_LAUNCH(launch_conv1_mfma(L, B, obs, L.wpk, L.bpk, buf(op.out_buf), p->trash,
+        switch (L.impl) {
+          case CONV1_U8_I8:
+            SF_LAUNCH(launch_conv1_i8(L, B, obs, L.ipk, L.spk, L.bpk, buf(op.out_buf), p->bf16_path,
                                       p->conv1_waves, st));
-        else if (L.impl == CONV_GEMM_MFMA)
-          SF_LAUNCH(launch_gemm_mfma((const float*)in, L.wpk, L.bpk, buf(op.out_buf), B, L.H, L.W,
-                                     L.cin, L.k, L.s, L.Ho, L.Wo, L.cout, L.relu_out, L.tile, op.conv + 1,
-                                     st));
-        else
-          SF_LAUNCH(launch_conv_generic(L, B, in, op.in_buf < 0, c.obs_sub, c.obs_mul,
-                                        buf(op.resid_buf), buf(op.out_buf), st));
+            break;
+          case CONV1_U8_MFMA:
+            SF_LAUNCH(launch_conv1_mfma(L, B, obs, L.wpk, L.bpk, buf(op.out_buf), p->trash,
+                                        p->conv1_waves, st));
+            break;
+          case CONV_GEMM_MFMA:
+            SF_LAUNCH(launch_gemm_mfma((const float*)in, L.wpk, L.bpk, buf(op.out_buf), B, L.H, L.W,
+                                       L.cin, L.k, L.s, L.Ho, L.Wo, L.cout, L.relu_out, L.tile,
+                                       op.conv + 1, st));
+            break;
+          case CONV_BF16:
+            SF_LAUNCH(launch_conv_bf16(in, L.wbf, L.bbf, buf(op.resid_buf), buf(op.out_buf), B, L.H,
+                                       L.W, L.cin, L.k, L.s, L.pad, L.Ho, L.Wo, L.cout, L.Kpad,
+                                       L.relu_in, L.relu_out, L.in_f32, 1, L.out_f32, p->act_f16,
+                                       op.conv + 1, st));
+            break;
+          case CONV3X3_U8_BF16:
+            SF_LAUNCH(launch_conv3x3_u8_bf16(B, L.cin, L.H, L.W, L.cout, obs, L.w_cpqo, L.bias,
+                                             buf(op.out_buf), c.obs_sub, c.obs_mul, p->act_f16, st));
+            break;
+          default:
+            SF_LAUNCH(launch_conv_generic(L, B, in, op.in_buf < 0, c.obs_sub, c.obs_mul,
+                                          buf(op.resid_buf), buf(op.out_buf), st));
+        }
         break;
       }
       case OP_POOL:
-        SF_LAUNCH(launch_maxpool3x3s2p1(B, op.C, op.H, op.W, buf(op.in_buf), buf(op.out_buf), st));
+        if (p->bf16_path)
+          SF_LAUNCH(launch_maxpool_bf16(B, op.C, op.H, op.W, buf(op.in_buf), buf(op.out_buf), 1,
+                                        p->act_f16, st));
+        else
+          SF_LAUNCH(launch_maxpool3x3s2p1(B, op.C, op.H, op.W, buf(op.in_buf), buf(op.out_buf), st));
         break;
       case OP_FC:
-        if (p->fc_wt)
+        if (p->fc_wbf)
+          SF_LAUNCH(launch_conv_bf16(buf(op.in_buf), p->fc_wbf, p->fc_bbf, nullptr, p->fc_out, B, 1, 1,
+                                     p->flat, 1, 1, 0, 1, 1, c.fc_dim, p->fc_Kpad, 0, 1,
+                                     c.encoder == SF_ENCODER_RESNET, 0, 1, p->act_f16, 0, st));
+        else if (p->fc_wt)
           SF_LAUNCH(launch_gemm_mfma(buf(op.in_buf), p->fc_wt, p->fc_b, p->fc_out, B, 1, 1, p->flat, 1,
                                      1, 1, 1, c.fc_dim, 1, p->fc_tile, 0, st));
         else
@@ -519,7 +619,7 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
                                           1, p->fc_out, st));
         break;
       case OP_GRU:
-        if (p->gru_wih && !misaligned(h_in, 16))
+        if (p->gru_wih)
           SF_LAUNCH(launch_gru_mfma(B, c.fc_dim, c.rnn_dim, p->fc_out, h_in, done, p->gru_wih,
                                     p->gru_whh, p->gru_bih, p->gru_bhh, h_out, p->gru_bm, st));
         else

@@ -27,8 +27,17 @@ struct ConvLayer {
   float* bpk;             // dev, bias as the chosen MFMA kernel wants it (or null)
   int* ipk;               // dev, int8 digit planes of the int8 first-convolution kernel
   float* spk;             // dev, per-channel scales of that kernel
+  uint16_t* wbf;          // dev, bf16 [Npad][Kpad] weights of the bf16 kernel
+  float* bbf;             // dev, bias padded to Npad
+  int Kpad;
+  int in_f32, out_f32;    // bf16 kernel: element type of its input / output tensors
+  float* w_cpqo;          // dev, fp32 [c][p][q][cout] for the byte-input 3x3 kernel
 };
-enum ConvImpl { CONV_GENERIC = 0, CONV1_U8_MFMA = 1, CONV_GEMM_MFMA = 2, CONV1_U8_I8 = 3 };
+enum ConvImpl {
+  CONV_GENERIC = 0, CONV1_U8_MFMA = 1, CONV_GEMM_MFMA = 2, CONV1_U8_I8 = 3,
+  CONV_BF16 = 4,        // bf16 MFMA implicit GEMM, bf16 activations
+  CONV3X3_U8_BF16 = 5   // first convolution of the residual encoder, bytes in, bf16 out
+};
 
 // One kernel launch of the step, fixed at create time.
 enum OpKind { OP_CONV, OP_POOL, OP_FC, OP_GRU, OP_HEADS };
@@ -52,6 +61,11 @@ struct Policy {
   float* fc_w_t;      // dev [flat (channels-last order)][fc_dim]
   float* fc_b;        // dev [fc_dim]
   float* fc_wt;       // dev [fc_dim][flat (channels-last order)] for the MFMA GEMM, or null
+  uint16_t* fc_wbf;   // dev bf16 [fc_dim pad 32][flat pad 64] for the bf16 kernel, or null
+  float* fc_bbf;
+  int fc_Kpad;
+  bool bf16_path;     // encoder and FC run on the 16-bit MFMA kernels with 16-bit activations
+  bool act_f16;       // ... whose activation element type is fp16 instead of bf16
   int fc_tile;
   float* gru_wih_t;   // dev [fc_dim][3H]
   float* gru_whh_t;   // dev [H][3H]
@@ -110,8 +124,22 @@ bool conv1_i8_supported(const ConvLayer& L);
 void conv1_i8_pack(const float* w, const float* bias, int cin, float obs_sub, float obs_mul,
                    std::vector<int>& wpk, std::vector<float>& scale, std::vector<float>& bpk);
 hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const int* wpk,
-                           const float* scale, const float* bpk, float* out, int waves_hint,
-                           hipStream_t st);
+                           const float* scale, const float* bpk, void* out, int out_bf16,
+                           int waves_hint, hipStream_t st);
+bool conv_bf16_supported(int Cin, int N);
+void conv_bf16_pack(const float* w, const float* bias, int cout, int cin, int k, bool f16,
+                    std::vector<uint16_t>& wt, std::vector<float>& b, int* Kpad);
+hipError_t launch_conv_bf16(const void* in, const uint16_t* wt, const float* bias,
+                            const void* resid, void* out, int B, int H, int W, int Cin, int ks,
+                            int stride, int pad, int Ho, int Wo, int N, int Kpad, int relu_in,
+                            int relu_out, int in_f32, int resid_f32, int out_f32, int f16,
+                            int tag, hipStream_t st);
+hipError_t launch_maxpool_bf16(int B, int C, int H, int W, const void* in, void* out, int out_f32,
+                               int f16, hipStream_t st);
+bool conv3x3_u8_bf16_supported(int cout);
+hipError_t launch_conv3x3_u8_bf16(int B, int Cin, int H, int W, int cout, const uint8_t* obs,
+                                  const float* w_cpqo, const float* bias, void* out, float obs_sub,
+                                  float obs_mul, int f16, hipStream_t st);
 bool gru_mfma_supported(int I, int H);
 hipError_t launch_gru_mfma(int B, int I, int H, const float* x, const float* h_in,
                            const uint8_t* done, const float* w_ih, const float* w_hh,

@@ -60,7 +60,14 @@ def test_tiny_four_steps_free_running(torch_cuda, ref):
     pol.close()
 
 
-@pytest.mark.parametrize("net", [SMALL_RESNET, ODD_NET], ids=lambda n: n["name"])
+RESNET_BF16_SMALL = dict(name="resnet_bf16_small", B=7, obs=(3, 20, 28), encoder="resnet", stages=[16, 32, 32],
+                         blocks_per_stage=2, fc=64, rnn=32, heads=[15], dtype="bf16", p_done=0.3, steps=1,
+                         obs_sub=0.0, obs_mul=wl.OBS_MUL, index=4)
+STD_BF16_SMALL = wl.network(2, B=37, name="standard_bf16_small")
+
+
+@pytest.mark.parametrize("net", [SMALL_RESNET, ODD_NET, RESNET_BF16_SMALL, STD_BF16_SMALL],
+                         ids=lambda n: n["name"])
 def test_small_networks_all_elements(torch_cuda, ref, net):
     torch = torch_cuda
     pol, w = _make(torch, net)
