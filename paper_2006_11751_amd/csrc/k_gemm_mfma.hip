@@ -93,24 +93,37 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   for (int r = 0; r < RB; ++r) b_ptr[r] = g.Wt + (size_t)(n0 + lrow + RPP * r) * g.K + lk4;
 
   // Two register sets: global loads run two chunks ahead of the MFMAs (one chunk of
-  // compute does not cover the latency of a load that misses the L2).
+  // compute does not cover the latency of a load that misses the L2).  The load
+  // cursor walks K chunk by chunk: within a row segment the A offset advances by BK,
+  // at a segment's end it jumps to the next filter row.
   f32x4 ra[2][RA], rb[2][RB];
-  auto gload = [&](auto set, int c) {
+  int ld_kk = 0, ld_off = 0, ld_in_seg = 0;
+  auto gload = [&](auto set) {
     constexpr int S = decltype(set)::value;
-    const int kk = c * BK;
-    const int seg = kk / g.seg_len;
-    const int off = kk - seg * g.seg_len + seg * g.seg_stride;
 #pragma unroll
-    for (int r = 0; r < RA; ++r) ra[S][r] = *(const f32x4*)(a_ptr[r] + off);
+    for (int r = 0; r < RA; ++r) ra[S][r] = *(const f32x4*)(a_ptr[r] + ld_off);
 #pragma unroll
-    for (int r = 0; r < RB; ++r) rb[S][r] = *(const f32x4*)(b_ptr[r] + kk);
+    for (int r = 0; r < RB; ++r) rb[S][r] = *(const f32x4*)(b_ptr[r] + ld_kk);
+    ld_kk += BK;
+    ld_off += BK;
+    ld_in_seg += BK;
+    if (ld_in_seg == g.seg_len) {
+      ld_in_seg = 0;
+      ld_off += g.seg_stride - g.seg_len;
+    }
   };
-  auto sstore = [&](auto set, int buf) {
+  // LDS addresses of this thread's staging stores and fragment loads, per buffer
+  float* as_st = As + lrow * P + lk4;
+  float* bs_st = Bs + lrow * P + lk4;
+  const float* a_fr = As + (wm * TM * 32 + li) * P + 4 * lh;
+  const float* b_fr = Bs + (wn * TN * 32 + li) * P + 4 * lh;
+  auto sstore = [&](auto set, auto bufc) {
     constexpr int S = decltype(set)::value;
+    constexpr int BUF = decltype(bufc)::value;
 #pragma unroll
-    for (int r = 0; r < RA; ++r) *(f32x4*)&As[((buf * BM) + lrow + RPP * r) * P + lk4] = ra[S][r];
+    for (int r = 0; r < RA; ++r) *(f32x4*)(as_st + (BUF * BM + RPP * r) * P) = ra[S][r];
 #pragma unroll
-    for (int r = 0; r < RB; ++r) *(f32x4*)&Bs[((buf * BN) + lrow + RPP * r) * P + lk4] = rb[S][r];
+    for (int r = 0; r < RB; ++r) *(f32x4*)(bs_st + (BUF * BN + RPP * r) * P) = rb[S][r];
   };
 
   f32x16 acc[TM][TN];
@@ -122,17 +135,16 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
   const int nchunks = g.K / BK;
-  auto compute = [&](int buf) {
-    const float* Ab = As + (buf * BM + wm * TM * 32 + li) * P + 4 * lh;
-    const float* Bb = Bs + (buf * BN + wn * TN * 32 + li) * P + 4 * lh;
+  auto compute = [&](auto bufc) {
+    constexpr int BUF = decltype(bufc)::value;
 #pragma unroll
     for (int gi = 0; gi < GPW; ++gi) {
       const int kg = (gi * WK + wk) * 8;
       f32x4 af[TM], bf[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *(const f32x4*)(Ab + i * 32 * P + kg);
+      for (int i = 0; i < TM; ++i) af[i] = *(const f32x4*)(a_fr + (BUF * BM + i * 32) * P + kg);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bf[j] = *(const f32x4*)(Bb + j * 32 * P + kg);
+      for (int j = 0; j < TN; ++j) bf[j] = *(const f32x4*)(b_fr + (BUF * BN + j * 32) * P + kg);
 #pragma unroll
       for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -142,21 +154,22 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
     }
   };
-  // iteration c: start the loads of chunk c+2 into set S, run the MFMAs of chunk c from
-  // LDS buffer c&1, then move chunk c+1 (set S^1, loaded one iteration ago) into the
-  // other LDS buffer; one barrier per chunk.
+  // iteration c (parity S): start the loads of chunk c+2 into register set S, run the
+  // MFMAs of chunk c from LDS buffer S, then move chunk c+1 (set S^1, loaded one
+  // iteration ago) into LDS buffer S^1; one barrier per chunk.
   auto step = [&](auto set, int c) {
     constexpr int S = decltype(set)::value;
-    if (c + 2 < nchunks) gload(set, c + 2);
-    compute(c & 1);
-    if (c + 1 < nchunks) sstore(std::integral_constant<int, S ^ 1>{}, (c + 1) & 1);
+    using Other = std::integral_constant<int, S ^ 1>;
+    if (c + 2 < nchunks) gload(set);
+    compute(set);
+    if (c + 1 < nchunks) sstore(Other{}, Other{});
     __syncthreads();
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
-  gload(I0{}, 0);
-  sstore(I0{}, 0);
-  if (nchunks > 1) gload(I1{}, 1);
+  gload(I0{});
+  sstore(I0{}, I0{});
+  if (nchunks > 1) gload(I1{});
   __syncthreads();
   for (int c = 0; c < nchunks; c += 2) {
     step(I0{}, c);
