@@ -15,6 +15,12 @@ import numpy as np
 
 MI355X_PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2500.0}
 
+# HBM bytes per launch of the standard workload (B=1024), from the two rocprofv3 --pmc runs
+# recorded in profiles/policy_step_standard_hbm_traffic.md: (FETCH_SIZE x 2.000 + WRITE_SIZE
+# x 1.000) KiB, the factors being what the same counters read for a 256 MiB plain copy.
+MEASURED_HBM_KIB = {"standard": {"conv1": 30840 + 67456, "conv2": 62688 + 25088, "conv3": 25698 + 9216,
+                                 "fc": 46198 + 2048, "gru": 53600 + 2048, "heads": 2264 + 24}}
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -87,8 +93,10 @@ def main():
               for (name, fl), ms in zip(ops, op_ms)}
     dom_tflops = ops[i_dom][1] * B / (op_ms[i_dom] * 1e-3) / 1e12
     whole_tflops = pol.flops_per_row() * B / (ms_per_step * 1e-3) / 1e12
+    kib = MEASURED_HBM_KIB.get(net["name"], {}).get(ops[i_dom][0]) if B == wl.CONFIGS[args.config]["B"] else None
     roofline = {"bound": "mfma", "kernel": ops[i_dom][0], "achieved": round(dom_tflops, 3), "peak": peak,
-                "unit": "TFLOP/s", "frac": round(dom_tflops / peak, 5), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(dom_tflops / peak, 5),
+                "traffic": kib * 1024 if kib is not None else None,
                 "avg_launch_ms": round(float(op_ms[i_dom]), 5),
                 "whole_step": {"achieved": round(whole_tflops, 3), "frac": round(whole_tflops / peak, 5)},
                 "per_kernel": per_op}
