@@ -9,16 +9,17 @@
 // filter row (no padding).  The FC layer is the case H = W = ksize = 1.  Wt is
 // [N][K] with K contiguous in the same order.
 //
-// Tiling: a 256-thread workgroup owns a BM x BN output tile, K is walked in chunks
-// of 32 staged through LDS (double buffered, one barrier per chunk, the next
-// chunk's global loads in flight during the MFMAs).  LDS rows have a pitch of 36
-// floats so that both the 16-byte tile stores and the 16-byte fragment loads are
-// bank-conflict free.  v_mfma_f32_32x32x2_f32 takes its K index from the lane half
+// Tiling: a workgroup of four wavefronts owns a BM x BN output tile, K is walked in
+// chunks of 32 or 64 staged through LDS (double buffered, one barrier per chunk, global
+// loads two chunks ahead of the MFMAs).  LDS rows have a pitch of BK + 4 floats so that
+// both the 16-byte tile stores and the 16-byte fragment loads are bank-conflict free.  v_mfma_f32_32x32x2_f32 takes its K index from the lane half
 // h = lane/32; a lane loads four consecutive k (one ds_read_b128) at 8g + 4h, and
 // instruction t of the group's four uses element t, for both operands alike.
 // The four wavefronts are arranged WM x WN x WK: WK > 1 splits the K groups of
 // every chunk between waves (for GEMMs with few output tiles) and the partial
 // tiles are summed through LDS in a fixed order.
+#include <stdlib.h>
+
 #include <type_traits>
 
 #include "sf_internal.h"
@@ -48,12 +49,12 @@ struct GemmArgs {
 // TAG only gives each layer of a network its own kernel symbol, so that a profiler's
 // per-kernel statistics do not merge layers that share a tile configuration.
 template <int BM, int BN, int BK, int WM, int WN, int WK, int TAG>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
-  static_assert(WM * WN * WK == 4, "four wavefronts");
+__global__ __launch_bounds__(64 * WM * WN * WK) void gemm_mfma_kernel(GemmArgs g) {
+  constexpr int NT = 64 * WM * WN * WK;      // threads: one to four wavefronts
   constexpr int P = BK + 4;                  // LDS row pitch in floats
   constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
   constexpr int TPR = BK / 4;                // threads (16-byte loads) per tile row
-  constexpr int RPP = 256 / TPR;             // tile rows covered by one pass of the workgroup
+  constexpr int RPP = NT / TPR;              // tile rows covered by one pass of the workgroup
   constexpr int RA = BM / RPP, RB = BN / RPP;
   constexpr int NG = BK / 8;                 // K groups per chunk
   constexpr int GPW = NG / WK;               // K groups per wave per chunk
@@ -238,7 +239,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
   }
   const int n_tiles = ((g.M + BM - 1) / BM) * (g.N / BN);
   const int per_xcd = (n_tiles + 7) / 8;
-  kern<<<per_xcd * 8, 256, lds, st>>>(g);
+  kern<<<per_xcd * 8, 64 * WM * WN * WK, lds, st>>>(g);
   return hipGetLastError();
 }
 

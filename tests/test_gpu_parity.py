@@ -279,3 +279,48 @@ def test_sampler_distribution_on_gpu(torch_cuda, ref):
         dof = len(p) - 1
         assert chi2 < dof + 5 * np.sqrt(2 * dof) + 5
     pol.close()
+
+
+def _random_net(rng, dtype):
+    """A random small plain-stack network; channel counts are drawn so that both the
+    MFMA kernels (multiples of 32 / 8) and the shape-agnostic ones are exercised."""
+    chans = [int(rng.choice([8, 16, 24, 32, 64])) for _ in range(int(rng.integers(1, 4)))]
+    convs, h, w = [], int(rng.integers(20, 41)), int(rng.integers(6, 13)) * 4
+    H, W = h, w
+    first = True
+    for co in chans:
+        if first and rng.random() < 0.6:
+            k, s, p, co = 8, 4, 0, 32          # the byte-input MFMA kernel's shape
+        else:
+            k = int(rng.choice([1, 2, 3, 4])); s = int(rng.choice([1, 2])); p = int(rng.choice([0, 0, 1]))
+        if (h + 2 * p - k) // s + 1 < 1 or (w + 2 * p - k) // s + 1 < 1 or h + 2 * p < k or w + 2 * p < k:
+            break
+        convs.append((co, k, s, p))
+        h, w = (h + 2 * p - k) // s + 1, (w + 2 * p - k) // s + 1
+        first = False
+    if not convs:
+        convs = [(32, 8, 4, 0)]
+    return dict(name="rand", B=int(rng.integers(1, 90)), obs=(int(rng.choice([1, 3, 4])), H, W), encoder="conv",
+                convs=convs, fc=int(rng.choice([32, 48, 64, 128])), rnn=int(rng.choice([32, 40, 64, 96])),
+                heads=[int(a) for a in rng.integers(1, 12, size=int(rng.integers(1, 5)))], dtype=dtype,
+                p_done=0.3, steps=1, obs_sub=float(rng.choice([0.0, 127.5])), obs_mul=wl.OBS_MUL, index=0)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_network_shapes(torch_cuda, ref, seed):
+    """Randomly drawn network descriptions, every element against the oracle."""
+    torch = torch_cuda
+    rng = np.random.default_rng(500 + seed)
+    net = _random_net(rng, "bf16" if seed % 3 == 2 else "fp32")
+    w = wl.weights(net, seed=600 + seed)
+    from paper_2006_11751_amd import binding
+    pol = binding.Policy(net, w)
+    B = net["B"]
+    obs = wl.observations(net, 0, B, seed=700 + seed)
+    h_in = wl.initial_state(net, B, seed=800 + seed)
+    done = wl.done_mask(net, 0, B, seed=900 + seed)
+    g = _gpu_step(torch, pol, obs, h_in, done, 11, seed)
+    o = ref.policy_step(net, w, obs, h_in, done, 11, seed)
+    stats = parity.check_against_oracle(net, g, o, ref, 11, seed)
+    print(net["obs"], net["convs"], net["fc"], net["rnn"], net["heads"], net["dtype"], B, stats)
+    pol.close()
