@@ -295,6 +295,13 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
           L.wbf = bld.upload(wt);
           L.bbf = bld.upload(bb);
           L.impl = CONV_BF16;
+          if (cfg->encoder == SF_ENCODER_RESNET && conv3x3_patch_supported(C, cout, k, s, pad) &&
+              !getenv("SF_NO_PATCH_CONV")) {
+            conv3x3_patch_pack(w->conv_w[ti], w->conv_b[ti], cout, C, p->act_f16, wt, bb);
+            L.wbf = bld.upload(wt);
+            L.bbf = bld.upload(bb);
+            L.impl = CONV3X3_PATCH;
+          }
           // Residual encoder: the stream x (pool outputs, block outputs) stays fp32 so that
           // its rounding does not accumulate over the blocks; branch intermediates and
           // stage-convolution outputs are bf16.  Plain stack: everything bf16.
@@ -319,6 +326,14 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
                       bld.q(w->conv_w[ti][(((size_t)o * C + c2) * 3 + a) * 3 + b2]);
           L.w_cpqo = bld.upload(t);
           L.impl = CONV3X3_U8_BF16;
+          if (conv3x3_stem_supported(C, cout) && !getenv("SF_NO_PATCH_CONV")) {
+            std::vector<uint16_t> wt;
+            std::vector<float> bb;
+            conv3x3_stem_pack(w->conv_w[ti], w->conv_b[ti], cout, p->act_f16, wt, bb);
+            L.wbf = bld.upload(wt);
+            L.bbf = bld.upload(bb);
+            L.impl = CONV3X3_STEM;
+          }
         }
       }
       if (in_buf >= 0 && allow_mfma && !relu_in && resid_buf < 0 &&
@@ -588,6 +603,15 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
                                        L.W, L.cin, L.k, L.s, L.pad, L.Ho, L.Wo, L.cout, L.Kpad,
                                        L.relu_in, L.relu_out, L.in_f32, 1, L.out_f32, p->act_f16,
                                        op.conv + 1, st));
+            break;
+          case CONV3X3_PATCH:
+            SF_LAUNCH(launch_conv3x3_patch(in, L.wbf, L.bbf, buf(op.resid_buf), buf(op.out_buf), B, L.H,
+                                           L.W, L.cin, L.cout, L.in_f32, L.relu_in, L.relu_out,
+                                           L.out_f32, p->act_f16, st));
+            break;
+          case CONV3X3_STEM:
+            SF_LAUNCH(launch_conv3x3_stem(obs, L.wbf, L.bbf, buf(op.out_buf), B, L.H, L.W, L.cout,
+                                          c.obs_sub, c.obs_mul, p->act_f16, st));
             break;
           case CONV3X3_U8_BF16:
             SF_LAUNCH(launch_conv3x3_u8_bf16(B, L.cin, L.H, L.W, L.cout, obs, L.w_cpqo, L.bias,

@@ -36,7 +36,9 @@ struct ConvLayer {
 enum ConvImpl {
   CONV_GENERIC = 0, CONV1_U8_MFMA = 1, CONV_GEMM_MFMA = 2, CONV1_U8_I8 = 3,
   CONV_BF16 = 4,        // bf16 MFMA implicit GEMM, bf16 activations
-  CONV3X3_U8_BF16 = 5   // first convolution of the residual encoder, bytes in, bf16 out
+  CONV3X3_U8_BF16 = 5,  // first convolution of the residual encoder, bytes in, 16-bit out (VALU)
+  CONV3X3_PATCH = 6,    // 3x3/s1/p1 on the 16-bit MFMA with an LDS-staged input patch
+  CONV3X3_STEM = 7      // first convolution of the residual encoder on the 16-bit MFMA
 };
 
 // One kernel launch of the step, fixed at create time.
@@ -140,6 +142,19 @@ bool conv3x3_u8_bf16_supported(int cout);
 hipError_t launch_conv3x3_u8_bf16(int B, int Cin, int H, int W, int cout, const uint8_t* obs,
                                   const float* w_cpqo, const float* bias, void* out, float obs_sub,
                                   float obs_mul, int f16, hipStream_t st);
+bool conv3x3_patch_supported(int cin, int cout, int k, int stride, int pad);
+void conv3x3_patch_pack(const float* w, const float* bias, int cout, int cin, bool f16,
+                        std::vector<uint16_t>& wpk, std::vector<float>& b32);
+hipError_t launch_conv3x3_patch(const void* in, const uint16_t* wpk, const float* bias32,
+                                const float* resid, void* out, int B, int H, int W, int cin,
+                                int cout, int in_f32, int relu_in, int relu_out, int out_f32,
+                                int f16, hipStream_t st);
+bool conv3x3_stem_supported(int cin, int cout);
+void conv3x3_stem_pack(const float* w, const float* bias, int cout, bool f16,
+                       std::vector<uint16_t>& wpk, std::vector<float>& b32);
+hipError_t launch_conv3x3_stem(const uint8_t* obs, const uint16_t* wpk, const float* bias32, void* out,
+                               int B, int H, int W, int cout, float obs_sub, float obs_mul, int f16,
+                               hipStream_t st);
 bool gru_mfma_supported(int I, int H);
 hipError_t launch_gru_mfma(int B, int I, int H, const float* x, const float* h_in,
                            const uint8_t* done, const float* w_ih, const float* w_hh,
