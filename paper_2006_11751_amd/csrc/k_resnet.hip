@@ -43,6 +43,11 @@ __device__ inline unsigned to_h(float f) {
   unsigned u = __float_as_uint(f);
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
+template <bool kF16>
+__device__ inline float from_h(unsigned h) {
+  if (kF16) return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+  return __uint_as_float(h << 16);
+}
 __device__ inline unsigned relu_h2(unsigned w) {
   unsigned neg = (w >> 15) & 0x00010001u;
   return w & ~(neg * 0xFFFFu);
@@ -60,11 +65,11 @@ struct PatchArgs {
   const void* in;      // fp32 or 16-bit [B][H][W][CIN]
   const u32x4* wpk;    // [9][CIN/16][64] A operands
   const float* bias;   // [32]
-  const float* resid;  // fp32 [B][H][W][N] or null
+  const void* resid;   // fp32 or 16-bit [B][H][W][N], or null
   void* out;           // 16-bit or fp32 [B][H][W][N]
   int B, H, W, N;
   int tiles_x, tiles_y;
-  int in_f32, relu_in, relu_out, out_f32;
+  int in_f32, relu_in, relu_out, out_f32, resid_f32;
 };
 
 // TWW: tile width in pixels (16 or 32); a wave's 32-pixel MFMA tile is 32/TWW rows
@@ -154,9 +159,17 @@ __global__ __launch_bounds__(256) void conv3x3_patch_kernel(PatchArgs g) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) r[u] = acc[4 * q4 + u] + g.bias[ch + u];
         if (g.resid) {
-          const f32x4 rv = *(const f32x4*)(g.resid + o + ch);
+          if (g.resid_f32) {
+            const f32x4 rv = *(const f32x4*)((const float*)g.resid + o + ch);
 #pragma unroll
-          for (int u = 0; u < 4; ++u) r[u] += rv[u];
+            for (int u = 0; u < 4; ++u) r[u] += rv[u];
+          } else {
+            const u32x2 rv = *(const u32x2*)((const uint16_t*)g.resid + o + ch);
+            r[0] += from_h<kF16>(rv[0] & 0xFFFFu);
+            r[1] += from_h<kF16>(rv[0] >> 16);
+            r[2] += from_h<kF16>(rv[1] & 0xFFFFu);
+            r[3] += from_h<kF16>(rv[1] >> 16);
+          }
         }
         if (g.relu_out) {
 #pragma unroll
@@ -332,15 +345,16 @@ void conv3x3_patch_pack(const float* w, const float* bias, int cout, int cin, bo
 }
 
 hipError_t launch_conv3x3_patch(const void* in, const uint16_t* wpk, const float* bias32,
-                                const float* resid, void* out, int B, int H, int W, int cin,
-                                int cout, int in_f32, int relu_in, int relu_out, int out_f32,
-                                int f16, hipStream_t st) {
+                                const void* resid, int resid_f32, void* out, int B, int H, int W,
+                                int cin, int cout, int in_f32, int relu_in, int relu_out,
+                                int out_f32, int f16, hipStream_t st) {
   if ((long long)B * H * W == 0) return hipSuccess;
   PatchArgs g;
   g.in = in; g.wpk = (const u32x4*)wpk; g.bias = bias32; g.resid = resid; g.out = out;
   g.B = B; g.H = H; g.W = W; g.N = cout;
   g.tiles_x = g.tiles_y = 0;
   g.in_f32 = in_f32; g.relu_in = relu_in; g.relu_out = relu_out; g.out_f32 = out_f32;
+  g.resid_f32 = resid_f32;
   const bool wide = W > 16;            // 32-pixel-wide tiles unless the image is narrow
   const bool tall = H % 12 == 0 && wide;  // three row tiles per wave when they divide the height
   if (cin == 16) {

@@ -268,6 +268,10 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
   // the activations alone exceeds the 2e-2 tolerance in the tails, so its 16-bit
   // activations are fp16 (the weights stay bf16 values, exactly representable in fp16).
   p->act_f16 = p->bf16_path && cfg->encoder == SF_ENCODER_RESNET && !getenv("SF_ACT_BF16");
+  // With bf16 activations the residual stream is kept in fp32 so that its rounding does not
+  // accumulate over the blocks; with fp16 activations that is not needed.
+  p->stream_f32 = p->bf16_path && cfg->encoder == SF_ENCODER_RESNET &&
+                  (!p->act_f16 || getenv("SF_STREAM_F32"));
 
   // ---- encoder plan ----
   size_t act_elems = 0;
@@ -305,7 +309,7 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
           // Residual encoder: the stream x (pool outputs, block outputs) stays fp32 so that
           // its rounding does not accumulate over the blocks; branch intermediates and
           // stage-convolution outputs are bf16.  Plain stack: everything bf16.
-          const bool resnet = cfg->encoder == SF_ENCODER_RESNET;
+          const bool resnet = p->stream_f32;
           L.in_f32 = resnet && !(relu_in == 0 && resid_buf >= 0);  // conv_b reads the bf16 branch
           L.out_f32 = resnet && resid_buf >= 0;
         } else if (cfg->encoder == SF_ENCODER_CONV) {
@@ -394,19 +398,43 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
       // buffer roles rotate: x holds the stage state, t and u are scratch
       int x = 0, t = 1, u = 2;
       int in_buf = -1;
+      // With fp16 activations throughout, a stage convolution and its max-pool run as one
+      // kernel, and so does each residual block.
+      const bool fuse = p->bf16_path && p->act_f16 && !p->stream_f32 && !getenv("SF_NO_PATCH_CONV") &&
+                        !getenv("SF_NO_FUSED_RESNET");
       for (int s = 0; s < cfg->n_stage; ++s) {
-        snprintf(name, sizeof(name), "stage%d.conv", s + 1);
-        add_conv(name, cfg->stage_ch[s], 3, 1, 1, 0, 0, in_buf, t, -1);
-        snprintf(name, sizeof(name), "stage%d.pool", s + 1);
-        p->ops.push_back(Op{OP_POOL, name, 0, -1, t, x, -1, C, H, W});
-        H = (H - 1) / 2 + 1;
-        W = (W - 1) / 2 + 1;
+        if (fuse && conv3x3_pool_supported(C, cfg->stage_ch[s], W)) {
+          const int Hin = H, Win = W;
+          snprintf(name, sizeof(name), "stage%d.conv_pool", s + 1);
+          add_conv(name, cfg->stage_ch[s], 3, 1, 1, 0, 0, in_buf, x, -1);
+          p->convs.back().impl = CONV3X3_POOL;
+          H = (Hin - 1) / 2 + 1;
+          W = (Win - 1) / 2 + 1;
+        } else {
+          snprintf(name, sizeof(name), "stage%d.conv", s + 1);
+          add_conv(name, cfg->stage_ch[s], 3, 1, 1, 0, 0, in_buf, t, -1);
+          snprintf(name, sizeof(name), "stage%d.pool", s + 1);
+          p->ops.push_back(Op{OP_POOL, name, 0, -1, t, x, -1, C, H, W});
+          H = (H - 1) / 2 + 1;
+          W = (W - 1) / 2 + 1;
+        }
         for (int b = 0; b < cfg->blocks_per_stage; ++b) {
           bool last = (s == cfg->n_stage - 1) && (b == cfg->blocks_per_stage - 1);
           snprintf(name, sizeof(name), "stage%d.block%d.conv_a", s + 1, b + 1);
           add_conv(name, cfg->stage_ch[s], 3, 1, 1, 1, 1, x, t, -1);
           snprintf(name, sizeof(name), "stage%d.block%d.conv_b", s + 1, b + 1);
           add_conv(name, cfg->stage_ch[s], 3, 1, 1, 0, last ? 1 : 0, t, u, x);
+          if (fuse && res_block_supported(cfg->stage_ch[s])) {
+            // merge the two operations: x -> u in one launch
+            const Op ob = p->ops.back();
+            p->ops.pop_back();
+            Op& oa = p->ops.back();
+            snprintf(name, sizeof(name), "stage%d.block%d", s + 1, b + 1);
+            oa.name = name;
+            oa.flops_per_row += ob.flops_per_row;
+            oa.out_buf = u;
+            p->convs[oa.conv].impl = RES_BLOCK;
+          }
           int tmp = x;
           x = u;
           u = tmp;
@@ -601,14 +629,24 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
           case CONV_BF16:
             SF_LAUNCH(launch_conv_bf16(in, L.wbf, L.bbf, buf(op.resid_buf), buf(op.out_buf), B, L.H,
                                        L.W, L.cin, L.k, L.s, L.pad, L.Ho, L.Wo, L.cout, L.Kpad,
-                                       L.relu_in, L.relu_out, L.in_f32, 1, L.out_f32, p->act_f16,
-                                       op.conv + 1, st));
+                                       L.relu_in, L.relu_out, L.in_f32, p->stream_f32, L.out_f32,
+                                       p->act_f16, op.conv + 1, st));
             break;
           case CONV3X3_PATCH:
-            SF_LAUNCH(launch_conv3x3_patch(in, L.wbf, L.bbf, buf(op.resid_buf), buf(op.out_buf), B, L.H,
-                                           L.W, L.cin, L.cout, L.in_f32, L.relu_in, L.relu_out,
+            SF_LAUNCH(launch_conv3x3_patch(in, L.wbf, L.bbf, buf(op.resid_buf), p->stream_f32,
+                                           buf(op.out_buf), B, L.H, L.W, L.cin, L.cout, L.in_f32, L.relu_in, L.relu_out,
                                            L.out_f32, p->act_f16, st));
             break;
+          case CONV3X3_POOL:
+            SF_LAUNCH(launch_conv3x3_pool(in, L.wbf, L.bbf, buf(op.out_buf), B, L.H, L.W, L.cin, L.cout,
+                                          c.obs_sub, c.obs_mul, st));
+            break;
+          case RES_BLOCK: {
+            const ConvLayer& Lb = p->convs[op.conv + 1];
+            SF_LAUNCH(launch_res_block(in, L.wbf, L.bbf, Lb.wbf, Lb.bbf, buf(op.out_buf), B, L.H, L.W,
+                                       L.cin, Lb.relu_out, st));
+            break;
+          }
           case CONV3X3_STEM:
             SF_LAUNCH(launch_conv3x3_stem(obs, L.wbf, L.bbf, buf(op.out_buf), B, L.H, L.W, L.cout,
                                           c.obs_sub, c.obs_mul, p->act_f16, st));
@@ -625,8 +663,8 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
       }
       case OP_POOL:
         if (p->bf16_path)
-          SF_LAUNCH(launch_maxpool_bf16(B, op.C, op.H, op.W, buf(op.in_buf), buf(op.out_buf), 1,
-                                        p->act_f16, st));
+          SF_LAUNCH(launch_maxpool_bf16(B, op.C, op.H, op.W, buf(op.in_buf), buf(op.out_buf),
+                                        p->stream_f32, p->act_f16, st));
         else
           SF_LAUNCH(launch_maxpool3x3s2p1(B, op.C, op.H, op.W, buf(op.in_buf), buf(op.out_buf), st));
         break;
@@ -634,7 +672,7 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
         if (p->fc_wbf)
           SF_LAUNCH(launch_conv_bf16(buf(op.in_buf), p->fc_wbf, p->fc_bbf, nullptr, p->fc_out, B, 1, 1,
                                      p->flat, 1, 1, 0, 1, 1, c.fc_dim, p->fc_Kpad, 0, 1,
-                                     c.encoder == SF_ENCODER_RESNET, 0, 1, p->act_f16, 0, st));
+                                     p->stream_f32, 0, 1, p->act_f16, 0, st));
         else if (p->fc_wt)
           SF_LAUNCH(launch_gemm_mfma(buf(op.in_buf), p->fc_wt, p->fc_b, p->fc_out, B, 1, 1, p->flat, 1,
                                      1, 1, 1, c.fc_dim, 1, p->fc_tile, 0, st));

@@ -38,7 +38,9 @@ enum ConvImpl {
   CONV_BF16 = 4,        // bf16 MFMA implicit GEMM, bf16 activations
   CONV3X3_U8_BF16 = 5,  // first convolution of the residual encoder, bytes in, 16-bit out (VALU)
   CONV3X3_PATCH = 6,    // 3x3/s1/p1 on the 16-bit MFMA with an LDS-staged input patch
-  CONV3X3_STEM = 7      // first convolution of the residual encoder on the 16-bit MFMA
+  CONV3X3_STEM = 7,     // first convolution of the residual encoder on the 16-bit MFMA
+  CONV3X3_POOL = 8,     // stage convolution fused with the max-pool behind it
+  RES_BLOCK = 9         // a whole residual block (this layer and the next) in one kernel
 };
 
 // One kernel launch of the step, fixed at create time.
@@ -68,6 +70,7 @@ struct Policy {
   int fc_Kpad;
   bool bf16_path;     // encoder and FC run on the 16-bit MFMA kernels with 16-bit activations
   bool act_f16;       // ... whose activation element type is fp16 instead of bf16
+  bool stream_f32;    // residual encoder: the residual stream is stored in fp32
   int fc_tile;
   float* gru_wih_t;   // dev [fc_dim][3H]
   float* gru_whh_t;   // dev [H][3H]
@@ -146,9 +149,17 @@ bool conv3x3_patch_supported(int cin, int cout, int k, int stride, int pad);
 void conv3x3_patch_pack(const float* w, const float* bias, int cout, int cin, bool f16,
                         std::vector<uint16_t>& wpk, std::vector<float>& b32);
 hipError_t launch_conv3x3_patch(const void* in, const uint16_t* wpk, const float* bias32,
-                                const float* resid, void* out, int B, int H, int W, int cin,
-                                int cout, int in_f32, int relu_in, int relu_out, int out_f32,
-                                int f16, hipStream_t st);
+                                const void* resid, int resid_f32, void* out, int B, int H, int W,
+                                int cin, int cout, int in_f32, int relu_in, int relu_out,
+                                int out_f32, int f16, hipStream_t st);
+bool conv3x3_pool_supported(int cin, int cout, int W);
+hipError_t launch_conv3x3_pool(const void* in, const uint16_t* wpk, const float* bias32, void* out,
+                               int B, int H, int W, int cin, int cout, float obs_sub, float obs_mul,
+                               hipStream_t st);
+bool res_block_supported(int c);
+hipError_t launch_res_block(const void* x, const uint16_t* wa, const float* ba, const uint16_t* wb,
+                            const float* bb, void* out, int B, int H, int W, int c, int relu_out,
+                            hipStream_t st);
 bool conv3x3_stem_supported(int cin, int cout);
 void conv3x3_stem_pack(const float* w, const float* bias, int cout, bool f16,
                        std::vector<uint16_t>& wpk, std::vector<float>& b32);

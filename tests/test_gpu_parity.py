@@ -63,10 +63,15 @@ def test_tiny_four_steps_free_running(torch_cuda, ref):
 RESNET_BF16_SMALL = dict(name="resnet_bf16_small", B=7, obs=(3, 20, 28), encoder="resnet", stages=[16, 32, 32],
                          blocks_per_stage=2, fc=64, rnn=32, heads=[15], dtype="bf16", p_done=0.3, steps=1,
                          obs_sub=0.0, obs_mul=wl.OBS_MUL, index=4)
+# several tiles of the fused residual-encoder kernels in both directions, ragged at the edges
+RESNET_BF16_MID = dict(RESNET_BF16_SMALL, name="resnet_bf16_mid", B=3, obs=(3, 50, 76))
+# width not a multiple of 4 (byte planes not dword-aligned), channel counts 32 -> 16 -> 32
+RESNET_BF16_MIX = dict(RESNET_BF16_SMALL, name="resnet_bf16_mix", B=4, obs=(3, 30, 42), stages=[32, 16, 32])
 STD_BF16_SMALL = wl.network(2, B=37, name="standard_bf16_small")
 
 
-@pytest.mark.parametrize("net", [SMALL_RESNET, ODD_NET, RESNET_BF16_SMALL, STD_BF16_SMALL],
+@pytest.mark.parametrize("net", [SMALL_RESNET, ODD_NET, RESNET_BF16_SMALL, RESNET_BF16_MID, RESNET_BF16_MIX,
+                                 STD_BF16_SMALL],
                          ids=lambda n: n["name"])
 def test_small_networks_all_elements(torch_cuda, ref, net):
     torch = torch_cuda
