@@ -54,6 +54,15 @@ __device__ inline f32x16 mfma_f16(u32x4 a, u32x4 b, f32x16 c) {
                                                 __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
+// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by block id.  This
+// maps block id -> tile index so that each XCD works through one contiguous run of tiles:
+// neighbouring tiles of a frame, which share halo pixels, then meet in the same L2.
+__device__ inline int xcd_contiguous_tile(int bid, int nblocks) {
+  const int per = nblocks >> 3, rem = nblocks & 7;
+  const int xcd = bid & 7, idx = bid >> 3;
+  return xcd * per + min(xcd, rem) + idx;
+}
+
 // Stages the PH x PW pixel patch whose pixel (0, 0) is image pixel (ya, xa) of an fp16
 // channels-last image; pixels outside the image are zero.  All of a thread's loads are
 // issued before the first of them is consumed.
@@ -177,7 +186,7 @@ __global__ __launch_bounds__(64 * NW) void conv3x3_pool_kernel(ConvPoolArgs g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 31, lh = lane >> 5;
-  int t = blockIdx.x;
+  int t = xcd_contiguous_tile(blockIdx.x, gridDim.x);
   const int tx = t % g.tiles_x;
   t /= g.tiles_x;
   const int ty = t % g.tiles_y;
@@ -363,7 +372,7 @@ __global__ __launch_bounds__(64 * NW) void res_block_kernel(BlockArgs g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 31, lh = lane >> 5;
-  int t = blockIdx.x;
+  int t = xcd_contiguous_tile(blockIdx.x, gridDim.x);
   const int tx = t % g.tiles_x;
   t /= g.tiles_x;
   const int ty = t % g.tiles_y;

@@ -406,8 +406,14 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
         if (fuse && conv3x3_pool_supported(C, cfg->stage_ch[s], W)) {
           const int Hin = H, Win = W;
           snprintf(name, sizeof(name), "stage%d.conv_pool", s + 1);
-          add_conv(name, cfg->stage_ch[s], 3, 1, 1, 0, 0, in_buf, x, -1);
+          // in_buf is the previous stage's x: the pooled result goes to t, which becomes x
+          add_conv(name, cfg->stage_ch[s], 3, 1, 1, 0, 0, in_buf, t, -1);
           p->convs.back().impl = CONV3X3_POOL;
+          {
+            const int tmp = x;
+            x = t;
+            t = tmp;
+          }
           H = (Hin - 1) / 2 + 1;
           W = (Win - 1) / 2 + 1;
         } else {
