@@ -67,6 +67,7 @@ def lib():
         L.ref_conv2d.restype = C.c_int
         L.ref_flat_size.restype = C.c_int64
         L.ref_policy_step.restype = C.c_int
+        L.ref_policy_step_indexed.restype = C.c_int
         L.ref_num_threads.restype = C.c_int
         L.ref_bits_to_uniform.restype = C.c_float
         L.ref_bits_to_uniform.argtypes = [C.c_uint32]
@@ -161,6 +162,34 @@ def policy_step(net, w, obs, h_in, done, seed, step, want_logits=True, want_marg
         _p(out["logits"]) if want_logits else None, _p(out["margin"]) if want_margin else None)
     if rc != 0:
         raise ValueError("ref_policy_step rejected the network description")
+    del keep
+    return out
+
+
+def policy_step_indexed(net, w, obs, h_table, env_ids, done, seed, step):
+    """One step on rows that name environments of a state table; h_table is updated in place."""
+    L = lib()
+    rn = make_net(net)
+    rp, keep = make_params(w)
+    B = int(obs.shape[0])
+    obs = np.ascontiguousarray(obs, dtype=np.uint8)
+    assert h_table.dtype == np.float32 and h_table.flags["C_CONTIGUOUS"]
+    env_ids = np.ascontiguousarray(env_ids, dtype=np.int32)
+    done = np.ascontiguousarray(done, dtype=np.uint8)
+    nh, sumA = len(net["heads"]), int(sum(net["heads"]))
+    out = {
+        "actions": np.zeros((B, nh), np.int32), "logp": np.zeros(B, np.float32),
+        "value": np.zeros(B, np.float32), "logits": np.zeros((B, sumA), np.float32),
+        "margin": np.zeros((B, nh), np.float32),
+    }
+    rc = L.ref_policy_step_indexed(
+        C.byref(rn), C.byref(rp), C.c_int32(B), _p(obs), _p(h_table), C.c_int32(h_table.shape[0]),
+        _p(env_ids), _p(done), C.c_uint64(seed), C.c_uint64(step), _p(out["actions"]),
+        _p(out["logp"]), _p(out["value"]), _p(out["logits"]), _p(out["margin"]))
+    if rc == -2:
+        raise ValueError("env_ids out of range or not distinct")
+    if rc != 0:
+        raise ValueError("ref_policy_step_indexed rejected the network description")
     del keep
     return out
 

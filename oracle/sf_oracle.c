@@ -281,10 +281,12 @@ int ref_num_threads(void) {
 #endif
 }
 
-static void step_row(const ref_net* net, const ref_params* p, int32_t b, const uint8_t* obs,
-                     const float* h_in, const uint8_t* done, uint64_t seed, uint64_t step,
-                     int32_t* actions, float* logp, float* value, float* h_out, float* logits_opt,
-                     float* margin_opt) {
+/* Row b of the batch.  env is the sampler's counter word for this row; h_in_row and
+ * h_out_row are this row's incoming and outgoing state (rnn_dim floats each). */
+static void step_row(const ref_net* net, const ref_params* p, int32_t b, uint32_t env,
+                     const uint8_t* obs, const float* h_in_row, const uint8_t* done, uint64_t seed,
+                     uint64_t step, int32_t* actions, float* logp, float* value, float* h_out_row,
+                     float* logits_opt, float* margin_opt) {
   const int C = net->obs_c, H = net->obs_h, W = net->obs_w, Hd = net->rnn_dim;
   size_t n_obs = (size_t)C * H * W;
 
@@ -328,9 +330,9 @@ static void step_row(const ref_net* net, const ref_params* p, int32_t b, const u
   /* recurrent core with the episode-boundary reset applied to the INCOMING state */
   double* h = (double*)malloc(sizeof(double) * (size_t)Hd);
   double* hn = (double*)malloc(sizeof(double) * (size_t)Hd);
-  for (int j = 0; j < Hd; ++j) h[j] = done[b] ? 0.0 : (double)h_in[(size_t)b * Hd + j];
+  for (int j = 0; j < Hd; ++j) h[j] = done[b] ? 0.0 : (double)h_in_row[j];
   ref_gru_cell(f, net->fc_dim, h, Hd, p->gru_w_ih, p->gru_w_hh, p->gru_b_ih, p->gru_b_hh, hn);
-  for (int j = 0; j < Hd; ++j) h_out[(size_t)b * Hd + j] = (float)hn[j];
+  for (int j = 0; j < Hd; ++j) h_out_row[j] = (float)hn[j];
 
   /* heads: action logits (all heads concatenated) and the baseline */
   int sumA = 0;
@@ -351,7 +353,7 @@ static void step_row(const ref_net* net, const ref_params* p, int32_t b, const u
     int32_t a;
     double lp;
     float mg;
-    ref_head_sample(lf + off, net->head_sizes[k], seed, (uint32_t)b, step, (uint32_t)k, NULL, &a,
+    ref_head_sample(lf + off, net->head_sizes[k], seed, env, step, (uint32_t)k, NULL, &a,
                     &lp, &mg);
     actions[(size_t)b * net->n_heads + k] = a;
     if (margin_opt) margin_opt[(size_t)b * net->n_heads + k] = mg;
@@ -368,20 +370,55 @@ static void step_row(const ref_net* net, const ref_params* p, int32_t b, const u
   free(lf);
 }
 
-int ref_policy_step(const ref_net* net, const ref_params* p, int32_t B, const uint8_t* obs,
-                    const float* h_in, const uint8_t* done, uint64_t seed, uint64_t step,
-                    int32_t* actions, float* logp, float* value, float* h_out,
-                    float* logits_opt, float* margin_opt) {
+static int check_net(const ref_net* net) {
   int C, H, W;
   if (encoder_shape(net, &C, &H, &W)) return -1;
   if (net->fc_dim < 1 || net->rnn_dim < 1 || net->n_heads < 1 || net->n_heads > REF_MAX_HEADS)
     return -1;
   for (int k = 0; k < net->n_heads; ++k)
     if (net->head_sizes[k] < 1) return -1;
-  if (B < 0) return -1;
+  return 0;
+}
+
+int ref_policy_step(const ref_net* net, const ref_params* p, int32_t B, const uint8_t* obs,
+                    const float* h_in, const uint8_t* done, uint64_t seed, uint64_t step,
+                    int32_t* actions, float* logp, float* value, float* h_out,
+                    float* logits_opt, float* margin_opt) {
+  if (check_net(net) || B < 0) return -1;
+  const size_t Hd = (size_t)net->rnn_dim;
 #pragma omp parallel for schedule(dynamic, 1)
   for (int32_t b = 0; b < B; ++b)
-    step_row(net, p, b, obs, h_in, done, seed, step, actions, logp, value, h_out, logits_opt,
-             margin_opt);
+    step_row(net, p, b, (uint32_t)b, obs, h_in + (size_t)b * Hd, done, seed, step, actions, logp,
+             value, h_out + (size_t)b * Hd, logits_opt, margin_opt);
+  return 0;
+}
+
+int ref_policy_step_indexed(const ref_net* net, const ref_params* p, int32_t B, const uint8_t* obs,
+                            float* h_table, int32_t n_env, const int32_t* env_ids,
+                            const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions,
+                            float* logp, float* value, float* logits_opt, float* margin_opt) {
+  if (check_net(net) || B < 0 || n_env < 0) return -1;
+  /* every row names its own environment */
+  unsigned char* seen = (unsigned char*)calloc((size_t)n_env + 1, 1);
+  int bad = 0;
+  for (int32_t b = 0; b < B; ++b) {
+    if (env_ids[b] < 0 || env_ids[b] >= n_env || seen[env_ids[b]]) {
+      bad = 1;
+      break;
+    }
+    seen[env_ids[b]] = 1;
+  }
+  free(seen);
+  if (bad) return -2;
+  const size_t Hd = (size_t)net->rnn_dim;
+  /* all rows read the table before any row writes it */
+  float* h_new = (float*)malloc(sizeof(float) * (size_t)(B > 0 ? B : 1) * Hd);
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t b = 0; b < B; ++b)
+    step_row(net, p, b, (uint32_t)env_ids[b], obs, h_table + (size_t)env_ids[b] * Hd, done, seed,
+             step, actions, logp, value, h_new + (size_t)b * Hd, logits_opt, margin_opt);
+  for (int32_t b = 0; b < B; ++b)
+    memcpy(h_table + (size_t)env_ids[b] * Hd, h_new + (size_t)b * Hd, sizeof(float) * Hd);
+  free(h_new);
   return 0;
 }

@@ -174,6 +174,23 @@ int ref_policy_step(const ref_net* net, const ref_params* p, int32_t B, const ui
                     int32_t* actions, float* logp, float* value, float* h_out,
                     float* logits_opt, float* margin_opt);
 
+/* The same step when the batch rows are a subset of a larger population of
+ * environments (paper, Sec. 3.3: components exchange indices into preallocated
+ * tensors; Sec. 3.2: with double-buffered sampling the policy worker serves the
+ * two halves of a worker's environments in alternation).  Row b belongs to
+ * environment e = env_ids[b]:
+ *   its incoming state is h_table[e] (zeroed by done[b] as above), its new
+ *   state is written back to h_table[e]; rows of the table that no batch row
+ *   names are left untouched; the sampler's counter word "env" is e, so what
+ *   an environment draws does not depend on where in which batch it sits.
+ * h_table [n_env][rnn_dim]; env_ids [B], distinct, each in [0, n_env).
+ * Returns 0, -1 on a bad description, -2 on an id out of range or named twice
+ * (nothing is written then). */
+int ref_policy_step_indexed(const ref_net* net, const ref_params* p, int32_t B, const uint8_t* obs,
+                            float* h_table, int32_t n_env, const int32_t* env_ids,
+                            const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions,
+                            float* logp, float* value, float* logits_opt, float* margin_opt);
+
 /* Threads ref_policy_step will use. */
 int ref_num_threads(void);
 

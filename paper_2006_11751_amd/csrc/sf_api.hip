@@ -451,6 +451,15 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
     }
   }
   p->act_elems = act_elems;
+  // Every encoder launch reads neighbouring pixels of its input from other workgroups' tiles:
+  // none may write the buffer it reads.
+  for (const Op& op : p->ops)
+    if ((op.kind == OP_CONV || op.kind == OP_POOL) &&
+        (op.out_buf == op.in_buf || (op.resid_buf >= 0 && op.out_buf == op.resid_buf))) {
+      set_error("sf_policy_create: internal error: encoder launch '%s' would run in place", op.name.c_str());
+      free_policy(p);
+      return SF_ERR_SHAPE;
+    }
 
   // ---- FC: columns permuted from (c, y, x) to the channels-last order (y, x, c), transposed ----
   {
