@@ -151,6 +151,32 @@ int sf_policy_step(sf_policy* p, int32_t B, const uint8_t* obs, const float* h_i
                    float* logp, float* value, float* h_out, float* logits_opt,
                    void* hip_stream);
 
+/* The same step when the batch rows are a subset of a larger population of
+ * environments whose recurrent states live in one device table (paper, Sec. 3.3:
+ * the components exchange indices into preallocated tensors, never the tensors;
+ * Sec. 3.2: with double-buffered sampling the policy worker is given the two
+ * halves of a worker's environments in alternation).  Row b stands for
+ * environment e = env_ids[b]:
+ *   h_table    dev  [n_env][rnn_dim] fp32, 16-byte aligned.  Row e is read as the
+ *                   row's incoming state (zeroed by done[b] as above) and
+ *                   overwritten with its new state; rows that no batch row names
+ *                   are not touched.
+ *   env_ids    dev  [B] int32, 4-byte aligned, distinct, each in [0, n_env).
+ *                   The sampler's counter word for row b is e (not b), so what an
+ *                   environment draws does not depend on its place in a batch.
+ * All other arguments as for sf_policy_step; logits_opt, actions, logp and value
+ * are indexed by the batch row b.  The ids are device data and are not checked
+ * on the host: a row whose id is outside [0, n_env) is computed from a zero
+ * state and its new state is dropped; if two rows name the same environment, the
+ * table row ends up with one of their states.  The new states pass through the
+ * handle's workspace, so the call is, like sf_policy_step, asynchronous and
+ * allocation-free.  Errors: SF_ERR_ARG (null handle or pointer, misaligned
+ * pointer, n_env < 1), SF_ERR_BATCH, SF_ERR_DEVICE. */
+int sf_policy_step_indexed(sf_policy* p, int32_t B, const uint8_t* obs, float* h_table,
+                           int32_t n_env, const int32_t* env_ids, const uint8_t* done,
+                           uint64_t seed, uint64_t step, int32_t* actions, float* logp,
+                           float* value, float* logits_opt, void* hip_stream);
+
 /* Free the workspace and the packed weights.  The caller must have synchronised
  * every stream the handle was stepped on.  NULL is accepted. */
 int sf_policy_destroy(sf_policy* p);
@@ -181,6 +207,44 @@ int sf_policy_last_op_times(sf_policy* p, float* ms_out /* host */, int n);
  * reference kernel against which hardware byte counters are scaled when the
  * step's HBM traffic is measured.  Errors: SF_ERR_ARG, SF_ERR_DEVICE. */
 int sf_copy_bytes(const void* src, void* dst, int64_t bytes, void* hip_stream);
+
+/* ---- double-buffered stepping -------------------------------------------------
+ * A pipeline owns `n_slots` (1 or 2) sets of device buffers for the inputs and
+ * outputs of an indexed step on up to slot_batch rows, and three streams of its
+ * own: host-to-device copies, compute, device-to-host copies.  While the step of
+ * one slot computes, the observations of the other slot cross the bus: this is
+ * the policy-worker side of double-buffered sampling (paper, Sec. 3.2), where two
+ * groups of environments take turns, one being simulated while the actions of the
+ * other are computed.  The steps of the slots run in submission order on the one
+ * compute stream (they share the policy's workspace and the state table).
+ *
+ * sf_pipeline_submit enqueues, for slot `slot`: the copies of obs, done and
+ * env_ids to the device, sf_policy_step_indexed on them, and the copies of
+ * actions, logp and value back to the host; it returns without waiting.
+ *   host_obs      host [B][obs_c][obs_h][obs_w] bytes
+ *   host_done     host [B] bytes;  host_env_ids  host [B] int32
+ *   h_table       dev  [n_env][rnn_dim] fp32 (stays on the device)
+ *   host_actions  host [B][n_heads] int32; host_logp, host_value  host [B] fp32
+ * Host buffers should be page-locked (hipHostMalloc); with pageable memory the
+ * copies still work but do not overlap.  They belong to the caller and must stay
+ * valid and unmodified (inputs) or unread (outputs) until sf_pipeline_wait(slot)
+ * has returned.  A slot that has been submitted must be waited for before it is
+ * submitted again (SF_ERR_ARG otherwise).  sf_pipeline_wait blocks the calling
+ * thread until the slot's results are in host memory; waiting for an idle slot
+ * returns at once.  The policy must outlive the pipeline and must not be stepped
+ * by other callers while a slot is in flight.
+ * Errors: SF_ERR_ARG (null pointer, bad slot, slot busy, n_slots not 1 or 2),
+ * SF_ERR_BATCH (B outside [0, slot_batch], slot_batch outside [1, max_batch]),
+ * SF_ERR_OOM, SF_ERR_DEVICE. */
+typedef struct sf_pipeline sf_pipeline; /* opaque */
+int sf_pipeline_create(sf_policy* policy, int32_t slot_batch, int32_t n_slots, sf_pipeline** out);
+int sf_pipeline_submit(sf_pipeline* pl, int32_t slot, int32_t B, const uint8_t* host_obs,
+                       const uint8_t* host_done, const int32_t* host_env_ids, float* h_table,
+                       int32_t n_env, uint64_t seed, uint64_t step, int32_t* host_actions,
+                       float* host_logp, float* host_value);
+int sf_pipeline_wait(sf_pipeline* pl, int32_t slot);
+/* Waits for every slot in flight, then frees buffers, streams and events.  NULL is accepted. */
+int sf_pipeline_destroy(sf_pipeline* pl);
 
 #ifdef __cplusplus
 }

@@ -90,7 +90,8 @@ class SfPolicyWeights(C.Structure):
 EXPORTS = ("sf_policy_create", "sf_policy_step", "sf_policy_destroy", "sf_last_error",
            "sf_policy_flops_per_row", "sf_policy_op_count", "sf_policy_op_name",
            "sf_policy_op_flops_per_row", "sf_policy_set_op_timing", "sf_policy_last_op_times",
-           "sf_copy_bytes")
+           "sf_copy_bytes", "sf_policy_step_indexed", "sf_pipeline_create", "sf_pipeline_submit",
+           "sf_pipeline_wait", "sf_pipeline_destroy")
 
 _lib = None
 
@@ -138,6 +139,21 @@ def load_library():
         L.sf_policy_last_op_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int]
         L.sf_copy_bytes.restype = C.c_int
         L.sf_copy_bytes.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.sf_policy_step_indexed.restype = C.c_int
+        L.sf_policy_step_indexed.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                             C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_void_p]
+        L.sf_pipeline_create.restype = C.c_int
+        L.sf_pipeline_create.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+        L.sf_pipeline_submit.restype = C.c_int
+        L.sf_pipeline_submit.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.c_int32, C.c_uint64, C.c_uint64,
+                                         C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sf_pipeline_wait.restype = C.c_int
+        L.sf_pipeline_wait.argtypes = [C.c_void_p, C.c_int32]
+        L.sf_pipeline_destroy.restype = C.c_int
+        L.sf_pipeline_destroy.argtypes = [C.c_void_p]
         _lib = L
     return _lib
 
@@ -203,6 +219,44 @@ def sf_policy_step(handle, B, obs, h_in, done, seed, step, actions, logp, value,
     """All buffers are device addresses (ints), e.g. torch.Tensor.data_ptr()."""
     rc = load_library().sf_policy_step(handle, B, obs, h_in, done, seed, step, actions, logp,
                                        value, h_out, logits_opt, hip_stream)
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+
+
+def sf_policy_step_indexed(handle, B, obs, h_table, n_env, env_ids, done, seed, step, actions, logp,
+                           value, logits_opt=None, hip_stream=None):
+    """Device addresses (ints); h_table [n_env, rnn_dim] is read and written at rows env_ids."""
+    rc = load_library().sf_policy_step_indexed(handle, B, obs, h_table, n_env, env_ids, done, seed,
+                                               step, actions, logp, value, logits_opt, hip_stream)
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+
+
+def sf_pipeline_create(policy_handle, slot_batch, n_slots):
+    h = C.c_void_p()
+    rc = load_library().sf_pipeline_create(policy_handle, slot_batch, n_slots, C.byref(h))
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+    return h
+
+
+def sf_pipeline_submit(handle, slot, B, host_obs, host_done, host_env_ids, h_table, n_env, seed, step,
+                       host_actions, host_logp, host_value):
+    """host_*: host addresses (page-locked for overlap); h_table: device address."""
+    rc = load_library().sf_pipeline_submit(handle, slot, B, host_obs, host_done, host_env_ids, h_table,
+                                           n_env, seed, step, host_actions, host_logp, host_value)
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+
+
+def sf_pipeline_wait(handle, slot):
+    rc = load_library().sf_pipeline_wait(handle, slot)
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+
+
+def sf_pipeline_destroy(handle):
+    rc = load_library().sf_pipeline_destroy(handle)
     if rc != SF_OK:
         raise SfError(rc, sf_last_error())
 
@@ -283,9 +337,80 @@ class Policy:
                        s.cuda_stream)
         return out
 
+    def step_indexed(self, obs, h_table, env_ids, done, seed, step, out=None, stream=None):
+        """obs u8 [B,C,H,W], h_table f32 [n_env,H] (updated in place at rows env_ids),
+        env_ids i32 [B], done u8 [B]: contiguous CUDA tensors."""
+        t = self._torch
+        B = obs.shape[0]
+        assert obs.dtype == t.uint8 and h_table.dtype == t.float32 and done.dtype == t.uint8
+        assert env_ids.dtype == t.int32 and env_ids.shape == (B,) and done.shape == (B,)
+        assert obs.is_contiguous() and h_table.is_contiguous() and done.is_contiguous()
+        assert env_ids.is_contiguous() and h_table.shape[1] == self.H
+        assert tuple(obs.shape[1:]) == tuple(self.net["obs"])
+        if out is None:
+            out = self.alloc_outputs(B)
+            del out["h_out"]
+        s = stream if stream is not None else t.cuda.current_stream(self.device)
+        sf_policy_step_indexed(self.handle, B, obs.data_ptr(), h_table.data_ptr(), h_table.shape[0],
+                               env_ids.data_ptr(), done.data_ptr(), seed, step,
+                               out["actions"].data_ptr(), out["logp"].data_ptr(),
+                               out["value"].data_ptr(),
+                               out["logits"].data_ptr() if out.get("logits") is not None else None,
+                               s.cuda_stream)
+        return out
+
     def close(self):
         if self.handle:
             sf_policy_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Pipeline:
+    """Double-buffered stepping around a Policy: page-locked host tensors in and out,
+    the state table stays on the device.  Marshalling only; see include/sf_policy.h."""
+
+    def __init__(self, policy, slot_batch, n_slots=2):
+        import torch
+        self._torch = torch
+        self.policy = policy
+        self.slot_batch = slot_batch
+        self.n_slots = n_slots
+        self.handle = sf_pipeline_create(policy.handle, slot_batch, n_slots)
+        self._keep = [None] * n_slots
+
+    def host_buffers(self, B=None):
+        """Page-locked tensors of the right shapes for one slot."""
+        t = self._torch
+        B = self.slot_batch if B is None else B
+        pin = dict(pin_memory=True)
+        return dict(obs=t.empty((B,) + tuple(self.policy.net["obs"]), dtype=t.uint8, **pin),
+                    done=t.empty(B, dtype=t.uint8, **pin), env_ids=t.empty(B, dtype=t.int32, **pin),
+                    actions=t.empty((B, self.policy.n_heads), dtype=t.int32, **pin),
+                    logp=t.empty(B, dtype=t.float32, **pin), value=t.empty(B, dtype=t.float32, **pin))
+
+    def submit(self, slot, hb, h_table, seed, step, B=None):
+        B = hb["obs"].shape[0] if B is None else B
+        for k in ("obs", "done", "env_ids", "actions", "logp", "value"):
+            assert hb[k].is_contiguous() and not hb[k].is_cuda
+        sf_pipeline_submit(self.handle, slot, B, hb["obs"].data_ptr(), hb["done"].data_ptr(),
+                           hb["env_ids"].data_ptr(), h_table.data_ptr(), h_table.shape[0], seed, step,
+                           hb["actions"].data_ptr(), hb["logp"].data_ptr(), hb["value"].data_ptr())
+        self._keep[slot] = (hb, h_table)  # the buffers stay alive while the slot is in flight
+
+    def wait(self, slot):
+        sf_pipeline_wait(self.handle, slot)
+        if 0 <= slot < self.n_slots:
+            self._keep[slot] = None
+
+    def close(self):
+        if self.handle:
+            sf_pipeline_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

@@ -101,13 +101,21 @@ __global__ __launch_bounds__(kThreads) void gru_generic_kernel(
     const float* __restrict__ x, const float* __restrict__ h_in, const uint8_t* __restrict__ done,
     const float* __restrict__ wih_t, const float* __restrict__ whh_t,
     const float* __restrict__ bih, const float* __restrict__ bhh, float* __restrict__ h_out,
-    int n_in, int H) {
+    int n_in, int H, const int32_t* __restrict__ ids, int n_env) {
   int j = blockIdx.x * kThreads + threadIdx.x;
   int b = blockIdx.y;
   if (j >= H) return;
-  const bool reset = done[b] != 0;
+  bool reset = done[b] != 0;
+  // with ids, the row's state is row ids[b] of a table; an id outside it reads as zero state
+  int hb = b;
+  if (ids) {
+    const int e = ids[b];
+    const bool ok = (unsigned)e < (unsigned)n_env;
+    hb = ok ? e : 0;
+    reset = reset || !ok;
+  }
   const float* xp = x + (size_t)b * n_in;
-  const float* hp = h_in + (size_t)b * H;
+  const float* hp = h_in + (size_t)hb * H;
   float ir = bih[j], iz = bih[H + j], in_ = bih[2 * H + j];
   for (int i = 0; i < n_in; ++i) {
     float v = xp[i];
@@ -180,11 +188,12 @@ hipError_t launch_linear_generic(int B, int n_in, int n_out, const float* in, co
 
 hipError_t launch_gru_generic(int B, int n_in, int H, const float* x, const float* h_in,
                               const uint8_t* done, const float* wih_t, const float* whh_t,
-                              const float* bih, const float* bhh, float* h_out, hipStream_t st) {
+                              const float* bih, const float* bhh, float* h_out,
+                              const int32_t* ids, int n_env, hipStream_t st) {
   if (B == 0) return hipSuccess;
   dim3 grid((H + kThreads - 1) / kThreads, B);
   gru_generic_kernel<<<grid, kThreads, 0, st>>>(x, h_in, done, wih_t, whh_t, bih, bhh, h_out,
-                                                n_in, H);
+                                                n_in, H, ids, n_env);
   return hipGetLastError();
 }
 

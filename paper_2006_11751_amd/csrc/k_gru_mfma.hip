@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void gru_mfma_kernel(
     const float* __restrict__ x, const float* __restrict__ h_in, const uint8_t* __restrict__ done,
     const float* __restrict__ w_ih, const float* __restrict__ w_hh,
     const float* __restrict__ b_ih, const float* __restrict__ b_hh, float* __restrict__ h_out,
-    int B, int I, int H) {
+    int B, int I, int H, const int32_t* __restrict__ ids, int n_env) {
   constexpr int WM = BM / 32, WK = 4 / WM;
   constexpr int RA = BM / 32;       // 16-byte A loads per thread per chunk (B: 3, one per gate)
   constexpr int GPW = 4 / WK;       // K groups per wave per chunk
@@ -57,13 +57,22 @@ __global__ __launch_bounds__(256) void gru_mfma_kernel(
   const int m0 = blockIdx.x * BM, j0 = blockIdx.y * kBJ;
   const int lrow = tid >> 3, lk4 = (tid & 7) * 4;
 
-  int am[RA];
+  // With ids, row m's state is row ids[m] of a table of n_env rows; an id outside the table
+  // reads as a zero state.
+  int am[RA], ah[RA];
   bool areset[RA];
 #pragma unroll
   for (int r = 0; r < RA; ++r) {
     int m = m0 + lrow + 32 * r;
     am[r] = m < B ? m : B - 1;  // rows past the end re-read the last row; never stored
     areset[r] = done[am[r]] != 0;
+    ah[r] = am[r];
+    if (ids) {
+      const int e = ids[am[r]];
+      const bool ok = (unsigned)e < (unsigned)n_env;
+      ah[r] = ok ? e : 0;
+      areset[r] = areset[r] || !ok;
+    }
   }
   f32x4 ra[2][RA], rb[2][3];
   const int nx_chunks = I / kBK, nchunks = nx_chunks + H / kBK;
@@ -80,7 +89,7 @@ __global__ __launch_bounds__(256) void gru_mfma_kernel(
       const int kk = (c - nx_chunks) * kBK + lk4;
 #pragma unroll
       for (int r = 0; r < RA; ++r) {
-        const f32x4 v = *(const f32x4*)(h_in + (size_t)am[r] * H + kk);
+        const f32x4 v = *(const f32x4*)(h_in + (size_t)ah[r] * H + kk);
         const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
         ra[S][r] = areset[r] ? zero : v;
       }
@@ -179,7 +188,15 @@ __global__ __launch_bounds__(256) void gru_mfma_kernel(
     }
     const int m = m0 + wm * 32 + (v & 3) + 4 * lh + 8 * (v >> 2);
     if (m < B) {
-      const float hprev = done[m] ? 0.0f : h_in[(size_t)m * H + j];
+      int hm = m;
+      bool reset = done[m] != 0;
+      if (ids) {
+        const int e = ids[m];
+        const bool ok = (unsigned)e < (unsigned)n_env;
+        hm = ok ? e : 0;
+        reset = reset || !ok;
+      }
+      const float hprev = reset ? 0.0f : h_in[(size_t)hm * H + j];
       const float r = sigmoid_acc(s[0] + bir);
       const float z = sigmoid_acc(s[1] + biz);
       const float n = tanhf(s[2] + bin + r * (s[3] + bhn));
@@ -202,14 +219,16 @@ int gru_mfma_pick_bm(int max_batch, int H) {
 hipError_t launch_gru_mfma(int B, int I, int H, const float* x, const float* h_in,
                            const uint8_t* done, const float* w_ih, const float* w_hh,
                            const float* b_ih, const float* b_hh, float* h_out, int bm,
-                           hipStream_t st) {
+                           const int32_t* ids, int n_env, hipStream_t st) {
   if (B == 0) return hipSuccess;
   if (bm == 64) {
     dim3 grid((B + 63) / 64, H / kBJ);
-    gru_mfma_kernel<64><<<grid, 256, 0, st>>>(x, h_in, done, w_ih, w_hh, b_ih, b_hh, h_out, B, I, H);
+    gru_mfma_kernel<64><<<grid, 256, 0, st>>>(x, h_in, done, w_ih, w_hh, b_ih, b_hh, h_out, B, I, H,
+                                                  ids, n_env);
   } else {
     dim3 grid((B + 31) / 32, H / kBJ);
-    gru_mfma_kernel<32><<<grid, 256, 0, st>>>(x, h_in, done, w_ih, w_hh, b_ih, b_hh, h_out, B, I, H);
+    gru_mfma_kernel<32><<<grid, 256, 0, st>>>(x, h_in, done, w_ih, w_hh, b_ih, b_hh, h_out, B, I, H,
+                                                  ids, n_env);
   }
   return hipGetLastError();
 }

@@ -544,6 +544,7 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
                           : nullptr;
   p->trash = (float*)bld.dev_alloc(256);
   p->fc_out = (float*)bld.dev_alloc(sizeof(float) * (size_t)cfg->fc_dim * cfg->max_batch);
+  p->h_new = (float*)bld.dev_alloc(sizeof(float) * (size_t)cfg->rnn_dim * cfg->max_batch);
 
   p->events.resize(p->ops.size() + 1, nullptr);
   for (auto& ev : p->events)
@@ -583,6 +584,20 @@ extern "C" int64_t sf_policy_flops_per_row(const sf_policy* handle) {
     }                                                                           \
   } while (0)
 
+namespace {
+
+// The launch sequence of one step.  h_in / h_out are row-indexed by the batch row, unless
+// ids is given: then row b reads its state from h_in[ids[b]] (a table of n_env rows), and
+// the heads launch copies the new state from h_out[b] to h_table[ids[b]].
+int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* h_in, const uint8_t* done,
+             uint64_t seed, uint64_t step, int32_t* actions, float* logp, float* value,
+             float* h_out, float* logits_opt, const int32_t* ids, float* h_table, int n_env,
+             hipStream_t st);
+
+bool misaligned(const void* q, uintptr_t a) { return (reinterpret_cast<uintptr_t>(q) & (a - 1)) != 0; }
+
+}  // namespace
+
 extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, const float* h_in,
                               const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions,
                               float* logp, float* value, float* h_out, float* logits_opt,
@@ -602,7 +617,6 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
     set_error("sf_policy_step: null buffer");
     return SF_ERR_ARG;
   }
-  auto misaligned = [](const void* q, uintptr_t a) { return (reinterpret_cast<uintptr_t>(q) & (a - 1)) != 0; };
   if (misaligned(obs, 4) || misaligned(h_in, 16) || misaligned(h_out, 16) || misaligned(actions, 4) ||
       misaligned(logp, 4) || misaligned(value, 4) || (logits_opt && misaligned(logits_opt, 4))) {
     set_error("sf_policy_step: misaligned buffer (obs, actions, logp, value, logits: 4 bytes; "
@@ -617,8 +631,50 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
       return SF_ERR_ALIAS;
     }
   }
-  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  return run_step(p, B, obs, h_in, done, seed, step, actions, logp, value, h_out, logits_opt, nullptr,
+                  nullptr, 0, reinterpret_cast<hipStream_t>(hip_stream));
+}
 
+extern "C" int sf_policy_step_indexed(sf_policy* handle, int32_t B, const uint8_t* obs, float* h_table,
+                                      int32_t n_env, const int32_t* env_ids, const uint8_t* done,
+                                      uint64_t seed, uint64_t step, int32_t* actions, float* logp,
+                                      float* value, float* logits_opt, void* hip_stream) {
+  Policy* p = reinterpret_cast<Policy*>(handle);
+  if (!p) {
+    set_error("sf_policy_step_indexed: null handle");
+    return SF_ERR_ARG;
+  }
+  const sf_policy_config& c = p->cfg;
+  if (B < 0 || B > c.max_batch) {
+    set_error("sf_policy_step_indexed: B = %d outside [0, max_batch = %d]", B, c.max_batch);
+    return SF_ERR_BATCH;
+  }
+  if (n_env < 1) {
+    set_error("sf_policy_step_indexed: n_env = %d, must be at least 1", n_env);
+    return SF_ERR_ARG;
+  }
+  if (B == 0) return SF_OK;
+  if (!obs || !h_table || !env_ids || !done || !actions || !logp || !value) {
+    set_error("sf_policy_step_indexed: null buffer");
+    return SF_ERR_ARG;
+  }
+  if (misaligned(obs, 4) || misaligned(h_table, 16) || misaligned(env_ids, 4) || misaligned(actions, 4) ||
+      misaligned(logp, 4) || misaligned(value, 4) || (logits_opt && misaligned(logits_opt, 4))) {
+    set_error("sf_policy_step_indexed: misaligned buffer (obs, env_ids, actions, logp, value, logits: "
+              "4 bytes; h_table: 16 bytes)");
+    return SF_ERR_ARG;
+  }
+  return run_step(p, B, obs, h_table, done, seed, step, actions, logp, value, p->h_new, logits_opt,
+                  env_ids, h_table, n_env, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+namespace {
+
+int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* h_in, const uint8_t* done,
+             uint64_t seed, uint64_t step, int32_t* actions, float* logp, float* value,
+             float* h_out, float* logits_opt, const int32_t* ids, float* h_table, int n_env,
+             hipStream_t st) {
+  const sf_policy_config& c = p->cfg;
   auto buf = [&](int i) -> float* { return i < 0 ? nullptr : p->act[i]; };
   if (p->timing) SF_LAUNCH(hipEventRecord(p->events[0], st));
   for (size_t i = 0; i < p->ops.size(); ++i) {
@@ -698,20 +754,24 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
       case OP_GRU:
         if (p->gru_wih)
           SF_LAUNCH(launch_gru_mfma(B, c.fc_dim, c.rnn_dim, p->fc_out, h_in, done, p->gru_wih,
-                                    p->gru_whh, p->gru_bih, p->gru_bhh, h_out, p->gru_bm, st));
+                                    p->gru_whh, p->gru_bih, p->gru_bhh, h_out, p->gru_bm, ids, n_env,
+                                    st));
         else
           SF_LAUNCH(launch_gru_generic(B, c.fc_dim, c.rnn_dim, p->fc_out, h_in, done, p->gru_wih_t,
-                                       p->gru_whh_t, p->gru_bih, p->gru_bhh, h_out, st));
+                                       p->gru_whh_t, p->gru_bih, p->gru_bhh, h_out, ids, n_env, st));
         break;
       case OP_HEADS:
         SF_LAUNCH(launch_heads(B, c.rnn_dim, c.n_heads, p->sumA, p->head_off, h_out, p->head_w,
-                               p->head_b, seed, step, actions, logp, value, logits_opt, st));
+                               p->head_b, seed, step, actions, logp, value, logits_opt, ids, h_table,
+                               n_env, st));
         break;
     }
     if (p->timing) SF_LAUNCH(hipEventRecord(p->events[i + 1], st));
   }
   return SF_OK;
 }
+
+}  // namespace
 
 // ---- measurement aids ------------------------------------------------------
 

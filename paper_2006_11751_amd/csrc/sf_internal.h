@@ -86,6 +86,7 @@ struct Policy {
   float* act[3];      // three activation buffers of act_elems floats per row
   size_t act_elems;
   float* fc_out;      // dev [max_batch][fc_dim]
+  float* h_new;       // dev [max_batch][rnn_dim]: new states of an indexed step before the scatter
   float* trash;       // dev, 64 floats: target of stores that fall outside a tensor
   std::vector<void*> allocations;
   int64_t flops_per_row;
@@ -109,11 +110,13 @@ hipError_t launch_linear_generic(int B, int n_in, int n_out, const float* in, co
                                  const float* bias, int relu, float* out, hipStream_t st);
 hipError_t launch_gru_generic(int B, int n_in, int H, const float* x, const float* h_in,
                               const uint8_t* done, const float* wih_t, const float* whh_t,
-                              const float* bih, const float* bhh, float* h_out, hipStream_t st);
+                              const float* bih, const float* bhh, float* h_out,
+                              const int32_t* ids, int n_env, hipStream_t st);
 hipError_t launch_heads(int B, int H, int n_heads, int sumA, const int32_t* head_off,
                         const float* h, const float* head_w, const float* head_b, uint64_t seed,
                         uint64_t step, int32_t* actions, float* logp, float* value,
-                        float* logits_opt, hipStream_t st);
+                        float* logits_opt, const int32_t* ids, float* h_table, int n_env,
+                        hipStream_t st);
 
 hipError_t launch_copy16(const void* src, void* dst, long long bytes, hipStream_t st);
 
@@ -170,7 +173,7 @@ bool gru_mfma_supported(int I, int H);
 hipError_t launch_gru_mfma(int B, int I, int H, const float* x, const float* h_in,
                            const uint8_t* done, const float* w_ih, const float* w_hh,
                            const float* b_ih, const float* b_hh, float* h_out, int bm,
-                           hipStream_t st);
+                           const int32_t* ids, int n_env, hipStream_t st);
 int gru_mfma_pick_bm(int max_batch, int H);
 bool gemm_mfma_supported(int Cin, int ksize, int pad, int N);
 int gemm_mfma_pick_tile(long long M, int N, int K, int seg_len);

@@ -18,3 +18,10 @@ def ref():
     from oracle import ref as _ref
     _ref.build(force=False)
     return _ref
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch

@@ -11,13 +11,6 @@ from tests import parity
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def torch_cuda():
-    import torch
-    assert torch.cuda.is_available(), "these tests need the GPU"
-    return torch
-
-
 def _to_np(out):
     return {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
 
