@@ -19,7 +19,50 @@ MI355X_PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2500.0}
 # recorded in profiles/policy_step_standard_hbm_traffic.md: (FETCH_SIZE x 2.000 + WRITE_SIZE
 # x 1.000) KiB, the factors being what the same counters read for a 256 MiB plain copy.
 MEASURED_HBM_KIB = {"standard": {"conv1": 30840 + 67456, "conv2": 62688 + 25088, "conv3": 25698 + 9216,
-                                 "fc": 46198 + 2048, "gru": 53600 + 2048, "heads": 2264 + 24}}
+                                 "fc": 46198 + 2048, "gru": 53600 + 2048, "heads": 2264 + 24},
+                    # profiles/policy_step_resnet_counters.md (FETCH_SIZE x 2 + WRITE_SIZE)
+                    "resnet_bf16": {"stage1.conv_pool": 2 * 110600 + 589820, "stage1.block1": 2 * 295000 + 589820,
+                                    "stage1.block2": 2 * 295000 + 589820, "stage2.conv_pool": 2 * 295100 + 294900,
+                                    "stage2.block1": 2 * 147800 + 294900, "stage2.block2": 2 * 147800 + 294900}}
+
+
+def measure_pipeline(torch, binding, wl, pol, net, rounds):
+    """Host-resident observations: env-frames/s of submit/wait through the pipeline with one
+    slot (copy, step, copy back, in sequence) and with two slots in alternation."""
+    B, dev = net["B"], pol.device
+    n_env = 2 * B
+    table = torch.zeros((n_env, net["rnn"]), dtype=torch.float32, device=dev)
+    obs, done = torch.from_numpy(wl.observations(net)), torch.from_numpy(wl.done_mask(net))
+    res = {}
+    for n_slots in (1, 2):
+        pipe = binding.Pipeline(pol, B, n_slots)
+        hbs = [pipe.host_buffers() for _ in range(n_slots)]
+        for s, hb in enumerate(hbs):
+            hb["obs"].copy_(obs)
+            hb["done"].copy_(done)
+            hb["env_ids"].copy_(torch.arange(s * B, (s + 1) * B, dtype=torch.int32))
+        t = 0
+
+        def go(n):
+            nonlocal t
+            for _ in range(n):
+                for s in range(n_slots):
+                    pipe.wait(s)
+                    pipe.submit(s, hbs[s], table, wl.PHILOX_SEED, t)
+                t += 1
+            for s in range(n_slots):
+                pipe.wait(s)
+
+        go(max(3, rounds // 10))
+        tic = time.perf_counter()
+        go(rounds)
+        dt = time.perf_counter() - tic
+        res[n_slots] = B * n_slots * rounds / dt
+        pipe.close()
+    obs_bytes = int(np.prod(net["obs"]))
+    return {"slot_batch": B, "rounds": rounds, "one_slot_fps": round(res[1], 1), "two_slot_fps": round(res[2], 1),
+            "two_slot_h2d_GBps": round(res[2] * obs_bytes / 1e9, 2),
+            "note": "host-to-device copy of the observations included; never the headline value"}
 
 
 def main():
@@ -29,6 +72,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = the headline one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="also measure the double-buffered pipeline with host-resident observations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -115,7 +160,9 @@ def main():
         cpu = {"value": round(n_rows * reps / spent, 2), "unit": "env-frames/s", "cores": ref.num_threads(),
                "kind": "oracle", "sample": "%d rows of the same workload x %d repeats (%.1f s)" % (n_rows, reps, spent)}
 
-    print(json.dumps({
+    pipeline = measure_pipeline(torch, binding, wl, pol, net, min(args.steps, 100)) if args.pipeline else None
+
+    line = {
         "metric": "policy-step env-frames/sec at B=1024 3x72x128 GRU-512; % MFMA/HBM roofline",
         "value": round(fps, 1), "unit": "env-frames/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
@@ -125,7 +172,10 @@ def main():
             net["name"], B, *net["obs"], net["encoder"], net["fc"], net["rnn"], net["heads"]),
             "paper_accounting_x4_frameskip_fps": round(4 * fps, 1),
             "inputs": "device-resident; host-to-device transfer excluded"},
-        "roofline": roofline, "cpu_baseline": cpu}))
+        "roofline": roofline, "cpu_baseline": cpu}
+    if pipeline is not None:
+        line["pipeline"] = pipeline
+    print(json.dumps(line))
     pol.close()
 
 
