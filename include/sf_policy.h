@@ -108,10 +108,10 @@ typedef struct {
   const float* conv_b[SF_MAX_CONV_TENSORS];
   const float* fc_w;
   const float* fc_b;
-  const float* gru_w_ih;
-  const float* gru_w_hh;
-  const float* gru_b_ih;
-  const float* gru_b_hh;
+  const float* rnn_w_ih;
+  const float* rnn_w_hh;
+  const float* rnn_b_ih;
+  const float* rnn_b_hh;
   const float* pi_w;
   const float* pi_b;
   const float* v_w;

@@ -15,6 +15,7 @@ _SO = os.path.join(_HERE, "libsf_oracle.so")
 _SRC = os.path.join(_HERE, "sf_oracle.c")
 
 MAX_CONV, MAX_STAGE, MAX_HEADS, MAX_CONV_TENSORS = 4, 4, 16, 20
+MAX_MEAS_LAYERS = 2
 
 
 def build(force=True):
@@ -40,6 +41,8 @@ class RefNet(C.Structure):
         ("fc_dim", C.c_int32), ("rnn_dim", C.c_int32),
         ("n_heads", C.c_int32), ("head_sizes", C.c_int32 * MAX_HEADS),
         ("obs_sub", C.c_float), ("obs_mul", C.c_float),
+        ("rnn_type", C.c_int32), ("meas_dim", C.c_int32), ("n_meas_layers", C.c_int32),
+        ("meas_hidden", C.c_int32 * MAX_MEAS_LAYERS),
     ]
 
 
@@ -50,8 +53,9 @@ class RefParams(C.Structure):
     _fields_ = [
         ("conv_w", _FP * MAX_CONV_TENSORS), ("conv_b", _FP * MAX_CONV_TENSORS),
         ("fc_w", _FP), ("fc_b", _FP),
-        ("gru_w_ih", _FP), ("gru_w_hh", _FP), ("gru_b_ih", _FP), ("gru_b_hh", _FP),
+        ("rnn_w_ih", _FP), ("rnn_w_hh", _FP), ("rnn_b_ih", _FP), ("rnn_b_hh", _FP),
         ("pi_w", _FP), ("pi_b", _FP), ("v_w", _FP), ("v_b", _FP),
+        ("meas_w", _FP * MAX_MEAS_LAYERS), ("meas_b", _FP * MAX_MEAS_LAYERS),
     ]
 
 
@@ -108,7 +112,17 @@ def make_net(net):
     for i, a in enumerate(net["heads"]):
         r.head_sizes[i] = a
     r.obs_sub, r.obs_mul = net["obs_sub"], net["obs_mul"]
+    r.rnn_type = 1 if net.get("rnn_type", "gru") == "lstm" else 0
+    r.meas_dim = net.get("meas_dim", 0)
+    hidden = net.get("meas_hidden", []) if r.meas_dim else []
+    r.n_meas_layers = len(hidden)
+    for i, m in enumerate(hidden):
+        r.meas_hidden[i] = m
     return r
+
+
+def state_dim(net):
+    return net["rnn"] * (2 if net.get("rnn_type", "gru") == "lstm" else 1)
 
 
 def make_params(w):
@@ -125,9 +139,12 @@ def make_params(w):
     for i, (cw, cb) in enumerate(zip(w["conv_w"], w["conv_b"])):
         p.conv_w[i] = fp(cw)
         p.conv_b[i] = fp(cb)
-    for name in ("fc_w", "fc_b", "gru_w_ih", "gru_w_hh", "gru_b_ih", "gru_b_hh", "pi_w", "pi_b",
+    for name in ("fc_w", "fc_b", "rnn_w_ih", "rnn_w_hh", "rnn_b_ih", "rnn_b_hh", "pi_w", "pi_b",
                  "v_w", "v_b"):
         setattr(p, name, fp(w[name]))
+    for i, (mw, mb) in enumerate(zip(w.get("meas_w", []), w.get("meas_b", []))):
+        p.meas_w[i] = fp(mw)
+        p.meas_b[i] = fp(mb)
     return p, keep
 
 
@@ -139,8 +156,17 @@ def num_threads():
     return int(lib().ref_num_threads())
 
 
-def policy_step(net, w, obs, h_in, done, seed, step, want_logits=True, want_margin=True):
-    """Run one step on host arrays; returns a dict of numpy outputs."""
+def _meas_arg(net, meas, B):
+    if not net.get("meas_dim", 0):
+        return None, None
+    meas = _f32(meas)
+    assert meas.shape == (B, net["meas_dim"])
+    return meas, _p(meas)
+
+
+def policy_step(net, w, obs, h_in, done, seed, step, want_logits=True, want_margin=True, meas=None):
+    """Run one step on host arrays; returns a dict of numpy outputs.  h_in / h_out rows hold
+    state_dim(net) floats ([h | c] for an LSTM)."""
     L = lib()
     rn = make_net(net)
     rp, keep = make_params(w)
@@ -148,7 +174,8 @@ def policy_step(net, w, obs, h_in, done, seed, step, want_logits=True, want_marg
     obs = np.ascontiguousarray(obs, dtype=np.uint8)
     h_in = _f32(h_in)
     done = np.ascontiguousarray(done, dtype=np.uint8)
-    nh, sumA, H = len(net["heads"]), int(sum(net["heads"])), net["rnn"]
+    nh, sumA, H = len(net["heads"]), int(sum(net["heads"])), state_dim(net)
+    meas, meas_p = _meas_arg(net, meas, B)
     out = {
         "actions": np.zeros((B, nh), np.int32), "logp": np.zeros(B, np.float32),
         "value": np.zeros(B, np.float32), "h_out": np.zeros((B, H), np.float32),
@@ -156,7 +183,7 @@ def policy_step(net, w, obs, h_in, done, seed, step, want_logits=True, want_marg
         "margin": np.zeros((B, nh), np.float32) if want_margin else None,
     }
     rc = L.ref_policy_step(
-        C.byref(rn), C.byref(rp), C.c_int32(B), _p(obs), _p(h_in), _p(done),
+        C.byref(rn), C.byref(rp), C.c_int32(B), _p(obs), meas_p, _p(h_in), _p(done),
         C.c_uint64(seed), C.c_uint64(step), _p(out["actions"]), _p(out["logp"]),
         _p(out["value"]), _p(out["h_out"]),
         _p(out["logits"]) if want_logits else None, _p(out["margin"]) if want_margin else None)
@@ -166,7 +193,7 @@ def policy_step(net, w, obs, h_in, done, seed, step, want_logits=True, want_marg
     return out
 
 
-def policy_step_indexed(net, w, obs, h_table, env_ids, done, seed, step):
+def policy_step_indexed(net, w, obs, h_table, env_ids, done, seed, step, meas=None):
     """One step on rows that name environments of a state table; h_table is updated in place."""
     L = lib()
     rn = make_net(net)
@@ -177,13 +204,15 @@ def policy_step_indexed(net, w, obs, h_table, env_ids, done, seed, step):
     env_ids = np.ascontiguousarray(env_ids, dtype=np.int32)
     done = np.ascontiguousarray(done, dtype=np.uint8)
     nh, sumA = len(net["heads"]), int(sum(net["heads"]))
+    meas, meas_p = _meas_arg(net, meas, B)
+    assert h_table.shape[1] == state_dim(net)
     out = {
         "actions": np.zeros((B, nh), np.int32), "logp": np.zeros(B, np.float32),
         "value": np.zeros(B, np.float32), "logits": np.zeros((B, sumA), np.float32),
         "margin": np.zeros((B, nh), np.float32),
     }
     rc = L.ref_policy_step_indexed(
-        C.byref(rn), C.byref(rp), C.c_int32(B), _p(obs), _p(h_table), C.c_int32(h_table.shape[0]),
+        C.byref(rn), C.byref(rp), C.c_int32(B), _p(obs), meas_p, _p(h_table), C.c_int32(h_table.shape[0]),
         _p(env_ids), _p(done), C.c_uint64(seed), C.c_uint64(step), _p(out["actions"]),
         _p(out["logp"]), _p(out["value"]), _p(out["logits"]), _p(out["margin"]))
     if rc == -2:
@@ -225,6 +254,15 @@ def linear(x, w, b, relu):
     out = np.zeros(w.shape[0], np.float64)
     lib().ref_linear(_p(x), x.shape[0], _p(w), _p(b), w.shape[0], int(relu), _p(out))
     return out
+
+
+def lstm_cell(x, h, c, w_ih, w_hh, b_ih, b_hh):
+    x, h, c = _f64(x), _f64(h), _f64(c)
+    w_ih, w_hh, b_ih, b_hh = _f32(w_ih), _f32(w_hh), _f32(b_ih), _f32(b_hh)
+    hn, cn = np.zeros(h.shape[0], np.float64), np.zeros(h.shape[0], np.float64)
+    lib().ref_lstm_cell(_p(x), x.shape[0], _p(h), _p(c), h.shape[0], _p(w_ih), _p(w_hh), _p(b_ih),
+                        _p(b_hh), _p(hn), _p(cn))
+    return hn, cn
 
 
 def gru_cell(x, h, w_ih, w_hh, b_ih, b_hh):

@@ -88,6 +88,25 @@ void ref_gru_cell(const double* x, int n_in, const double* h, int H, const float
   free(gh);
 }
 
+void ref_lstm_cell(const double* x, int n_in, const double* h, const double* c, int H,
+                   const float* w_ih, const float* w_hh, const float* b_ih, const float* b_hh,
+                   double* h_new, double* c_new) {
+  double* gi = (double*)malloc(sizeof(double) * 4 * (size_t)H);
+  double* gh = (double*)malloc(sizeof(double) * 4 * (size_t)H);
+  ref_linear(x, n_in, w_ih, b_ih, 4 * H, 0, gi); /* W_i* x + b_i* for i, f, g, o */
+  ref_linear(h, H, w_hh, b_hh, 4 * H, 0, gh);    /* W_h* h + b_h* for i, f, g, o */
+  for (int j = 0; j < H; ++j) {
+    double ig = sigmoid(gi[j] + gh[j]);
+    double fg = sigmoid(gi[H + j] + gh[H + j]);
+    double gg = tanh(gi[2 * H + j] + gh[2 * H + j]);
+    double og = sigmoid(gi[3 * H + j] + gh[3 * H + j]);
+    c_new[j] = fg * c[j] + ig * gg;
+    h_new[j] = og * tanh(c_new[j]);
+  }
+  free(gi);
+  free(gh);
+}
+
 static void relu_copy(const double* in, size_t n, double* out) {
   for (size_t i = 0; i < n; ++i) out[i] = in[i] > 0.0 ? in[i] : 0.0;
 }
@@ -284,7 +303,8 @@ int ref_num_threads(void) {
 /* Row b of the batch.  env is the sampler's counter word for this row; h_in_row and
  * h_out_row are this row's incoming and outgoing state (rnn_dim floats each). */
 static void step_row(const ref_net* net, const ref_params* p, int32_t b, uint32_t env,
-                     const uint8_t* obs, const float* h_in_row, const uint8_t* done, uint64_t seed,
+                     const uint8_t* obs, const float* meas, const float* h_in_row,
+                     const uint8_t* done, uint64_t seed,
                      uint64_t step, int32_t* actions, float* logp, float* value, float* h_out_row,
                      float* logits_opt, float* margin_opt) {
   const int C = net->obs_c, H = net->obs_h, W = net->obs_w, Hd = net->rnn_dim;
@@ -327,12 +347,41 @@ static void step_row(const ref_net* net, const ref_params* p, int32_t b, uint32_
   double* f = (double*)malloc(sizeof(double) * (size_t)net->fc_dim);
   ref_linear(enc, (int)flat, p->fc_w, p->fc_b, net->fc_dim, 1, f);
 
-  /* recurrent core with the episode-boundary reset applied to the INCOMING state */
-  double* h = (double*)malloc(sizeof(double) * (size_t)Hd);
-  double* hn = (double*)malloc(sizeof(double) * (size_t)Hd);
-  for (int j = 0; j < Hd; ++j) h[j] = done[b] ? 0.0 : (double)h_in_row[j];
-  ref_gru_cell(f, net->fc_dim, h, Hd, p->gru_w_ih, p->gru_w_hh, p->gru_b_ih, p->gru_b_hh, hn);
-  for (int j = 0; j < Hd; ++j) h_out_row[j] = (float)hn[j];
+  /* full architecture: the low-dimensional measurement vector goes through its own
+   * fully connected layers (+ReLU) and is appended to the encoder's features */
+  int n_core_in = net->fc_dim;
+  double* core_in = f;
+  if (net->meas_dim > 0) {
+    int n_cur = net->meas_dim;
+    double* cur = (double*)malloc(sizeof(double) * (size_t)n_cur);
+    for (int i = 0; i < n_cur; ++i) cur[i] = (double)meas[(size_t)b * net->meas_dim + i];
+    for (int l = 0; l < net->n_meas_layers; ++l) {
+      double* nxt = (double*)malloc(sizeof(double) * (size_t)net->meas_hidden[l]);
+      ref_linear(cur, n_cur, p->meas_w[l], p->meas_b[l], net->meas_hidden[l], 1, nxt);
+      free(cur);
+      cur = nxt;
+      n_cur = net->meas_hidden[l];
+    }
+    n_core_in = net->fc_dim + n_cur;
+    core_in = (double*)malloc(sizeof(double) * (size_t)n_core_in);
+    memcpy(core_in, f, sizeof(double) * (size_t)net->fc_dim);
+    memcpy(core_in + net->fc_dim, cur, sizeof(double) * (size_t)n_cur);
+    free(cur);
+  }
+
+  /* recurrent core with the episode-boundary reset applied to the INCOMING state; an
+   * LSTM's state row is [h | c] and both halves are reset */
+  const int lstm = net->rnn_type == 1;
+  double* h = (double*)malloc(sizeof(double) * (size_t)Hd * 2);
+  double* hn = (double*)malloc(sizeof(double) * (size_t)Hd * 2);
+  for (int j = 0; j < (lstm ? 2 * Hd : Hd); ++j) h[j] = done[b] ? 0.0 : (double)h_in_row[j];
+  if (lstm)
+    ref_lstm_cell(core_in, n_core_in, h, h + Hd, Hd, p->rnn_w_ih, p->rnn_w_hh, p->rnn_b_ih,
+                  p->rnn_b_hh, hn, hn + Hd);
+  else
+    ref_gru_cell(core_in, n_core_in, h, Hd, p->rnn_w_ih, p->rnn_w_hh, p->rnn_b_ih, p->rnn_b_hh, hn);
+  for (int j = 0; j < (lstm ? 2 * Hd : Hd); ++j) h_out_row[j] = (float)hn[j];
+  if (core_in != f) free(core_in);
 
   /* heads: action logits (all heads concatenated) and the baseline */
   int sumA = 0;
@@ -377,27 +426,38 @@ static int check_net(const ref_net* net) {
     return -1;
   for (int k = 0; k < net->n_heads; ++k)
     if (net->head_sizes[k] < 1) return -1;
+  if (net->rnn_type != 0 && net->rnn_type != 1) return -1;
+  if (net->meas_dim < 0) return -1;
+  if (net->meas_dim > 0) {
+    if (net->n_meas_layers < 1 || net->n_meas_layers > REF_MAX_MEAS_LAYERS) return -1;
+    for (int l = 0; l < net->n_meas_layers; ++l)
+      if (net->meas_hidden[l] < 1) return -1;
+  }
   return 0;
 }
 
+int ref_state_dim(const ref_net* net) { return net->rnn_dim * (net->rnn_type == 1 ? 2 : 1); }
+
 int ref_policy_step(const ref_net* net, const ref_params* p, int32_t B, const uint8_t* obs,
-                    const float* h_in, const uint8_t* done, uint64_t seed, uint64_t step,
-                    int32_t* actions, float* logp, float* value, float* h_out,
+                    const float* meas, const float* h_in, const uint8_t* done, uint64_t seed,
+                    uint64_t step, int32_t* actions, float* logp, float* value, float* h_out,
                     float* logits_opt, float* margin_opt) {
   if (check_net(net) || B < 0) return -1;
-  const size_t Hd = (size_t)net->rnn_dim;
+  if (net->meas_dim > 0 && B > 0 && !meas) return -1;
+  const size_t Sd = (size_t)ref_state_dim(net);
 #pragma omp parallel for schedule(dynamic, 1)
   for (int32_t b = 0; b < B; ++b)
-    step_row(net, p, b, (uint32_t)b, obs, h_in + (size_t)b * Hd, done, seed, step, actions, logp,
-             value, h_out + (size_t)b * Hd, logits_opt, margin_opt);
+    step_row(net, p, b, (uint32_t)b, obs, meas, h_in + (size_t)b * Sd, done, seed, step, actions,
+             logp, value, h_out + (size_t)b * Sd, logits_opt, margin_opt);
   return 0;
 }
 
 int ref_policy_step_indexed(const ref_net* net, const ref_params* p, int32_t B, const uint8_t* obs,
-                            float* h_table, int32_t n_env, const int32_t* env_ids,
+                            const float* meas, float* h_table, int32_t n_env, const int32_t* env_ids,
                             const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions,
                             float* logp, float* value, float* logits_opt, float* margin_opt) {
   if (check_net(net) || B < 0 || n_env < 0) return -1;
+  if (net->meas_dim > 0 && B > 0 && !meas) return -1;
   /* every row names its own environment */
   unsigned char* seen = (unsigned char*)calloc((size_t)n_env + 1, 1);
   int bad = 0;
@@ -410,12 +470,12 @@ int ref_policy_step_indexed(const ref_net* net, const ref_params* p, int32_t B, 
   }
   free(seen);
   if (bad) return -2;
-  const size_t Hd = (size_t)net->rnn_dim;
+  const size_t Hd = (size_t)ref_state_dim(net);
   /* all rows read the table before any row writes it */
   float* h_new = (float*)malloc(sizeof(float) * (size_t)(B > 0 ? B : 1) * Hd);
 #pragma omp parallel for schedule(dynamic, 1)
   for (int32_t b = 0; b < B; ++b)
-    step_row(net, p, b, (uint32_t)env_ids[b], obs, h_table + (size_t)env_ids[b] * Hd, done, seed,
+    step_row(net, p, b, (uint32_t)env_ids[b], obs, meas, h_table + (size_t)env_ids[b] * Hd, done, seed,
              step, actions, logp, value, h_new + (size_t)b * Hd, logits_opt, margin_opt);
   for (int32_t b = 0; b < B; ++b)
     memcpy(h_table + (size_t)env_ids[b] * Hd, h_new + (size_t)b * Hd, sizeof(float) * Hd);

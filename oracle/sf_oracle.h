@@ -47,6 +47,7 @@ extern "C" {
 #define REF_MAX_CONV 4
 #define REF_MAX_STAGE 4
 #define REF_MAX_HEADS 16
+#define REF_MAX_MEAS_LAYERS 2
 #define REF_MAX_CONV_TENSORS 20
 
 /* Network description.  encoder 0: n_conv plain convolutions (each + ReLU).
@@ -64,13 +65,20 @@ typedef struct {
   int32_t n_heads;
   int32_t head_sizes[REF_MAX_HEADS];
   float obs_sub, obs_mul; /* x = ((double)u8 - obs_sub) * obs_mul */
+  int32_t rnn_type;       /* 0 GRU, 1 LSTM (state row = [h | c], 2 * rnn_dim floats) */
+  int32_t meas_dim;       /* length of the measurement vector of the "full" architecture; 0 = none */
+  int32_t n_meas_layers;  /* 1..REF_MAX_MEAS_LAYERS fully connected + ReLU layers on it */
+  int32_t meas_hidden[REF_MAX_MEAS_LAYERS];
 } ref_net;
 
 /* fp32 parameters in their canonical layouts (all host memory, read only).
  * conv_w[i]: [cout][cin][k][k]; conv_b[i]: [cout].  Residual encoder order:
  * per stage the stage convolution, then for each block its two convolutions.
  * fc_w: [fc_dim][flat] with flat = c*(H*W) + y*W + x.  GRU: w_ih [3H][fc_dim],
- * w_hh [3H][H], b_ih [3H], b_hh [3H], gate rows ordered r, z, n.
+ * w_hh [3H][H], b_ih [3H], b_hh [3H], gate rows ordered r, z, n.  LSTM: the same
+ * four tensors with 4H rows, gate rows ordered i, f, g, o.  With a measurement
+ * encoder the recurrent core's input is [fc output | encoded measurements], so
+ * w_ih has fc_dim + meas_hidden[last] columns.
  * pi_w: [sum(head_sizes)][H] (heads concatenated), pi_b likewise.
  * v_w: [H], v_b: [1]. */
 typedef struct {
@@ -78,14 +86,16 @@ typedef struct {
   const float* conv_b[REF_MAX_CONV_TENSORS];
   const float* fc_w;
   const float* fc_b;
-  const float* gru_w_ih;
-  const float* gru_w_hh;
-  const float* gru_b_ih;
-  const float* gru_b_hh;
+  const float* rnn_w_ih;
+  const float* rnn_w_hh;
+  const float* rnn_b_ih;
+  const float* rnn_b_hh;
   const float* pi_w;
   const float* pi_b;
   const float* v_w;
   const float* v_b;
+  const float* meas_w[REF_MAX_MEAS_LAYERS]; /* [meas_hidden[l]][previous width] */
+  const float* meas_b[REF_MAX_MEAS_LAYERS];
 } ref_params;
 
 /* ---- building blocks (exported so that each can be pinned on its own) ---- */
@@ -113,6 +123,16 @@ void ref_linear(const double* in, int n_in, const float* w, const float* bias, i
  * h is the state AFTER the episode-boundary reset (the caller zeroes it). */
 void ref_gru_cell(const double* x, int n_in, const double* h, int H, const float* w_ih,
                   const float* w_hh, const float* b_ih, const float* b_hh, double* h_new);
+
+/* LSTM cell (paper, App. "Model architectures": the benchmark model's core), the
+ * convention of the framework the paper was built on:
+ *   i = sigma(W_ii x + b_ii + W_hi h + b_hi)      f = sigma(W_if x + b_if + W_hf h + b_hf)
+ *   g = tanh (W_ig x + b_ig + W_hg h + b_hg)      o = sigma(W_io x + b_io + W_ho h + b_ho)
+ *   c' = f * c + i * g                             h' = o * tanh(c')
+ * h, c are the state AFTER the episode-boundary reset. */
+void ref_lstm_cell(const double* x, int n_in, const double* h, const double* c, int H,
+                   const float* w_ih, const float* w_hh, const float* b_ih, const float* b_hh,
+                   double* h_new, double* c_new);
 
 /* Residual encoder (the reading of "ResNet backbone as in IMPALA"): per stage
  * conv3x3/s1/pad1 (bias, no ReLU) -> ref_maxpool3x3s2p1 -> blocks of
@@ -161,18 +181,23 @@ void ref_log_softmax(const float* logits, int A, double* out);
 int64_t ref_flat_size(const ref_net* net);
 
 /* One policy step on B rows (all host pointers).
- *   obs   [B][C][H][W] u8;  h_in [B][rnn_dim];  done [B] (non-zero = this
+ *   obs   [B][C][H][W] u8;  meas [B][meas_dim] fp32 (NULL when meas_dim is 0: the
+ *   "full" architecture's low-dimensional game information, paper, App. "VizDoom
+ *   experiments");  h_in [B][state_dim];  done [B] (non-zero = this
  *   observation starts a new episode: the incoming state is zeroed BEFORE the
  *   cell, so stale state cannot reach this step's outputs)
  *   actions [B][n_heads]; logp [B] joint log-probability; value [B];
- *   h_out [B][rnn_dim]; logits_opt [B][sumA] or NULL; margin_opt [B][n_heads]
+ *   h_out [B][state_dim]; logits_opt [B][sumA] or NULL; margin_opt [B][n_heads]
  *   or NULL (top-2 perturbed margin per head).
  * Sampler counter word "env" is the batch row index.  Rows are independent and
  * are spread over OpenMP threads.  Returns 0, -1 on a bad description. */
 int ref_policy_step(const ref_net* net, const ref_params* p, int32_t B, const uint8_t* obs,
-                    const float* h_in, const uint8_t* done, uint64_t seed, uint64_t step,
-                    int32_t* actions, float* logp, float* value, float* h_out,
+                    const float* meas, const float* h_in, const uint8_t* done, uint64_t seed,
+                    uint64_t step, int32_t* actions, float* logp, float* value, float* h_out,
                     float* logits_opt, float* margin_opt);
+
+/* Floats per state row: rnn_dim for a GRU, 2 * rnn_dim ([h | c]) for an LSTM. */
+int ref_state_dim(const ref_net* net);
 
 /* The same step when the batch rows are a subset of a larger population of
  * environments (paper, Sec. 3.3: components exchange indices into preallocated
@@ -183,11 +208,11 @@ int ref_policy_step(const ref_net* net, const ref_params* p, int32_t B, const ui
  *   state is written back to h_table[e]; rows of the table that no batch row
  *   names are left untouched; the sampler's counter word "env" is e, so what
  *   an environment draws does not depend on where in which batch it sits.
- * h_table [n_env][rnn_dim]; env_ids [B], distinct, each in [0, n_env).
+ * h_table [n_env][state_dim]; env_ids [B], distinct, each in [0, n_env).
  * Returns 0, -1 on a bad description, -2 on an id out of range or named twice
  * (nothing is written then). */
 int ref_policy_step_indexed(const ref_net* net, const ref_params* p, int32_t B, const uint8_t* obs,
-                            float* h_table, int32_t n_env, const int32_t* env_ids,
+                            const float* meas, float* h_table, int32_t n_env, const int32_t* env_ids,
                             const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions,
                             float* logp, float* value, float* logits_opt, float* margin_opt);
 

@@ -82,7 +82,7 @@ class SfPolicyWeights(C.Structure):
     _fields_ = [
         ("conv_w", _FP * SF_MAX_CONV_TENSORS), ("conv_b", _FP * SF_MAX_CONV_TENSORS),
         ("fc_w", _FP), ("fc_b", _FP),
-        ("gru_w_ih", _FP), ("gru_w_hh", _FP), ("gru_b_ih", _FP), ("gru_b_hh", _FP),
+        ("rnn_w_ih", _FP), ("rnn_w_hh", _FP), ("rnn_b_ih", _FP), ("rnn_b_hh", _FP),
         ("pi_w", _FP), ("pi_b", _FP), ("v_w", _FP), ("v_b", _FP),
     ]
 
@@ -199,7 +199,7 @@ def make_weights(w):
 
     for i, (cw, cb) in enumerate(zip(w["conv_w"], w["conv_b"])):
         s.conv_w[i], s.conv_b[i] = fp(cw), fp(cb)
-    for name in ("fc_w", "fc_b", "gru_w_ih", "gru_w_hh", "gru_b_ih", "gru_b_hh", "pi_w", "pi_b",
+    for name in ("fc_w", "fc_b", "rnn_w_ih", "rnn_w_hh", "rnn_b_ih", "rnn_b_hh", "pi_w", "pi_b",
                  "v_w", "v_b"):
         setattr(s, name, fp(w[name]))
     return s, keep

@@ -205,7 +205,7 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
       set_error("sf_policy_create: conv tensor %d is null", i);
       return SF_ERR_ARG;
     }
-  if (!w->fc_w || !w->fc_b || !w->gru_w_ih || !w->gru_w_hh || !w->gru_b_ih || !w->gru_b_hh ||
+  if (!w->fc_w || !w->fc_b || !w->rnn_w_ih || !w->rnn_w_hh || !w->rnn_b_ih || !w->rnn_b_hh ||
       !w->pi_w || !w->pi_b || !w->v_w || !w->v_b) {
     set_error("sf_policy_create: a weight pointer is null");
     return SF_ERR_ARG;
@@ -502,16 +502,16 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
   }
   // ---- GRU ----
   const int H3 = 3 * cfg->rnn_dim;
-  p->gru_wih_t = bld.pack_transposed(w->gru_w_ih, H3, cfg->fc_dim);
-  p->gru_whh_t = bld.pack_transposed(w->gru_w_hh, H3, cfg->rnn_dim);
+  p->gru_wih_t = bld.pack_transposed(w->rnn_w_ih, H3, cfg->fc_dim);
+  p->gru_whh_t = bld.pack_transposed(w->rnn_w_hh, H3, cfg->rnn_dim);
   p->gru_wih = p->gru_whh = nullptr;
   if (!getenv("SF_FORCE_GENERIC") && gru_mfma_supported(cfg->fc_dim, cfg->rnn_dim)) {
-    p->gru_wih = bld.pack_vec(w->gru_w_ih, (size_t)H3 * cfg->fc_dim);
-    p->gru_whh = bld.pack_vec(w->gru_w_hh, (size_t)H3 * cfg->rnn_dim);
+    p->gru_wih = bld.pack_vec(w->rnn_w_ih, (size_t)H3 * cfg->fc_dim);
+    p->gru_whh = bld.pack_vec(w->rnn_w_hh, (size_t)H3 * cfg->rnn_dim);
     p->gru_bm = getenv("SF_GRU_BM") ? atoi(getenv("SF_GRU_BM")) : gru_mfma_pick_bm(cfg->max_batch, cfg->rnn_dim);
   }
-  p->gru_bih = bld.pack_vec(w->gru_b_ih, H3);
-  p->gru_bhh = bld.pack_vec(w->gru_b_hh, H3);
+  p->gru_bih = bld.pack_vec(w->rnn_b_ih, H3);
+  p->gru_bhh = bld.pack_vec(w->rnn_b_hh, H3);
   macs += (int64_t)H3 * (cfg->fc_dim + cfg->rnn_dim);
   p->ops.push_back(Op{OP_GRU, "gru", 2 * (int64_t)H3 * (cfg->fc_dim + cfg->rnn_dim), -1, -1, -1, -1, 0, 0, 0});
   // ---- heads: action logits then the value row ----

@@ -28,6 +28,14 @@ CONFIGS = [
          fc=512, rnn=512, heads=[3, 3, 2, 2, 2, 11], dtype="fp32", p_done=0.1, steps=16),
     dict(name="resnet_bf16", B=8192, obs=(3, 72, 128), encoder="resnet", stages=[16, 32, 32],
          blocks_per_stage=2, fc=256, rnn=256, heads=[15], dtype="bf16", p_done=0.05, steps=1),
+    # the benchmark model as the paper describes it: the standard network with an LSTM core
+    dict(name="standard_lstm", B=1024, obs=(3, 72, 128), encoder="conv", convs=_STD_CONVS,
+         fc=512, rnn=512, rnn_type="lstm", heads=[7], dtype="fp32", p_done=0.05, steps=4),
+    # the "full" architecture: measurement vector through two FC layers, appended to the
+    # encoder's features; GRU core; the seven action heads of the paper's action-space table
+    dict(name="full", B=1024, obs=(3, 72, 128), encoder="conv", convs=_STD_CONVS,
+         fc=512, rnn=512, meas_dim=23, meas_hidden=[128, 128], heads=[3, 3, 2, 2, 2, 8, 21],
+         dtype="fp32", p_done=0.05, steps=4),
 ]
 
 
@@ -37,8 +45,21 @@ def network(index, **overrides):
     cfg["index"] = index
     cfg.setdefault("obs_sub", 0.0)
     cfg.setdefault("obs_mul", OBS_MUL)
+    cfg.setdefault("rnn_type", "gru")
+    cfg.setdefault("meas_dim", 0)
+    cfg.setdefault("meas_hidden", [])
     cfg.update(overrides)
     return cfg
+
+
+def state_dim(net):
+    """Floats per recurrent-state row: H for a GRU, 2H ([h | c]) for an LSTM."""
+    return net["rnn"] * (2 if net.get("rnn_type", "gru") == "lstm" else 1)
+
+
+def core_input_dim(net):
+    hidden = net.get("meas_hidden", []) if net.get("meas_dim", 0) else []
+    return net["fc"] + (hidden[-1] if hidden else 0)
 
 
 def conv_out_hw(h, w, k, s, p):
@@ -102,10 +123,19 @@ def weights(net, seed=None):
         w["conv_b"].append(draw((co,), fan))
     flat, fc, H, sumA = flat_size(net), net["fc"], net["rnn"], sum(net["heads"])
     w["fc_w"], w["fc_b"] = draw((fc, flat), flat), draw((fc,), flat)
-    w["gru_w_ih"], w["gru_b_ih"] = draw((3 * H, fc), fc), draw((3 * H,), fc)
-    w["gru_w_hh"], w["gru_b_hh"] = draw((3 * H, H), H), draw((3 * H,), H)
+    G = 4 if net.get("rnn_type", "gru") == "lstm" else 3      # gate blocks of the recurrent core
+    cin = core_input_dim(net)
+    w["rnn_w_ih"], w["rnn_b_ih"] = draw((G * H, cin), cin), draw((G * H,), cin)
+    w["rnn_w_hh"], w["rnn_b_hh"] = draw((G * H, H), H), draw((G * H,), H)
     w["pi_w"], w["pi_b"] = draw((sumA, H), H), draw((sumA,), H)
     w["v_w"], w["v_b"] = draw((H,), H), draw((1,), H)
+    # drawn last, so that networks without a measurement input keep their values
+    w["meas_w"], w["meas_b"] = [], []
+    n_prev = net.get("meas_dim", 0)
+    for m in (net.get("meas_hidden", []) if n_prev else []):
+        w["meas_w"].append(draw((m, n_prev), n_prev))
+        w["meas_b"].append(draw((m,), n_prev))
+        n_prev = m
     return w
 
 
@@ -120,7 +150,7 @@ def initial_state(net, B=None, seed=None):
     B = net["B"] if B is None else B
     seed = 3000 + net.get("index", 0) if seed is None else seed
     rng = np.random.default_rng(seed)
-    return (0.1 * rng.standard_normal((B, net["rnn"]))).astype(np.float32)
+    return (0.1 * rng.standard_normal((B, state_dim(net)))).astype(np.float32)
 
 
 def done_mask(net, t=0, B=None, seed=None):
@@ -128,6 +158,17 @@ def done_mask(net, t=0, B=None, seed=None):
     seed = 4000 + 100 * net.get("index", 0) + t if seed is None else seed
     rng = np.random.default_rng(seed)
     return (rng.random(B) < net["p_done"]).astype(np.uint8)
+
+
+def measurements(net, t=0, B=None, seed=None):
+    """The "full" architecture's low-dimensional game information (health, ammunition, ...):
+    here N(0, 1) fp32 [B, meas_dim], or None for networks without that input."""
+    if not net.get("meas_dim", 0):
+        return None
+    B = net["B"] if B is None else B
+    seed = 5000 + 100 * net.get("index", 0) + t if seed is None else seed
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((B, net["meas_dim"])).astype(np.float32)
 
 
 PHILOX_SEED = 1

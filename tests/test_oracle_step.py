@@ -35,10 +35,10 @@ def torch_step(net, w, obs, h_in, done):
     h = t(h_in) * (1.0 - torch.from_numpy(done.astype(np.float64)))[:, None]
     cell = torch.nn.GRUCell(net["fc"], net["rnn"]).double()
     with torch.no_grad():
-        cell.weight_ih.copy_(t(w["gru_w_ih"]))
-        cell.weight_hh.copy_(t(w["gru_w_hh"]))
-        cell.bias_ih.copy_(t(w["gru_b_ih"]))
-        cell.bias_hh.copy_(t(w["gru_b_hh"]))
+        cell.weight_ih.copy_(t(w["rnn_w_ih"]))
+        cell.weight_hh.copy_(t(w["rnn_w_hh"]))
+        cell.bias_ih.copy_(t(w["rnn_b_ih"]))
+        cell.bias_hh.copy_(t(w["rnn_b_hh"]))
         hn = cell(f, h)
         logits = F.linear(hn, t(w["pi_w"]), t(w["pi_b"]))
         value = F.linear(hn, t(w["v_w"])[None], t(w["v_b"]))[:, 0]
@@ -159,10 +159,10 @@ def test_observation_normalisation_is_affine_in_the_byte(ref):
     w["fc_w"][:] = 1.0
     w["fc_b"][:] = 0.0
     # make the GRU pass f through: z -> 0 (h' = n), r irrelevant, n = tanh(f): invert with atanh
-    w["gru_w_ih"][:] = np.array([[0.0], [0.0], [1.0]], np.float32)
-    w["gru_w_hh"][:] = 0.0
-    w["gru_b_ih"][:] = np.array([0.0, -80.0, 0.0], np.float32)
-    w["gru_b_hh"][:] = 0.0
+    w["rnn_w_ih"][:] = np.array([[0.0], [0.0], [1.0]], np.float32)
+    w["rnn_w_hh"][:] = 0.0
+    w["rnn_b_ih"][:] = np.array([0.0, -80.0, 0.0], np.float32)
+    w["rnn_b_hh"][:] = 0.0
     obs = np.array([0, 16, 20, 24], np.uint8).reshape(4, 1, 1, 1)
     out = ref.policy_step(net, w, obs, np.zeros((4, 1), np.float32), np.zeros(4, np.uint8), 1, 0)
     want = np.tanh(np.maximum((obs.reshape(4).astype(np.float64) - 16.0) * 0.125, 0.0))
@@ -209,8 +209,8 @@ def test_weight_recipe():
     net = wl.network(1)
     w = wl.weights(net)
     assert w["conv_w"][0].shape == (32, 3, 8, 8) and w["fc_w"].shape == (512, 2304)
-    assert w["gru_w_ih"].shape == (1536, 512) and w["pi_w"].shape == (7, 512) and w["v_w"].shape == (512,)
-    assert abs(w["fc_w"].var() * 2304 - 1) < 0.01 and abs(w["gru_w_hh"].var() * 512 - 1) < 0.01
+    assert w["rnn_w_ih"].shape == (1536, 512) and w["pi_w"].shape == (7, 512) and w["v_w"].shape == (512,)
+    assert abs(w["fc_w"].var() * 2304 - 1) < 0.01 and abs(w["rnn_w_hh"].var() * 512 - 1) < 0.01
     assert np.abs(w["fc_b"]).max() > 0
     wb = wl.weights(wl.network(2))
     for a in [wb["fc_w"], wb["conv_w"][1], wb["v_b"]]:
