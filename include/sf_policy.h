@@ -41,11 +41,12 @@
 extern "C" {
 #endif
 
-#define SF_ABI_VERSION 1u
+#define SF_ABI_VERSION 2u
 #define SF_MAX_CONV 4
 #define SF_MAX_STAGE 4
 #define SF_MAX_HEADS 16
 #define SF_MAX_CONV_TENSORS 20
+#define SF_MAX_MEAS_LAYERS 2
 
 enum {
   SF_OK = 0,
@@ -60,6 +61,7 @@ enum {
 
 enum { SF_ENCODER_CONV = 0, SF_ENCODER_RESNET = 1 };
 enum { SF_DTYPE_FP32 = 0, SF_DTYPE_BF16 = 1 };
+enum { SF_RNN_GRU = 0, SF_RNN_LSTM = 1 };
 
 typedef struct sf_policy sf_policy; /* opaque */
 
@@ -83,24 +85,41 @@ typedef struct {
   int32_t stage_ch[SF_MAX_STAGE];
   int32_t blocks_per_stage;
   int32_t fc_dim;  /* fully connected layer after the encoder, followed by ReLU */
-  int32_t rnn_dim; /* GRU hidden size H */
+  int32_t rnn_dim; /* hidden size H of the recurrent core */
   int32_t n_heads; /* independent categorical heads */
   int32_t head_sizes[SF_MAX_HEADS];
   int32_t dtype; /* SF_DTYPE_FP32, or SF_DTYPE_BF16: weights and encoder/FC activations
                     in bf16 with fp32 accumulation; the GRU state, the gate arithmetic,
                     the heads and the sampler stay fp32 */
   float obs_sub, obs_mul; /* normalisation: x = ((float)byte - obs_sub) * obs_mul */
+  int32_t rnn_type; /* SF_RNN_GRU, or SF_RNN_LSTM (the core of the paper's benchmark model, App.
+                       "Model architectures").  A state row ("state_dim" floats below) is
+                       h [rnn_dim] for a GRU and [h | c] = 2 * rnn_dim floats for an LSTM. */
+  int32_t meas_dim; /* > 0: the "full" architecture (paper, App. "VizDoom experiments"): each row
+                       also carries meas_dim fp32 measurements (health, ammunition, ...), which
+                       pass n_meas_layers fully connected + ReLU layers of widths meas_hidden[]
+                       and are appended to the FC layer's output: the core's input then has
+                       fc_dim + meas_hidden[n_meas_layers - 1] features.  0: no such input. */
+  int32_t n_meas_layers; /* 1..SF_MAX_MEAS_LAYERS when meas_dim > 0 */
+  int32_t meas_hidden[SF_MAX_MEAS_LAYERS];
 } sf_policy_config;
 
 /* HOST pointers to fp32 parameters in canonical layouts; read during create only.
  *   conv_w[i]: [cout][cin][k][k], conv_b[i]: [cout].  Residual encoder: per stage
  *              the stage convolution, then each block's two convolutions in order.
  *   fc_w: [fc_dim][flat], flat index = c*(Hf*Wf) + y*Wf + x of the encoder output.
- *   GRU:  w_ih [3H][fc_dim], w_hh [3H][H], b_ih [3H], b_hh [3H]; gate rows r, z, n:
+ *   GRU:  rnn_w_ih [3H][core_in], rnn_w_hh [3H][H], rnn_b_ih [3H], rnn_b_hh [3H], with
+ *         core_in = fc_dim (+ the last measurement layer's width); gate rows r, z, n:
  *           r = sigmoid(W_ir x + b_ir + W_hr h + b_hr)
  *           z = sigmoid(W_iz x + b_iz + W_hz h + b_hz)
  *           n = tanh   (W_in x + b_in + r * (W_hn h + b_hn))
  *           h_out = (1 - z) * n + z * h,   h = done ? 0 : h_in
+ *   LSTM: the same four tensors with 4H rows; gate rows i, f, g, o:
+ *           i, f, o = sigmoid(W_i* x + b_i* + W_h* h + b_h*)
+ *           g = tanh(W_ig x + b_ig + W_hg h + b_hg)
+ *           c_out = f * c + i * g,  h_out = o * tanh(c_out),  (h, c) = done ? 0 : state_in
+ *   meas_w[l]: [meas_hidden[l]][width of the previous layer (meas_dim for l = 0)],
+ *   meas_b[l]: [meas_hidden[l]]; unused when meas_dim == 0
  *   pi_w: [sum(head_sizes)][H], pi_b: [sum(head_sizes)] (heads concatenated in order)
  *   v_w:  [H], v_b: [1] */
 typedef struct {
@@ -116,6 +135,8 @@ typedef struct {
   const float* pi_b;
   const float* v_w;
   const float* v_b;
+  const float* meas_w[SF_MAX_MEAS_LAYERS];
+  const float* meas_b[SF_MAX_MEAS_LAYERS];
 } sf_policy_weights;
 
 /* Build a policy on HIP device `hip_device`: validates the description, packs the
@@ -128,7 +149,9 @@ int sf_policy_create(const sf_policy_config* cfg, const sf_policy_weights* weigh
 /* One step of the policy worker (paper, Sec. 3.1) on B rows, enqueued
  * asynchronously on `hip_stream` (a hipStream_t; NULL = the default stream).
  *   obs        dev  [B][obs_c][obs_h][obs_w] bytes (planar frames), 4-byte aligned
- *   h_in       dev  [B][rnn_dim] fp32, 16-byte aligned
+ *   meas       dev  [B][meas_dim] fp32, 4-byte aligned; ignored (may be NULL) when the
+ *                   policy has no measurement input
+ *   h_in       dev  [B][state_dim] fp32, 16-byte aligned
  *   done       dev  [B] bytes; non-zero = this observation is the first of a new
  *                   episode: the incoming state is zeroed before the GRU cell
  *   seed, step      sampler key and time step.  Category i of head k in row b is
@@ -140,15 +163,15 @@ int sf_policy_create(const sf_policy_config* cfg, const sf_policy_weights* weigh
  *   actions    dev  [B][n_heads] int32
  *   logp       dev  [B] fp32, log-probability of the sampled joint action
  *   value      dev  [B] fp32
- *   h_out      dev  [B][rnn_dim] fp32, 16-byte aligned; must not overlap h_in
+ *   h_out      dev  [B][state_dim] fp32, 16-byte aligned; must not overlap h_in
  *   logits_opt dev  [B][sum(head_sizes)] fp32, or NULL if not wanted
  * B == 0 is accepted and does nothing.  Errors: SF_ERR_ARG (null handle or
  * pointer, misaligned pointer), SF_ERR_BATCH, SF_ERR_ALIAS,
  * SF_ERR_DEVICE (a launch failed).  Nothing is enqueued when an error is
  * returned for the arguments. */
-int sf_policy_step(sf_policy* p, int32_t B, const uint8_t* obs, const float* h_in,
-                   const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions,
-                   float* logp, float* value, float* h_out, float* logits_opt,
+int sf_policy_step(sf_policy* p, int32_t B, const uint8_t* obs, const float* meas,
+                   const float* h_in, const uint8_t* done, uint64_t seed, uint64_t step,
+                   int32_t* actions, float* logp, float* value, float* h_out, float* logits_opt,
                    void* hip_stream);
 
 /* The same step when the batch rows are a subset of a larger population of
@@ -157,7 +180,7 @@ int sf_policy_step(sf_policy* p, int32_t B, const uint8_t* obs, const float* h_i
  * Sec. 3.2: with double-buffered sampling the policy worker is given the two
  * halves of a worker's environments in alternation).  Row b stands for
  * environment e = env_ids[b]:
- *   h_table    dev  [n_env][rnn_dim] fp32, 16-byte aligned.  Row e is read as the
+ *   h_table    dev  [n_env][state_dim] fp32, 16-byte aligned.  Row e is read as the
  *                   row's incoming state (zeroed by done[b] as above) and
  *                   overwritten with its new state; rows that no batch row names
  *                   are not touched.
@@ -172,10 +195,13 @@ int sf_policy_step(sf_policy* p, int32_t B, const uint8_t* obs, const float* h_i
  * handle's workspace, so the call is, like sf_policy_step, asynchronous and
  * allocation-free.  Errors: SF_ERR_ARG (null handle or pointer, misaligned
  * pointer, n_env < 1), SF_ERR_BATCH, SF_ERR_DEVICE. */
-int sf_policy_step_indexed(sf_policy* p, int32_t B, const uint8_t* obs, float* h_table,
-                           int32_t n_env, const int32_t* env_ids, const uint8_t* done,
+int sf_policy_step_indexed(sf_policy* p, int32_t B, const uint8_t* obs, const float* meas,
+                           float* h_table, int32_t n_env, const int32_t* env_ids, const uint8_t* done,
                            uint64_t seed, uint64_t step, int32_t* actions, float* logp,
                            float* value, float* logits_opt, void* hip_stream);
+
+/* Floats per recurrent-state row of this policy: rnn_dim (GRU) or 2 * rnn_dim (LSTM). */
+int32_t sf_policy_state_dim(const sf_policy* p);
 
 /* Free the workspace and the packed weights.  The caller must have synchronised
  * every stream the handle was stepped on.  NULL is accepted. */
@@ -218,12 +244,13 @@ int sf_copy_bytes(const void* src, void* dst, int64_t bytes, void* hip_stream);
  * other are computed.  The steps of the slots run in submission order on the one
  * compute stream (they share the policy's workspace and the state table).
  *
- * sf_pipeline_submit enqueues, for slot `slot`: the copies of obs, done and
+ * sf_pipeline_submit enqueues, for slot `slot`: the copies of obs, meas, done and
  * env_ids to the device, sf_policy_step_indexed on them, and the copies of
  * actions, logp and value back to the host; it returns without waiting.
  *   host_obs      host [B][obs_c][obs_h][obs_w] bytes
+ *   host_meas     host [B][meas_dim] fp32; ignored (may be NULL) without a measurement input
  *   host_done     host [B] bytes;  host_env_ids  host [B] int32
- *   h_table       dev  [n_env][rnn_dim] fp32 (stays on the device)
+ *   h_table       dev  [n_env][state_dim] fp32 (stays on the device)
  *   host_actions  host [B][n_heads] int32; host_logp, host_value  host [B] fp32
  * Host buffers should be page-locked (hipHostMalloc); with pageable memory the
  * copies still work but do not overlap.  They belong to the caller and must stay
@@ -239,7 +266,8 @@ int sf_copy_bytes(const void* src, void* dst, int64_t bytes, void* hip_stream);
 typedef struct sf_pipeline sf_pipeline; /* opaque */
 int sf_pipeline_create(sf_policy* policy, int32_t slot_batch, int32_t n_slots, sf_pipeline** out);
 int sf_pipeline_submit(sf_pipeline* pl, int32_t slot, int32_t B, const uint8_t* host_obs,
-                       const uint8_t* host_done, const int32_t* host_env_ids, float* h_table,
+                       const float* host_meas, const uint8_t* host_done,
+                       const int32_t* host_env_ids, float* h_table,
                        int32_t n_env, uint64_t seed, uint64_t step, int32_t* host_actions,
                        float* host_logp, float* host_value);
 int sf_pipeline_wait(sf_pipeline* pl, int32_t slot);

@@ -16,8 +16,10 @@ _ROOT = os.path.dirname(_PKG)
 _CSRC = os.path.join(_PKG, "csrc")
 _SO = os.path.join(_PKG, "libsf_policy.so")
 
-SF_ABI_VERSION = 1
+SF_ABI_VERSION = 2
 SF_MAX_CONV, SF_MAX_STAGE, SF_MAX_HEADS, SF_MAX_CONV_TENSORS = 4, 4, 16, 20
+SF_MAX_MEAS_LAYERS = 2
+SF_RNN_GRU, SF_RNN_LSTM = 0, 1
 SF_OK, SF_ERR_ARG, SF_ERR_SHAPE, SF_ERR_BATCH, SF_ERR_ALIAS = 0, -1, -2, -3, -4
 SF_ERR_DEVICE, SF_ERR_OOM, SF_ERR_ARCH = -5, -6, -7
 
@@ -72,6 +74,8 @@ class SfPolicyConfig(C.Structure):
         ("fc_dim", C.c_int32), ("rnn_dim", C.c_int32), ("n_heads", C.c_int32),
         ("head_sizes", C.c_int32 * SF_MAX_HEADS), ("dtype", C.c_int32),
         ("obs_sub", C.c_float), ("obs_mul", C.c_float),
+        ("rnn_type", C.c_int32), ("meas_dim", C.c_int32), ("n_meas_layers", C.c_int32),
+        ("meas_hidden", C.c_int32 * SF_MAX_MEAS_LAYERS),
     ]
 
 
@@ -84,6 +88,7 @@ class SfPolicyWeights(C.Structure):
         ("fc_w", _FP), ("fc_b", _FP),
         ("rnn_w_ih", _FP), ("rnn_w_hh", _FP), ("rnn_b_ih", _FP), ("rnn_b_hh", _FP),
         ("pi_w", _FP), ("pi_b", _FP), ("v_w", _FP), ("v_b", _FP),
+        ("meas_w", _FP * SF_MAX_MEAS_LAYERS), ("meas_b", _FP * SF_MAX_MEAS_LAYERS),
     ]
 
 
@@ -91,7 +96,7 @@ EXPORTS = ("sf_policy_create", "sf_policy_step", "sf_policy_destroy", "sf_last_e
            "sf_policy_flops_per_row", "sf_policy_op_count", "sf_policy_op_name",
            "sf_policy_op_flops_per_row", "sf_policy_set_op_timing", "sf_policy_last_op_times",
            "sf_copy_bytes", "sf_policy_step_indexed", "sf_pipeline_create", "sf_pipeline_submit",
-           "sf_pipeline_wait", "sf_pipeline_destroy")
+           "sf_pipeline_wait", "sf_pipeline_destroy", "sf_policy_state_dim")
 
 _lib = None
 
@@ -120,8 +125,10 @@ def load_library():
                                        C.c_int, C.POINTER(C.c_void_p)]
         L.sf_policy_step.restype = C.c_int
         L.sf_policy_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
-                                     C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
-                                     C.c_void_p, C.c_void_p, C.c_void_p]
+                                     C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sf_policy_state_dim.restype = C.c_int32
+        L.sf_policy_state_dim.argtypes = [C.c_void_p]
         L.sf_policy_destroy.restype = C.c_int
         L.sf_policy_destroy.argtypes = [C.c_void_p]
         L.sf_last_error.restype = C.c_char_p
@@ -140,15 +147,16 @@ def load_library():
         L.sf_copy_bytes.restype = C.c_int
         L.sf_copy_bytes.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.sf_policy_step_indexed.restype = C.c_int
-        L.sf_policy_step_indexed.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
-                                             C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
+        L.sf_policy_step_indexed.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_int32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.c_void_p]
         L.sf_pipeline_create.restype = C.c_int
         L.sf_pipeline_create.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
         L.sf_pipeline_submit.restype = C.c_int
         L.sf_pipeline_submit.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
-                                         C.c_void_p, C.c_void_p, C.c_int32, C.c_uint64, C.c_uint64,
+                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_uint64,
+                                         C.c_uint64,
                                          C.c_void_p, C.c_void_p, C.c_void_p]
         L.sf_pipeline_wait.restype = C.c_int
         L.sf_pipeline_wait.argtypes = [C.c_void_p, C.c_int32]
@@ -184,6 +192,12 @@ def make_config(net, max_batch):
         c.head_sizes[i] = a
     c.dtype = 1 if net["dtype"] == "bf16" else 0
     c.obs_sub, c.obs_mul = net["obs_sub"], net["obs_mul"]
+    c.rnn_type = SF_RNN_LSTM if net.get("rnn_type", "gru") == "lstm" else SF_RNN_GRU
+    c.meas_dim = net.get("meas_dim", 0)
+    hidden = net.get("meas_hidden", []) if c.meas_dim else []
+    c.n_meas_layers = len(hidden)
+    for i, m in enumerate(hidden):
+        c.meas_hidden[i] = m
     return c
 
 
@@ -202,6 +216,8 @@ def make_weights(w):
     for name in ("fc_w", "fc_b", "rnn_w_ih", "rnn_w_hh", "rnn_b_ih", "rnn_b_hh", "pi_w", "pi_b",
                  "v_w", "v_b"):
         setattr(s, name, fp(w[name]))
+    for i, (mw, mb) in enumerate(zip(w.get("meas_w", []), w.get("meas_b", []))):
+        s.meas_w[i], s.meas_b[i] = fp(mw), fp(mb)
     return s, keep
 
 
@@ -214,20 +230,21 @@ def sf_policy_create(cfg, weights, hip_device=0):
     return h.value
 
 
-def sf_policy_step(handle, B, obs, h_in, done, seed, step, actions, logp, value, h_out,
+def sf_policy_step(handle, B, obs, meas, h_in, done, seed, step, actions, logp, value, h_out,
                    logits_opt=None, hip_stream=None):
-    """All buffers are device addresses (ints), e.g. torch.Tensor.data_ptr()."""
-    rc = load_library().sf_policy_step(handle, B, obs, h_in, done, seed, step, actions, logp,
+    """All buffers are device addresses (ints), e.g. torch.Tensor.data_ptr(); meas is None for
+    policies without a measurement input."""
+    rc = load_library().sf_policy_step(handle, B, obs, meas, h_in, done, seed, step, actions, logp,
                                        value, h_out, logits_opt, hip_stream)
     if rc != SF_OK:
         raise SfError(rc, sf_last_error())
 
 
-def sf_policy_step_indexed(handle, B, obs, h_table, n_env, env_ids, done, seed, step, actions, logp,
-                           value, logits_opt=None, hip_stream=None):
-    """Device addresses (ints); h_table [n_env, rnn_dim] is read and written at rows env_ids."""
-    rc = load_library().sf_policy_step_indexed(handle, B, obs, h_table, n_env, env_ids, done, seed,
-                                               step, actions, logp, value, logits_opt, hip_stream)
+def sf_policy_step_indexed(handle, B, obs, meas, h_table, n_env, env_ids, done, seed, step, actions,
+                           logp, value, logits_opt=None, hip_stream=None):
+    """Device addresses (ints); h_table [n_env, state_dim] is read and written at rows env_ids."""
+    rc = load_library().sf_policy_step_indexed(handle, B, obs, meas, h_table, n_env, env_ids, done,
+                                               seed, step, actions, logp, value, logits_opt, hip_stream)
     if rc != SF_OK:
         raise SfError(rc, sf_last_error())
 
@@ -240,11 +257,12 @@ def sf_pipeline_create(policy_handle, slot_batch, n_slots):
     return h
 
 
-def sf_pipeline_submit(handle, slot, B, host_obs, host_done, host_env_ids, h_table, n_env, seed, step,
-                       host_actions, host_logp, host_value):
+def sf_pipeline_submit(handle, slot, B, host_obs, host_meas, host_done, host_env_ids, h_table, n_env,
+                       seed, step, host_actions, host_logp, host_value):
     """host_*: host addresses (page-locked for overlap); h_table: device address."""
-    rc = load_library().sf_pipeline_submit(handle, slot, B, host_obs, host_done, host_env_ids, h_table,
-                                           n_env, seed, step, host_actions, host_logp, host_value)
+    rc = load_library().sf_pipeline_submit(handle, slot, B, host_obs, host_meas, host_done,
+                                           host_env_ids, h_table, n_env, seed, step, host_actions,
+                                           host_logp, host_value)
     if rc != SF_OK:
         raise SfError(rc, sf_last_error())
 
@@ -284,7 +302,9 @@ class Policy:
         ws, keep = make_weights(weights)
         self.handle = sf_policy_create(cfg, ws, device)
         del keep
-        self.n_heads, self.sumA, self.H = len(net["heads"]), sum(net["heads"]), net["rnn"]
+        self.n_heads, self.sumA = len(net["heads"]), sum(net["heads"])
+        self.H = int(load_library().sf_policy_state_dim(self.handle))  # floats per state row
+        self.meas_dim = net.get("meas_dim", 0)
 
     def flops_per_row(self):
         return int(load_library().sf_policy_flops_per_row(self.handle))
@@ -319,8 +339,17 @@ class Policy:
                     h_out=t.empty((B, self.H), dtype=t.float32, device=d),
                     logits=t.empty((B, self.sumA), dtype=t.float32, device=d) if logits else None)
 
-    def step(self, obs, h_in, done, seed, step, out=None, stream=None):
-        """obs u8 [B,C,H,W], h_in f32 [B,H], done u8 [B]: contiguous CUDA tensors."""
+    def _meas_ptr(self, meas, B):
+        if not self.meas_dim:
+            return None
+        t = self._torch
+        assert meas is not None and meas.dtype == t.float32 and meas.is_contiguous()
+        assert tuple(meas.shape) == (B, self.meas_dim)
+        return meas.data_ptr()
+
+    def step(self, obs, h_in, done, seed, step, out=None, stream=None, meas=None):
+        """obs u8 [B,C,H,W], h_in f32 [B,state_dim], done u8 [B], meas f32 [B,meas_dim] (full
+        architecture only): contiguous tensors (CUDA, or page-locked for meas in a Pipeline)."""
         t = self._torch
         B = obs.shape[0]
         assert obs.dtype == t.uint8 and h_in.dtype == t.float32 and done.dtype == t.uint8
@@ -330,14 +359,15 @@ class Policy:
         if out is None:
             out = self.alloc_outputs(B)
         s = stream if stream is not None else t.cuda.current_stream(self.device)
-        sf_policy_step(self.handle, B, obs.data_ptr(), h_in.data_ptr(), done.data_ptr(), seed, step,
+        sf_policy_step(self.handle, B, obs.data_ptr(), self._meas_ptr(meas, B), h_in.data_ptr(),
+                       done.data_ptr(), seed, step,
                        out["actions"].data_ptr(), out["logp"].data_ptr(), out["value"].data_ptr(),
                        out["h_out"].data_ptr(),
                        out["logits"].data_ptr() if out.get("logits") is not None else None,
                        s.cuda_stream)
         return out
 
-    def step_indexed(self, obs, h_table, env_ids, done, seed, step, out=None, stream=None):
+    def step_indexed(self, obs, h_table, env_ids, done, seed, step, out=None, stream=None, meas=None):
         """obs u8 [B,C,H,W], h_table f32 [n_env,H] (updated in place at rows env_ids),
         env_ids i32 [B], done u8 [B]: contiguous CUDA tensors."""
         t = self._torch
@@ -351,7 +381,8 @@ class Policy:
             out = self.alloc_outputs(B)
             del out["h_out"]
         s = stream if stream is not None else t.cuda.current_stream(self.device)
-        sf_policy_step_indexed(self.handle, B, obs.data_ptr(), h_table.data_ptr(), h_table.shape[0],
+        sf_policy_step_indexed(self.handle, B, obs.data_ptr(), self._meas_ptr(meas, B),
+                               h_table.data_ptr(), h_table.shape[0],
                                env_ids.data_ptr(), done.data_ptr(), seed, step,
                                out["actions"].data_ptr(), out["logp"].data_ptr(),
                                out["value"].data_ptr(),
@@ -389,7 +420,9 @@ class Pipeline:
         t = self._torch
         B = self.slot_batch if B is None else B
         pin = dict(pin_memory=True)
+        md = self.policy.meas_dim
         return dict(obs=t.empty((B,) + tuple(self.policy.net["obs"]), dtype=t.uint8, **pin),
+                    meas=t.empty((B, md), dtype=t.float32, **pin) if md else None,
                     done=t.empty(B, dtype=t.uint8, **pin), env_ids=t.empty(B, dtype=t.int32, **pin),
                     actions=t.empty((B, self.policy.n_heads), dtype=t.int32, **pin),
                     logp=t.empty(B, dtype=t.float32, **pin), value=t.empty(B, dtype=t.float32, **pin))
@@ -398,7 +431,9 @@ class Pipeline:
         B = hb["obs"].shape[0] if B is None else B
         for k in ("obs", "done", "env_ids", "actions", "logp", "value"):
             assert hb[k].is_contiguous() and not hb[k].is_cuda
-        sf_pipeline_submit(self.handle, slot, B, hb["obs"].data_ptr(), hb["done"].data_ptr(),
+        sf_pipeline_submit(self.handle, slot, B, hb["obs"].data_ptr(),
+                           self.policy._meas_ptr(hb.get("meas"), hb["obs"].shape[0]),
+                           hb["done"].data_ptr(),
                            hb["env_ids"].data_ptr(), h_table.data_ptr(), h_table.shape[0], seed, step,
                            hb["actions"].data_ptr(), hb["logp"].data_ptr(), hb["value"].data_ptr())
         self._keep[slot] = (hb, h_table)  # the buffers stay alive while the slot is in flight

@@ -95,13 +95,19 @@ __global__ __launch_bounds__(kThreads) void linear_generic_kernel(
 
 __device__ inline float sigmoidf_acc(float a) { return 1.0f / (1.0f + expf(-a)); }
 
-// GRU cell with the episode-boundary reset applied to the incoming state.
-// Gate columns of the transposed weights: [0,H) r, [H,2H) z, [2H,3H) n.
-__global__ __launch_bounds__(kThreads) void gru_generic_kernel(
-    const float* __restrict__ x, const float* __restrict__ h_in, const uint8_t* __restrict__ done,
+// Recurrent cell (GRU or LSTM) with the episode-boundary reset applied to the incoming
+// state, any sizes.  One thread per (row, hidden unit).  The input features come in one or
+// two pieces (x2 may be null); the transposed weights have one column block of H per gate:
+// GRU r, z, n; LSTM i, f, g, o.  State rows hold H floats (GRU) or [h | c] (LSTM).
+template <bool LSTM>
+__global__ __launch_bounds__(kThreads) void rnn_generic_kernel(
+    const float* __restrict__ x1, int n1, const float* __restrict__ x2, int n2,
+    const float* __restrict__ h_in, const uint8_t* __restrict__ done,
     const float* __restrict__ wih_t, const float* __restrict__ whh_t,
     const float* __restrict__ bih, const float* __restrict__ bhh, float* __restrict__ h_out,
-    int n_in, int H, const int32_t* __restrict__ ids, int n_env) {
+    int H, const int32_t* __restrict__ ids, int n_env) {
+  constexpr int G = LSTM ? 4 : 3;
+  const int S = LSTM ? 2 * H : H;
   int j = blockIdx.x * kThreads + threadIdx.x;
   int b = blockIdx.y;
   if (j >= H) return;
@@ -114,32 +120,45 @@ __global__ __launch_bounds__(kThreads) void gru_generic_kernel(
     hb = ok ? e : 0;
     reset = reset || !ok;
   }
-  const float* xp = x + (size_t)b * n_in;
-  const float* hp = h_in + (size_t)hb * H;
-  float ir = bih[j], iz = bih[H + j], in_ = bih[2 * H + j];
-  for (int i = 0; i < n_in; ++i) {
-    float v = xp[i];
-    const float* wp = wih_t + (size_t)i * 3 * H + j;
-    ir = fmaf(v, wp[0], ir);
-    iz = fmaf(v, wp[H], iz);
-    in_ = fmaf(v, wp[2 * H], in_);
+  const float* hp = h_in + (size_t)hb * S;
+  float gi[G], gh[G];
+#pragma unroll
+  for (int q = 0; q < G; ++q) {
+    gi[q] = bih[q * H + j];
+    gh[q] = bhh[q * H + j];
   }
-  float hr = bhh[j], hz = bhh[H + j], hn = bhh[2 * H + j];
+  for (int i = 0; i < n1 + n2; ++i) {
+    const float v = i < n1 ? x1[(size_t)b * n1 + i] : x2[(size_t)b * n2 + (i - n1)];
+    const float* wp = wih_t + (size_t)i * G * H + j;
+#pragma unroll
+    for (int q = 0; q < G; ++q) gi[q] = fmaf(v, wp[q * H], gi[q]);
+  }
   if (!reset) {
     for (int i = 0; i < H; ++i) {
-      float v = hp[i];
-      const float* wp = whh_t + (size_t)i * 3 * H + j;
-      hr = fmaf(v, wp[0], hr);
-      hz = fmaf(v, wp[H], hz);
-      hn = fmaf(v, wp[2 * H], hn);
+      const float v = hp[i];
+      const float* wp = whh_t + (size_t)i * G * H + j;
+#pragma unroll
+      for (int q = 0; q < G; ++q) gh[q] = fmaf(v, wp[q * H], gh[q]);
     }
   }
-  float hprev = reset ? 0.0f : hp[j];
-  float r = sigmoidf_acc(ir + hr);
-  float z = sigmoidf_acc(iz + hz);
-  float n = tanhf(in_ + r * hn);
-  h_out[(size_t)b * H + j] = (1.0f - z) * n + z * hprev;
+  if (LSTM) {
+    const float cprev = reset ? 0.0f : hp[H + j];
+    const float ig = sigmoidf_acc(gi[0] + gh[0]);
+    const float fg = sigmoidf_acc(gi[1] + gh[1]);
+    const float gg = tanhf(gi[2] + gh[2]);
+    const float og = sigmoidf_acc(gi[G - 1] + gh[G - 1]);
+    const float cn = fg * cprev + ig * gg;
+    h_out[(size_t)b * S + H + j] = cn;
+    h_out[(size_t)b * S + j] = og * tanhf(cn);
+  } else {
+    const float hprev = reset ? 0.0f : hp[j];
+    const float r = sigmoidf_acc(gi[0] + gh[0]);
+    const float z = sigmoidf_acc(gi[1] + gh[1]);
+    const float n = tanhf(gi[2] + r * gh[2]);
+    h_out[(size_t)b * S + j] = (1.0f - z) * n + z * hprev;
+  }
 }
+
 
 // Plain copy of 16-byte words: the known-size reference for scaling HBM byte counters.
 __global__ __launch_bounds__(kThreads) void copy16_kernel(const uint4* __restrict__ src,
@@ -186,14 +205,19 @@ hipError_t launch_linear_generic(int B, int n_in, int n_out, const float* in, co
   return hipGetLastError();
 }
 
-hipError_t launch_gru_generic(int B, int n_in, int H, const float* x, const float* h_in,
-                              const uint8_t* done, const float* wih_t, const float* whh_t,
-                              const float* bih, const float* bhh, float* h_out,
+hipError_t launch_rnn_generic(int lstm, int B, int n1, int n2, int H, const float* x1, const float* x2,
+                              const float* h_in, const uint8_t* done, const float* wih_t,
+                              const float* whh_t, const float* bih, const float* bhh, float* h_out,
                               const int32_t* ids, int n_env, hipStream_t st) {
   if (B == 0) return hipSuccess;
   dim3 grid((H + kThreads - 1) / kThreads, B);
-  gru_generic_kernel<<<grid, kThreads, 0, st>>>(x, h_in, done, wih_t, whh_t, bih, bhh, h_out,
-                                                n_in, H, ids, n_env);
+  if (!x2) n2 = 0;
+  if (lstm)
+    rnn_generic_kernel<true><<<grid, kThreads, 0, st>>>(x1, n1, x2, n2, h_in, done, wih_t, whh_t, bih,
+                                                        bhh, h_out, H, ids, n_env);
+  else
+    rnn_generic_kernel<false><<<grid, kThreads, 0, st>>>(x1, n1, x2, n2, h_in, done, wih_t, whh_t, bih,
+                                                         bhh, h_out, H, ids, n_env);
   return hipGetLastError();
 }
 

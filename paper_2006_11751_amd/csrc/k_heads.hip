@@ -58,20 +58,21 @@ __global__ __launch_bounds__(kWave* kRowsPerBlock) void heads_kernel(
     int n_heads, int sumA, uint32_t seed_lo, uint32_t seed_hi, uint32_t step_lo,
     uint32_t step_hi, int32_t* __restrict__ actions, float* __restrict__ logp,
     float* __restrict__ value, float* __restrict__ logits_opt, const int32_t* __restrict__ ids,
-    float* __restrict__ h_table, int n_env) {
+    float* __restrict__ h_table, int n_env, int S) {
   __shared__ float s_logits[kRowsPerBlock][kMaxLogits];
   const int lane = threadIdx.x % kWave;
   const int wave = threadIdx.x / kWave;
   const int b = blockIdx.x * kRowsPerBlock + wave;
   if (b >= B) return;  // whole wave leaves together; no block-level barrier below
   float* lg = s_logits[wave];
-  const float* hp = h + (size_t)b * H;
+  // state rows hold S >= H floats; the heads read the first H (an LSTM's h)
+  const float* hp = h + (size_t)b * S;
   // With ids, the row stands for environment ids[b]: that is the sampler's counter word, and
   // the row's new state goes back to row ids[b] of the state table (ids outside the table
   // write nothing).
   const uint32_t env = ids ? (uint32_t)ids[b] : (uint32_t)b;
   if (h_table && env < (uint32_t)n_env)
-    for (int i = lane; i < H; i += kWave) h_table[(size_t)env * H + i] = hp[i];
+    for (int i = lane; i < S; i += kWave) h_table[(size_t)env * S + i] = hp[i];
 
   // logits and value: lane-strided dot products, butterfly reduction (fixed order).
   // Outputs are processed eight at a time so that their loads are all in flight
@@ -151,14 +152,14 @@ hipError_t launch_heads(int B, int H, int n_heads, int sumA, const int32_t* head
                         const float* h, const float* head_w, const float* head_b, uint64_t seed,
                         uint64_t step, int32_t* actions, float* logp, float* value,
                         float* logits_opt, const int32_t* ids, float* h_table, int n_env,
-                        hipStream_t st) {
+                        int state_dim, hipStream_t st) {
   if (B == 0) return hipSuccess;
   if (sumA + 1 > kMaxLogits) return hipErrorInvalidValue;
   unsigned blocks = (unsigned)((B + kRowsPerBlock - 1) / kRowsPerBlock);
   heads_kernel<<<blocks, kWave * kRowsPerBlock, 0, st>>>(
       h, head_w, head_b, head_off, B, H, n_heads, sumA, (uint32_t)seed, (uint32_t)(seed >> 32),
       (uint32_t)step, (uint32_t)(step >> 32), actions, logp, value, logits_opt, ids, h_table,
-      n_env);
+      n_env, state_dim);
   return hipGetLastError();
 }
 

@@ -160,6 +160,25 @@ int check_config(const sf_policy_config* c, int* Cf, int* Hf, int* Wf) {
     set_error("unknown dtype %d", c->dtype);
     return SF_ERR_SHAPE;
   }
+  if (c->rnn_type != SF_RNN_GRU && c->rnn_type != SF_RNN_LSTM) {
+    set_error("unknown rnn_type %d", c->rnn_type);
+    return SF_ERR_SHAPE;
+  }
+  if (c->meas_dim < 0 || c->meas_dim > 65535) {
+    set_error("meas_dim %d outside [0, 65535]", c->meas_dim);
+    return SF_ERR_SHAPE;
+  }
+  if (c->meas_dim > 0) {
+    if (c->n_meas_layers < 1 || c->n_meas_layers > SF_MAX_MEAS_LAYERS) {
+      set_error("n_meas_layers %d outside [1, %d]", c->n_meas_layers, SF_MAX_MEAS_LAYERS);
+      return SF_ERR_SHAPE;
+    }
+    for (int l = 0; l < c->n_meas_layers; ++l)
+      if (c->meas_hidden[l] < 1 || c->meas_hidden[l] > 65535) {
+        set_error("measurement layer %d has width %d", l, c->meas_hidden[l]);
+        return SF_ERR_SHAPE;
+      }
+  }
   *Cf = C;
   *Hf = H;
   *Wf = W;
@@ -210,6 +229,11 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
     set_error("sf_policy_create: a weight pointer is null");
     return SF_ERR_ARG;
   }
+  for (int l = 0; cfg->meas_dim > 0 && l < cfg->n_meas_layers; ++l)
+    if (!w->meas_w[l] || !w->meas_b[l]) {
+      set_error("sf_policy_create: measurement layer %d has a null weight pointer", l);
+      return SF_ERR_ARG;
+    }
 
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) != hipSuccess || hip_device < 0 || hip_device >= n_dev) {
@@ -500,20 +524,42 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
     macs += (int64_t)p->flat * cfg->fc_dim;
     p->ops.push_back(Op{OP_FC, "fc", 2 * (int64_t)p->flat * cfg->fc_dim, -1, p->enc_buf, -1, -1, 0, 0, 0});
   }
-  // ---- GRU ----
-  const int H3 = 3 * cfg->rnn_dim;
-  p->gru_wih_t = bld.pack_transposed(w->rnn_w_ih, H3, cfg->fc_dim);
-  p->gru_whh_t = bld.pack_transposed(w->rnn_w_hh, H3, cfg->rnn_dim);
-  p->gru_wih = p->gru_whh = nullptr;
-  if (!getenv("SF_FORCE_GENERIC") && gru_mfma_supported(cfg->fc_dim, cfg->rnn_dim)) {
-    p->gru_wih = bld.pack_vec(w->rnn_w_ih, (size_t)H3 * cfg->fc_dim);
-    p->gru_whh = bld.pack_vec(w->rnn_w_hh, (size_t)H3 * cfg->rnn_dim);
-    p->gru_bm = getenv("SF_GRU_BM") ? atoi(getenv("SF_GRU_BM")) : gru_mfma_pick_bm(cfg->max_batch, cfg->rnn_dim);
+  // ---- measurement encoder (full architecture): FC + ReLU layers, any sizes ----
+  p->n_meas = cfg->meas_dim > 0 ? cfg->n_meas_layers : 0;
+  p->meas_out_dim = 0;
+  {
+    int n_prev = cfg->meas_dim;
+    for (int l = 0; l < p->n_meas; ++l) {
+      const int n_out = cfg->meas_hidden[l];
+      p->meas_w_t[l] = bld.pack_transposed(w->meas_w[l], n_out, n_prev);
+      p->meas_b[l] = bld.pack_vec(w->meas_b[l], n_out);
+      p->meas_in_dim[l] = n_prev;
+      macs += (int64_t)n_out * n_prev;
+      char nm[32];
+      snprintf(nm, sizeof(nm), "meas.fc%d", l + 1);
+      p->ops.push_back(Op{OP_MEAS, nm, 2 * (int64_t)n_out * n_prev, l, -1, -1, -1, 0, 0, 0});
+      n_prev = n_out;
+    }
+    if (p->n_meas) p->meas_out_dim = n_prev;
   }
-  p->gru_bih = bld.pack_vec(w->rnn_b_ih, H3);
-  p->gru_bhh = bld.pack_vec(w->rnn_b_hh, H3);
-  macs += (int64_t)H3 * (cfg->fc_dim + cfg->rnn_dim);
-  p->ops.push_back(Op{OP_GRU, "gru", 2 * (int64_t)H3 * (cfg->fc_dim + cfg->rnn_dim), -1, -1, -1, -1, 0, 0, 0});
+  // ---- recurrent core: its input is [FC output | encoded measurements] ----
+  const bool lstm = cfg->rnn_type == SF_RNN_LSTM;
+  const int core_in = cfg->fc_dim + p->meas_out_dim;
+  const int HG = (lstm ? 4 : 3) * cfg->rnn_dim;
+  p->state_dim = (lstm ? 2 : 1) * cfg->rnn_dim;
+  p->gru_wih_t = bld.pack_transposed(w->rnn_w_ih, HG, core_in);
+  p->gru_whh_t = bld.pack_transposed(w->rnn_w_hh, HG, cfg->rnn_dim);
+  p->gru_wih = p->gru_whh = nullptr;
+  if (!getenv("SF_FORCE_GENERIC") && rnn_mfma_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
+    p->gru_wih = bld.pack_vec(w->rnn_w_ih, (size_t)HG * core_in);
+    p->gru_whh = bld.pack_vec(w->rnn_w_hh, (size_t)HG * cfg->rnn_dim);
+    p->gru_bm = getenv("SF_GRU_BM") ? atoi(getenv("SF_GRU_BM")) : rnn_mfma_pick_bm(cfg->max_batch, cfg->rnn_dim);
+  }
+  p->gru_bih = bld.pack_vec(w->rnn_b_ih, HG);
+  p->gru_bhh = bld.pack_vec(w->rnn_b_hh, HG);
+  macs += (int64_t)HG * (core_in + cfg->rnn_dim);
+  p->ops.push_back(Op{OP_GRU, lstm ? "lstm" : "gru", 2 * (int64_t)HG * (core_in + cfg->rnn_dim), -1, -1, -1,
+                      -1, 0, 0, 0});
   // ---- heads: action logits then the value row ----
   {
     int sumA = 0;
@@ -544,7 +590,9 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
                           : nullptr;
   p->trash = (float*)bld.dev_alloc(256);
   p->fc_out = (float*)bld.dev_alloc(sizeof(float) * (size_t)cfg->fc_dim * cfg->max_batch);
-  p->h_new = (float*)bld.dev_alloc(sizeof(float) * (size_t)cfg->rnn_dim * cfg->max_batch);
+  p->h_new = (float*)bld.dev_alloc(sizeof(float) * (size_t)p->state_dim * cfg->max_batch);
+  for (int l = 0; l < p->n_meas; ++l)
+    p->meas_buf[l] = (float*)bld.dev_alloc(sizeof(float) * (size_t)cfg->meas_hidden[l] * cfg->max_batch);
 
   p->events.resize(p->ops.size() + 1, nullptr);
   for (auto& ev : p->events)
@@ -589,19 +637,19 @@ namespace {
 // The launch sequence of one step.  h_in / h_out are row-indexed by the batch row, unless
 // ids is given: then row b reads its state from h_in[ids[b]] (a table of n_env rows), and
 // the heads launch copies the new state from h_out[b] to h_table[ids[b]].
-int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* h_in, const uint8_t* done,
-             uint64_t seed, uint64_t step, int32_t* actions, float* logp, float* value,
-             float* h_out, float* logits_opt, const int32_t* ids, float* h_table, int n_env,
-             hipStream_t st);
+int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const float* h_in,
+             const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions, float* logp,
+             float* value, float* h_out, float* logits_opt, const int32_t* ids, float* h_table,
+             int n_env, hipStream_t st);
 
 bool misaligned(const void* q, uintptr_t a) { return (reinterpret_cast<uintptr_t>(q) & (a - 1)) != 0; }
 
 }  // namespace
 
-extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, const float* h_in,
-                              const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions,
-                              float* logp, float* value, float* h_out, float* logits_opt,
-                              void* hip_stream) {
+extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, const float* meas,
+                              const float* h_in, const uint8_t* done, uint64_t seed, uint64_t step,
+                              int32_t* actions, float* logp, float* value, float* h_out,
+                              float* logits_opt, void* hip_stream) {
   Policy* p = reinterpret_cast<Policy*>(handle);
   if (!p) {
     set_error("sf_policy_step: null handle");
@@ -613,11 +661,11 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
     return SF_ERR_BATCH;
   }
   if (B == 0) return SF_OK;
-  if (!obs || !h_in || !done || !actions || !logp || !value || !h_out) {
+  if (!obs || !h_in || !done || !actions || !logp || !value || !h_out || (c.meas_dim > 0 && !meas)) {
     set_error("sf_policy_step: null buffer");
     return SF_ERR_ARG;
   }
-  if (misaligned(obs, 4) || misaligned(h_in, 16) || misaligned(h_out, 16) || misaligned(actions, 4) ||
+  if (misaligned(obs, 4) || (c.meas_dim > 0 && misaligned(meas, 4)) || misaligned(h_in, 16) || misaligned(h_out, 16) || misaligned(actions, 4) ||
       misaligned(logp, 4) || misaligned(value, 4) || (logits_opt && misaligned(logits_opt, 4))) {
     set_error("sf_policy_step: misaligned buffer (obs, actions, logp, value, logits: 4 bytes; "
               "h_in, h_out: 16 bytes)");
@@ -625,18 +673,19 @@ extern "C" int sf_policy_step(sf_policy* handle, int32_t B, const uint8_t* obs, 
   }
   {
     uintptr_t a0 = (uintptr_t)h_in, b0 = (uintptr_t)h_out;
-    uintptr_t n = sizeof(float) * (uintptr_t)B * c.rnn_dim;
+    uintptr_t n = sizeof(float) * (uintptr_t)B * p->state_dim;
     if (a0 < b0 + n && b0 < a0 + n) {
       set_error("sf_policy_step: h_out overlaps h_in");
       return SF_ERR_ALIAS;
     }
   }
-  return run_step(p, B, obs, h_in, done, seed, step, actions, logp, value, h_out, logits_opt, nullptr,
-                  nullptr, 0, reinterpret_cast<hipStream_t>(hip_stream));
+  return run_step(p, B, obs, meas, h_in, done, seed, step, actions, logp, value, h_out, logits_opt,
+                  nullptr, nullptr, 0, reinterpret_cast<hipStream_t>(hip_stream));
 }
 
-extern "C" int sf_policy_step_indexed(sf_policy* handle, int32_t B, const uint8_t* obs, float* h_table,
-                                      int32_t n_env, const int32_t* env_ids, const uint8_t* done,
+extern "C" int sf_policy_step_indexed(sf_policy* handle, int32_t B, const uint8_t* obs,
+                                      const float* meas, float* h_table, int32_t n_env,
+                                      const int32_t* env_ids, const uint8_t* done,
                                       uint64_t seed, uint64_t step, int32_t* actions, float* logp,
                                       float* value, float* logits_opt, void* hip_stream) {
   Policy* p = reinterpret_cast<Policy*>(handle);
@@ -654,26 +703,26 @@ extern "C" int sf_policy_step_indexed(sf_policy* handle, int32_t B, const uint8_
     return SF_ERR_ARG;
   }
   if (B == 0) return SF_OK;
-  if (!obs || !h_table || !env_ids || !done || !actions || !logp || !value) {
+  if (!obs || !h_table || !env_ids || !done || !actions || !logp || !value || (c.meas_dim > 0 && !meas)) {
     set_error("sf_policy_step_indexed: null buffer");
     return SF_ERR_ARG;
   }
-  if (misaligned(obs, 4) || misaligned(h_table, 16) || misaligned(env_ids, 4) || misaligned(actions, 4) ||
+  if (misaligned(obs, 4) || (c.meas_dim > 0 && misaligned(meas, 4)) || misaligned(h_table, 16) || misaligned(env_ids, 4) || misaligned(actions, 4) ||
       misaligned(logp, 4) || misaligned(value, 4) || (logits_opt && misaligned(logits_opt, 4))) {
     set_error("sf_policy_step_indexed: misaligned buffer (obs, env_ids, actions, logp, value, logits: "
               "4 bytes; h_table: 16 bytes)");
     return SF_ERR_ARG;
   }
-  return run_step(p, B, obs, h_table, done, seed, step, actions, logp, value, p->h_new, logits_opt,
+  return run_step(p, B, obs, meas, h_table, done, seed, step, actions, logp, value, p->h_new, logits_opt,
                   env_ids, h_table, n_env, reinterpret_cast<hipStream_t>(hip_stream));
 }
 
 namespace {
 
-int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* h_in, const uint8_t* done,
-             uint64_t seed, uint64_t step, int32_t* actions, float* logp, float* value,
-             float* h_out, float* logits_opt, const int32_t* ids, float* h_table, int n_env,
-             hipStream_t st) {
+int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const float* h_in,
+             const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions, float* logp,
+             float* value, float* h_out, float* logits_opt, const int32_t* ids, float* h_table,
+             int n_env, hipStream_t st) {
   const sf_policy_config& c = p->cfg;
   auto buf = [&](int i) -> float* { return i < 0 ? nullptr : p->act[i]; };
   if (p->timing) SF_LAUNCH(hipEventRecord(p->events[0], st));
@@ -751,19 +800,30 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* h_in, const 
           SF_LAUNCH(launch_linear_generic(B, p->flat, c.fc_dim, buf(op.in_buf), p->fc_w_t, p->fc_b,
                                           1, p->fc_out, st));
         break;
-      case OP_GRU:
-        if (p->gru_wih)
-          SF_LAUNCH(launch_gru_mfma(B, c.fc_dim, c.rnn_dim, p->fc_out, h_in, done, p->gru_wih,
-                                    p->gru_whh, p->gru_bih, p->gru_bhh, h_out, p->gru_bm, ids, n_env,
-                                    st));
-        else
-          SF_LAUNCH(launch_gru_generic(B, c.fc_dim, c.rnn_dim, p->fc_out, h_in, done, p->gru_wih_t,
-                                       p->gru_whh_t, p->gru_bih, p->gru_bhh, h_out, ids, n_env, st));
+      case OP_MEAS: {
+        const int l = op.conv;
+        SF_LAUNCH(launch_linear_generic(B, p->meas_in_dim[l], c.meas_hidden[l],
+                                        l == 0 ? meas : p->meas_buf[l - 1], p->meas_w_t[l],
+                                        p->meas_b[l], 1, p->meas_buf[l], st));
         break;
+      }
+      case OP_GRU: {
+        const float* x2 = p->n_meas ? p->meas_buf[p->n_meas - 1] : nullptr;
+        const int lstm = c.rnn_type == SF_RNN_LSTM;
+        if (p->gru_wih)
+          SF_LAUNCH(launch_rnn_mfma(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out, x2, h_in,
+                                    done, p->gru_wih, p->gru_whh, p->gru_bih, p->gru_bhh, h_out,
+                                    p->gru_bm, ids, n_env, st));
+        else
+          SF_LAUNCH(launch_rnn_generic(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out, x2,
+                                       h_in, done, p->gru_wih_t, p->gru_whh_t, p->gru_bih, p->gru_bhh,
+                                       h_out, ids, n_env, st));
+        break;
+      }
       case OP_HEADS:
         SF_LAUNCH(launch_heads(B, c.rnn_dim, c.n_heads, p->sumA, p->head_off, h_out, p->head_w,
                                p->head_b, seed, step, actions, logp, value, logits_opt, ids, h_table,
-                               n_env, st));
+                               n_env, p->state_dim, st));
         break;
     }
     if (p->timing) SF_LAUNCH(hipEventRecord(p->events[i + 1], st));
@@ -772,6 +832,10 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* h_in, const 
 }
 
 }  // namespace
+
+extern "C" int32_t sf_policy_state_dim(const sf_policy* handle) {
+  return handle ? reinterpret_cast<const Policy*>(handle)->state_dim : 0;
+}
 
 // ---- measurement aids ------------------------------------------------------
 

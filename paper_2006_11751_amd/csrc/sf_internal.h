@@ -44,12 +44,12 @@ enum ConvImpl {
 };
 
 // One kernel launch of the step, fixed at create time.
-enum OpKind { OP_CONV, OP_POOL, OP_FC, OP_GRU, OP_HEADS };
+enum OpKind { OP_CONV, OP_POOL, OP_FC, OP_MEAS, OP_GRU, OP_HEADS };
 struct Op {
   OpKind kind;
   std::string name;
   int64_t flops_per_row;  // 2 per multiply-add
-  int conv;               // index into Policy::convs (OP_CONV), else -1
+  int conv;               // index into Policy::convs (OP_CONV) or measurement layer (OP_MEAS), else -1
   int in_buf, out_buf;    // activation buffer indices; in_buf -1 = the observation
   int resid_buf;          // buffer added to the result, or -1
   int C, H, W;            // OP_POOL: input shape
@@ -72,13 +72,22 @@ struct Policy {
   bool act_f16;       // ... whose activation element type is fp16 instead of bf16
   bool stream_f32;    // residual encoder: the residual stream is stored in fp32
   int fc_tile;
-  float* gru_wih_t;   // dev [fc_dim][3H]
-  float* gru_whh_t;   // dev [H][3H]
-  float* gru_wih;     // dev [3H][fc_dim] (canonical) for the MFMA kernel, or null
-  float* gru_whh;     // dev [3H][H]
-  int gru_bm;         // rows per workgroup of the MFMA GRU kernel, fixed at create
-  float* gru_bih;     // dev [3H]
-  float* gru_bhh;     // dev [3H]
+  // recurrent core (GRU: G = 3 gate blocks, LSTM: G = 4); core input = fc_dim + meas_out_dim
+  float* gru_wih_t;   // dev [core input][G*H]
+  float* gru_whh_t;   // dev [H][G*H]
+  float* gru_wih;     // dev [G*H][core input] (canonical) for the MFMA kernel, or null
+  float* gru_whh;     // dev [G*H][H]
+  int gru_bm;         // rows per workgroup of the MFMA kernel, fixed at create
+  float* gru_bih;     // dev [G*H]
+  float* gru_bhh;     // dev [G*H]
+  int state_dim;      // floats per state row: H (GRU) or 2H (LSTM: [h | c])
+  // measurement encoder of the full architecture (n_meas = 0: none)
+  int n_meas;
+  int meas_out_dim;
+  int meas_in_dim[SF_MAX_MEAS_LAYERS];
+  float* meas_w_t[SF_MAX_MEAS_LAYERS];  // dev [in][out]
+  float* meas_b[SF_MAX_MEAS_LAYERS];
+  float* meas_buf[SF_MAX_MEAS_LAYERS];  // dev [max_batch][meas_hidden[l]]
   float* head_w;      // dev [sumA + 1][H]   (last row: value head)
   float* head_b;      // dev [sumA + 1]
   int32_t* head_off;  // dev [n_heads + 1]   prefix sums of head_sizes
@@ -86,7 +95,7 @@ struct Policy {
   float* act[3];      // three activation buffers of act_elems floats per row
   size_t act_elems;
   float* fc_out;      // dev [max_batch][fc_dim]
-  float* h_new;       // dev [max_batch][rnn_dim]: new states of an indexed step before the scatter
+  float* h_new;       // dev [max_batch][state_dim]: new states of an indexed step before the scatter
   float* trash;       // dev, 64 floats: target of stores that fall outside a tensor
   std::vector<void*> allocations;
   int64_t flops_per_row;
@@ -108,15 +117,15 @@ hipError_t launch_maxpool3x3s2p1(int B, int C, int H, int W, const float* in, fl
                                  hipStream_t st);
 hipError_t launch_linear_generic(int B, int n_in, int n_out, const float* in, const float* w_t,
                                  const float* bias, int relu, float* out, hipStream_t st);
-hipError_t launch_gru_generic(int B, int n_in, int H, const float* x, const float* h_in,
-                              const uint8_t* done, const float* wih_t, const float* whh_t,
-                              const float* bih, const float* bhh, float* h_out,
+hipError_t launch_rnn_generic(int lstm, int B, int n1, int n2, int H, const float* x1, const float* x2,
+                              const float* h_in, const uint8_t* done, const float* wih_t,
+                              const float* whh_t, const float* bih, const float* bhh, float* h_out,
                               const int32_t* ids, int n_env, hipStream_t st);
 hipError_t launch_heads(int B, int H, int n_heads, int sumA, const int32_t* head_off,
                         const float* h, const float* head_w, const float* head_b, uint64_t seed,
                         uint64_t step, int32_t* actions, float* logp, float* value,
                         float* logits_opt, const int32_t* ids, float* h_table, int n_env,
-                        hipStream_t st);
+                        int state_dim, hipStream_t st);
 
 hipError_t launch_copy16(const void* src, void* dst, long long bytes, hipStream_t st);
 
@@ -169,12 +178,12 @@ void conv3x3_stem_pack(const float* w, const float* bias, int cout, bool f16,
 hipError_t launch_conv3x3_stem(const uint8_t* obs, const uint16_t* wpk, const float* bias32, void* out,
                                int B, int H, int W, int cout, float obs_sub, float obs_mul, int f16,
                                hipStream_t st);
-bool gru_mfma_supported(int I, int H);
-hipError_t launch_gru_mfma(int B, int I, int H, const float* x, const float* h_in,
-                           const uint8_t* done, const float* w_ih, const float* w_hh,
-                           const float* b_ih, const float* b_hh, float* h_out, int bm,
-                           const int32_t* ids, int n_env, hipStream_t st);
-int gru_mfma_pick_bm(int max_batch, int H);
+bool rnn_mfma_supported(int I1, int I2, int H);
+hipError_t launch_rnn_mfma(int lstm, int B, int I1, int I2, int H, const float* x1, const float* x2,
+                           const float* h_in, const uint8_t* done, const float* w_ih,
+                           const float* w_hh, const float* b_ih, const float* b_hh, float* h_out,
+                           int bm, const int32_t* ids, int n_env, hipStream_t st);
+int rnn_mfma_pick_bm(int max_batch, int H);
 bool gemm_mfma_supported(int Cin, int ksize, int pad, int N);
 int gemm_mfma_pick_tile(long long M, int N, int K, int seg_len);
 hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,

@@ -3,7 +3,7 @@
 // environments cross the bus while the step of the other half computes.
 //
 // Three streams, all at the default priority:
-//   in   host -> device copies of obs, done, env_ids
+//   in   host -> device copies of obs, measurements, done, env_ids
 //   cmp  the indexed step (both slots, in submission order: they share the policy's
 //        workspace and the state table)
 //   out  device -> host copies of actions, logp, value
@@ -18,6 +18,7 @@ namespace {
 
 struct Slot {
   uint8_t* obs = nullptr;
+  float* meas = nullptr;
   uint8_t* done = nullptr;
   int32_t* ids = nullptr;
   int32_t* actions = nullptr;
@@ -39,6 +40,7 @@ void free_pipeline(Pipeline* pl) {
   if (!pl) return;
   for (Slot& s : pl->slots) {
     (void)hipFree(s.obs);
+    (void)hipFree(s.meas);
     (void)hipFree(s.done);
     (void)hipFree(s.ids);
     (void)hipFree(s.actions);
@@ -98,6 +100,9 @@ extern "C" int sf_pipeline_create(sf_policy* policy, int32_t slot_batch, int32_t
   const size_t n = (size_t)slot_batch;
   for (Slot& s : pl->slots) {
     SF_PL_TRY(hipMalloc((void**)&s.obs, n * pl->obs_row), free_pipeline(pl); return SF_ERR_OOM);
+    if (c.meas_dim > 0)
+      SF_PL_TRY(hipMalloc((void**)&s.meas, n * c.meas_dim * sizeof(float)), free_pipeline(pl);
+                return SF_ERR_OOM);
     SF_PL_TRY(hipMalloc((void**)&s.done, n), free_pipeline(pl); return SF_ERR_OOM);
     SF_PL_TRY(hipMalloc((void**)&s.ids, n * sizeof(int32_t)), free_pipeline(pl); return SF_ERR_OOM);
     SF_PL_TRY(hipMalloc((void**)&s.actions, n * c.n_heads * sizeof(int32_t)), free_pipeline(pl);
@@ -116,7 +121,8 @@ extern "C" int sf_pipeline_create(sf_policy* policy, int32_t slot_batch, int32_t
 }
 
 extern "C" int sf_pipeline_submit(sf_pipeline* handle, int32_t slot, int32_t B, const uint8_t* host_obs,
-                                  const uint8_t* host_done, const int32_t* host_env_ids,
+                                  const float* host_meas, const uint8_t* host_done,
+                                  const int32_t* host_env_ids,
                                   float* h_table, int32_t n_env, uint64_t seed, uint64_t step,
                                   int32_t* host_actions, float* host_logp, float* host_value) {
   static const char* fn = "sf_pipeline_submit";
@@ -145,8 +151,16 @@ extern "C" int sf_pipeline_submit(sf_pipeline* handle, int32_t slot, int32_t B, 
     return SF_ERR_ARG;
   }
   const sf_policy_config& c = pl->policy->cfg;
+  if (c.meas_dim > 0 && !host_meas) {
+    set_error("%s: null measurement buffer", fn);
+    return SF_ERR_ARG;
+  }
   const size_t n = (size_t)B;
   SF_PL_TRY(hipSetDevice(pl->policy->device), return SF_ERR_DEVICE);
+  if (c.meas_dim > 0)
+    SF_PL_TRY(hipMemcpyAsync(s.meas, host_meas, n * c.meas_dim * sizeof(float), hipMemcpyHostToDevice,
+                             pl->s_in),
+              return SF_ERR_DEVICE);
   SF_PL_TRY(hipMemcpyAsync(s.obs, host_obs, n * pl->obs_row, hipMemcpyHostToDevice, pl->s_in),
             return SF_ERR_DEVICE);
   SF_PL_TRY(hipMemcpyAsync(s.done, host_done, n, hipMemcpyHostToDevice, pl->s_in), return SF_ERR_DEVICE);
@@ -154,7 +168,7 @@ extern "C" int sf_pipeline_submit(sf_pipeline* handle, int32_t slot, int32_t B, 
             return SF_ERR_DEVICE);
   SF_PL_TRY(hipEventRecord(s.ev_in, pl->s_in), return SF_ERR_DEVICE);
   SF_PL_TRY(hipStreamWaitEvent(pl->s_cmp, s.ev_in, 0), return SF_ERR_DEVICE);
-  int rc = sf_policy_step_indexed(reinterpret_cast<sf_policy*>(pl->policy), B, s.obs, h_table, n_env,
+  int rc = sf_policy_step_indexed(reinterpret_cast<sf_policy*>(pl->policy), B, s.obs, s.meas, h_table, n_env,
                                   s.ids, s.done, seed, step, s.actions, s.logp, s.value, nullptr,
                                   pl->s_cmp);
   if (rc != SF_OK) return rc;

@@ -47,7 +47,7 @@ def test_struct_layout_matches_the_header():
 def test_null_handle_calls_fail_cleanly_without_a_gpu():
     from paper_2006_11751_amd import binding
     lib = binding.load_library()
-    assert lib.sf_policy_step(None, 1, None, None, None, 0, 0, None, None, None, None, None, None) == binding.SF_ERR_ARG
+    assert lib.sf_policy_step(None, 1, None, None, None, None, 0, 0, None, None, None, None, None, None) == binding.SF_ERR_ARG
     assert "null handle" in binding.sf_last_error()
     assert lib.sf_policy_destroy(None) == binding.SF_OK
     assert lib.sf_policy_op_count(None) == 0

@@ -192,7 +192,7 @@ def test_indexed_and_pipeline_error_paths(torch_cuda):
     def call(**kw):
         a = dict(B=B, obs=obs.data_ptr(), tab=tab.data_ptr(), n_env=B, ids=ids.data_ptr())
         a.update(kw)
-        binding.sf_policy_step_indexed(pol.handle, a["B"], a["obs"], a["tab"], a["n_env"], a["ids"],
+        binding.sf_policy_step_indexed(pol.handle, a["B"], a["obs"], None, a["tab"], a["n_env"], a["ids"],
                                        done.data_ptr(), 1, 0, out["actions"].data_ptr(),
                                        out["logp"].data_ptr(), out["value"].data_ptr(), None, None)
 

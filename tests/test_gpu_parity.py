@@ -200,7 +200,7 @@ def test_purity_done_reset_and_edges(torch_cuda, ref):
     o8 = pol.alloc_outputs(8)
 
     def call(B=8, obs_p=None, h_p=None, hout_p=None, act_p=None):
-        binding.sf_policy_step(pol.handle, B, t_obs.data_ptr() if obs_p is None else obs_p,
+        binding.sf_policy_step(pol.handle, B, t_obs.data_ptr() if obs_p is None else obs_p, None,
                                t_h.data_ptr() if h_p is None else h_p, t_d.data_ptr(), 1, 0,
                                o8["actions"].data_ptr() if act_p is None else act_p,
                                o8["logp"].data_ptr(), o8["value"].data_ptr(),
@@ -216,7 +216,7 @@ def test_purity_done_reset_and_edges(torch_cuda, ref):
             call(**kwargs)
         assert ei.value.code == code and binding.sf_last_error()
     with pytest.raises(binding.SfError) as ei:
-        binding.sf_policy_step(pol.handle, 8, None, t_h.data_ptr(), t_d.data_ptr(), 1, 0,
+        binding.sf_policy_step(pol.handle, 8, None, None, t_h.data_ptr(), t_d.data_ptr(), 1, 0,
                                o8["actions"].data_ptr(), o8["logp"].data_ptr(), o8["value"].data_ptr(),
                                o8["h_out"].data_ptr(), None, None)
     assert ei.value.code == binding.SF_ERR_ARG
