@@ -31,7 +31,8 @@ def measure_pipeline(torch, binding, wl, pol, net, rounds):
     slot (copy, step, copy back, in sequence) and with two slots in alternation."""
     B, dev = net["B"], pol.device
     n_env = 2 * B
-    table = torch.zeros((n_env, net["rnn"]), dtype=torch.float32, device=dev)
+    table = torch.zeros((n_env, wl.state_dim(net)), dtype=torch.float32, device=dev)
+    meas = wl.measurements(net)
     obs, done = torch.from_numpy(wl.observations(net)), torch.from_numpy(wl.done_mask(net))
     res = {}
     for n_slots in (1, 2):
@@ -40,6 +41,8 @@ def measure_pipeline(torch, binding, wl, pol, net, rounds):
         for s, hb in enumerate(hbs):
             hb["obs"].copy_(obs)
             hb["done"].copy_(done)
+            if meas is not None:
+                hb["meas"].copy_(torch.from_numpy(meas))
             hb["env_ids"].copy_(torch.arange(s * B, (s + 1) * B, dtype=torch.int32))
         t = 0
 
@@ -92,14 +95,16 @@ def main():
     dev = pol.device
     obs = torch.from_numpy(wl.observations(net)).to(dev)
     done = torch.from_numpy(wl.done_mask(net)).to(dev)
-    h = [torch.from_numpy(wl.initial_state(net)).to(dev), torch.empty((B, net["rnn"]), device=dev)]
+    h = [torch.from_numpy(wl.initial_state(net)).to(dev), torch.empty((B, wl.state_dim(net)), device=dev)]
+    meas = wl.measurements(net)
+    meas = None if meas is None else torch.from_numpy(meas).to(dev)
     out = [pol.alloc_outputs(B, logits=False) for _ in range(2)]
     out[0]["h_out"], out[1]["h_out"] = h[1], h[0]
     stream = torch.cuda.current_stream(dev)
 
     def run(n, t0):
         for t in range(t0, t0 + n):
-            pol.step(obs, h[t & 1], done, wl.PHILOX_SEED, t, out=out[t & 1], stream=stream)
+            pol.step(obs, h[t & 1], done, wl.PHILOX_SEED, t, out=out[t & 1], stream=stream, meas=meas)
 
     if args.calibrate_copy:
         n = 256 << 20
@@ -154,7 +159,8 @@ def main():
         reps, spent = 0, 0.0
         while spent < 10.0 and reps < 50:
             tic = time.perf_counter()
-            ref.policy_step(net, w, o_obs, o_h, o_done, wl.PHILOX_SEED, reps, want_logits=False, want_margin=False)
+            ref.policy_step(net, w, o_obs, o_h, o_done, wl.PHILOX_SEED, reps, want_logits=False, want_margin=False,
+                            meas=wl.measurements(net, B=n_rows))
             spent += time.perf_counter() - tic
             reps += 1
         cpu = {"value": round(n_rows * reps / spent, 2), "unit": "env-frames/s", "cores": ref.num_threads(),
@@ -168,8 +174,9 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32" if dtype == "fp32" else "bf16",
         "data": "synthetic",
-        "config": {"workload": "%s: B=%d obs u8 %dx%dx%d, %s encoder, FC%d, GRU%d, heads %s" % (
-            net["name"], B, *net["obs"], net["encoder"], net["fc"], net["rnn"], net["heads"]),
+        "config": {"workload": "%s: B=%d obs u8 %dx%dx%d, %s encoder, FC%d, %s%d, heads %s%s" % (
+            net["name"], B, *net["obs"], net["encoder"], net["fc"], net["rnn_type"].upper(), net["rnn"],
+            net["heads"], ", %d measurements -> FC%s" % (net["meas_dim"], net["meas_hidden"]) if net["meas_dim"] else ""),
             "paper_accounting_x4_frameskip_fps": round(4 * fps, 1),
             "inputs": "device-resident; host-to-device transfer excluded"},
         "roofline": roofline, "cpu_baseline": cpu}

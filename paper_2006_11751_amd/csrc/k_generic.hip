@@ -93,6 +93,64 @@ __global__ __launch_bounds__(kThreads) void linear_generic_kernel(
   out[(size_t)b * n_out + o] = acc;
 }
 
+// Measurement encoder of the full architecture: one or two fully connected + ReLU layers
+// in one launch.  A workgroup handles kMeasRows rows; the rows' inputs and the hidden
+// activations sit in LDS, every weight is read once per workgroup.  Sums run in the same
+// order as linear_generic_kernel's.
+constexpr int kMeasRows = 4;
+constexpr int kMeasThreads = 128;
+
+__global__ __launch_bounds__(kMeasThreads) void meas_mlp_kernel(
+    const float* __restrict__ meas, int B, int n0, const float* __restrict__ w1_t,
+    const float* __restrict__ b1, int n1, const float* __restrict__ w2_t,
+    const float* __restrict__ b2, int n2, float* __restrict__ out) {
+  extern __shared__ float sm[];
+  float* s_in = sm;                   // [kMeasRows][n0]
+  float* s_h = sm + kMeasRows * n0;   // [kMeasRows][n1]
+  const int r0 = blockIdx.x * kMeasRows;
+  const int tid = threadIdx.x;
+  for (int i = tid; i < kMeasRows * n0; i += kMeasThreads) {
+    const int r = i / n0;
+    s_in[i] = r0 + r < B ? meas[(size_t)(r0 + r) * n0 + (i - r * n0)] : 0.0f;
+  }
+  __syncthreads();
+  for (int o = tid; o < n1; o += kMeasThreads) {
+    float acc[kMeasRows];
+#pragma unroll
+    for (int r = 0; r < kMeasRows; ++r) acc[r] = b1[o];
+#pragma unroll 8
+    for (int i = 0; i < n0; ++i) {
+      const float w = w1_t[(size_t)i * n1 + o];
+#pragma unroll
+      for (int r = 0; r < kMeasRows; ++r) acc[r] = fmaf(s_in[r * n0 + i], w, acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < kMeasRows; ++r) {
+      const float v = fmaxf(acc[r], 0.0f);
+      if (n2 > 0)
+        s_h[r * n1 + o] = v;
+      else if (r0 + r < B)
+        out[(size_t)(r0 + r) * n1 + o] = v;
+    }
+  }
+  if (n2 == 0) return;
+  __syncthreads();
+  for (int o = tid; o < n2; o += kMeasThreads) {
+    float acc[kMeasRows];
+#pragma unroll
+    for (int r = 0; r < kMeasRows; ++r) acc[r] = b2[o];
+#pragma unroll 8
+    for (int i = 0; i < n1; ++i) {
+      const float w = w2_t[(size_t)i * n2 + o];
+#pragma unroll
+      for (int r = 0; r < kMeasRows; ++r) acc[r] = fmaf(s_h[r * n1 + i], w, acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < kMeasRows; ++r)
+      if (r0 + r < B) out[(size_t)(r0 + r) * n2 + o] = fmaxf(acc[r], 0.0f);
+  }
+}
+
 __device__ inline float sigmoidf_acc(float a) { return 1.0f / (1.0f + expf(-a)); }
 
 // Recurrent cell (GRU or LSTM) with the episode-boundary reset applied to the incoming
@@ -202,6 +260,20 @@ hipError_t launch_linear_generic(int B, int n_in, int n_out, const float* in, co
   if (B == 0) return hipSuccess;
   dim3 grid((n_out + kThreads - 1) / kThreads, B);
   linear_generic_kernel<<<grid, kThreads, 0, st>>>(in, w_t, bias, out, n_in, n_out, relu);
+  return hipGetLastError();
+}
+
+bool meas_mlp_supported(int n0, int n1) { return (size_t)kMeasRows * (n0 + n1) * sizeof(float) <= 48 * 1024; }
+
+// w1_t [n0][n1], w2_t [n1][n2] (transposed weights); n2 == 0: a single layer.
+// out [B][n2 ? n2 : n1].
+hipError_t launch_meas_mlp(int B, int n0, const float* meas, const float* w1_t, const float* b1, int n1,
+                           const float* w2_t, const float* b2, int n2, float* out, hipStream_t st) {
+  if (B == 0) return hipSuccess;
+  if (!meas_mlp_supported(n0, n1)) return hipErrorInvalidValue;
+  const unsigned blocks = (unsigned)((B + kMeasRows - 1) / kMeasRows);
+  const size_t lds = (size_t)kMeasRows * (n0 + n1) * sizeof(float);
+  meas_mlp_kernel<<<blocks, kMeasThreads, lds, st>>>(meas, B, n0, w1_t, b1, n1, w2_t, b2, n2, out);
   return hipGetLastError();
 }
 

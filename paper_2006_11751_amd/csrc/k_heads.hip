@@ -60,11 +60,13 @@ __global__ __launch_bounds__(kWave* kRowsPerBlock) void heads_kernel(
     float* __restrict__ value, float* __restrict__ logits_opt, const int32_t* __restrict__ ids,
     float* __restrict__ h_table, int n_env, int S) {
   __shared__ float s_logits[kRowsPerBlock][kMaxLogits];
+  __shared__ float s_pert[kRowsPerBlock][kMaxLogits];
   const int lane = threadIdx.x % kWave;
   const int wave = threadIdx.x / kWave;
   const int b = blockIdx.x * kRowsPerBlock + wave;
   if (b >= B) return;  // whole wave leaves together; no block-level barrier below
   float* lg = s_logits[wave];
+  float* pt = s_pert[wave];
   // state rows hold S >= H floats; the heads read the first H (an LSTM's h)
   const float* hp = h + (size_t)b * S;
   // With ids, the row stands for environment ids[b]: that is the sampler's counter word, and
@@ -74,34 +76,63 @@ __global__ __launch_bounds__(kWave* kRowsPerBlock) void heads_kernel(
   if (h_table && env < (uint32_t)n_env)
     for (int i = lane; i < S; i += kWave) h_table[(size_t)env * S + i] = hp[i];
 
-  // logits and value: lane-strided dot products, butterfly reduction (fixed order).
-  // Outputs are processed eight at a time so that their loads are all in flight
-  // together instead of one dependent reduction after another.
+  // Logits and value: lane-strided dot products, eight outputs at a time so that their
+  // loads are all in flight together.  The eight partial sums per lane are reduced over
+  // the wave by a transposing butterfly (fixed order): at distance 32, 16 and 8 each lane
+  // hands half of its remaining outputs to its partner and adds the partner's share of the
+  // other half, so an 8-lane group ends up with one output, which three more steps finish:
+  // 10 cross-lane moves for 8 outputs instead of 48.
   constexpr int kGroup = 8;
+  const bool b5 = (lane & 32) != 0, b4 = (lane & 16) != 0, b3 = (lane & 8) != 0;
+  const int u_own = (b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0);
   for (int a0 = 0; a0 <= sumA; a0 += kGroup) {
     float part[kGroup];
 #pragma unroll
     for (int u = 0; u < kGroup; ++u) part[u] = 0.0f;
+    const float* wrow[kGroup];
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u)  // clamp: duplicates are computed but not stored
+      wrow[u] = head_w + (size_t)(a0 + u <= sumA ? a0 + u : sumA) * H;
+#pragma unroll 4
     for (int i = lane; i < H; i += kWave) {
       const float hv = hp[i];
 #pragma unroll
-      for (int u = 0; u < kGroup; ++u) {
-        const int a = a0 + u <= sumA ? a0 + u : sumA;  // clamp: duplicates are not stored
-        part[u] = fmaf(hv, head_w[(size_t)a * H + i], part[u]);
-      }
+      for (int u = 0; u < kGroup; ++u) part[u] = fmaf(hv, wrow[u][i], part[u]);
     }
+    float q4[4], q2[2];
 #pragma unroll
-    for (int u = 0; u < kGroup; ++u) {
-      float acc = wave_sum(part[u]);
-      const int a = a0 + u;
-      if (a <= sumA && lane == 0) lg[a] = acc + head_b[a];
-    }
+    for (int u = 0; u < 4; ++u)
+      q4[u] = (b5 ? part[u + 4] : part[u]) + __shfl_xor(b5 ? part[u] : part[u + 4], 32, kWave);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      q2[u] = (b4 ? q4[u + 2] : q4[u]) + __shfl_xor(b4 ? q4[u] : q4[u + 2], 16, kWave);
+    float q1 = (b3 ? q2[1] : q2[0]) + __shfl_xor(b3 ? q2[0] : q2[1], 8, kWave);
+    q1 += __shfl_xor(q1, 4, kWave);
+    q1 += __shfl_xor(q1, 2, kWave);
+    q1 += __shfl_xor(q1, 1, kWave);
+    const int a = a0 + u_own;
+    if (a <= sumA && (lane & 7) == 0) lg[a] = q1 + head_b[a];
   }
   __builtin_amdgcn_wave_barrier();
   __threadfence_block();
   if (lane == 0) value[b] = lg[sumA];
   if (logits_opt)
     for (int a = lane; a < sumA; a += kWave) logits_opt[(size_t)b * sumA + a] = lg[a];
+
+  // Gumbel perturbation of every logit of every head in one pass over the lanes.
+  for (int idx = lane; idx < sumA; idx += kWave) {
+    int k = 0;
+    while (head_off[k + 1] <= idx) ++k;
+    const int i = idx - head_off[k];
+    uint32_t wd[4];
+    philox4x32_10(env, step_lo, step_hi, ((uint32_t)k << 16) | (uint32_t)(i >> 2), seed_lo, seed_hi,
+                  wd);
+    const uint32_t word = wd[i & 3];
+    const float u = ((float)(word >> 9) + 0.5f) * 0x1.0p-23f;
+    pt[idx] = lg[idx] + -logf(-logf(u));
+  }
+  __builtin_amdgcn_wave_barrier();
+  __threadfence_block();
 
   float lp_total = 0.0f;
   for (int k = 0; k < n_heads; ++k) {
@@ -110,36 +141,35 @@ __global__ __launch_bounds__(kWave* kRowsPerBlock) void heads_kernel(
     float best = -INFINITY, lmax = -INFINITY;
     int arg = 0x7FFFFFFF;
     for (int i = lane; i < A; i += kWave) {
-      uint32_t wd[4];
-      philox4x32_10(env, step_lo, step_hi, ((uint32_t)k << 16) | (uint32_t)(i >> 2),
-                    seed_lo, seed_hi, wd);
-      uint32_t word = wd[i & 3];
-      float u = ((float)(word >> 9) + 0.5f) * 0x1.0p-23f;
-      float g = -logf(-logf(u));
-      float l = lg[off + i];
-      float pert = l + g;
+      const float pert = pt[off + i];
       if (arg == 0x7FFFFFFF || pert > best) {
         best = pert;
         arg = i;
       }
-      lmax = fmaxf(lmax, l);
+      lmax = fmaxf(lmax, lg[off + i]);
     }
-    // wave argmax, ties to the lowest index
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-      float ob = __shfl_xor(best, m, kWave);
-      int oa = __shfl_xor(arg, m, kWave);
-      bool take = (oa != 0x7FFFFFFF) && (arg == 0x7FFFFFFF || ob > best || (ob == best && oa < arg));
+    // Butterfly over the lanes that hold categories: P = the power of two covering
+    // min(A, 64); lanes below P end with the result, lane 0 broadcasts it.
+    int P = 1;
+    while (P < A && P < kWave) P <<= 1;
+    // argmax, ties to the lowest index
+    for (int m = P >> 1; m >= 1; m >>= 1) {
+      const float ob = __shfl_xor(best, m, kWave);
+      const int oa = __shfl_xor(arg, m, kWave);
+      const bool take = (oa != 0x7FFFFFFF) && (arg == 0x7FFFFFFF || ob > best || (ob == best && oa < arg));
       if (take) {
         best = ob;
         arg = oa;
       }
+      lmax = fmaxf(lmax, __shfl_xor(lmax, m, kWave));
     }
-    lmax = wave_max(lmax);
+    arg = __shfl(arg, 0, kWave);
+    lmax = __shfl(lmax, 0, kWave);
     float se = 0.0f;
     for (int i = lane; i < A; i += kWave) se += expf(lg[off + i] - lmax);
-    se = wave_sum(se);
-    float lse = lmax + logf(se);
+    for (int m = P >> 1; m >= 1; m >>= 1) se += __shfl_xor(se, m, kWave);
+    se = __shfl(se, 0, kWave);
+    const float lse = lmax + logf(se);
     lp_total += lg[off + arg] - lse;
     if (lane == 0) actions[(size_t)b * n_heads + k] = arg;
   }

@@ -529,17 +529,23 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
   p->meas_out_dim = 0;
   {
     int n_prev = cfg->meas_dim;
+    int64_t m_all = 0;
+    const bool fused = p->n_meas > 0 && meas_mlp_supported(cfg->meas_dim, cfg->meas_hidden[0]);
     for (int l = 0; l < p->n_meas; ++l) {
       const int n_out = cfg->meas_hidden[l];
       p->meas_w_t[l] = bld.pack_transposed(w->meas_w[l], n_out, n_prev);
       p->meas_b[l] = bld.pack_vec(w->meas_b[l], n_out);
       p->meas_in_dim[l] = n_prev;
       macs += (int64_t)n_out * n_prev;
-      char nm[32];
-      snprintf(nm, sizeof(nm), "meas.fc%d", l + 1);
-      p->ops.push_back(Op{OP_MEAS, nm, 2 * (int64_t)n_out * n_prev, l, -1, -1, -1, 0, 0, 0});
+      m_all += (int64_t)n_out * n_prev;
+      if (!fused) {
+        char nm[32];
+        snprintf(nm, sizeof(nm), "meas.fc%d", l + 1);
+        p->ops.push_back(Op{OP_MEAS, nm, 2 * (int64_t)n_out * n_prev, l, -1, -1, -1, 0, 0, 0});
+      }
       n_prev = n_out;
     }
+    if (fused) p->ops.push_back(Op{OP_MEAS, "meas.fc", 2 * m_all, -1, -1, -1, -1, 0, 0, 0});
     if (p->n_meas) p->meas_out_dim = n_prev;
   }
   // ---- recurrent core: its input is [FC output | encoded measurements] ----
@@ -802,6 +808,13 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
         break;
       case OP_MEAS: {
         const int l = op.conv;
+        if (l < 0) {  // every layer in one launch
+          const bool two = p->n_meas == 2;
+          SF_LAUNCH(launch_meas_mlp(B, c.meas_dim, meas, p->meas_w_t[0], p->meas_b[0], c.meas_hidden[0],
+                                    two ? p->meas_w_t[1] : nullptr, two ? p->meas_b[1] : nullptr,
+                                    two ? c.meas_hidden[1] : 0, p->meas_buf[p->n_meas - 1], st));
+          break;
+        }
         SF_LAUNCH(launch_linear_generic(B, p->meas_in_dim[l], c.meas_hidden[l],
                                         l == 0 ? meas : p->meas_buf[l - 1], p->meas_w_t[l],
                                         p->meas_b[l], 1, p->meas_buf[l], st));

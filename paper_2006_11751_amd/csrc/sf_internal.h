@@ -49,7 +49,8 @@ struct Op {
   OpKind kind;
   std::string name;
   int64_t flops_per_row;  // 2 per multiply-add
-  int conv;               // index into Policy::convs (OP_CONV) or measurement layer (OP_MEAS), else -1
+  int conv;               // index into Policy::convs (OP_CONV); measurement layer, or -1 = all
+                          // layers in one launch (OP_MEAS); else -1
   int in_buf, out_buf;    // activation buffer indices; in_buf -1 = the observation
   int resid_buf;          // buffer added to the result, or -1
   int C, H, W;            // OP_POOL: input shape
@@ -117,6 +118,9 @@ hipError_t launch_maxpool3x3s2p1(int B, int C, int H, int W, const float* in, fl
                                  hipStream_t st);
 hipError_t launch_linear_generic(int B, int n_in, int n_out, const float* in, const float* w_t,
                                  const float* bias, int relu, float* out, hipStream_t st);
+bool meas_mlp_supported(int n0, int n1);
+hipError_t launch_meas_mlp(int B, int n0, const float* meas, const float* w1_t, const float* b1, int n1,
+                           const float* w2_t, const float* b2, int n2, float* out, hipStream_t st);
 hipError_t launch_rnn_generic(int lstm, int B, int n1, int n2, int H, const float* x1, const float* x2,
                               const float* h_in, const uint8_t* done, const float* wih_t,
                               const float* whh_t, const float* bih, const float* bhh, float* h_out,
