@@ -200,6 +200,19 @@ int sf_policy_step_indexed(sf_policy* p, int32_t B, const uint8_t* obs, const fl
                            uint64_t seed, uint64_t step, int32_t* actions, float* logp,
                            float* value, float* logits_opt, void* hip_stream);
 
+/* Replace the policy's parameters by new values of the same shapes (paper, Sec. 3.3: after
+ * every learner step the policy workers fetch the new parameters; Sec. 3.4: the fresher
+ * the sampling policy, the smaller the policy lag).  `weights` as for sf_policy_create:
+ * host pointers, read and repacked before the call returns; the packed values then travel
+ * to the device as asynchronous copies on `hip_stream`, into the buffers the kernels read.
+ * Ordering is the stream's: steps enqueued on that stream before the call use the old
+ * parameters, steps enqueued after it the new ones, and no step sees a mixture.  Work on
+ * other streams is not ordered against the update.  The first call allocates a page-locked
+ * staging area of the size of the packed weights (kept until destroy); a later call first
+ * waits for the previous update's copies.  Errors: SF_ERR_ARG (null handle or weight
+ * pointer), SF_ERR_OOM (staging area), SF_ERR_DEVICE, SF_ERR_SHAPE (internal mismatch). */
+int sf_policy_update_weights(sf_policy* p, const sf_policy_weights* weights, void* hip_stream);
+
 /* Floats per recurrent-state row of this policy: rnn_dim (GRU) or 2 * rnn_dim (LSTM). */
 int32_t sf_policy_state_dim(const sf_policy* p);
 

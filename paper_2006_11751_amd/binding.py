@@ -96,7 +96,8 @@ EXPORTS = ("sf_policy_create", "sf_policy_step", "sf_policy_destroy", "sf_last_e
            "sf_policy_flops_per_row", "sf_policy_op_count", "sf_policy_op_name",
            "sf_policy_op_flops_per_row", "sf_policy_set_op_timing", "sf_policy_last_op_times",
            "sf_copy_bytes", "sf_policy_step_indexed", "sf_pipeline_create", "sf_pipeline_submit",
-           "sf_pipeline_wait", "sf_pipeline_destroy", "sf_policy_state_dim")
+           "sf_pipeline_wait", "sf_pipeline_destroy", "sf_policy_state_dim",
+           "sf_policy_update_weights")
 
 _lib = None
 
@@ -127,6 +128,8 @@ def load_library():
         L.sf_policy_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sf_policy_update_weights.restype = C.c_int
+        L.sf_policy_update_weights.argtypes = [C.c_void_p, C.POINTER(SfPolicyWeights), C.c_void_p]
         L.sf_policy_state_dim.restype = C.c_int32
         L.sf_policy_state_dim.argtypes = [C.c_void_p]
         L.sf_policy_destroy.restype = C.c_int
@@ -279,6 +282,13 @@ def sf_pipeline_destroy(handle):
         raise SfError(rc, sf_last_error())
 
 
+def sf_policy_update_weights(handle, weights, hip_stream=None):
+    """weights: SfPolicyWeights (host pointers); copies are enqueued on hip_stream."""
+    rc = load_library().sf_policy_update_weights(handle, C.byref(weights), hip_stream)
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+
+
 def sf_copy_bytes(src, dst, nbytes, hip_stream=None):
     rc = load_library().sf_copy_bytes(src, dst, nbytes, hip_stream)
     if rc != SF_OK:
@@ -305,6 +315,13 @@ class Policy:
         self.n_heads, self.sumA = len(net["heads"]), sum(net["heads"])
         self.H = int(load_library().sf_policy_state_dim(self.handle))  # floats per state row
         self.meas_dim = net.get("meas_dim", 0)
+
+    def update_weights(self, weights, stream=None):
+        """weights: dict as for the constructor; enqueued on `stream` (default: current)."""
+        ws, keep = make_weights(weights)
+        s = stream if stream is not None else self._torch.cuda.current_stream(self.device)
+        sf_policy_update_weights(self.handle, ws, s.cuda_stream)
+        del keep
 
     def flops_per_row(self):
         return int(load_library().sf_policy_flops_per_row(self.handle))

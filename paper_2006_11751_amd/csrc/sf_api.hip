@@ -31,14 +31,31 @@ float bf16_round(float v) {
   return v;
 }
 
+// Allocates and fills the device buffers of a policy.  In replay mode (a weight update)
+// nothing is allocated: the k-th request returns the k-th buffer of `target`, whose size
+// must match, and uploads become asynchronous copies on `stream` out of `target`'s
+// page-locked staging area.
 struct Builder {
   Policy* p;
   bool bf16;
   int status = SF_OK;
+  Policy* target = nullptr;  // replay: the live policy whose buffers are refilled
+  hipStream_t stream = nullptr;
+  size_t next = 0, stage_off = 0;
 
   void* dev_alloc(size_t bytes) {
-    void* d = nullptr;
     if (bytes == 0) bytes = 4;
+    if (target) {
+      if (next >= target->allocations.size() || target->alloc_bytes[next] != bytes) {
+        if (status == SF_OK) {
+          set_error("weight update: buffer %zu does not match the policy built at create", next);
+          status = SF_ERR_SHAPE;
+        }
+        return nullptr;
+      }
+      return target->allocations[next++];
+    }
+    void* d = nullptr;
     hipError_t e = hipMalloc(&d, bytes);
     if (e != hipSuccess) {
       set_error("hipMalloc(%zu bytes) failed: %s", bytes, hipGetErrorString(e));
@@ -46,6 +63,7 @@ struct Builder {
       return nullptr;
     }
     p->allocations.push_back(d);
+    p->alloc_bytes.push_back(bytes);
     return d;
   }
 
@@ -53,7 +71,22 @@ struct Builder {
   T* upload(const std::vector<T>& host) {
     T* d = (T*)dev_alloc(host.size() * sizeof(T));
     if (!d) return nullptr;
-    hipError_t e = hipMemcpy(d, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice);
+    const size_t n = host.size() * sizeof(T);
+    hipError_t e;
+    if (target) {
+      const size_t off = (stage_off + 15) & ~(size_t)15;
+      if (off + n > target->stage_bytes) {
+        set_error("weight update: staging area too small");
+        status = SF_ERR_SHAPE;
+        return nullptr;
+      }
+      memcpy(target->stage + off, host.data(), n);
+      stage_off = off + n;
+      e = hipMemcpyAsync(d, target->stage + off, n, hipMemcpyHostToDevice, stream);
+    } else {
+      p->upload_bytes += n + 16;
+      e = hipMemcpy(d, host.data(), n, hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
       set_error("hipMemcpy to device failed: %s", hipGetErrorString(e));
       status = SF_ERR_DEVICE;
@@ -190,6 +223,8 @@ void free_policy(Policy* p) {
   for (void* d : p->allocations) (void)hipFree(d);
   for (hipEvent_t ev : p->events)
     if (ev) (void)hipEventDestroy(ev);
+  if (p->stage_ev) (void)hipEventDestroy(p->stage_ev);
+  if (p->stage) (void)hipHostFree(p->stage);
   delete p;
 }
 
@@ -198,73 +233,16 @@ void free_policy(Policy* p) {
 
 using namespace sf;
 
-extern "C" const char* sf_last_error(void) { return g_err; }
+namespace {
 
-extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_weights* w,
-                                int hip_device, sf_policy** out) {
-  if (out) *out = nullptr;
-  if (!cfg || !w || !out) {
-    set_error("sf_policy_create: null argument");
-    return SF_ERR_ARG;
-  }
-  if (cfg->struct_size != sizeof(sf_policy_config) || cfg->abi_version != SF_ABI_VERSION) {
-    set_error("sf_policy_create: struct_size %u / abi_version %u do not match this library (%zu / %u)",
-              cfg->struct_size, cfg->abi_version, sizeof(sf_policy_config), SF_ABI_VERSION);
-    return SF_ERR_ARG;
-  }
-  int Cf, Hf, Wf;
-  int rc = check_config(cfg, &Cf, &Hf, &Wf);
-  if (rc != SF_OK) return rc;
-
-  // every parameter tensor the description needs must be present
-  int n_tensors = cfg->encoder == SF_ENCODER_CONV ? cfg->n_conv
-                                                  : cfg->n_stage * (1 + 2 * cfg->blocks_per_stage);
-  for (int i = 0; i < n_tensors; ++i)
-    if (!w->conv_w[i] || !w->conv_b[i]) {
-      set_error("sf_policy_create: conv tensor %d is null", i);
-      return SF_ERR_ARG;
-    }
-  if (!w->fc_w || !w->fc_b || !w->rnn_w_ih || !w->rnn_w_hh || !w->rnn_b_ih || !w->rnn_b_hh ||
-      !w->pi_w || !w->pi_b || !w->v_w || !w->v_b) {
-    set_error("sf_policy_create: a weight pointer is null");
-    return SF_ERR_ARG;
-  }
-  for (int l = 0; cfg->meas_dim > 0 && l < cfg->n_meas_layers; ++l)
-    if (!w->meas_w[l] || !w->meas_b[l]) {
-      set_error("sf_policy_create: measurement layer %d has a null weight pointer", l);
-      return SF_ERR_ARG;
-    }
-
-  int n_dev = 0;
-  if (hipGetDeviceCount(&n_dev) != hipSuccess || hip_device < 0 || hip_device >= n_dev) {
-    set_error("sf_policy_create: HIP device %d not available (%d devices)", hip_device, n_dev);
-    return SF_ERR_DEVICE;
-  }
-  hipDeviceProp_t prop;
-  if (hipGetDeviceProperties(&prop, hip_device) != hipSuccess) {
-    set_error("sf_policy_create: hipGetDeviceProperties failed");
-    return SF_ERR_DEVICE;
-  }
-  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
-    set_error("sf_policy_create: device %d is %s; this library is built for gfx950 only",
-              hip_device, prop.gcnArchName);
-    return SF_ERR_ARCH;
-  }
-  if (hipSetDevice(hip_device) != hipSuccess) {
-    set_error("sf_policy_create: hipSetDevice(%d) failed", hip_device);
-    return SF_ERR_DEVICE;
-  }
-
-  Policy* p = new (std::nothrow) Policy();
-  if (!p) {
-    set_error("sf_policy_create: out of host memory");
-    return SF_ERR_OOM;
-  }
+// Chooses the kernels, packs the weights and sizes the workspace of `p` for `cfg`.  Shared by
+// create (bld allocates) and by a weight update (bld replays into the live policy's buffers;
+// `p` is then a scratch object whose plan and pointers come out identical).
+int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights* w, Builder& bld,
+                 int Cf, int Hf, int Wf) {
   p->cfg = *cfg;
-  p->device = hip_device;
   p->flat = Cf * Hf * Wf;
   p->conv1_waves = getenv("SF_CONV1_WAVES") ? atoi(getenv("SF_CONV1_WAVES")) : 0;
-  Builder bld{p, cfg->dtype == SF_DTYPE_BF16};
 
   // bf16 configurations run the encoder and the FC layer on the bf16 kernels with bf16
   // activations, provided every layer has a shape those kernels take; otherwise the
@@ -481,7 +459,6 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
     if ((op.kind == OP_CONV || op.kind == OP_POOL) &&
         (op.out_buf == op.in_buf || (op.resid_buf >= 0 && op.out_buf == op.resid_buf))) {
       set_error("sf_policy_create: internal error: encoder launch '%s' would run in place", op.name.c_str());
-      free_policy(p);
       return SF_ERR_SHAPE;
     }
 
@@ -600,6 +577,82 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
   for (int l = 0; l < p->n_meas; ++l)
     p->meas_buf[l] = (float*)bld.dev_alloc(sizeof(float) * (size_t)cfg->meas_hidden[l] * cfg->max_batch);
 
+  return bld.status;
+}
+
+int check_weights(const sf_policy_config* cfg, const sf_policy_weights* w, const char* fn) {
+  int n_tensors = cfg->encoder == SF_ENCODER_CONV ? cfg->n_conv
+                                                  : cfg->n_stage * (1 + 2 * cfg->blocks_per_stage);
+  for (int i = 0; i < n_tensors; ++i)
+    if (!w->conv_w[i] || !w->conv_b[i]) {
+      set_error("%s: conv tensor %d is null", fn, i);
+      return SF_ERR_ARG;
+    }
+  if (!w->fc_w || !w->fc_b || !w->rnn_w_ih || !w->rnn_w_hh || !w->rnn_b_ih || !w->rnn_b_hh ||
+      !w->pi_w || !w->pi_b || !w->v_w || !w->v_b) {
+    set_error("%s: a weight pointer is null", fn);
+    return SF_ERR_ARG;
+  }
+  for (int l = 0; cfg->meas_dim > 0 && l < cfg->n_meas_layers; ++l)
+    if (!w->meas_w[l] || !w->meas_b[l]) {
+      set_error("%s: measurement layer %d has a null weight pointer", fn, l);
+      return SF_ERR_ARG;
+    }
+  return SF_OK;
+}
+
+}  // namespace
+
+extern "C" const char* sf_last_error(void) { return g_err; }
+
+extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_weights* w,
+                                int hip_device, sf_policy** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !w || !out) {
+    set_error("sf_policy_create: null argument");
+    return SF_ERR_ARG;
+  }
+  if (cfg->struct_size != sizeof(sf_policy_config) || cfg->abi_version != SF_ABI_VERSION) {
+    set_error("sf_policy_create: struct_size %u / abi_version %u do not match this library (%zu / %u)",
+              cfg->struct_size, cfg->abi_version, sizeof(sf_policy_config), SF_ABI_VERSION);
+    return SF_ERR_ARG;
+  }
+  int Cf, Hf, Wf;
+  int rc = check_config(cfg, &Cf, &Hf, &Wf);
+  if (rc != SF_OK) return rc;
+
+  // every parameter tensor the description needs must be present
+  rc = check_weights(cfg, w, "sf_policy_create");
+  if (rc != SF_OK) return rc;
+
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || hip_device < 0 || hip_device >= n_dev) {
+    set_error("sf_policy_create: HIP device %d not available (%d devices)", hip_device, n_dev);
+    return SF_ERR_DEVICE;
+  }
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, hip_device) != hipSuccess) {
+    set_error("sf_policy_create: hipGetDeviceProperties failed");
+    return SF_ERR_DEVICE;
+  }
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+    set_error("sf_policy_create: device %d is %s; this library is built for gfx950 only",
+              hip_device, prop.gcnArchName);
+    return SF_ERR_ARCH;
+  }
+  if (hipSetDevice(hip_device) != hipSuccess) {
+    set_error("sf_policy_create: hipSetDevice(%d) failed", hip_device);
+    return SF_ERR_DEVICE;
+  }
+
+  Policy* p = new (std::nothrow) Policy();
+  if (!p) {
+    set_error("sf_policy_create: out of host memory");
+    return SF_ERR_OOM;
+  }
+  p->device = hip_device;
+  Builder bld{p, cfg->dtype == SF_DTYPE_BF16};
+  bld.status = build_policy(p, cfg, w, bld, Cf, Hf, Wf);
   p->events.resize(p->ops.size() + 1, nullptr);
   for (auto& ev : p->events)
     if (bld.status == SF_OK && hipEventCreate(&ev) != hipSuccess) {
@@ -618,6 +671,55 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
   }
   *out = reinterpret_cast<sf_policy*>(p);
   return SF_OK;
+}
+
+extern "C" int sf_policy_update_weights(sf_policy* handle, const sf_policy_weights* w, void* hip_stream) {
+  static const char* fn = "sf_policy_update_weights";
+  Policy* p = reinterpret_cast<Policy*>(handle);
+  if (!p || !w) {
+    set_error("%s: null argument", fn);
+    return SF_ERR_ARG;
+  }
+  int rc = check_weights(&p->cfg, w, fn);
+  if (rc != SF_OK) return rc;
+  if (hipSetDevice(p->device) != hipSuccess) {
+    set_error("%s: hipSetDevice(%d) failed", fn, p->device);
+    return SF_ERR_DEVICE;
+  }
+  if (!p->stage) {
+    p->stage_bytes = p->upload_bytes;
+    if (hipHostMalloc((void**)&p->stage, p->stage_bytes, hipHostMallocDefault) != hipSuccess) {
+      p->stage = nullptr;
+      set_error("%s: page-locked staging allocation of %zu bytes failed", fn, p->stage_bytes);
+      return SF_ERR_OOM;
+    }
+    if (hipEventCreateWithFlags(&p->stage_ev, hipEventDisableTiming) != hipSuccess) {
+      set_error("%s: hipEventCreate failed", fn);
+      return SF_ERR_DEVICE;
+    }
+  } else if (hipEventSynchronize(p->stage_ev) != hipSuccess) {  // the previous update's copies
+    set_error("%s: waiting for the previous update failed", fn);
+    return SF_ERR_DEVICE;
+  }
+  int Cf, Hf, Wf;
+  rc = check_config(&p->cfg, &Cf, &Hf, &Wf);
+  if (rc != SF_OK) return rc;
+  Policy scratch;  // receives a copy of the plan; owns nothing
+  scratch.device = p->device;
+  Builder bld{&scratch, p->cfg.dtype == SF_DTYPE_BF16};
+  bld.target = p;
+  bld.stream = reinterpret_cast<hipStream_t>(hip_stream);
+  rc = build_policy(&scratch, &p->cfg, w, bld, Cf, Hf, Wf);
+  if (rc == SF_OK && bld.next != p->allocations.size()) {
+    set_error("%s: the update visited %zu of the policy's %zu buffers", fn, bld.next, p->allocations.size());
+    rc = SF_ERR_SHAPE;
+  }
+  // recorded also after a failure, so that the next update waits for whatever was enqueued
+  if (hipEventRecord(p->stage_ev, bld.stream) != hipSuccess && rc == SF_OK) {
+    set_error("%s: hipEventRecord failed", fn);
+    rc = SF_ERR_DEVICE;
+  }
+  return rc;
 }
 
 extern "C" int sf_policy_destroy(sf_policy* handle) {

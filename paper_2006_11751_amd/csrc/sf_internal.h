@@ -99,6 +99,13 @@ struct Policy {
   float* h_new;       // dev [max_batch][state_dim]: new states of an indexed step before the scatter
   float* trash;       // dev, 64 floats: target of stores that fall outside a tensor
   std::vector<void*> allocations;
+  std::vector<size_t> alloc_bytes;   // size of each allocation, in allocation order
+  size_t upload_bytes = 0;           // bytes of packed weights uploaded at create (+ alignment slack)
+  // weight updates: page-locked staging area for the packed weights and the event that
+  // marks the end of the last update's copies out of it
+  unsigned char* stage = nullptr;
+  size_t stage_bytes = 0;
+  hipEvent_t stage_ev = nullptr;
   int64_t flops_per_row;
   std::vector<Op> ops;    // the launch sequence
   int enc_buf;            // buffer holding the encoder output
