@@ -288,7 +288,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
       L.cout = cout; L.k = k; L.s = s; L.pad = pad;
       L.Ho = (H + 2 * pad - k) / s + 1;
       L.Wo = (W + 2 * pad - k) / s + 1;
-      L.w_khwc_o = bld.pack_conv(w->conv_w[ti], cout, C, k);
+      L.w_khwc_o = nullptr;  // packed below if the shape-agnostic kernel runs this layer
       L.bias = bld.pack_vec(w->conv_b[ti], cout);
       L.relu_in = relu_in; L.relu_out = relu_out; L.add_residual = resid_buf >= 0;
       L.impl = CONV_GENERIC;
@@ -375,6 +375,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
         L.bpk = bld.upload(bpk);
         L.impl = CONV1_U8_MFMA;
       }
+      if (L.impl == CONV_GENERIC) L.w_khwc_o = bld.pack_conv(w->conv_w[ti], cout, C, k);
       ++ti;
       int64_t m = (int64_t)L.Ho * L.Wo * cout * C * k * k;
       Op op{OP_CONV, name, 2 * m, (int)p->convs.size(), in_buf, out_buf, resid_buf, 0, 0, 0};
@@ -464,32 +465,33 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
 
   // ---- FC: columns permuted from (c, y, x) to the channels-last order (y, x, c), transposed ----
   {
-    std::vector<float> t((size_t)p->flat * cfg->fc_dim);
-    for (int o = 0; o < cfg->fc_dim; ++o)
+    // u: [fc][flat in channels-last order]
+    std::vector<float> u((size_t)p->flat * cfg->fc_dim);
+    for (int o = 0; o < cfg->fc_dim; ++o) {
+      const float* src = w->fc_w + (size_t)o * p->flat;
+      float* dst = u.data() + (size_t)o * p->flat;
       for (int c = 0; c < Cf; ++c)
-        for (int y = 0; y < Hf; ++y)
-          for (int x = 0; x < Wf; ++x) {
-            size_t src = (size_t)o * p->flat + ((size_t)c * Hf + y) * Wf + x;
-            size_t dst = ((size_t)(y * Wf + x) * Cf + c) * cfg->fc_dim + o;
-            t[dst] = bld.q(w->fc_w[src]);
-          }
-    p->fc_w_t = bld.upload(t);
+        for (int yx = 0; yx < Hf * Wf; ++yx) dst[(size_t)yx * Cf + c] = bld.q(src[(size_t)c * Hf * Wf + yx]);
+    }
     p->fc_b = bld.pack_vec(w->fc_b, cfg->fc_dim);
     p->fc_wt = nullptr;
-    if (!getenv("SF_FORCE_GENERIC") && !p->bf16_path && gemm_mfma_supported(p->flat, 1, 0, cfg->fc_dim)) {
-      std::vector<float> u((size_t)p->flat * cfg->fc_dim);  // [fc][flat in channels-last order]
-      for (int o = 0; o < cfg->fc_dim; ++o)
-        for (int i = 0; i < p->flat; ++i) u[(size_t)o * p->flat + i] = t[(size_t)i * cfg->fc_dim + o];
+    p->fc_w_t = nullptr;
+    const bool fc_mfma = !getenv("SF_FORCE_GENERIC") && !p->bf16_path &&
+                         gemm_mfma_supported(p->flat, 1, 0, cfg->fc_dim);
+    if (fc_mfma) {
       p->fc_wt = bld.upload(u);
       const char* th = getenv("SF_FC_TILE");
       p->fc_tile = th ? atoi(th) : gemm_mfma_pick_tile(cfg->max_batch, cfg->fc_dim, p->flat, p->flat);
+    } else if (!p->bf16_path) {
+      // the shape-agnostic kernel reads the transposed matrix [flat][fc]
+      std::vector<float> t((size_t)p->flat * cfg->fc_dim);
+      for (int o = 0; o < cfg->fc_dim; ++o)
+        for (int i = 0; i < p->flat; ++i) t[(size_t)i * cfg->fc_dim + o] = u[(size_t)o * p->flat + i];
+      p->fc_w_t = bld.upload(t);
     }
     p->fc_wbf = nullptr;
     if (p->bf16_path) {
-      // the FC is a 1x1 "convolution" over a 1x1 image with flat channels; t is [flat][fc]
-      std::vector<float> u((size_t)cfg->fc_dim * p->flat);  // [fc][flat][1][1]
-      for (int o = 0; o < cfg->fc_dim; ++o)
-        for (int i = 0; i < p->flat; ++i) u[(size_t)o * p->flat + i] = t[(size_t)i * cfg->fc_dim + o];
+      // the FC is a 1x1 "convolution" over a 1x1 image with flat channels: u is [fc][flat][1][1]
       std::vector<uint16_t> wt;
       std::vector<float> bb;
       std::vector<float> fb(cfg->fc_dim);
@@ -530,10 +532,12 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
   const int core_in = cfg->fc_dim + p->meas_out_dim;
   const int HG = (lstm ? 4 : 3) * cfg->rnn_dim;
   p->state_dim = (lstm ? 2 : 1) * cfg->rnn_dim;
-  p->gru_wih_t = bld.pack_transposed(w->rnn_w_ih, HG, core_in);
-  p->gru_whh_t = bld.pack_transposed(w->rnn_w_hh, HG, cfg->rnn_dim);
+  p->gru_wih_t = p->gru_whh_t = nullptr;
   p->gru_wih = p->gru_whh = nullptr;
-  if (!getenv("SF_FORCE_GENERIC") && rnn_mfma_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
+  if (getenv("SF_FORCE_GENERIC") || !rnn_mfma_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
+    p->gru_wih_t = bld.pack_transposed(w->rnn_w_ih, HG, core_in);
+    p->gru_whh_t = bld.pack_transposed(w->rnn_w_hh, HG, cfg->rnn_dim);
+  } else {
     p->gru_wih = bld.pack_vec(w->rnn_w_ih, (size_t)HG * core_in);
     p->gru_whh = bld.pack_vec(w->rnn_w_hh, (size_t)HG * cfg->rnn_dim);
     p->gru_bm = getenv("SF_GRU_BM") ? atoi(getenv("SF_GRU_BM")) : rnn_mfma_pick_bm(cfg->max_batch, cfg->rnn_dim);
