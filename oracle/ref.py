@@ -223,6 +223,39 @@ def policy_step_indexed(net, w, obs, h_table, env_ids, done, seed, step, meas=No
     return out
 
 
+class RefLossCfg(C.Structure):
+    _fields_ = [("T", C.c_int32), ("N", C.c_int32), ("n_heads", C.c_int32),
+                ("head_sizes", C.c_int32 * MAX_HEADS),
+                ("gamma", C.c_float), ("rho_bar", C.c_float), ("c_bar", C.c_float), ("clip", C.c_float),
+                ("critic_coef", C.c_float), ("entropy_coef", C.c_float)]
+
+
+def appo_loss(hp, logits, actions, logp_mu, values, rewards, dones):
+    """hp: dict(heads, gamma, rho_bar, c_bar, clip, critic_coef, entropy_coef); arrays
+    time-major: logits [T,N,sumA], actions [T,N,nh], logp_mu/rewards/dones [T,N], values [T+1,N].
+    Returns dict(vs, adv, loss[4], dlogits, dvalues) in fp64."""
+    T, N, sumA = logits.shape
+    cfg = RefLossCfg()
+    cfg.T, cfg.N, cfg.n_heads = T, N, len(hp["heads"])
+    for i, a in enumerate(hp["heads"]):
+        cfg.head_sizes[i] = a
+    for k in ("gamma", "rho_bar", "c_bar", "clip", "critic_coef", "entropy_coef"):
+        setattr(cfg, k, hp[k])
+    logits, logp_mu, values, rewards = _f32(logits), _f32(logp_mu), _f32(values), _f32(rewards)
+    actions = np.ascontiguousarray(actions, dtype=np.int32)
+    dones = np.ascontiguousarray(dones, dtype=np.uint8)
+    assert sumA == sum(hp["heads"]) and values.shape == (T + 1, N) and actions.shape == (T, N, len(hp["heads"]))
+    out = dict(vs=np.zeros((T, N)), adv=np.zeros((T, N)), loss=np.zeros(4), dlogits=np.zeros((T, N, sumA)),
+               dvalues=np.zeros((T, N)))
+    L = lib()
+    L.ref_appo_loss.restype = C.c_int
+    rc = L.ref_appo_loss(C.byref(cfg), _p(logits), _p(actions), _p(logp_mu), _p(values), _p(rewards), _p(dones),
+                         _p(out["vs"]), _p(out["adv"]), _p(out["loss"]), _p(out["dlogits"]), _p(out["dvalues"]))
+    if rc != 0:
+        raise ValueError("ref_appo_loss rejected its arguments")
+    return out
+
+
 # ---- building blocks ---------------------------------------------------------
 
 def conv2d(x, w, b, stride, pad, relu):

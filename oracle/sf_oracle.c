@@ -482,3 +482,109 @@ int ref_policy_step_indexed(const ref_net* net, const ref_params* p, int32_t B, 
   free(h_new);
   return 0;
 }
+
+/* ---- learner-side loss ----------------------------------------------------- */
+
+int ref_appo_loss(const ref_loss_cfg* cfg, const float* logits, const int32_t* actions,
+                  const float* logp_mu, const float* values, const float* rewards,
+                  const uint8_t* dones, double* vs, double* adv, double* loss, double* dlogits,
+                  double* dvalues) {
+  const int T = cfg->T, N = cfg->N, nh = cfg->n_heads;
+  if (T < 1 || N < 1 || nh < 1 || nh > REF_MAX_HEADS || !(cfg->clip >= 1.0f)) return -1;
+  int sumA = 0;
+  for (int k = 0; k < nh; ++k) {
+    if (cfg->head_sizes[k] < 1) return -1;
+    sumA += cfg->head_sizes[k];
+  }
+  const size_t M = (size_t)T * N;
+  for (size_t s = 0; s < M; ++s)
+    for (int k = 0; k < nh; ++k)
+      if (actions[s * nh + k] < 0 || actions[s * nh + k] >= cfg->head_sizes[k]) return -1;
+
+  double* ratio = (double*)malloc(sizeof(double) * M);
+  double* ent = (double*)malloc(sizeof(double) * M);
+  double* lsm = (double*)malloc(sizeof(double) * M * (size_t)sumA); /* log softmax per head */
+  for (size_t s = 0; s < M; ++s) {
+    double lp = 0.0, h = 0.0;
+    int off = 0;
+    for (int k = 0; k < nh; ++k) {
+      const int A = cfg->head_sizes[k];
+      double* ls = lsm + s * sumA + off;
+      ref_log_softmax(logits + s * sumA + off, A, ls);
+      lp += ls[actions[s * nh + k]];
+      for (int i = 0; i < A; ++i) h -= exp(ls[i]) * ls[i];
+      off += A;
+    }
+    ratio[s] = exp(lp - (double)logp_mu[s]);
+    ent[s] = h;
+  }
+
+  /* V-trace targets by their defining sum, then the advantages */
+  const double gam = cfg->gamma;
+  for (int n = 0; n < N; ++n) {
+    for (int t = 0; t < T; ++t) {
+      double acc = 0.0, prod = 1.0;
+      for (int k = t; k < T; ++k) {
+        const size_t s = (size_t)k * N + n;
+        const double g = dones[s] ? 0.0 : gam;
+        const double rho = ratio[s] < cfg->rho_bar ? ratio[s] : (double)cfg->rho_bar;
+        const double c = ratio[s] < cfg->c_bar ? ratio[s] : (double)cfg->c_bar;
+        const double delta = rho * ((double)rewards[s] + g * (double)values[s + N] - (double)values[s]);
+        acc += prod * delta;
+        prod *= g * c;
+      }
+      vs[(size_t)t * N + n] = (double)values[(size_t)t * N + n] + acc;
+    }
+    for (int t = 0; t < T; ++t) {
+      const size_t s = (size_t)t * N + n;
+      const double g = dones[s] ? 0.0 : gam;
+      const double vnext = t + 1 < T ? vs[s + N] : (double)values[(size_t)T * N + n];
+      adv[s] = (double)rewards[s] + g * vnext - (double)values[s];
+    }
+  }
+
+  const double lo = 1.0 / (double)cfg->clip, hi = (double)cfg->clip;
+  double l_pi = 0.0, l_v = 0.0, l_h = 0.0;
+  for (size_t s = 0; s < M; ++s) {
+    const double rc = ratio[s] < lo ? lo : (ratio[s] > hi ? hi : ratio[s]);
+    const double a = ratio[s] * adv[s], b = rc * adv[s];
+    l_pi -= a < b ? a : b;
+    const double dv = (double)values[s] - vs[s];
+    l_v += dv * dv;
+    l_h -= ent[s];
+  }
+  loss[0] = l_pi / (double)M;
+  loss[1] = (double)cfg->critic_coef * l_v / (double)M;
+  loss[2] = (double)cfg->entropy_coef * l_h / (double)M;
+  loss[3] = loss[0] + loss[1] + loss[2];
+
+  if (dvalues)
+    for (size_t s = 0; s < M; ++s)
+      dvalues[s] = 2.0 * (double)cfg->critic_coef * ((double)values[s] - vs[s]) / (double)M;
+  if (dlogits)
+    for (size_t s = 0; s < M; ++s) {
+      /* the surrogate follows the unclipped branch where it is the smaller one (ties: the
+       * unclipped branch, whose slope the clamped one shares inside the range) */
+      const double rc = ratio[s] < lo ? lo : (ratio[s] > hi ? hi : ratio[s]);
+      const int unclipped = ratio[s] * adv[s] <= rc * adv[s];
+      const double dlp = unclipped ? -adv[s] * ratio[s] / (double)M : 0.0; /* d L_pi / d logp_pi */
+      int off = 0;
+      for (int k = 0; k < nh; ++k) {
+        const int A = cfg->head_sizes[k];
+        const double* ls = lsm + s * sumA + off;
+        double hk = 0.0;
+        for (int i = 0; i < A; ++i) hk -= exp(ls[i]) * ls[i];
+        for (int i = 0; i < A; ++i) {
+          const double p = exp(ls[i]);
+          const double dpol = dlp * ((i == actions[s * nh + k] ? 1.0 : 0.0) - p);
+          const double dent = (double)cfg->entropy_coef / (double)M * p * (ls[i] + hk);
+          dlogits[s * sumA + off + i] = dpol + dent;
+        }
+        off += A;
+      }
+    }
+  free(ratio);
+  free(ent);
+  free(lsm);
+  return 0;
+}

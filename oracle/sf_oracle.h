@@ -216,6 +216,41 @@ int ref_policy_step_indexed(const ref_net* net, const ref_params* p, int32_t B, 
                             const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions,
                             float* logp, float* value, float* logits_opt, float* margin_opt);
 
+/* ---- learner-side loss on a batch of trajectories -------------------------- */
+
+/* The loss of the paper's learner (Sec. 3.4 and the hyperparameter table of App.
+ * "VizDoom experiments": V-trace targets with rho_bar = c_bar = 1 combined with the PPO
+ * clipping range [1/1.1, 1.1], entropy coefficient 0.003, critic-loss coefficient 0.5) on N
+ * trajectories of T steps, time-major.  The paper names the two methods and cites them
+ * without formulas; the formulas below are the published ones, the combination is this
+ * build's reading.
+ *   pi      = softmax per head of logits[t][n];  logp_pi = sum over heads of log pi(a)
+ *   ratio   = exp(logp_pi - logp_mu)                       (mu: the behaviour policy)
+ *   rho     = min(rho_bar, ratio),  c = min(c_bar, ratio),  g_t = gamma * (1 - done_t)
+ *   delta_t = rho_t * (r_t + g_t * V_{t+1} - V_t)
+ *   vs_t    = V_t + sum_{k=t}^{T-1} (prod_{i=t}^{k-1} g_i c_i) * delta_k      (V-trace target)
+ *   adv_t   = r_t + g_t * vs_{t+1} - V_t        with vs_T = V_T (the bootstrap value)
+ *   L_pi    = -mean( min(ratio * adv, clamp(ratio, 1/clip, clip) * adv) )
+ *   L_v     = critic_coef * mean( (V_t - vs_t)^2 )
+ *   L_ent   = -entropy_coef * mean( sum over heads of entropy(pi) )
+ *   total   = L_pi + L_v + L_ent          (means over the T*N samples)
+ * Gradients treat vs and adv as constants:
+ *   dlogits = d total / d logits,  dvalues[t][n] = d L_v / d V_t  (t < T).
+ * logits [T][N][sumA]; actions [T][N][n_heads]; logp_mu, rewards, dones [T][N];
+ * values [T+1][N] (row T: bootstrap).  Outputs in fp64: vs, adv [T][N]; loss[4] =
+ * {L_pi, L_v, L_ent, total}; dlogits [T][N][sumA] and dvalues [T][N] may be NULL.
+ * Returns 0, -1 on bad sizes or an action outside its head. */
+typedef struct {
+  int32_t T, N, n_heads;
+  int32_t head_sizes[REF_MAX_HEADS];
+  float gamma, rho_bar, c_bar, clip, critic_coef, entropy_coef;
+} ref_loss_cfg;
+
+int ref_appo_loss(const ref_loss_cfg* cfg, const float* logits, const int32_t* actions,
+                  const float* logp_mu, const float* values, const float* rewards,
+                  const uint8_t* dones, double* vs, double* adv, double* loss, double* dlogits,
+                  double* dvalues);
+
 /* Threads ref_policy_step will use. */
 int ref_num_threads(void);
 

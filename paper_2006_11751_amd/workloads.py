@@ -172,3 +172,30 @@ def measurements(net, t=0, B=None, seed=None):
 
 
 PHILOX_SEED = 1
+
+
+# ---- learner-side loss (paper, hyperparameter table of App. "VizDoom experiments") ----
+
+LOSS_HP = dict(gamma=0.99, rho_bar=1.0, c_bar=1.0, clip=1.1, critic_coef=0.5, entropy_coef=0.003)
+
+
+def loss_config(heads=(7,), T=32, N=64, **overrides):
+    """Rollout length 32 and 2048 samples per batch = 64 trajectories, as in the paper."""
+    hp = dict(LOSS_HP, heads=list(heads), T=T, N=N)
+    hp.update(overrides)
+    return hp
+
+
+def trajectories(hp, seed=6000):
+    """Seeded stand-in for a batch of trajectories, time-major.  The behaviour log-probability
+    is that of a uniform policy plus noise and the logits are small, so the importance ratios
+    scatter around 1 on both sides of the clipping range."""
+    rng = np.random.default_rng(seed)
+    T, N, heads = hp["T"], hp["N"], hp["heads"]
+    logits = (0.3 * rng.standard_normal((T, N, sum(heads)))).astype(np.float32)
+    actions = np.stack([rng.integers(0, a, size=(T, N)) for a in heads], axis=-1).astype(np.int32)
+    logp_mu = (-float(np.sum(np.log(heads))) + 0.15 * rng.standard_normal((T, N))).astype(np.float32)
+    values = rng.standard_normal((T + 1, N)).astype(np.float32)
+    rewards = (rng.standard_normal((T, N)) * (rng.random((T, N)) < 0.2)).astype(np.float32)
+    dones = (rng.random((T, N)) < 0.03).astype(np.uint8)
+    return dict(logits=logits, actions=actions, logp_mu=logp_mu, values=values, rewards=rewards, dones=dones)
