@@ -287,6 +287,46 @@ int sf_pipeline_wait(sf_pipeline* pl, int32_t slot);
 /* Waits for every slot in flight, then frees buffers, streams and events.  NULL is accepted. */
 int sf_pipeline_destroy(sf_pipeline* pl);
 
+/* ---- learner-side loss -------------------------------------------------------
+ * The loss of the paper's learner on N trajectories of T steps (Sec. 3.4: V-trace
+ * value targets with truncated importance weights, combined with the PPO clipping
+ * range; hyperparameter table of App. "VizDoom experiments": rho_bar = c_bar = 1,
+ * clipping range [1/1.1, 1.1], entropy coefficient 0.003, critic-loss coefficient
+ * 0.5, rollout length 32, 2048 samples per batch), forward values and the gradients
+ * with respect to the network's outputs.  The paper cites the two methods without
+ * formulas; these are the published ones:
+ *   pi = softmax per head of logits[t][n],  logp_pi = sum over heads of log pi(action)
+ *   ratio = exp(logp_pi - logp_mu),  rho = min(rho_bar, ratio),  c = min(c_bar, ratio)
+ *   g_t = gamma * (1 - done_t),       delta_t = rho_t * (r_t + g_t V_{t+1} - V_t)
+ *   vs_t - V_t = delta_t + g_t c_t (vs_{t+1} - V_{t+1}),  vs_T = V_T
+ *   adv_t = r_t + g_t vs_{t+1} - V_t
+ *   L_pi = -mean min(ratio adv, clamp(ratio, 1/clip, clip) adv)
+ *   L_v = critic_coef * mean (V_t - vs_t)^2,   L_ent = -entropy_coef * mean sum_heads entropy
+ * with means over the T*N samples; the gradients treat vs and adv as constants.
+ * All arrays are device memory, time-major, 4-byte aligned:
+ *   logits   [T][N][sum(head_sizes)] fp32     actions [T][N][n_heads] int32 (an action
+ *                                             outside its head is clamped into it)
+ *   logp_mu  [T][N] fp32: joint log-probability under the behaviour policy (the logp
+ *                         output of sf_policy_step when the sample was taken)
+ *   values   [T+1][N] fp32, row T = bootstrap value;  rewards [T][N] fp32;  dones [T][N] bytes
+ *   vs, adv  [T][N] fp32 out;  loss [4] fp32 out = {L_pi, L_v, L_ent, their sum}
+ *   dlogits_opt [T][N][sum(head_sizes)], dvalues_opt [T][N] (d/dV_t of L_v) fp32 out, or NULL
+ *   workspace   sf_appo_loss_workspace_bytes(cfg) bytes, owned by the caller
+ * Asynchronous on hip_stream, allocation-free, and bitwise reproducible (the partial sums
+ * are added in a fixed order).  Errors: SF_ERR_ARG (null or misaligned pointer, struct_size),
+ * SF_ERR_SHAPE (sizes or hyperparameters out of range), SF_ERR_DEVICE. */
+typedef struct {
+  uint32_t struct_size; /* sizeof(sf_loss_config) */
+  int32_t T, N, n_heads;
+  int32_t head_sizes[SF_MAX_HEADS];
+  float gamma, rho_bar, c_bar, clip, critic_coef, entropy_coef;
+} sf_loss_config;
+int64_t sf_appo_loss_workspace_bytes(const sf_loss_config* cfg); /* -1 on a bad configuration */
+int sf_appo_loss(const sf_loss_config* cfg, const float* logits, const int32_t* actions,
+                 const float* logp_mu, const float* values, const float* rewards,
+                 const uint8_t* dones, float* vs, float* adv, float* loss, float* dlogits_opt,
+                 float* dvalues_opt, void* workspace, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

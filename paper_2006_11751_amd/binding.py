@@ -82,6 +82,13 @@ class SfPolicyConfig(C.Structure):
 _FP = C.POINTER(C.c_float)
 
 
+class SfLossConfig(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("T", C.c_int32), ("N", C.c_int32), ("n_heads", C.c_int32),
+                ("head_sizes", C.c_int32 * SF_MAX_HEADS),
+                ("gamma", C.c_float), ("rho_bar", C.c_float), ("c_bar", C.c_float), ("clip", C.c_float),
+                ("critic_coef", C.c_float), ("entropy_coef", C.c_float)]
+
+
 class SfPolicyWeights(C.Structure):
     _fields_ = [
         ("conv_w", _FP * SF_MAX_CONV_TENSORS), ("conv_b", _FP * SF_MAX_CONV_TENSORS),
@@ -97,7 +104,7 @@ EXPORTS = ("sf_policy_create", "sf_policy_step", "sf_policy_destroy", "sf_last_e
            "sf_policy_op_flops_per_row", "sf_policy_set_op_timing", "sf_policy_last_op_times",
            "sf_copy_bytes", "sf_policy_step_indexed", "sf_pipeline_create", "sf_pipeline_submit",
            "sf_pipeline_wait", "sf_pipeline_destroy", "sf_policy_state_dim",
-           "sf_policy_update_weights")
+           "sf_policy_update_weights", "sf_appo_loss", "sf_appo_loss_workspace_bytes")
 
 _lib = None
 
@@ -130,6 +137,10 @@ def load_library():
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sf_policy_update_weights.restype = C.c_int
         L.sf_policy_update_weights.argtypes = [C.c_void_p, C.POINTER(SfPolicyWeights), C.c_void_p]
+        L.sf_appo_loss_workspace_bytes.restype = C.c_int64
+        L.sf_appo_loss_workspace_bytes.argtypes = [C.POINTER(SfLossConfig)]
+        L.sf_appo_loss.restype = C.c_int
+        L.sf_appo_loss.argtypes = [C.POINTER(SfLossConfig)] + [C.c_void_p] * 13
         L.sf_policy_state_dim.restype = C.c_int32
         L.sf_policy_state_dim.argtypes = [C.c_void_p]
         L.sf_policy_destroy.restype = C.c_int
@@ -287,6 +298,59 @@ def sf_policy_update_weights(handle, weights, hip_stream=None):
     rc = load_library().sf_policy_update_weights(handle, C.byref(weights), hip_stream)
     if rc != SF_OK:
         raise SfError(rc, sf_last_error())
+
+
+def make_loss_config(hp):
+    """hp: dict(T, N, heads, gamma, rho_bar, c_bar, clip, critic_coef, entropy_coef)."""
+    c = SfLossConfig()
+    c.struct_size = C.sizeof(SfLossConfig)
+    c.T, c.N, c.n_heads = hp["T"], hp["N"], len(hp["heads"])
+    for i, a in enumerate(hp["heads"]):
+        c.head_sizes[i] = a
+    for k in ("gamma", "rho_bar", "c_bar", "clip", "critic_coef", "entropy_coef"):
+        setattr(c, k, hp[k])
+    return c
+
+
+def sf_appo_loss_workspace_bytes(cfg):
+    n = load_library().sf_appo_loss_workspace_bytes(C.byref(cfg))
+    if n < 0:
+        raise SfError(SF_ERR_SHAPE, sf_last_error())
+    return int(n)
+
+
+def sf_appo_loss(cfg, logits, actions, logp_mu, values, rewards, dones, vs, adv, loss, dlogits_opt,
+                 dvalues_opt, workspace, hip_stream=None):
+    """All buffers are device addresses (ints)."""
+    rc = load_library().sf_appo_loss(C.byref(cfg), logits, actions, logp_mu, values, rewards, dones, vs,
+                                     adv, loss, dlogits_opt, dvalues_opt, workspace, hip_stream)
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+
+
+def appo_loss(hp, tr, want_grads=True, stream=None, out=None):
+    """tr: dict of contiguous CUDA tensors (logits, actions, logp_mu, values, rewards, dones),
+    time-major.  Returns dict(vs, adv, loss[4], dlogits, dvalues) of CUDA tensors."""
+    import torch
+    cfg = make_loss_config(hp)
+    T, N, sumA = tr["logits"].shape
+    d = tr["logits"].device
+    for k, dt in (("logits", torch.float32), ("actions", torch.int32), ("logp_mu", torch.float32),
+                  ("values", torch.float32), ("rewards", torch.float32), ("dones", torch.uint8)):
+        assert tr[k].dtype == dt and tr[k].is_contiguous() and tr[k].is_cuda, k
+    assert (T, N) == (hp["T"], hp["N"]) and sumA == sum(hp["heads"]) and tuple(tr["values"].shape) == (T + 1, N)
+    if out is None:
+        out = dict(vs=torch.empty((T, N), device=d), adv=torch.empty((T, N), device=d),
+                   loss=torch.empty(4, device=d),
+                   dlogits=torch.empty((T, N, sumA), device=d) if want_grads else None,
+                   dvalues=torch.empty((T, N), device=d) if want_grads else None,
+                   workspace=torch.empty(sf_appo_loss_workspace_bytes(cfg), dtype=torch.uint8, device=d))
+    s = stream if stream is not None else torch.cuda.current_stream(d)
+    p = lambda x: None if x is None else x.data_ptr()
+    sf_appo_loss(cfg, p(tr["logits"]), p(tr["actions"]), p(tr["logp_mu"]), p(tr["values"]), p(tr["rewards"]),
+                 p(tr["dones"]), p(out["vs"]), p(out["adv"]), p(out["loss"]), p(out["dlogits"]),
+                 p(out["dvalues"]), p(out["workspace"]), s.cuda_stream)
+    return out
 
 
 def sf_copy_bytes(src, dst, nbytes, hip_stream=None):
