@@ -68,6 +68,30 @@ def measure_pipeline(torch, binding, wl, pol, net, rounds):
             "note": "host-to-device copy of the observations included; never the headline value"}
 
 
+def measure_loss(torch, binding, wl, reps):
+    """Learner-side loss kernels on the paper's batch (T=32, 2048 samples) and on a 32x larger one."""
+    res = {}
+    for name, hp in (("paper_batch_T32_N64", wl.loss_config((7,), 32, 64)),
+                     ("T32_N2048", wl.loss_config((7,), 32, 2048)),
+                     ("full_heads_T32_N2048", wl.loss_config((3, 3, 2, 2, 2, 8, 21), 32, 2048))):
+        tr = {k: torch.from_numpy(v).cuda() for k, v in wl.trajectories(hp).items()}
+        out = binding.appo_loss(hp, tr)
+        for _ in range(5):
+            binding.appo_loss(hp, tr, out=out)
+        torch.cuda.synchronize()
+        tic = time.perf_counter()
+        for _ in range(reps):
+            binding.appo_loss(hp, tr, out=out)
+        torch.cuda.synchronize()
+        us = 1e6 * (time.perf_counter() - tic) / reps
+        M, sumA, nh = hp["T"] * hp["N"], sum(hp["heads"]), len(hp["heads"])
+        # logits and actions are read for the forward pass and again for the gradient; the rest once
+        nbytes = M * (2 * (4 * sumA + 4 * nh) + 4 * 4 + 1 + 4 * 4 + 4 * sumA)
+        res[name] = {"us_per_call": round(us, 2), "samples_per_s": round(M / us * 1e6, 1),
+                     "algorithmic_GBps": round(nbytes / us / 1e3, 2)}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,6 +101,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pipeline", action="store_true",
                     help="also measure the double-buffered pipeline with host-resident observations")
+    ap.add_argument("--loss", action="store_true", help="also time the learner-side loss kernels")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -182,6 +207,8 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu}
     if pipeline is not None:
         line["pipeline"] = pipeline
+    if args.loss:
+        line["loss_kernels"] = measure_loss(torch, binding, wl, 200)
     print(json.dumps(line))
     pol.close()
 
