@@ -1,0 +1,274 @@
+// Recurrent core of the bf16 configurations on the 16-bit MFMA (paper, App. "Model
+// architectures": LSTM core of the benchmark model, GRU cells in the large-scale runs).
+//
+// Same cell arithmetic, reset rule and state layout as the fp32 kernel.  The weights of a
+// bf16 configuration are bf16 numbers, the core's input is a bf16 activation (rounded to
+// nearest even while it is staged), and the fp32 state h enters the contraction as the
+// exact sum of two bf16 numbers, h = hi + lo with hi = bf16(h), lo = bf16(h - hi)
+// (relative error below 2^-16): K runs over the input features, then over hi, then over
+// lo, the last two against the same rows of W_hh.  The state itself, the gates and the
+// blend stay fp32.
+//
+// v_mfma_f32_32x32x16_bf16: lane l supplies A[i = l%32][k = 8*(l/32) + e] and
+// B[k = 8*(l/32) + e][j = l%32].  The weights take the A role (i = hidden unit), the batch
+// rows the B role, so a lane ends up with 4 consecutive hidden units of one batch row per
+// register quad and the epilogue moves 16-byte pieces of the state.
+// Workgroup: 128 batch rows (one 32-row block per wave) x 32 hidden units x all gates:
+// four accumulator tiles per wave (GRU r, z, n_x, n_h; LSTM i, f, g, o).  K in chunks of 64
+// through double-buffered LDS (pitch 144 bytes), global loads one chunk ahead.
+#include <string.h>
+
+#include "sf_internal.h"
+
+namespace sf {
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBK = 64;       // K elements per chunk
+constexpr int kPitch = 144;   // LDS row pitch in bytes (128 + 16)
+constexpr int kBR = 128;      // batch rows per workgroup
+constexpr int kBJ = 32;       // hidden units per workgroup
+
+__device__ inline float sigmoid_acc(float a) { return 1.0f / (1.0f + expf(-a)); }
+__device__ inline unsigned bf16_rne(float f) {
+  const unsigned u = __float_as_uint(f);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;  // finite inputs
+}
+__device__ inline float bf16_value(unsigned h) { return __uint_as_float(h << 16); }
+
+struct RnnBf16Args {
+  const float* x1;        // [B][I1]
+  const float* x2;        // [B][I2] or null
+  const float* h_in;      // state rows of S floats, row index = batch row or ids[row]
+  const uint8_t* done;    // [B]
+  const uint16_t* w_ih;   // bf16 [G*H][I1 + I2]
+  const uint16_t* w_hh;   // bf16 [G*H][H]
+  const float* b_ih;      // [G*H]
+  const float* b_hh;      // [G*H]
+  float* h_out;           // [B][S]
+  int B, I1, I2, H;
+  const int32_t* ids;
+  int n_env;
+};
+
+// 8 consecutive fp32 -> 8 bf16 (phase 0: the value; 1: hi part; 2: lo part)
+__device__ inline u32x4 to_bf16x8(const f32x4& a, const f32x4& b, int phase) {
+  float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  unsigned h[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    unsigned hi = bf16_rne(v[e]);
+    h[e] = phase == 2 ? bf16_rne(v[e] - bf16_value(hi)) : hi;
+  }
+  u32x4 o = {h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+  return o;
+}
+
+template <bool LSTM>
+__global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
+  constexpr int NG = LSTM ? 4 : 3;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (kBR + NG * kBJ) * kPitch];
+  unsigned char* Rs = smem;                       // [2][128][pitch] batch rows
+  unsigned char* Ws = smem + 2 * kBR * kPitch;    // [2][NG*32][pitch] weight rows
+
+  const int B = g.B, H = g.H, I = g.I1 + g.I2;
+  const int S = LSTM ? 2 * H : H;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 31, lh = lane >> 5;
+  const int m0 = blockIdx.x * kBR, j0 = blockIdx.y * kBJ;
+  const int lrow = tid >> 3, lk8 = (tid & 7) * 8;  // 8 threads x 8 elements per tile row
+
+  int am[4], ah[4];
+  bool areset[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    int m = m0 + lrow + 32 * r;
+    am[r] = m < B ? m : B - 1;  // rows past the end re-read the last row; never stored
+    areset[r] = g.done[am[r]] != 0;
+    ah[r] = am[r];
+    if (g.ids) {
+      const int e = g.ids[am[r]];
+      const bool ok = (unsigned)e < (unsigned)g.n_env;
+      ah[r] = ok ? e : 0;
+      areset[r] = areset[r] || !ok;
+    }
+  }
+  const int n1c = g.I1 / kBK, nxc = I / kBK, nhc = H / kBK;
+  const int nchunks = nxc + 2 * nhc;  // x, then h's hi parts, then its lo parts
+
+  f32x4 ra[4][2];
+  u32x4 rw[NG];
+  int rphase = 0;
+  auto gload = [&](int c) {
+    if (c < nxc) {
+      rphase = 0;
+      const int kk = c * kBK + lk8;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float* src = c < n1c ? g.x1 + (size_t)am[r] * g.I1 + kk
+                                   : g.x2 + (size_t)am[r] * g.I2 + (kk - g.I1);
+        ra[r][0] = *(const f32x4*)src;
+        ra[r][1] = *(const f32x4*)(src + 4);
+      }
+#pragma unroll
+      for (int q = 0; q < NG; ++q)
+        rw[q] = *(const u32x4*)(g.w_ih + (size_t)(q * H + j0 + lrow) * I + kk);
+    } else {
+      const int ch = c - nxc;
+      rphase = ch < nhc ? 1 : 2;
+      const int kk = (ch < nhc ? ch : ch - nhc) * kBK + lk8;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float* src = g.h_in + (size_t)ah[r] * S + kk;
+        const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+        ra[r][0] = areset[r] ? zero : *(const f32x4*)src;
+        ra[r][1] = areset[r] ? zero : *(const f32x4*)(src + 4);
+      }
+#pragma unroll
+      for (int q = 0; q < NG; ++q)
+        rw[q] = *(const u32x4*)(g.w_hh + (size_t)(q * H + j0 + lrow) * H + kk);
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      *(u32x4*)(Rs + (buf * kBR + lrow + 32 * r) * kPitch + lk8 * 2) = to_bf16x8(ra[r][0], ra[r][1], rphase);
+#pragma unroll
+    for (int q = 0; q < NG; ++q)
+      *(u32x4*)(Ws + (buf * NG * kBJ + q * kBJ + lrow) * kPitch + lk8 * 2) = rw[q];
+  };
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+
+  auto compute = [&](int c) {
+    const int buf = c & 1;
+    const unsigned char* rb = Rs + (buf * kBR + wave * 32 + li) * kPitch + lh * 16;
+    const unsigned char* wb = Ws + (buf * NG * kBJ + li) * kPitch + lh * 16;
+    const bool xphase = c < nxc;
+#pragma unroll
+    for (int ks = 0; ks < kBK / 16; ++ks) {
+      const bf16x8 bfrag = __builtin_bit_cast(bf16x8, *(const u32x4*)(rb + ks * 32));
+      bf16x8 afrag[NG];
+#pragma unroll
+      for (int q = 0; q < NG; ++q)
+        afrag[q] = __builtin_bit_cast(bf16x8, *(const u32x4*)(wb + q * kBJ * kPitch + ks * 32));
+      if (LSTM) {
+#pragma unroll
+        for (int q = 0; q < NG; ++q)
+          acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[q], bfrag, acc[q], 0, 0, 0);
+      } else {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[0], bfrag, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[1], bfrag, acc[1], 0, 0, 0);
+        if (xphase)
+          acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[2], bfrag, acc[2], 0, 0, 0);
+        else
+          acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[2], bfrag, acc[3], 0, 0, 0);
+      }
+    }
+  };
+
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  for (int c = 0; c < nchunks; ++c) {
+    if (c + 1 < nchunks) gload(c + 1);
+    compute(c);
+    if (c + 1 < nchunks) sstore((c + 1) & 1);
+    __syncthreads();
+  }
+
+  // epilogue: register 4*q4 + u of a tile holds hidden unit j0 + 8*q4 + 4*lh + u of batch
+  // row m0 + wave*32 + li
+  const int m = m0 + wave * 32 + li;
+  if (m >= B) return;
+  int hm = m;
+  bool reset = g.done[m] != 0;
+  if (g.ids) {
+    const int e = g.ids[m];
+    const bool ok = (unsigned)e < (unsigned)g.n_env;
+    hm = ok ? e : 0;
+    reset = reset || !ok;
+  }
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4) {
+    const int j = j0 + 8 * q4 + 4 * lh;
+    f32x4 bi[NG], bh[NG];
+#pragma unroll
+    for (int q = 0; q < NG; ++q) {
+      bi[q] = *(const f32x4*)(g.b_ih + q * H + j);
+      bh[q] = *(const f32x4*)(g.b_hh + q * H + j);
+    }
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (LSTM) {
+      const f32x4 cprev = reset ? zero : *(const f32x4*)(g.h_in + (size_t)hm * S + H + j);
+      f32x4 hn, cn;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float ig = sigmoid_acc(acc[0][4 * q4 + u] + bi[0][u] + bh[0][u]);
+        const float fg = sigmoid_acc(acc[1][4 * q4 + u] + bi[1][u] + bh[1][u]);
+        const float gg = tanhf(acc[2][4 * q4 + u] + bi[2][u] + bh[2][u]);
+        const float og = sigmoid_acc(acc[3][4 * q4 + u] + bi[NG - 1][u] + bh[NG - 1][u]);
+        cn[u] = fg * cprev[u] + ig * gg;
+        hn[u] = og * tanhf(cn[u]);
+      }
+      *(f32x4*)(g.h_out + (size_t)m * S + H + j) = cn;
+      *(f32x4*)(g.h_out + (size_t)m * S + j) = hn;
+    } else {
+      const f32x4 hprev = reset ? zero : *(const f32x4*)(g.h_in + (size_t)hm * S + j);
+      f32x4 hn;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float r = sigmoid_acc(acc[0][4 * q4 + u] + bi[0][u] + bh[0][u]);
+        const float z = sigmoid_acc(acc[1][4 * q4 + u] + bi[1][u] + bh[1][u]);
+        const float n = tanhf(acc[2][4 * q4 + u] + bi[2][u] + r * (acc[3][4 * q4 + u] + bh[2][u]));
+        hn[u] = (1.0f - z) * n + z * hprev[u];
+      }
+      *(f32x4*)(g.h_out + (size_t)m * S + j) = hn;
+    }
+  }
+}
+
+}  // namespace
+
+// Every piece of the input and the state width must be whole 64-wide K chunks.
+bool rnn_bf16_supported(int I1, int I2, int H) {
+  return I1 > 0 && (I1 % kBK) == 0 && (I2 % kBK) == 0 && (H % kBK) == 0;
+}
+
+// bf16 bits of weights that are bf16 numbers already (rounded to nearest even otherwise)
+void rnn_bf16_pack(const float* w, size_t n, std::vector<uint16_t>& out) {
+  out.resize(n);
+  for (size_t i = 0; i < n; ++i) {
+    uint32_t u;
+    memcpy(&u, &w[i], 4);
+    out[i] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+  }
+}
+
+hipError_t launch_rnn_bf16(int lstm, int B, int I1, int I2, int H, const float* x1, const float* x2,
+                           const float* h_in, const uint8_t* done, const uint16_t* w_ih,
+                           const uint16_t* w_hh, const float* b_ih, const float* b_hh, float* h_out,
+                           const int32_t* ids, int n_env, hipStream_t st) {
+  if (B == 0) return hipSuccess;
+  RnnBf16Args g;
+  g.x1 = x1; g.x2 = x2; g.h_in = h_in; g.done = done;
+  g.w_ih = w_ih; g.w_hh = w_hh; g.b_ih = b_ih; g.b_hh = b_hh; g.h_out = h_out;
+  g.B = B; g.I1 = I1; g.I2 = x2 ? I2 : 0; g.H = H; g.ids = ids; g.n_env = n_env;
+  dim3 grid((B + kBR - 1) / kBR, H / kBJ);
+  if (lstm)
+    rnn_bf16_kernel<true><<<grid, 256, 0, st>>>(g);
+  else
+    rnn_bf16_kernel<false><<<grid, 256, 0, st>>>(g);
+  return hipGetLastError();
+}
+
+}  // namespace sf

@@ -534,7 +534,16 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
   p->state_dim = (lstm ? 2 : 1) * cfg->rnn_dim;
   p->gru_wih_t = p->gru_whh_t = nullptr;
   p->gru_wih = p->gru_whh = nullptr;
-  if (getenv("SF_FORCE_GENERIC") || !rnn_mfma_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
+  p->rnn_wih_bf = p->rnn_whh_bf = nullptr;
+  if (cfg->dtype == SF_DTYPE_BF16 && !getenv("SF_FORCE_GENERIC") && !getenv("SF_NO_RNN_BF16") &&
+      rnn_bf16_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
+    // bf16 configuration: gate GEMMs on the 16-bit MFMA, state split into two bf16 terms
+    std::vector<uint16_t> t;
+    rnn_bf16_pack(w->rnn_w_ih, (size_t)HG * core_in, t);
+    p->rnn_wih_bf = bld.upload(t);
+    rnn_bf16_pack(w->rnn_w_hh, (size_t)HG * cfg->rnn_dim, t);
+    p->rnn_whh_bf = bld.upload(t);
+  } else if (getenv("SF_FORCE_GENERIC") || !rnn_mfma_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
     p->gru_wih_t = bld.pack_transposed(w->rnn_w_ih, HG, core_in);
     p->gru_whh_t = bld.pack_transposed(w->rnn_w_hh, HG, cfg->rnn_dim);
   } else {
@@ -929,7 +938,11 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
       case OP_GRU: {
         const float* x2 = p->n_meas ? p->meas_buf[p->n_meas - 1] : nullptr;
         const int lstm = c.rnn_type == SF_RNN_LSTM;
-        if (p->gru_wih)
+        if (p->rnn_wih_bf)
+          SF_LAUNCH(launch_rnn_bf16(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out, x2, h_in,
+                                    done, p->rnn_wih_bf, p->rnn_whh_bf, p->gru_bih, p->gru_bhh, h_out,
+                                    ids, n_env, st));
+        else if (p->gru_wih)
           SF_LAUNCH(launch_rnn_mfma(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out, x2, h_in,
                                     done, p->gru_wih, p->gru_whh, p->gru_bih, p->gru_bhh, h_out,
                                     p->gru_bm, ids, n_env, st));

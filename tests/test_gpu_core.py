@@ -23,6 +23,11 @@ NETS = [
     dict(_BASE, name="full_mfma", fc=64, rnn=64, meas_dim=23, meas_hidden=[40, 32], heads=[3, 3, 2, 2, 2, 8, 21], index=6),
     dict(_BASE, name="full_lstm_mfma", fc=96, rnn=32, rnn_type="lstm", meas_dim=5, meas_hidden=[64], heads=[7], index=6),
     dict(_BASE, name="full_mixed", fc=64, rnn=64, meas_dim=9, meas_hidden=[17], heads=[2, 3], index=6),  # x2 not a K chunk
+    # bf16 configurations whose core runs on the 16-bit MFMA (64-wide K chunks), ragged batch of 137
+    dict(_BASE, name="lstm_bf16_mfma", B=137, fc=64, rnn=128, rnn_type="lstm", heads=[4, 4], index=5, dtype="bf16"),
+    dict(_BASE, name="gru_bf16_mfma", B=137, fc=128, rnn=64, heads=[9], index=5, dtype="bf16"),
+    dict(_BASE, name="full_bf16_mfma", B=137, fc=64, rnn=64, meas_dim=11, meas_hidden=[20, 64], heads=[3, 2], index=6,
+         dtype="bf16"),
 ]
 
 
@@ -86,7 +91,7 @@ def test_lstm_done_resets_both_halves(torch_cuda):
     pol.close()
 
 
-@pytest.mark.parametrize("net", [NETS[1], NETS[5], NETS[3]], ids=lambda n: n["name"])
+@pytest.mark.parametrize("net", [NETS[1], NETS[5], NETS[3], NETS[7], NETS[9]], ids=lambda n: n["name"])
 def test_indexed_step_and_pipeline_with_wide_state_rows_and_measurements(torch_cuda, ref, net):
     torch = torch_cuda
     from paper_2006_11751_amd import binding
