@@ -75,7 +75,10 @@ struct ConvBf16Args {
   int relu_in, relu_out, out_f32, in_f32, resid_f32;
 };
 
-template <int TAG, bool kF16>
+// kSimple: no padding, K a whole number of chunks and every chunk inside one filter row
+// (ks * Cin a multiple of 64).  The loader then needs no bounds checks and no divisions: a
+// cursor walks each pixel row's K axis, jumping to the next filter row at a segment's end.
+template <int TAG, bool kF16, bool kSimple>
 __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (kBP + kBC) * kPitchB];
   unsigned char* Ps = smem;                        // [2][128][pitch] pixels
@@ -106,11 +109,52 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
     ix0[r] = ox * g.stride - g.pad;
   }
   const uint16_t* wrow = g.Wt + (size_t)(n0 + lrow) * g.Kpad + lk8;  // 32 rows x 8 pieces = 256 threads
+  // kSimple: element offset of this thread's piece of chunk 0 in each of its pixel rows
+  long long sbase[4];
+  int ld_off = 0, ld_in_seg = 0;
+  const int seg_len = g.ks * g.Cin, seg_jump = g.W * g.Cin - seg_len;
+  if (kSimple) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      sbase[r] = pbase[r] + ((long long)iy0[r] * g.W + ix0[r]) * g.Cin + lk8;
+  }
 
   u32x4 rp[2][4], rw[2];
   const int nchunks = g.Kpad / kBK;
   auto gload = [&](auto set, int c) {
     constexpr int S = decltype(set)::value;
+    if (kSimple) {  // chunks are requested in order
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const long long e = sbase[r] + ld_off;
+        u32x4 v;
+        if (g.in_f32) {
+          const f32x4 lo = *(const f32x4*)((const float*)g.in + e);
+          const f32x4 hi = *(const f32x4*)((const float*)g.in + e + 4);
+          v[0] = f32_to_h<kF16>(lo[0]) | (f32_to_h<kF16>(lo[1]) << 16);
+          v[1] = f32_to_h<kF16>(lo[2]) | (f32_to_h<kF16>(lo[3]) << 16);
+          v[2] = f32_to_h<kF16>(hi[0]) | (f32_to_h<kF16>(hi[1]) << 16);
+          v[3] = f32_to_h<kF16>(hi[2]) | (f32_to_h<kF16>(hi[3]) << 16);
+        } else {
+          v = *(const u32x4*)((const uint16_t*)g.in + e);
+        }
+        if (g.relu_in) {
+          v[0] = relu_bf16x2(v[0]);
+          v[1] = relu_bf16x2(v[1]);
+          v[2] = relu_bf16x2(v[2]);
+          v[3] = relu_bf16x2(v[3]);
+        }
+        rp[S][r] = v;
+      }
+      rw[S] = *(const u32x4*)(wrow + c * kBK);
+      ld_off += kBK;
+      ld_in_seg += kBK;
+      if (ld_in_seg == seg_len) {
+        ld_in_seg = 0;
+        ld_off += seg_jump;
+      }
+      return;
+    }
     const int k0 = c * kBK + lk8;
     const int pq = k0 / g.Cin;
     const int c0 = k0 - pq * g.Cin;
@@ -317,10 +361,15 @@ template <int TAG>
 hipError_t launch_tagged(const ConvBf16Args& g, bool f16, hipStream_t st) {
   const int n_tiles = ((g.M + kBP - 1) / kBP) * ((g.N + kBC - 1) / kBC);
   const int per_xcd = (n_tiles + 7) / 8;
-  if (f16)
-    conv_bf16_kernel<TAG, true><<<per_xcd * 8, 256, 0, st>>>(g);
+  const bool simple = g.pad == 0 && g.K == g.Kpad && (g.ks * g.Cin) % kBK == 0;
+  if (f16 && simple)
+    conv_bf16_kernel<TAG, true, true><<<per_xcd * 8, 256, 0, st>>>(g);
+  else if (f16)
+    conv_bf16_kernel<TAG, true, false><<<per_xcd * 8, 256, 0, st>>>(g);
+  else if (simple)
+    conv_bf16_kernel<TAG, false, true><<<per_xcd * 8, 256, 0, st>>>(g);
   else
-    conv_bf16_kernel<TAG, false><<<per_xcd * 8, 256, 0, st>>>(g);
+    conv_bf16_kernel<TAG, false, false><<<per_xcd * 8, 256, 0, st>>>(g);
   return hipGetLastError();
 }
 
