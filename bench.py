@@ -169,11 +169,17 @@ def main():
     dom_tflops = ops[i_dom][1] * B / (op_ms[i_dom] * 1e-3) / 1e12
     whole_tflops = pol.flops_per_row() * B / (ms_per_step * 1e-3) / 1e12
     kib = MEASURED_HBM_KIB.get(net["name"], {}).get(ops[i_dom][0]) if B == wl.CONFIGS[args.config]["B"] else None
+    kib_all = MEASURED_HBM_KIB.get(net["name"]) if B == wl.CONFIGS[args.config]["B"] else None
+    whole = {"achieved": round(whole_tflops, 3), "frac": round(whole_tflops / peak, 5)}
+    if kib_all and set(kib_all) >= {name for name, _ in ops}:
+        # second roof: measured HBM bytes of all launches of the step over the step's time
+        hbm = sum(kib_all[name] for name, _ in ops) * 1024 / (ms_per_step * 1e-3) / 1e9
+        whole.update({"hbm_GBps": round(hbm, 1), "hbm_frac": round(hbm / 8000.0, 4)})
     roofline = {"bound": "mfma", "kernel": ops[i_dom][0], "achieved": round(dom_tflops, 3), "peak": peak,
                 "unit": "TFLOP/s", "frac": round(dom_tflops / peak, 5),
                 "traffic": kib * 1024 if kib is not None else None,
                 "avg_launch_ms": round(float(op_ms[i_dom]), 5),
-                "whole_step": {"achieved": round(whole_tflops, 3), "frac": round(whole_tflops / peak, 5)},
+                "whole_step": whole,
                 "per_kernel": per_op}
 
     cpu = None
