@@ -98,6 +98,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = the headline one)")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pipeline", action="store_true",
                     help="also measure the double-buffered pipeline with host-resident observations")
@@ -113,7 +114,7 @@ def main():
     from paper_2006_11751_amd import binding, workloads as wl
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
-    net = wl.network(args.config)
+    net = wl.network(args.config, **({"B": args.batch} if args.batch > 0 else {}))
     B = net["B"]
     w = wl.weights(net)
     pol = binding.Policy(net, w)

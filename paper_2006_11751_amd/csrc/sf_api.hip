@@ -454,6 +454,21 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
     }
   }
   p->act_elems = act_elems;
+  // bytes per batch row of the largest tensor any encoder launch writes
+  size_t act_row_bytes = 0;
+  for (const Op& op : p->ops) {
+    size_t bytes = 0;
+    if (op.kind == OP_CONV) {
+      const ConvLayer& L = p->convs[op.conv];
+      size_t elems = (size_t)L.Ho * L.Wo * L.cout;
+      if (L.impl == CONV3X3_POOL) elems = (size_t)((L.Ho - 1) / 2 + 1) * ((L.Wo - 1) / 2 + 1) * L.cout;
+      bytes = elems * (p->bf16_path && !L.out_f32 ? 2 : 4);
+    } else if (op.kind == OP_POOL) {
+      bytes = (size_t)((op.H - 1) / 2 + 1) * ((op.W - 1) / 2 + 1) * op.C * (p->bf16_path && !p->stream_f32 ? 2 : 4);
+    }
+    if (bytes > act_row_bytes) act_row_bytes = bytes;
+  }
+  act_row_bytes = (act_row_bytes + 15) & ~(size_t)15;
   // Every encoder launch reads neighbouring pixels of its input from other workgroups' tiles:
   // none may write the buffer it reads.
   for (const Op& op : p->ops)
@@ -582,7 +597,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
   // ---- workspace ----
   int n_act = cfg->encoder == SF_ENCODER_RESNET ? 3 : 2;
   for (int i = 0; i < 3; ++i)
-    p->act[i] = i < n_act ? (float*)bld.dev_alloc(sizeof(float) * act_elems * cfg->max_batch)
+    p->act[i] = i < n_act ? (float*)bld.dev_alloc(act_row_bytes * cfg->max_batch)
                           : nullptr;
   p->trash = (float*)bld.dev_alloc(256);
   p->fc_out = (float*)bld.dev_alloc(sizeof(float) * (size_t)cfg->fc_dim * cfg->max_batch);

@@ -322,3 +322,37 @@ def test_random_network_shapes(torch_cuda, ref, seed):
     stats = parity.check_against_oracle(net, g, o, ref, 11, seed)
     print(net["obs"], net["convs"], net["fc"], net["rnn"], net["heads"], net["dtype"], B, stats)
     pol.close()
+
+
+def test_maximum_batch_size(torch_cuda, ref):
+    """max_batch = 65535 (the largest the boundary accepts) on the standard network: offsets
+    beyond 2^32 bytes, grids of 200,000 workgroups.  Sampled rows against the oracle, and the
+    first 1024 rows bit for bit against a B = 1024 call on the same handle."""
+    torch = torch_cuda
+    net = wl.network(1, B=65535, name="standard_max_batch")
+    pol, w = _make(torch, net)
+    B, d = net["B"], pol.device
+    rng = np.random.default_rng(12345)
+    obs = rng.integers(0, 256, size=(B,) + tuple(net["obs"]), dtype=np.uint8)
+    h_in = (0.1 * rng.standard_normal((B, net["rnn"]))).astype(np.float32)
+    done = (rng.random(B) < 0.05).astype(np.uint8)
+    t_obs, t_h, t_d = torch.from_numpy(obs).to(d), torch.from_numpy(h_in).to(d), torch.from_numpy(done).to(d)
+    big = pol.step(t_obs, t_h, t_d, 1, 3)
+    torch.cuda.synchronize()
+    small = pol.step(t_obs[:1024].contiguous(), t_h[:1024].contiguous(), t_d[:1024].contiguous(), 1, 3)
+    torch.cuda.synchronize()
+    for k in ("actions", "logp", "value", "h_out", "logits"):
+        assert torch.equal(big[k][:1024], small[k]), k
+    g = _to_np(big)
+    rows = np.unique(np.concatenate([[0, B - 1, B - 2, 40000, 65000], rng.integers(0, B, 40)]))
+    o = ref.policy_step(net, w, obs[rows], h_in[rows], done[rows], 1, 3)
+    off = 0
+    for k, A in enumerate(net["heads"]):
+        for i, r in enumerate(rows):
+            a, _, mg = ref.head_sample(o["logits"][i, off:off + A], 1, int(r), 3, k)
+            o["actions"][i, k], o["margin"][i, k] = a, mg
+        off += A
+    o["logp"] = np.array([ref.log_softmax(o["logits"][i])[o["actions"][i, 0]] for i in range(len(rows))], np.float32)
+    parity.check_against_oracle(net, {k: v[rows] for k, v in g.items()}, o, ref, 1, 3, rows=rows)
+    assert np.all(np.isfinite(g["h_out"])) and np.all(np.abs(g["h_out"]) <= 1.0 + 1e-6)
+    pol.close()
