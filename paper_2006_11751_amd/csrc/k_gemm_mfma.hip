@@ -135,6 +135,12 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void gemm_mfma_kernel(GemmArgs g
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
+  // The bias is fetched before the K loop: after it, the load's latency would sit between
+  // the last MFMA and the stores of every tile.
+  float bj[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bj[j] = g.bias[n0 + (wn * TN + j) * 32 + li];
+
   const int nchunks = g.K / BK;
   auto compute = [&](auto bufc) {
     constexpr int BUF = decltype(bufc)::value;
@@ -209,13 +215,12 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void gemm_mfma_kernel(GemmArgs g
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int col = n0 + (wn * TN + j) * 32 + li;
-    const float bj = g.bias[col];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int m = m0 + (wm * TM + i) * 32 + (v & 3) + 4 * lh + 8 * (v >> 2);
-        float r = acc[i][j][v] + bj;
+        float r = acc[i][j][v] + bj[j];
         if (g.relu) r = fmaxf(r, 0.0f);
         if (m < g.M) g.out[(size_t)m * g.N + col] = r;
       }

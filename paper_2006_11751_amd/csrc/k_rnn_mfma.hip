@@ -132,6 +132,41 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
       *(f32x4*)&Bs[(buf * NG * kBJ + q * kBJ + lrow) * kP + lk4] = rb[SET][q];
   };
 
+  // What the gate epilogue needs from memory is fetched before the K loop (biases, the
+  // previous state of this thread's outputs): after the loop each of these loads would add
+  // its latency to every workgroup, and in a one-round grid nothing else hides it.
+  // Wave wk finishes tile rows v in [wk*16/WK, (wk+1)*16/WK); tile element (v, lane) is row
+  // i = (v%4) + 4*(lane/32) + 8*(v/4), column j = lane%32.
+  constexpr int VPW = 16 / WK;
+  const int j = j0 + li;
+  float bias[4];
+  if (LSTM) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) bias[q] = g.b_ih[q * H + j] + g.b_hh[q * H + j];
+  } else {
+    bias[0] = g.b_ih[j] + g.b_hh[j];
+    bias[1] = g.b_ih[H + j] + g.b_hh[H + j];
+    bias[2] = g.b_ih[2 * H + j];
+    bias[3] = g.b_hh[2 * H + j];
+  }
+  float sprev[VPW];  // GRU: previous h; LSTM: previous c (zero after a reset)
+#pragma unroll
+  for (int u = 0; u < VPW; ++u) {
+    const int v = wk * VPW + u;
+    int m = m0 + wm * 32 + (v & 3) + 4 * lh + 8 * (v >> 2);
+    m = m < B ? m : B - 1;
+    int hm = m;
+    bool reset = g.done[m] != 0;
+    if (g.ids) {
+      const int e = g.ids[m];
+      const bool ok = (unsigned)e < (unsigned)g.n_env;
+      hm = ok ? e : 0;
+      reset = reset || !ok;
+    }
+    const float sv = g.h_in[(size_t)hm * S + (LSTM ? H : 0) + j];
+    sprev[u] = reset ? 0.0f : sv;
+  }
+
   // GRU: r, z, n_x, n_h.  LSTM: i, f, g, o.
   f32x16 acc[4];
 #pragma unroll
@@ -200,21 +235,7 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
     for (int v = 0; v < 16; ++v) red[((wave * 4 + t) * 16 + v) * 64 + lane] = acc[t][v];
   __syncthreads();
 
-  // wave wk finishes tile rows v in [wk*16/WK, (wk+1)*16/WK): sum over the K split in
-  // the order k-split 0, 1, ..., then gates.  Tile element (v, lane): row
-  // i = (v%4) + 4*(lane/32) + 8*(v/4), column j = lane%32.
-  const int j = j0 + li;
-  float bias[4];
-  if (LSTM) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) bias[q] = g.b_ih[q * H + j] + g.b_hh[q * H + j];
-  } else {
-    bias[0] = g.b_ih[j] + g.b_hh[j];
-    bias[1] = g.b_ih[H + j] + g.b_hh[H + j];
-    bias[2] = g.b_ih[2 * H + j];
-    bias[3] = g.b_hh[2 * H + j];
-  }
-  constexpr int VPW = 16 / WK;
+  // sum over the K split in the order k-split 0, 1, ..., then the gates
 #pragma unroll
   for (int u = 0; u < VPW; ++u) {
     const int v = wk * VPW + u;
@@ -227,16 +248,8 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
     }
     const int m = m0 + wm * 32 + (v & 3) + 4 * lh + 8 * (v >> 2);
     if (m < B) {
-      int hm = m;
-      bool reset = g.done[m] != 0;
-      if (g.ids) {
-        const int e = g.ids[m];
-        const bool ok = (unsigned)e < (unsigned)g.n_env;
-        hm = ok ? e : 0;
-        reset = reset || !ok;
-      }
       if (LSTM) {
-        const float cprev = reset ? 0.0f : g.h_in[(size_t)hm * S + H + j];
+        const float cprev = sprev[u];
         const float ig = sigmoid_acc(s[0] + bias[0]);
         const float fg = sigmoid_acc(s[1] + bias[1]);
         const float gg = tanhf(s[2] + bias[2]);
@@ -245,7 +258,7 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
         g.h_out[(size_t)m * S + H + j] = cn;
         g.h_out[(size_t)m * S + j] = og * tanhf(cn);
       } else {
-        const float hprev = reset ? 0.0f : g.h_in[(size_t)hm * S + j];
+        const float hprev = sprev[u];
         const float r = sigmoid_acc(s[0] + bias[0]);
         const float z = sigmoid_acc(s[1] + bias[1]);
         const float n = tanhf(s[2] + bias[2] + r * (s[3] + bias[3]));
