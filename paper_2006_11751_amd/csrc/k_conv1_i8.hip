@@ -29,6 +29,8 @@ namespace {
 
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kCout = 32;
 constexpr int kK = 8;
@@ -60,42 +62,84 @@ __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_k
       for (int w = 0; w < 4; ++w) wd[s][d][w] = wpk[((s * 3 + d) * 4 + w) * 64 + lane];
   const float s_n = scale[n], b_n = bias[n];
 
+  // Items are dealt in contiguous runs, so everything that names an item (frame, output row,
+  // x chunk, the two base addresses) is the same for the 64 lanes and lives in scalar
+  // registers; it moves from item to item by carries, without divisions.  The vector ALU is
+  // what bounds this kernel once the addresses are out of it.
   const long long per = n_items / n_waves_total, rem = n_items % n_waves_total;
-  long long it = wave * per + (wave < rem ? wave : rem);
-  const long long it_end = it + per + (wave < rem ? 1 : 0);
-  if (it >= it_end) return;
+  const long long first = wave * per + (wave < rem ? wave : rem);
+  int count = (int)(per + (wave < rem ? 1 : 0));
+  count = __builtin_amdgcn_readfirstlane(count);
+  if (count <= 0) return;
 
-  const size_t frame_bytes = (size_t)CIN * H * W;
   const int items_per_frame = Ho * n_xchunks;
-
-  auto item_src = [&](long long item, int& oy, int& xc) -> const uint8_t* {
-    long long b = item / items_per_frame;
-    int r = (int)(item - b * items_per_frame);
-    oy = r / n_xchunks;
-    xc = r - oy * n_xchunks;
-    int ox = xc * 32 + n;
-    if (ox > Wo - 1) ox = Wo - 1;  // lanes past the row end repeat the last pixel
-    return obs + (size_t)b * frame_bytes + (size_t)(oy * kS) * W + ox * kS;
+  const long long frame0 = first / items_per_frame;
+  const int r0 = (int)(first - frame0 * items_per_frame);
+  int oy = __builtin_amdgcn_readfirstlane(r0 / n_xchunks);
+  int xc = __builtin_amdgcn_readfirstlane(r0 % n_xchunks);
+  const size_t frame_bytes = (size_t)CIN * H * W;
+  constexpr int ELT = OUT_BF16 ? 2 : 4;
+  const size_t out_row_bytes = (size_t)Wo * kCout * ELT;
+  size_t in_off = (size_t)frame0 * frame_bytes + (size_t)(oy * kS) * W;      // frame, first input row
+  size_t out_off = ((size_t)frame0 * Ho + oy) * out_row_bytes;               // frame, output row
+  auto uniform = [](size_t v) -> size_t {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((size_t)hi << 32) | lo;
   };
-  auto load_item = [&](const uint8_t* src, U2 (&dst)[NSTEP][2]) {
+  in_off = uniform(in_off);
+  out_off = uniform(out_off);
+
+  // per-lane parts: the (channel, filter row) group offsets of the 2*NSTEP loads, and the
+  // output offset of tile row 4h, channel n
+  uint32_t goff[NSTEP][2];
+#pragma unroll
+  for (int s = 0; s < NSTEP; ++s)
+#pragma unroll
+    for (int pp = 0; pp < 2; ++pp) {
+      const int g = 4 * s + 2 * h + pp;  // (channel, filter row) group
+      goff[s][pp] = (uint32_t)(((g / kK) * H + (g % kK)) * W);
+    }
+  const uint32_t lane_out = (uint32_t)((4 * h * kCout + n) * ELT);
+
+  // lanes past the row end repeat the last pixel (and store nothing)
+  auto lane_x = [&](int xchunk) -> uint32_t {
+    int ox = xchunk * 32 + n;
+    ox = ox < Wo ? ox : Wo - 1;
+    return (uint32_t)(ox * kS);
+  };
+  auto load_item = [&](size_t ioff, uint32_t lx, U2 (&dst)[NSTEP][2]) {
+    const uint8_t* base = obs + ioff;
 #pragma unroll
     for (int s = 0; s < NSTEP; ++s)
 #pragma unroll
-      for (int pp = 0; pp < 2; ++pp) {
-        const int g = 4 * s + 2 * h + pp;  // (channel, filter row) group
-        const int c = g / kK, p = g % kK;
-        dst[s][pp] = *(const U2*)(src + ((size_t)c * H + p) * W);
-      }
+      for (int pp = 0; pp < 2; ++pp) dst[s][pp] = *(const U2*)(base + (goff[s][pp] + lx));
   };
 
-  U2 cur[NSTEP][2], nxt[NSTEP][2];
-  int oy, xc;
-  load_item(item_src(it, oy, xc), cur);
-  for (; it < it_end; ++it) {
-    int oy_n = 0, xc_n = 0;
-    const bool more = it + 1 < it_end;
-    if (more) load_item(item_src(it + 1, oy_n, xc_n), nxt);
-
+  // One item of compute (about 0.5 us) does not cover a load from memory: three register
+  // sets, loads two items ahead of the MFMAs, roles rotating without copies.  The load
+  // cursor (lx, ly, l_in) runs ahead of the compute cursor (xc, oy, out_off).
+  int lx = xc, ly = oy;
+  size_t l_in = in_off;
+  auto advance_load = [&]() {
+    if (++lx == n_xchunks) {
+      lx = 0;
+      l_in += (size_t)kS * W;
+      if (++ly == Ho) {  // next frame: its rows follow this frame's last filter window
+        ly = 0;
+        l_in += frame_bytes - (size_t)Ho * kS * W;
+      }
+    }
+  };
+  int issued = 0;
+  auto issue = [&](U2 (&dst)[NSTEP][2]) {
+    if (issued < count) {
+      load_item(l_in, lane_x(lx), dst);
+      advance_load();
+    }
+    ++issued;
+  };
+  auto run_item = [&](const U2 (&cur)[NSTEP][2]) {
     i32x16 s1, s2, s3;
 #pragma unroll
     for (int v = 0; v < 16; ++v) s1[v] = s2[v] = s3[v] = 0;
@@ -112,30 +156,52 @@ __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_k
     }
     // epilogue.  D[i][j]: j = n, i = (v%4) + 4h + 8(v/4).  S2*128 + S3 fits int32
     // (|S2|, |S3| <= 192*128*64); its float image is exact to 6e-8 relative.
-    const long long b = it / items_per_frame;
-    const size_t dst0 = (((size_t)b * Ho + oy) * Wo) * kCout + n;
+    float r[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      int ox = xc * 32 + (v & 3) + 4 * h + 8 * (v >> 2);
-      ox = ox < Wo ? ox : Wo - 1;  // duplicate rows hold the last pixel's result bit for bit
       const float lo = (float)(s2[v] * 128 + s3[v]);
       const float q = fmaf(lo, 0x1.0p-14f, (float)s1[v]);
-      const float r = fmaxf(fmaf(q, s_n, b_n), 0.0f);
-      if (OUT_BF16) {
-        const unsigned u = __float_as_uint(r);
-        ((uint16_t*)out_v)[dst0 + ox * kCout] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
-      } else {
-        ((float*)out_v)[dst0 + ox * kCout] = r;
+      r[v] = fmaxf(fmaf(q, s_n, b_n), 0.0f);
+    }
+    // tile row (v%4) + 8(v/4) + 4h is pixel xc*32 + that; the row part is a constant of the
+    // store instruction, the lane part sits in lane_out
+    uint8_t* obase = (uint8_t*)out_v + out_off + (size_t)(xc * 32) * (kCout * ELT);
+    const int rows_left = Wo - xc * 32 - 4 * h;  // tile rows v with (v%4) + 8(v/4) < rows_left exist
+    if (OUT_BF16) {
+#pragma unroll
+      for (int v = 0; v < 16; v += 2) {
+        const f32x2 pair = {r[v], r[v + 1]};
+        const unsigned word = __builtin_bit_cast(unsigned, __builtin_convertvector(pair, bf16x2));
+        const int row = (v & 3) + 8 * (v >> 2);
+        if (row < rows_left) *(uint16_t*)(obase + lane_out + row * kCout * ELT) = (uint16_t)word;
+        if (row + 1 < rows_left) *(uint16_t*)(obase + lane_out + (row + 1) * kCout * ELT) = (uint16_t)(word >> 16);
+      }
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = (v & 3) + 8 * (v >> 2);
+        if (row < rows_left) *(float*)(obase + lane_out + row * kCout * ELT) = r[v];
       }
     }
-    if (more) {
-#pragma unroll
-      for (int s = 0; s < NSTEP; ++s) {
-        cur[s][0] = nxt[s][0];
-        cur[s][1] = nxt[s][1];
-      }
-      oy = oy_n;
-      xc = xc_n;
+    if (++xc == n_xchunks) {
+      xc = 0;
+      out_off += out_row_bytes;  // output rows of consecutive frames are contiguous
+    }
+  };
+
+  U2 b0[NSTEP][2], b1[NSTEP][2], b2[NSTEP][2];
+  issue(b0);
+  issue(b1);
+  for (int i = 0; i < count; i += 3) {
+    issue(b2);
+    run_item(b0);
+    if (i + 1 < count) {
+      issue(b0);
+      run_item(b1);
+    }
+    if (i + 2 < count) {
+      issue(b1);
+      run_item(b2);
     }
   }
 }
