@@ -100,7 +100,19 @@ __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_k
       const int g = 4 * s + 2 * h + pp;  // (channel, filter row) group
       goff[s][pp] = (uint32_t)(((g / kK) * H + (g % kK)) * W);
     }
-  const uint32_t lane_out = (uint32_t)((4 * h * kCout + n) * ELT);
+  // byte offset of tile row (v%4) + 8(v/4) + 4h, channel n, within the item's 32 output
+  // pixels; rows past the end of the image row point at its last pixel
+  uint32_t voff[16];
+  auto set_store_offsets = [&](int xchunk) {
+    const int nvalid = Wo - xchunk * 32;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      int i = (v & 3) + 8 * (v >> 2) + 4 * h;
+      i = i < nvalid ? i : nvalid - 1;
+      voff[v] = (uint32_t)((i * kCout + n) * ELT);
+    }
+  };
+  set_store_offsets(xc);
 
   // lanes past the row end repeat the last pixel (and store nothing)
   auto lane_x = [&](int xchunk) -> uint32_t {
@@ -163,25 +175,21 @@ __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_k
       const float q = fmaf(lo, 0x1.0p-14f, (float)s1[v]);
       r[v] = fmaxf(fmaf(q, s_n, b_n), 0.0f);
     }
-    // tile row (v%4) + 8(v/4) + 4h is pixel xc*32 + that; the row part is a constant of the
-    // store instruction, the lane part sits in lane_out
+    // no predicated stores (each would become a branch): lanes past the row end write the
+    // last pixel again, with the same bits
     uint8_t* obase = (uint8_t*)out_v + out_off + (size_t)(xc * 32) * (kCout * ELT);
-    const int rows_left = Wo - xc * 32 - 4 * h;  // tile rows v with (v%4) + 8(v/4) < rows_left exist
+    if (n_xchunks > 1) set_store_offsets(xc);
     if (OUT_BF16) {
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
         const f32x2 pair = {r[v], r[v + 1]};
         const unsigned word = __builtin_bit_cast(unsigned, __builtin_convertvector(pair, bf16x2));
-        const int row = (v & 3) + 8 * (v >> 2);
-        if (row < rows_left) *(uint16_t*)(obase + lane_out + row * kCout * ELT) = (uint16_t)word;
-        if (row + 1 < rows_left) *(uint16_t*)(obase + lane_out + (row + 1) * kCout * ELT) = (uint16_t)(word >> 16);
+        *(uint16_t*)(obase + voff[v]) = (uint16_t)word;
+        *(uint16_t*)(obase + voff[v + 1]) = (uint16_t)(word >> 16);
       }
     } else {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = (v & 3) + 8 * (v >> 2);
-        if (row < rows_left) *(float*)(obase + lane_out + row * kCout * ELT) = r[v];
-      }
+      for (int v = 0; v < 16; ++v) *(float*)(obase + voff[v]) = r[v];
     }
     if (++xc == n_xchunks) {
       xc = 0;
