@@ -211,20 +211,29 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void gemm_mfma_kernel(GemmArgs g
     if (wk != 0) return;
   }
 
-  // epilogue: D[i][j] of a 32x32 tile: j = lane%32, i = (v%4) + 4*(lane/32) + 8*(v/4)
+  // epilogue: D[i][j] of a 32x32 tile: j = lane%32, i = (v%4) + 4*(lane/32) + 8*(v/4).
+  // A per-lane predicate puts a branch around every store; only the last row tile can hold
+  // rows past the end, so the choice is made once per workgroup.
+  auto write_tile = [&](auto checked) {
+    constexpr bool CHECK = decltype(checked)::value;
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int col = n0 + (wn * TN + j) * 32 + li;
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + (wn * TN + j) * 32 + li;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + (wm * TM + i) * 32 + (v & 3) + 4 * lh + 8 * (v >> 2);
-        float r = acc[i][j][v] + bj[j];
-        if (g.relu) r = fmaxf(r, 0.0f);
-        if (m < g.M) g.out[(size_t)m * g.N + col] = r;
-      }
-  }
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + (wm * TM + i) * 32 + (v & 3) + 4 * lh + 8 * (v >> 2);
+          float r = acc[i][j][v] + bj[j];
+          if (g.relu) r = fmaxf(r, 0.0f);
+          if (!CHECK || m < g.M) g.out[(size_t)m * g.N + col] = r;
+        }
+    }
+  };
+  if (m0 + BM <= g.M)
+    write_tile(std::false_type{});
+  else
+    write_tile(std::true_type{});
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int WK, int TAG>
