@@ -235,37 +235,46 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
     for (int v = 0; v < 16; ++v) red[((wave * 4 + t) * 16 + v) * 64 + lane] = acc[t][v];
   __syncthreads();
 
-  // sum over the K split in the order k-split 0, 1, ..., then the gates
+  // sum over the K split in the order k-split 0, 1, ..., then the gates.  Only the last row
+  // block can hold rows past the end: the row check (a branch per output) is compiled in
+  // for that block alone.
+  auto finish = [&](auto checked) {
+    constexpr bool CHECK = decltype(checked)::value;
 #pragma unroll
-  for (int u = 0; u < VPW; ++u) {
-    const int v = wk * VPW + u;
-    float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int u = 0; u < VPW; ++u) {
+      const int v = wk * VPW + u;
+      float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-    for (int k = 0; k < WK; ++k) {
-      const int src = wm + WM * k;  // wave index holding k-split k of this row block
+      for (int k = 0; k < WK; ++k) {
+        const int src = wm + WM * k;  // wave index holding k-split k of this row block
 #pragma unroll
-      for (int t = 0; t < 4; ++t) s[t] += red[((src * 4 + t) * 16 + v) * 64 + lane];
-    }
-    const int m = m0 + wm * 32 + (v & 3) + 4 * lh + 8 * (v >> 2);
-    if (m < B) {
-      if (LSTM) {
-        const float cprev = sprev[u];
-        const float ig = sigmoid_acc(s[0] + bias[0]);
-        const float fg = sigmoid_acc(s[1] + bias[1]);
-        const float gg = tanhf(s[2] + bias[2]);
-        const float og = sigmoid_acc(s[3] + bias[3]);
-        const float cn = fg * cprev + ig * gg;
-        g.h_out[(size_t)m * S + H + j] = cn;
-        g.h_out[(size_t)m * S + j] = og * tanhf(cn);
-      } else {
-        const float hprev = sprev[u];
-        const float r = sigmoid_acc(s[0] + bias[0]);
-        const float z = sigmoid_acc(s[1] + bias[1]);
-        const float n = tanhf(s[2] + bias[2] + r * (s[3] + bias[3]));
-        g.h_out[(size_t)m * S + j] = (1.0f - z) * n + z * hprev;
+        for (int t = 0; t < 4; ++t) s[t] += red[((src * 4 + t) * 16 + v) * 64 + lane];
+      }
+      const int m = m0 + wm * 32 + (v & 3) + 4 * lh + 8 * (v >> 2);
+      if (!CHECK || m < B) {
+        if (LSTM) {
+          const float cprev = sprev[u];
+          const float ig = sigmoid_acc(s[0] + bias[0]);
+          const float fg = sigmoid_acc(s[1] + bias[1]);
+          const float gg = tanhf(s[2] + bias[2]);
+          const float og = sigmoid_acc(s[3] + bias[3]);
+          const float cn = fg * cprev + ig * gg;
+          g.h_out[(size_t)m * S + H + j] = cn;
+          g.h_out[(size_t)m * S + j] = og * tanhf(cn);
+        } else {
+          const float hprev = sprev[u];
+          const float r = sigmoid_acc(s[0] + bias[0]);
+          const float z = sigmoid_acc(s[1] + bias[1]);
+          const float n = tanhf(s[2] + bias[2] + r * (s[3] + bias[3]));
+          g.h_out[(size_t)m * S + j] = (1.0f - z) * n + z * hprev;
+        }
       }
     }
-  }
+  };
+  if (m0 + BM <= B)
+    finish(std::false_type{});
+  else
+    finish(std::true_type{});
 }
 
 }  // namespace
