@@ -53,6 +53,16 @@ __device__ inline unsigned f32_to_h(float f) {
   unsigned u = __float_as_uint(f);
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;  // round to nearest even (finite inputs)
 }
+// two floats -> one 32-bit word of two 16-bit values (first in the low half), round to
+// nearest even; bf16 through the packed hardware conversion
+template <bool kF16>
+__device__ inline unsigned f32x2_to_h2(float a, float b) {
+  if (kF16) return f32_to_h<true>(a) | (f32_to_h<true>(b) << 16);
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
+}
 template <bool kF16>
 __device__ inline float h_to_f32(unsigned h) {
   if (kF16) return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
@@ -223,6 +233,17 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
     if (c + 1 < nchunks) sstore(std::integral_constant<int, S ^ 1>{}, (c + 1) & 1);
     __syncthreads();
   };
+  // The bias is fetched before the K loop (after it, its latency would end every tile).
+  // Channels of this lane: n0 + 8*q4 + 4*lh .. +3; a tile that reaches past N (a multiple
+  // of 4, not of 32) checks each group of four.
+  const bool whole_n = n0 + kBC <= g.N;
+  f32x4 bq[4];
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4) {
+    int ch = n0 + 8 * q4 + 4 * lh;
+    ch = ch < g.N ? ch : g.N - 4;
+    bq[q4] = *(const f32x4*)(g.bias + ch);
+  }
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
   gload(I0{}, 0);
@@ -240,10 +261,10 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
 #pragma unroll
   for (int q4 = 0; q4 < 4; ++q4) {
     const int ch = n0 + 8 * q4 + 4 * lh;
-    if (ch >= g.N) continue;  // N is a multiple of 4
+    if (!whole_n && ch >= g.N) continue;  // N is a multiple of 4
     float r[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) r[t] = acc[4 * q4 + t] + g.bias[ch + t];
+    for (int t = 0; t < 4; ++t) r[t] = acc[4 * q4 + t] + bq[q4][t];
     if (g.resid) {
       if (g.resid_f32) {
         const f32x4 rv = *(const f32x4*)((const float*)g.resid + (size_t)m * g.N + ch);
@@ -266,8 +287,8 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
       *(f32x4*)((float*)g.out + (size_t)m * g.N + ch) = o;
     } else {
       u32x2 o;
-      o[0] = f32_to_h<kF16>(r[0]) | (f32_to_h<kF16>(r[1]) << 16);
-      o[1] = f32_to_h<kF16>(r[2]) | (f32_to_h<kF16>(r[3]) << 16);
+      o[0] = f32x2_to_h2<kF16>(r[0], r[1]);
+      o[1] = f32x2_to_h2<kF16>(r[2], r[3]);
       *(u32x2*)((uint16_t*)g.out + (size_t)m * g.N + ch) = o;
     }
   }
