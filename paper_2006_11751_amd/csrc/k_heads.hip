@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kWave* kRowsPerBlock) void heads_kernel(
     int n_heads, int sumA, uint32_t seed_lo, uint32_t seed_hi, uint32_t step_lo,
     uint32_t step_hi, int32_t* __restrict__ actions, float* __restrict__ logp,
     float* __restrict__ value, float* __restrict__ logits_opt, const int32_t* __restrict__ ids,
-    float* __restrict__ h_table, int n_env, int S) {
+    float* __restrict__ h_table, int n_env, int S, int lane_per_head) {
   __shared__ float s_logits[kRowsPerBlock][kMaxLogits];
   __shared__ float s_pert[kRowsPerBlock][kMaxLogits];
   const int lane = threadIdx.x % kWave;
@@ -135,6 +135,31 @@ __global__ __launch_bounds__(kWave* kRowsPerBlock) void heads_kernel(
   __threadfence_block();
 
   float lp_total = 0.0f;
+  if (lane_per_head) {
+    // Several small heads (none above 32 categories): lane k finishes head k on its own, all
+    // heads side by side, instead of one wave-wide butterfly per head after another.  Categories
+    // are visited in ascending order, so the first maximum wins ties.
+    float lp = 0.0f;
+    if (lane < n_heads) {
+      const int off = head_off[lane];
+      const int A = head_off[lane + 1] - off;
+      float best = pt[off], lmax = lg[off];
+      int arg = 0;
+      for (int i = 1; i < A; ++i) {
+        const float pert = pt[off + i];
+        if (pert > best) {
+          best = pert;
+          arg = i;
+        }
+        lmax = fmaxf(lmax, lg[off + i]);
+      }
+      float se = 0.0f;
+      for (int i = 0; i < A; ++i) se += expf(lg[off + i] - lmax);
+      lp = lg[off + arg] - (lmax + logf(se));
+      actions[(size_t)b * n_heads + lane] = arg;
+    }
+    lp_total = wave_sum(lp);
+  } else
   for (int k = 0; k < n_heads; ++k) {
     const int off = head_off[k];
     const int A = head_off[k + 1] - off;
@@ -182,14 +207,14 @@ hipError_t launch_heads(int B, int H, int n_heads, int sumA, const int32_t* head
                         const float* h, const float* head_w, const float* head_b, uint64_t seed,
                         uint64_t step, int32_t* actions, float* logp, float* value,
                         float* logits_opt, const int32_t* ids, float* h_table, int n_env,
-                        int state_dim, hipStream_t st) {
+                        int state_dim, int max_head, hipStream_t st) {
   if (B == 0) return hipSuccess;
   if (sumA + 1 > kMaxLogits) return hipErrorInvalidValue;
   unsigned blocks = (unsigned)((B + kRowsPerBlock - 1) / kRowsPerBlock);
   heads_kernel<<<blocks, kWave * kRowsPerBlock, 0, st>>>(
       h, head_w, head_b, head_off, B, H, n_heads, sumA, (uint32_t)seed, (uint32_t)(seed >> 32),
       (uint32_t)step, (uint32_t)(step >> 32), actions, logp, value, logits_opt, ids, h_table,
-      n_env, state_dim);
+      n_env, state_dim, (n_heads > 1 && n_heads <= kWave && max_head <= 32) ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -580,6 +580,9 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
       off[k + 1] = sumA;
     }
     p->sumA = sumA;
+    p->max_head = 0;
+    for (int k = 0; k < cfg->n_heads; ++k)
+      if (cfg->head_sizes[k] > p->max_head) p->max_head = cfg->head_sizes[k];
     const int Hd = cfg->rnn_dim;
     std::vector<float> hw((size_t)(sumA + 1) * Hd), hb(sumA + 1);
     for (size_t i = 0; i < (size_t)sumA * Hd; ++i) hw[i] = bld.q(w->pi_w[i]);
@@ -970,7 +973,7 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
       case OP_HEADS:
         SF_LAUNCH(launch_heads(B, c.rnn_dim, c.n_heads, p->sumA, p->head_off, h_out, p->head_w,
                                p->head_b, seed, step, actions, logp, value, logits_opt, ids, h_table,
-                               n_env, p->state_dim, st));
+                               n_env, p->state_dim, p->max_head, st));
         break;
     }
     if (p->timing) SF_LAUNCH(hipEventRecord(p->events[i + 1], st));

@@ -61,6 +61,7 @@ struct Policy {
   int device;
   int flat;   // encoder output elements per row
   int sumA;   // total logits per row
+  int max_head = 0;  // categories of the largest head
   std::vector<ConvLayer> convs;  // in execution order
   // packed weights
   float* fc_w_t;      // dev [flat (channels-last order)][fc_dim]
@@ -138,7 +139,7 @@ hipError_t launch_heads(int B, int H, int n_heads, int sumA, const int32_t* head
                         const float* h, const float* head_w, const float* head_b, uint64_t seed,
                         uint64_t step, int32_t* actions, float* logp, float* value,
                         float* logits_opt, const int32_t* ids, float* h_table, int n_env,
-                        int state_dim, hipStream_t st);
+                        int state_dim, int max_head, hipStream_t st);
 
 hipError_t launch_copy16(const void* src, void* dst, long long bytes, hipStream_t st);
 
