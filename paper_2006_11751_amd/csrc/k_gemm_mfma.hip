@@ -164,23 +164,41 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void gemm_mfma_kernel(GemmArgs g
   // iteration c (parity S): start the loads of chunk c+2 into register set S, run the
   // MFMAs of chunk c from LDS buffer S, then move chunk c+1 (set S^1, loaded one
   // iteration ago) into LDS buffer S^1; one barrier per chunk.
-  auto step = [&](auto set, int c) {
+  auto step = [&](auto set, auto loadc, auto storec) {
     constexpr int S = decltype(set)::value;
     using Other = std::integral_constant<int, S ^ 1>;
-    if (c + 2 < nchunks) gload(set);
+    if (decltype(loadc)::value) gload(set);
     compute(set);
-    if (c + 1 < nchunks) sstore(Other{}, Other{});
+    if (decltype(storec)::value) sstore(Other{}, Other{});
     __syncthreads();
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
+  using Yes = std::true_type;
+  using No = std::false_type;
   gload(I0{});
   sstore(I0{}, I0{});
   if (nchunks > 1) gload(I1{});
   __syncthreads();
-  for (int c = 0; c < nchunks; c += 2) {
-    step(I0{}, c);
-    if (c + 1 < nchunks) step(I1{}, c + 1);
+  // Steady state without conditions around the loads: a load that is issued on one path only
+  // makes the compiler wait for every outstanding load before each LDS store (it must cover
+  // the path without the new loads), which takes the prefetch distance from two chunks to
+  // none.  The last two chunks are peeled off instead.
+  int c = 0;
+  for (; c + 3 < nchunks; c += 2) {
+    step(I0{}, Yes{}, Yes{});
+    step(I1{}, Yes{}, Yes{});
+  }
+  // here 1, 2 or 3 chunks remain: c + 1 <= nchunks <= c + 3
+  if (c + 3 == nchunks) {
+    step(I0{}, Yes{}, Yes{});
+    step(I1{}, No{}, Yes{});
+    step(I0{}, No{}, No{});
+  } else if (c + 2 == nchunks) {
+    step(I0{}, No{}, Yes{});
+    step(I1{}, No{}, No{});
+  } else {
+    step(I0{}, No{}, No{});
   }
 
   // sum the K-split partial tiles in a fixed order (wk = 1, 2, 3 into wk = 0)
