@@ -209,22 +209,56 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
       }
     }
   };
-  auto step = [&](auto set, int c) {
+  auto step = [&](auto set, int c, auto loadc, auto storec) {
     constexpr int SET = decltype(set)::value;
-    if (c + 2 < nchunks) gload(set, c + 2);
+    if (decltype(loadc)::value) gload(set, c + 2);
     compute(c);
-    if (c + 1 < nchunks) sstore(std::integral_constant<int, SET ^ 1>{}, (c + 1) & 1);
+    if (decltype(storec)::value) sstore(std::integral_constant<int, SET ^ 1>{}, (c + 1) & 1);
     __syncthreads();
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
+  using Yes = std::true_type;
+  using No = std::false_type;
   gload(I0{}, 0);
   sstore(I0{}, 0);
   if (nchunks > 1) gload(I1{}, 1);
   __syncthreads();
-  for (int c = 0; c < nchunks; c += 2) {
-    step(I0{}, c);
-    if (c + 1 < nchunks) step(I1{}, c + 1);
+  if (LSTM) {
+    // Steady state without a condition around the loads (with one, the compiler waits for
+    // every outstanding load before each LDS store, and nothing stays in flight across a
+    // chunk); the last chunks are peeled off.  Measured: 53 -> 49 us at B = 1024, H = 512.
+    int c = 0;
+    for (; c + 3 < nchunks; c += 2) {
+      step(I0{}, c, Yes{}, Yes{});
+      step(I1{}, c + 1, Yes{}, Yes{});
+    }
+    if (c + 3 == nchunks) {
+      step(I0{}, c, Yes{}, Yes{});
+      step(I1{}, c + 1, No{}, Yes{});
+      step(I0{}, c + 2, No{}, No{});
+    } else if (c + 2 == nchunks) {
+      step(I0{}, c, No{}, Yes{});
+      step(I1{}, c + 1, No{}, No{});
+    } else {
+      step(I0{}, c, No{}, No{});
+    }
+  } else {
+    // The GRU keeps the conditions: its two accumulator sets (x chunks, h chunks) make the
+    // peeled form take so many more accumulator registers that it runs slower (45-62 us
+    // against 42 us in every variant that was measured).
+    for (int c = 0; c < nchunks; c += 2) {
+      if (c + 2 < nchunks) gload(I0{}, c + 2);
+      compute(c);
+      if (c + 1 < nchunks) sstore(I1{}, (c + 1) & 1);
+      __syncthreads();
+      if (c + 1 < nchunks) {
+        if (c + 3 < nchunks) gload(I1{}, c + 3);
+        compute(c + 1);
+        if (c + 2 < nchunks) sstore(I0{}, c & 1);
+        __syncthreads();
+      }
+    }
   }
 
   // partial tiles of every wave -> LDS (the tile buffers are no longer read)
