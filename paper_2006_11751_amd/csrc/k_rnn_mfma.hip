@@ -57,7 +57,9 @@ struct RnnArgs {
   int n_env;
 };
 
-template <int BM, bool LSTM>
+// PAIRS (GRU only): the x chunks and the h chunks both come in pairs (I1 + I2 and H multiples
+// of 64), which lets the K loop be written as two plain loops, one per accumulator set.
+template <int BM, bool LSTM, bool PAIRS>
 __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
   constexpr int NG = LSTM ? 4 : 3;  // gate blocks of the weight matrices
   constexpr int WM = BM / 32, WK = 4 / WM;
@@ -174,11 +176,13 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
 
-  auto compute = [&](int c) {
+  // PH: 0 = x chunk, 1 = h chunk, 2 = by the chunk index (the LSTM's chunks are all alike)
+  auto compute = [&](int c, auto phase) {
+    constexpr int PH = decltype(phase)::value;
     const int buf = c & 1;
     const float* Ab = As + (buf * BM + wm * 32 + li) * kP + 4 * lh;
     const float* Bb = Bs + (buf * NG * kBJ + li) * kP + 4 * lh;
-    const bool xphase = c < nx_chunks;
+    const bool xphase = PH == 2 ? c < nx_chunks : PH == 0;
 #pragma unroll
     for (int gi = 0; gi < GPW; ++gi) {
       const int kg = (gi * WK + wk) * 8;
@@ -209,10 +213,11 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
       }
     }
   };
-  auto step = [&](auto set, int c, auto loadc, auto storec) {
+  using I2 = std::integral_constant<int, 2>;
+  auto step = [&](auto set, int c, auto phase, auto loadc, auto storec) {
     constexpr int SET = decltype(set)::value;
     if (decltype(loadc)::value) gload(set, c + 2);
-    compute(c);
+    compute(c, phase);
     if (decltype(storec)::value) sstore(std::integral_constant<int, SET ^ 1>{}, (c + 1) & 1);
     __syncthreads();
   };
@@ -230,31 +235,44 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
     // chunk); the last chunks are peeled off.  Measured: 53 -> 49 us at B = 1024, H = 512.
     int c = 0;
     for (; c + 3 < nchunks; c += 2) {
-      step(I0{}, c, Yes{}, Yes{});
-      step(I1{}, c + 1, Yes{}, Yes{});
+      step(I0{}, c, I2{}, Yes{}, Yes{});
+      step(I1{}, c + 1, I2{}, Yes{}, Yes{});
     }
     if (c + 3 == nchunks) {
-      step(I0{}, c, Yes{}, Yes{});
-      step(I1{}, c + 1, No{}, Yes{});
-      step(I0{}, c + 2, No{}, No{});
+      step(I0{}, c, I2{}, Yes{}, Yes{});
+      step(I1{}, c + 1, I2{}, No{}, Yes{});
+      step(I0{}, c + 2, I2{}, No{}, No{});
     } else if (c + 2 == nchunks) {
-      step(I0{}, c, No{}, Yes{});
-      step(I1{}, c + 1, No{}, No{});
+      step(I0{}, c, I2{}, No{}, Yes{});
+      step(I1{}, c + 1, I2{}, No{}, No{});
     } else {
-      step(I0{}, c, No{}, No{});
+      step(I0{}, c, I2{}, No{}, No{});
     }
+  } else if (PAIRS) {
+    // GRU, x chunks and h chunks in pairs: one plain loop per accumulator set, the loads
+    // running on across the change of phase, the last pair without loads.
+    int c = 0;
+    for (; c < nx_chunks; c += 2) {
+      step(I0{}, c, I0{}, Yes{}, Yes{});
+      step(I1{}, c + 1, I0{}, Yes{}, Yes{});
+    }
+    for (; c + 2 < nchunks; c += 2) {
+      step(I0{}, c, I1{}, Yes{}, Yes{});
+      step(I1{}, c + 1, I1{}, Yes{}, Yes{});
+    }
+    step(I0{}, c, I1{}, No{}, Yes{});
+    step(I1{}, c + 1, I1{}, No{}, No{});
   } else {
-    // The GRU keeps the conditions: its two accumulator sets (x chunks, h chunks) make the
-    // peeled form take so many more accumulator registers that it runs slower (45-62 us
-    // against 42 us in every variant that was measured).
+    // GRU, any chunk counts: conditions around the loads and the accumulator set chosen
+    // per chunk (peeling this form costs so many accumulator registers that it runs slower).
     for (int c = 0; c < nchunks; c += 2) {
       if (c + 2 < nchunks) gload(I0{}, c + 2);
-      compute(c);
+      compute(c, I2{});
       if (c + 1 < nchunks) sstore(I1{}, (c + 1) & 1);
       __syncthreads();
       if (c + 1 < nchunks) {
         if (c + 3 < nchunks) gload(I1{}, c + 3);
-        compute(c + 1);
+        compute(c + 1, I2{});
         if (c + 2 < nchunks) sstore(I0{}, c & 1);
         __syncthreads();
       }
@@ -328,24 +346,25 @@ int rnn_mfma_pick_bm(int max_batch, int H) {
 hipError_t launch_rnn_mfma(int lstm, int B, int I1, int I2, int H, const float* x1, const float* x2,
                            const float* h_in, const uint8_t* done, const float* w_ih,
                            const float* w_hh, const float* b_ih, const float* b_hh, float* h_out,
-                           int bm, const int32_t* ids, int n_env, hipStream_t st) {
+                           int bm, int plain_loops, const int32_t* ids, int n_env, hipStream_t st) {
   if (B == 0) return hipSuccess;
   RnnArgs g;
   g.x1 = x1; g.x2 = x2; g.h_in = h_in; g.done = done;
   g.w_ih = w_ih; g.w_hh = w_hh; g.b_ih = b_ih; g.b_hh = b_hh; g.h_out = h_out;
   g.B = B; g.I1 = I1; g.I2 = x2 ? I2 : 0; g.H = H; g.ids = ids; g.n_env = n_env;
+  const bool pairs = plain_loops && ((g.I1 + g.I2) % 64) == 0 && (H % 64) == 0;
   if (bm == 64) {
     dim3 grid((B + 63) / 64, H / kBJ);
     if (lstm)
-      rnn_mfma_kernel<64, true><<<grid, 256, 0, st>>>(g);
+      rnn_mfma_kernel<64, true, false><<<grid, 256, 0, st>>>(g);
     else
-      rnn_mfma_kernel<64, false><<<grid, 256, 0, st>>>(g);
+      if (pairs) rnn_mfma_kernel<64, false, true><<<grid, 256, 0, st>>>(g); else rnn_mfma_kernel<64, false, false><<<grid, 256, 0, st>>>(g);
   } else {
     dim3 grid((B + 31) / 32, H / kBJ);
     if (lstm)
-      rnn_mfma_kernel<32, true><<<grid, 256, 0, st>>>(g);
+      rnn_mfma_kernel<32, true, false><<<grid, 256, 0, st>>>(g);
     else
-      rnn_mfma_kernel<32, false><<<grid, 256, 0, st>>>(g);
+      if (pairs) rnn_mfma_kernel<32, false, true><<<grid, 256, 0, st>>>(g); else rnn_mfma_kernel<32, false, false><<<grid, 256, 0, st>>>(g);
   }
   return hipGetLastError();
 }

@@ -565,6 +565,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
     p->gru_wih = bld.pack_vec(w->rnn_w_ih, (size_t)HG * core_in);
     p->gru_whh = bld.pack_vec(w->rnn_w_hh, (size_t)HG * cfg->rnn_dim);
     p->gru_bm = getenv("SF_GRU_BM") ? atoi(getenv("SF_GRU_BM")) : rnn_mfma_pick_bm(cfg->max_batch, cfg->rnn_dim);
+    p->rnn_plain_loops = getenv("SF_NO_RNN_PAIRS") ? 0 : 1;
   }
   p->gru_bih = bld.pack_vec(w->rnn_b_ih, HG);
   p->gru_bhh = bld.pack_vec(w->rnn_b_hh, HG);
@@ -963,7 +964,7 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
         else if (p->gru_wih)
           SF_LAUNCH(launch_rnn_mfma(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out, x2, h_in,
                                     done, p->gru_wih, p->gru_whh, p->gru_bih, p->gru_bhh, h_out,
-                                    p->gru_bm, ids, n_env, st));
+                                    p->gru_bm, p->rnn_plain_loops, ids, n_env, st));
         else
           SF_LAUNCH(launch_rnn_generic(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out, x2,
                                        h_in, done, p->gru_wih_t, p->gru_whh_t, p->gru_bih, p->gru_bhh,

@@ -80,6 +80,7 @@ struct Policy {
   float* gru_wih;     // dev [G*H][core input] (canonical) for the MFMA kernel, or null
   float* gru_whh;     // dev [G*H][H]
   int gru_bm;         // rows per workgroup of the MFMA kernel, fixed at create
+  int rnn_plain_loops = 1;  // GRU on the MFMA: the two-plain-loops form where the chunk counts allow it
   uint16_t* rnn_wih_bf;  // dev bf16 [G*H][core input] for the 16-bit MFMA kernel, or null
   uint16_t* rnn_whh_bf;  // dev bf16 [G*H][H]
   float* gru_bih;     // dev [G*H]
@@ -196,7 +197,7 @@ bool rnn_mfma_supported(int I1, int I2, int H);
 hipError_t launch_rnn_mfma(int lstm, int B, int I1, int I2, int H, const float* x1, const float* x2,
                            const float* h_in, const uint8_t* done, const float* w_ih,
                            const float* w_hh, const float* b_ih, const float* b_hh, float* h_out,
-                           int bm, const int32_t* ids, int n_env, hipStream_t st);
+                           int bm, int plain_loops, const int32_t* ids, int n_env, hipStream_t st);
 int rnn_mfma_pick_bm(int max_batch, int H);
 bool rnn_bf16_supported(int I1, int I2, int H);
 void rnn_bf16_pack(const float* w, size_t n, std::vector<uint16_t>& out);

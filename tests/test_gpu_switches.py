@@ -25,6 +25,7 @@ CASES = [
     ("SF_CONV1", "fp32", STD_SMALL),
     ("SF_GEMM_TILE", "4", STD_SMALL),
     ("SF_GRU_BM", "64", STD_SMALL),
+    ("SF_NO_RNN_PAIRS", "1", STD_SMALL),
     ("SF_NO_BF16_PATH", "1", STD_BF16_SMALL),
     ("SF_NO_RNN_BF16", "1", STD_BF16_SMALL),
     ("SF_NO_RNN_BF16", "1", BY_NAME["lstm_bf16_mfma"]),
