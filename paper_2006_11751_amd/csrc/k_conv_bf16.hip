@@ -226,11 +226,11 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
       }
     }
   };
-  auto step = [&](auto set, int c) {
+  auto step = [&](auto set, int c, auto loadc, auto storec) {
     constexpr int S = decltype(set)::value;
-    if (c + 2 < nchunks) gload(set, c + 2);
+    if (decltype(loadc)::value) gload(set, c + 2);
     compute(c & 1);
-    if (c + 1 < nchunks) sstore(std::integral_constant<int, S ^ 1>{}, (c + 1) & 1);
+    if (decltype(storec)::value) sstore(std::integral_constant<int, S ^ 1>{}, (c + 1) & 1);
     __syncthreads();
   };
   // The bias is fetched before the K loop (after it, its latency would end every tile).
@@ -250,9 +250,25 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
   sstore(I0{}, 0);
   if (nchunks > 1) gload(I1{}, 1);
   __syncthreads();
-  for (int c = 0; c < nchunks; c += 2) {
-    step(I0{}, c);
-    if (c + 1 < nchunks) step(I1{}, c + 1);
+  // Steady state without a condition around the loads (with one, the compiler waits for
+  // every outstanding load before each LDS store, and nothing stays in flight across a
+  // chunk); the last chunks are peeled off.
+  using Yes = std::true_type;
+  using No = std::false_type;
+  int c = 0;
+  for (; c + 3 < nchunks; c += 2) {
+    step(I0{}, c, Yes{}, Yes{});
+    step(I1{}, c + 1, Yes{}, Yes{});
+  }
+  if (c + 3 == nchunks) {
+    step(I0{}, c, Yes{}, Yes{});
+    step(I1{}, c + 1, No{}, Yes{});
+    step(I0{}, c + 2, No{}, No{});
+  } else if (c + 2 == nchunks) {
+    step(I0{}, c, No{}, Yes{});
+    step(I1{}, c + 1, No{}, No{});
+  } else {
+    step(I0{}, c, No{}, No{});
   }
 
   // epilogue: D[i][j], i = channel = (v%4) + 4*lh + 8*(v/4), j = pixel = li
