@@ -97,8 +97,13 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
   }
   f32x4 ra[2][RA], rb[2][NG];
   const int n1_chunks = g.I1 / kBK, nx_chunks = I / kBK, nchunks = nx_chunks + H / kBK;
+  // The reset (state rows of finished episodes read as zero) is applied when a set moves to
+  // LDS, not when it is loaded: a select right behind the load would wait for it there and
+  // then, with every other load of the prefetch.
+  bool set_is_h[2] = {false, false};
   auto gload = [&](auto set, int c) {
     constexpr int SET = decltype(set)::value;
+    set_is_h[SET] = c >= nx_chunks;
     if (c < nx_chunks) {
       const int kk = c * kBK + lk4;  // column of W_ih
       if (c < n1_chunks) {
@@ -115,11 +120,7 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
     } else {
       const int kk = (c - nx_chunks) * kBK + lk4;
 #pragma unroll
-      for (int r = 0; r < RA; ++r) {
-        const f32x4 v = *(const f32x4*)(g.h_in + (size_t)ah[r] * S + kk);
-        const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-        ra[SET][r] = areset[r] ? zero : v;
-      }
+      for (int r = 0; r < RA; ++r) ra[SET][r] = *(const f32x4*)(g.h_in + (size_t)ah[r] * S + kk);
 #pragma unroll
       for (int q = 0; q < NG; ++q)
         rb[SET][q] = *(const f32x4*)(g.w_hh + (size_t)(q * H + j0 + lrow) * H + kk);
@@ -128,7 +129,10 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
   auto sstore = [&](auto set, int buf) {
     constexpr int SET = decltype(set)::value;
 #pragma unroll
-    for (int r = 0; r < RA; ++r) *(f32x4*)&As[(buf * BM + lrow + 32 * r) * kP + lk4] = ra[SET][r];
+    for (int r = 0; r < RA; ++r) {
+      const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+      *(f32x4*)&As[(buf * BM + lrow + 32 * r) * kP + lk4] = (set_is_h[SET] && areset[r]) ? zero : ra[SET][r];
+    }
 #pragma unroll
     for (int q = 0; q < NG; ++q)
       *(f32x4*)&Bs[(buf * NG * kBJ + q * kBJ + lrow) * kP + lk4] = rb[SET][q];
