@@ -38,7 +38,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kBK = 32;
 constexpr int kP = 36;    // LDS row pitch (floats)
 constexpr int kBJ = 32;   // hidden units per workgroup
-constexpr int kRedFloats = 4 * 4 * 16 * 64;  // [wave][tile][v][lane]
+constexpr int kRedFloats = 4 * 2 * 16 * 64;  // [wave][tile of a pair][v][lane]: 32 KB, below the operand tiles
 
 __device__ inline float sigmoid_acc(float a) { return 1.0f / (1.0f + expf(-a)); }
 
@@ -283,29 +283,42 @@ __global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
     }
   }
 
-  // partial tiles of every wave -> LDS (the tile buffers are no longer read)
+  // Partial tiles of every wave -> LDS (the tile buffers are no longer read), two of the four
+  // tiles at a time so that the exchange fits into the operand tiles' 36 KB and four
+  // workgroups share a CU.  Wave wk then owns tile rows v in [wk*VPW, (wk+1)*VPW) and sums
+  // the K split in the order 0, 1, ...
   float* red = smem;
+  float sums[VPW][4];
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
+  for (int half = 0; half < 2; ++half) {
+    if (half) __syncthreads();  // the first pair has been read
 #pragma unroll
-    for (int v = 0; v < 16; ++v) red[((wave * 4 + t) * 16 + v) * 64 + lane] = acc[t][v];
-  __syncthreads();
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        red[((wave * 2 + tt) * 16 + v) * 64 + lane] = acc[2 * half + tt][v];
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < VPW; ++u) {
+      const int v = wk * VPW + u;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        float a = 0.0f;
+#pragma unroll
+        for (int k = 0; k < WK; ++k) a += red[(((wm + WM * k) * 2 + tt) * 16 + v) * 64 + lane];
+        sums[u][2 * half + tt] = a;
+      }
+    }
+  }
 
-  // sum over the K split in the order k-split 0, 1, ..., then the gates.  Only the last row
-  // block can hold rows past the end: the row check (a branch per output) is compiled in
-  // for that block alone.
+  // the gates.  Only the last row block can hold rows past the end: the row check (a branch
+  // per output) is compiled in for that block alone.
   auto finish = [&](auto checked) {
     constexpr bool CHECK = decltype(checked)::value;
 #pragma unroll
     for (int u = 0; u < VPW; ++u) {
       const int v = wk * VPW + u;
-      float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-      for (int k = 0; k < WK; ++k) {
-        const int src = wm + WM * k;  // wave index holding k-split k of this row block
-#pragma unroll
-        for (int t = 0; t < 4; ++t) s[t] += red[((src * 4 + t) * 16 + v) * 64 + lane];
-      }
+      const float* s = sums[u];
       const int m = m0 + wm * 32 + (v & 3) + 4 * lh + 8 * (v >> 2);
       if (!CHECK || m < B) {
         if (LSTM) {
