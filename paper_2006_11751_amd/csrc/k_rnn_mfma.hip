@@ -60,7 +60,7 @@ struct RnnArgs {
 // PAIRS (GRU only): the x chunks and the h chunks both come in pairs (I1 + I2 and H multiples
 // of 64), which lets the K loop be written as two plain loops, one per accumulator set.
 template <int BM, bool LSTM, bool PAIRS>
-__global__ __launch_bounds__(256) void rnn_mfma_kernel(RnnArgs g) {
+__global__ __launch_bounds__(256, (BM == 32 && !LSTM && PAIRS) ? 3 : 1) void rnn_mfma_kernel(RnnArgs g) {
   constexpr int NG = LSTM ? 4 : 3;  // gate blocks of the weight matrices
   constexpr int WM = BM / 32, WK = 4 / WM;
   constexpr int RA = BM / 32;       // 16-byte A loads per thread per chunk (B: one per gate)
