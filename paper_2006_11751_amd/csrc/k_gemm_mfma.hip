@@ -48,7 +48,10 @@ struct GemmArgs {
 
 // TAG only gives each layer of a network its own kernel symbol, so that a profiler's
 // per-kernel statistics do not merge layers that share a tile configuration.
-template <int BM, int BN, int BK, int WM, int WN, int WK, int TAG>
+// PIPE: LDS fragment reads one K group ahead of their MFMAs (see below); it pays in grids of
+// one round (FC, conv3 at B = 1024: -4 %) and costs registers and time in grids of several
+// rounds (conv2: +1..5 %), so the launcher picks.
+template <int BM, int BN, int BK, int WM, int WN, int WK, int TAG, bool PIPE>
 __global__ __launch_bounds__(64 * WM * WN * WK) void gemm_mfma_kernel(GemmArgs g) {
   constexpr int NT = 64 * WM * WN * WK;      // threads: one to four wavefronts
   constexpr int P = BK + 4;                  // LDS row pitch in floats
@@ -59,6 +62,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void gemm_mfma_kernel(GemmArgs g
   constexpr int NG = BK / 8;                 // K groups per chunk
   constexpr int GPW = NG / WK;               // K groups per wave per chunk
   static_assert(RA >= 1 && RB >= 1 && GPW >= 1, "tile too small for this BK");
+  static_assert(GPW == 1 || GPW % 2 == 0, "fragment slots alternate with the running K group index");
   extern __shared__ float smem[];
   float* As = smem;                 // [2][BM][P]
   float* Bs = smem + 2 * BM * P;    // [2][BN][P]
@@ -142,24 +146,28 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void gemm_mfma_kernel(GemmArgs g
   for (int j = 0; j < TN; ++j) bj[j] = g.bias[n0 + (wn * TN + j) * 32 + li];
 
   const int nchunks = g.K / BK;
-  auto compute = [&](auto bufc) {
-    constexpr int BUF = decltype(bufc)::value;
+  // Fragments are read one K group ahead of their MFMAs, in two register slots (slot = parity
+  // of the running group index), also across the barrier: the first group of chunk c+1 is
+  // read right after the barrier that publishes it, before the MFMAs of chunk c's last group,
+  // so no MFMA waits for an LDS read issued just before it.
+  f32x4 af[2][TM], bf[2][TN];
+  auto rd = [&](auto bufc, auto groupc, auto slotc) {
+    constexpr int BUF = decltype(bufc)::value, GI = decltype(groupc)::value, SL = decltype(slotc)::value;
+    const int kg = (GI * WK + wk) * 8;
 #pragma unroll
-    for (int gi = 0; gi < GPW; ++gi) {
-      const int kg = (gi * WK + wk) * 8;
-      f32x4 af[TM], bf[TN];
+    for (int i = 0; i < TM; ++i) af[SL][i] = *(const f32x4*)(a_fr + (BUF * BM + i * 32) * P + kg);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *(const f32x4*)(a_fr + (BUF * BM + i * 32) * P + kg);
+    for (int j = 0; j < TN; ++j) bf[SL][j] = *(const f32x4*)(b_fr + (BUF * BN + j * 32) * P + kg);
+  };
+  auto mm = [&](auto slotc) {
+    constexpr int SL = decltype(slotc)::value;
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bf[j] = *(const f32x4*)(b_fr + (BUF * BN + j * 32) * P + kg);
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-      for (int t = 0; t < 4; ++t)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
-    }
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[SL][i][t], bf[SL][j][t], acc[i][j], 0, 0, 0);
   };
   // iteration c (parity S): start the loads of chunk c+2 into register set S, run the
   // MFMAs of chunk c from LDS buffer S, then move chunk c+1 (set S^1, loaded one
@@ -168,9 +176,36 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void gemm_mfma_kernel(GemmArgs g
     constexpr int S = decltype(set)::value;
     using Other = std::integral_constant<int, S ^ 1>;
     if (decltype(loadc)::value) gload(set);
-    compute(set);
-    if (decltype(storec)::value) sstore(Other{}, Other{});
-    __syncthreads();
+    if constexpr (PIPE) {
+      // groups 0 .. GPW-2: read the next group, multiply this one
+      auto groups = [&](auto self, auto gic) -> void {
+        constexpr int GI = decltype(gic)::value;
+        if constexpr (GI + 1 < GPW) {
+          rd(set, std::integral_constant<int, GI + 1>{}, std::integral_constant<int, (S * GPW + GI + 1) & 1>{});
+          mm(std::integral_constant<int, (S * GPW + GI) & 1>{});
+          self(self, std::integral_constant<int, GI + 1>{});
+        }
+      };
+      groups(groups, std::integral_constant<int, 0>{});
+      if (decltype(storec)::value) sstore(Other{}, Other{});
+      __syncthreads();
+      if (decltype(storec)::value)  // there is a next chunk: its first group
+        rd(Other{}, std::integral_constant<int, 0>{}, std::integral_constant<int, ((S ^ 1) * GPW) & 1>{});
+      mm(std::integral_constant<int, (S * GPW + GPW - 1) & 1>{});
+    } else {
+      // every group read right before its MFMAs (slot 0 only)
+      auto groups = [&](auto self, auto gic) -> void {
+        constexpr int GI = decltype(gic)::value;
+        if constexpr (GI < GPW) {
+          rd(set, gic, std::integral_constant<int, 0>{});
+          mm(std::integral_constant<int, 0>{});
+          self(self, std::integral_constant<int, GI + 1>{});
+        }
+      };
+      groups(groups, std::integral_constant<int, 0>{});
+      if (decltype(storec)::value) sstore(Other{}, Other{});
+      __syncthreads();
+    }
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
@@ -180,6 +215,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void gemm_mfma_kernel(GemmArgs g
   sstore(I0{}, I0{});
   if (nchunks > 1) gload(I1{});
   __syncthreads();
+  if (PIPE) rd(I0{}, I0{}, I0{});
   // Steady state without conditions around the loads: a load that is issued on one path only
   // makes the compiler wait for every outstanding load before each LDS store (it must cover
   // the path without the new loads), which takes the prefetch distance from two chunks to
@@ -254,14 +290,14 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void gemm_mfma_kernel(GemmArgs g
     write_tile(std::true_type{});
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int WK, int TAG>
+template <int BM, int BN, int BK, int WM, int WN, int WK, int TAG, bool PIPE>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
   constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
   if (g.K % BK != 0 || g.seg_len % BK != 0) return hipErrorInvalidValue;
   size_t lds = sizeof(float) * 2 * (BM + BN) * (BK + 4);
   size_t red = WK > 1 ? sizeof(float) * WM * WN * TM * TN * 16 * 64 : 0;
   if (red > lds) lds = red;
-  auto kern = gemm_mfma_kernel<BM, BN, BK, WM, WN, WK, TAG>;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, WM, WN, WK, TAG, PIPE>;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -279,12 +315,17 @@ template <int TAG>
 hipError_t launch_tile(const GemmArgs& g, int tile, hipStream_t st) {
   const bool n64 = (g.N % 64) == 0;
   switch (tile) {
-    case 1: return n64 ? launch_cfg<128, 64, 32, 4, 1, 1, TAG>(g, st) : hipErrorInvalidValue;
-    case 2: return n64 ? launch_cfg<64, 64, 32, 2, 2, 1, TAG>(g, st) : hipErrorInvalidValue;
-    case 3: return launch_cfg<64, 32, 32, 2, 1, 2, TAG>(g, st);
-    case 4: return launch_cfg<32, 32, 32, 1, 1, 4, TAG>(g, st);
-    case 6: return launch_cfg<64, 32, 64, 2, 1, 2, TAG>(g, st);
-    case 7: return launch_cfg<32, 32, 64, 1, 1, 4, TAG>(g, st);
+    case 1: return n64 ? launch_cfg<128, 64, 32, 4, 1, 1, TAG, false>(g, st) : hipErrorInvalidValue;
+    case 2: return n64 ? launch_cfg<64, 64, 32, 2, 2, 1, TAG, false>(g, st) : hipErrorInvalidValue;
+    case 3: {
+      // one round of workgroups (5 per CU): fragment reads pipelined; results are the same bits
+      const long long n_tiles = (long long)((g.M + 63) / 64) * (g.N / 32);
+      return n_tiles <= 1280 ? launch_cfg<64, 32, 32, 2, 1, 2, TAG, true>(g, st)
+                             : launch_cfg<64, 32, 32, 2, 1, 2, TAG, false>(g, st);
+    }
+    case 4: return launch_cfg<32, 32, 32, 1, 1, 4, TAG, true>(g, st);
+    case 6: return launch_cfg<64, 32, 64, 2, 1, 2, TAG, false>(g, st);
+    case 7: return launch_cfg<32, 32, 64, 1, 1, 4, TAG, true>(g, st);
     default: return hipErrorInvalidValue;
   }
 }
