@@ -217,13 +217,53 @@ __global__ __launch_bounds__(256, (BM == 32 && !LSTM && PAIRS) ? 3 : 1) void rnn
       }
     }
   };
+  // One K group per wave and chunk (32-row blocks): the fragments of chunk c+1 are read right
+  // after the barrier that publishes them, before the MFMAs of chunk c, in two register
+  // slots (slot = chunk parity), so that no MFMA waits for an LDS read issued just before it.
+  constexpr bool FRAG_AHEAD = GPW == 1;
+  f32x4 faf[2], fbf[2][NG];
+  auto rd = [&](int c, auto slotc) {
+    constexpr int SL = decltype(slotc)::value;
+    const int buf = c & 1, kg = wk * 8;
+    faf[SL] = *(const f32x4*)(As + (buf * BM + wm * 32 + li) * kP + 4 * lh + kg);
+#pragma unroll
+    for (int q = 0; q < NG; ++q)
+      fbf[SL][q] = *(const f32x4*)(Bs + (buf * NG * kBJ + q * kBJ + li) * kP + 4 * lh + kg);
+  };
+  auto mm = [&](int c, auto phase, auto slotc) {
+    constexpr int PH = decltype(phase)::value, SL = decltype(slotc)::value;
+    const bool xphase = PH == 2 ? c < nx_chunks : PH == 0;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (LSTM) {
+#pragma unroll
+        for (int q = 0; q < NG; ++q)
+          acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(faf[SL][t], fbf[SL][q][t], acc[q], 0, 0, 0);
+      } else {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(faf[SL][t], fbf[SL][0][t], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(faf[SL][t], fbf[SL][1][t], acc[1], 0, 0, 0);
+        if (xphase)
+          acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(faf[SL][t], fbf[SL][2][t], acc[2], 0, 0, 0);
+        else
+          acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(faf[SL][t], fbf[SL][2][t], acc[3], 0, 0, 0);
+      }
+    }
+  };
   using I2 = std::integral_constant<int, 2>;
   auto step = [&](auto set, int c, auto phase, auto loadc, auto storec) {
     constexpr int SET = decltype(set)::value;
+    using Other = std::integral_constant<int, SET ^ 1>;
     if (decltype(loadc)::value) gload(set, c + 2);
-    compute(c, phase);
-    if (decltype(storec)::value) sstore(std::integral_constant<int, SET ^ 1>{}, (c + 1) & 1);
-    __syncthreads();
+    if constexpr (FRAG_AHEAD) {
+      if (decltype(storec)::value) sstore(Other{}, (c + 1) & 1);
+      __syncthreads();
+      if (decltype(storec)::value) rd(c + 1, Other{});
+      mm(c, phase, set);
+    } else {
+      compute(c, phase);
+      if (decltype(storec)::value) sstore(Other{}, (c + 1) & 1);
+      __syncthreads();
+    }
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
@@ -233,6 +273,7 @@ __global__ __launch_bounds__(256, (BM == 32 && !LSTM && PAIRS) ? 3 : 1) void rnn
   sstore(I0{}, 0);
   if (nchunks > 1) gload(I1{}, 1);
   __syncthreads();
+  if (FRAG_AHEAD) rd(0, I0{});
   if (LSTM) {
     // Steady state without a condition around the loads (with one, the compiler waits for
     // every outstanding load before each LDS store, and nothing stays in flight across a
@@ -271,14 +312,22 @@ __global__ __launch_bounds__(256, (BM == 32 && !LSTM && PAIRS) ? 3 : 1) void rnn
     // per chunk (peeling this form costs so many accumulator registers that it runs slower).
     for (int c = 0; c < nchunks; c += 2) {
       if (c + 2 < nchunks) gload(I0{}, c + 2);
-      compute(c, I2{});
+      if (!FRAG_AHEAD) compute(c, I2{});
       if (c + 1 < nchunks) sstore(I1{}, (c + 1) & 1);
       __syncthreads();
+      if (FRAG_AHEAD) {
+        if (c + 1 < nchunks) rd(c + 1, I1{});
+        mm(c, I2{}, I0{});
+      }
       if (c + 1 < nchunks) {
         if (c + 3 < nchunks) gload(I1{}, c + 3);
-        compute(c + 1, I2{});
+        if (!FRAG_AHEAD) compute(c + 1, I2{});
         if (c + 2 < nchunks) sstore(I0{}, c & 1);
         __syncthreads();
+        if (FRAG_AHEAD) {
+          if (c + 2 < nchunks) rd(c + 2, I0{});
+          mm(c + 1, I2{}, I1{});
+        }
       }
     }
   }
