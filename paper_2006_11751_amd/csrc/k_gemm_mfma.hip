@@ -316,7 +316,7 @@ hipError_t launch_tile(const GemmArgs& g, int tile, hipStream_t st) {
   const bool n64 = (g.N % 64) == 0;
   switch (tile) {
     case 1: return n64 ? launch_cfg<128, 64, 32, 4, 1, 1, TAG, false>(g, st) : hipErrorInvalidValue;
-    case 2: return n64 ? launch_cfg<64, 64, 32, 2, 2, 1, TAG, false>(g, st) : hipErrorInvalidValue;
+    case 2: return n64 ? launch_cfg<64, 64, 32, 2, 2, 1, TAG, true>(g, st) : hipErrorInvalidValue;
     case 3: {
       // one round of workgroups (5 per CU): fragment reads pipelined; results are the same bits
       const long long n_tiles = (long long)((g.M + 63) / 64) * (g.N / 32);
@@ -338,13 +338,15 @@ bool gemm_mfma_supported(int Cin, int ksize, int pad, int N) {
   return pad == 0 && (Cin % 4) == 0 && ((ksize * Cin) % kBK) == 0 && (N % 32) == 0;
 }
 
-// Tile configuration for an M x N x K problem.  Measured on MI355X: these GEMMs are
-// bound by latency and occupancy rather than by operand traffic, so the small 64x32
-// tile with an in-workgroup K split wins whenever it yields enough workgroups, and
-// the 32x32 tile with a four-way K split (chunks of 64 where K allows) otherwise.
-// Callers fix the choice once (from the largest batch) so that results do not depend
-// on the batch size of a call.
+// Tile configuration for an M x N x K problem, measured on MI355X.  Grids of several rounds
+// of workgroups (conv2 from B = 1024, conv3 from B = 2048) run best on the 64x64 tile (each
+// wave one 32x32 block over the whole K, no K-split reduction, fragment reads pipelined);
+// below that the 64x32 tile with a two-way in-workgroup K split wins as long as it yields
+// about a thousand workgroups, and the 32x32 tile with a four-way K split (chunks of 64
+// where K allows) otherwise.  Callers fix the choice once (from the largest batch) so that
+// results do not depend on the batch size of a call.
 int gemm_mfma_pick_tile(long long M, int N, int K, int seg_len) {
+  if ((N % 64) == 0 && ((M + 63) / 64) * (N / 64) >= 1024) return 2;
   long long wgs = ((M + 63) / 64) * (N / 32);
   if (wgs >= 1024) return 3;
   return (K % 64 == 0 && seg_len % 64 == 0) ? 7 : 4;
