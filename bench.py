@@ -18,8 +18,8 @@ MI355X_PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2500.0}
 # HBM bytes per launch of the standard workload (B=1024), from the two rocprofv3 --pmc runs
 # recorded in profiles/policy_step_standard_hbm_traffic.md: (FETCH_SIZE x 2.000 + WRITE_SIZE
 # x 1.000) KiB, the factors being what the same counters read for a 256 MiB plain copy.
-MEASURED_HBM_KIB = {"standard": {"conv1": 30904 + 67456, "conv2": 62586 + 25088, "conv3": 25710 + 9216,
-                                 "fc": 46276 + 2048, "gru": 55310 + 2048, "heads": 2293 + 24},
+MEASURED_HBM_KIB = {"standard": {"conv1": 30902 + 67456, "conv2": 76932 + 25088, "conv3": 25710 + 9216,
+                                 "fc": 46216 + 2048, "gru": 54646 + 2048, "heads": 2293 + 24},
                     # profiles/policy_step_resnet_counters.md (FETCH_SIZE x 2 + WRITE_SIZE)
                     "resnet_bf16": {"stage1.conv_pool": 2 * 110600 + 589820, "stage1.block1": 2 * 295000 + 589820,
                                     "stage1.block2": 2 * 295000 + 589820, "stage2.conv_pool": 2 * 295100 + 294900,
