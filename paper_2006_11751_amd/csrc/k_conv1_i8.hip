@@ -18,7 +18,8 @@
 // v_mfma_i32_32x32x32_i8: lane l supplies 16 bytes A[i = l%32][k = 16*(l/32) + e] and
 // B[k = 16*(l/32) + e][j = l%32].  One instruction covers four (channel, filter row)
 // groups of 8 filter columns: lane half h holds groups 4s+2h and 4s+2h+1, i.e. two
-// 8-byte runs of the frame.  Work split and prefetch as in the fp32 kernel.
+// 8-byte runs of the frame.  A wave walks a contiguous run of (frame, output row, x chunk)
+// items, three register sets of frame bytes in rotation (loads two items ahead).
 #include <math.h>
 
 #include "sf_internal.h"

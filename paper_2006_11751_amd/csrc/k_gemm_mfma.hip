@@ -12,7 +12,8 @@
 // Tiling: a workgroup of four wavefronts owns a BM x BN output tile, K is walked in
 // chunks of 32 or 64 staged through LDS (double buffered, one barrier per chunk, global
 // loads two chunks ahead of the MFMAs).  LDS rows have a pitch of BK + 4 floats so that
-// both the 16-byte tile stores and the 16-byte fragment loads are bank-conflict free.  v_mfma_f32_32x32x2_f32 takes its K index from the lane half
+// both the 16-byte tile stores and the 16-byte fragment loads are bank-conflict free.
+// v_mfma_f32_32x32x2_f32 takes its K index from the lane half
 // h = lane/32; a lane loads four consecutive k (one ds_read_b128) at 8g + 4h, and
 // instruction t of the group's four uses element t, for both operands alike.
 // The four wavefronts are arranged WM x WN x WK: WK > 1 splits the K groups of
