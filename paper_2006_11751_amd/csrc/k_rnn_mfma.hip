@@ -41,6 +41,12 @@ constexpr int kBJ = 32;   // hidden units per workgroup
 constexpr int kRedFloats = 4 * 2 * 16 * 64;  // [wave][tile of a pair][v][lane]: 32 KB, below the operand tiles
 
 __device__ inline float sigmoid_acc(float a) { return 1.0f / (1.0f + expf(-a)); }
+// tanh without the library routine's branches: (1 - e) / (1 + e) with e = exp(-2|a|), sign
+// restored; e <= 1, so nothing overflows, and the error stays at a few ulp
+__device__ inline float tanh_acc(float a) {
+  const float e = expf(-2.0f * fabsf(a));
+  return copysignf((1.0f - e) / (1.0f + e), a);
+}
 
 struct RnnArgs {
   const float* x1;      // [B][I1]
@@ -374,16 +380,16 @@ __global__ __launch_bounds__(256, (BM == 32 && !LSTM && PAIRS) ? 3 : 1) void rnn
           const float cprev = sprev[u];
           const float ig = sigmoid_acc(s[0] + bias[0]);
           const float fg = sigmoid_acc(s[1] + bias[1]);
-          const float gg = tanhf(s[2] + bias[2]);
+          const float gg = tanh_acc(s[2] + bias[2]);
           const float og = sigmoid_acc(s[3] + bias[3]);
           const float cn = fg * cprev + ig * gg;
           g.h_out[(size_t)m * S + H + j] = cn;
-          g.h_out[(size_t)m * S + j] = og * tanhf(cn);
+          g.h_out[(size_t)m * S + j] = og * tanh_acc(cn);
         } else {
           const float hprev = sprev[u];
           const float r = sigmoid_acc(s[0] + bias[0]);
           const float z = sigmoid_acc(s[1] + bias[1]);
-          const float n = tanhf(s[2] + bias[2] + r * (s[3] + bias[3]));
+          const float n = tanh_acc(s[2] + bias[2] + r * (s[3] + bias[3]));
           g.h_out[(size_t)m * S + j] = (1.0f - z) * n + z * hprev;
         }
       }
