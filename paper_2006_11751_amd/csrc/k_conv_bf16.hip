@@ -23,6 +23,8 @@
 
 #include <string.h>
 
+#include <stdlib.h>
+
 #include "sf_internal.h"
 
 namespace sf {
@@ -88,20 +90,24 @@ struct ConvBf16Args {
 // kSimple: no padding, K a whole number of chunks and every chunk inside one filter row
 // (ks * Cin a multiple of 64).  The loader then needs no bounds checks and no divisions: a
 // cursor walks each pixel row's K axis, jumping to the next filter row at a segment's end.
-template <int TAG, bool kF16, bool kSimple>
+// TC: 32-channel blocks per workgroup (1 or 2).  With two, a wave reuses each pixel fragment
+// for two MFMAs and the pixel tile is fetched once for 64 channels (40 % less L2 -> LDS
+// traffic when N is 64).
+template <int TAG, bool kF16, bool kSimple, int TC>
 __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (kBP + kBC) * kPitchB];
+  constexpr int BC = kBC * TC;  // channels per workgroup
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (kBP + BC) * kPitchB];
   unsigned char* Ps = smem;                        // [2][128][pitch] pixels
-  unsigned char* Cs = smem + 2 * kBP * kPitchB;    // [2][32][pitch] channels (weights)
+  unsigned char* Cs = smem + 2 * kBP * kPitchB;    // [2][BC][pitch] channels (weights)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 31, lh = lane >> 5;
-  const int n_ctiles = (g.N + kBC - 1) / kBC;
+  const int n_ctiles = (g.N + BC - 1) / BC;
   const int n_tiles = ((g.M + kBP - 1) / kBP) * n_ctiles;
   const int per_xcd = (n_tiles + 7) / 8;
   const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (tile_id >= n_tiles) return;
-  const int m0 = (tile_id / n_ctiles) * kBP, n0 = (tile_id % n_ctiles) * kBC;
+  const int m0 = (tile_id / n_ctiles) * kBP, n0 = (tile_id % n_ctiles) * BC;
   const int lrow = tid >> 3, lk8 = (tid & 7) * 8;  // 8 threads x 16 bytes per tile row
 
   // pixel rows handled by this thread when staging (4 rows, 32 apart)
@@ -118,7 +124,8 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
     iy0[r] = oy * g.stride - g.pad;
     ix0[r] = ox * g.stride - g.pad;
   }
-  const uint16_t* wrow = g.Wt + (size_t)(n0 + lrow) * g.Kpad + lk8;  // 32 rows x 8 pieces = 256 threads
+  const uint16_t* wrow = g.Wt + (size_t)(n0 + lrow) * g.Kpad + lk8;  // 32 rows x 8 pieces = 256 threads, per block
+  const size_t wblock = (size_t)kBC * g.Kpad;
   // kSimple: element offset of this thread's piece of chunk 0 in each of its pixel rows
   long long sbase[4];
   int ld_off = 0, ld_in_seg = 0;
@@ -129,7 +136,7 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
       sbase[r] = pbase[r] + ((long long)iy0[r] * g.W + ix0[r]) * g.Cin + lk8;
   }
 
-  u32x4 rp[2][4], rw[2];
+  u32x4 rp[2][4], rw[2][TC];
   const int nchunks = g.Kpad / kBK;
   auto gload = [&](auto set, int c) {
     constexpr int S = decltype(set)::value;
@@ -156,7 +163,8 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
         }
         rp[S][r] = v;
       }
-      rw[S] = *(const u32x4*)(wrow + c * kBK);
+#pragma unroll
+      for (int tc = 0; tc < TC; ++tc) rw[S][tc] = *(const u32x4*)(wrow + tc * wblock + c * kBK);
       ld_off += kBK;
       ld_in_seg += kBK;
       if (ld_in_seg == seg_len) {
@@ -196,33 +204,44 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
       }
       rp[S][r] = v;
     }
-    rw[S] = *(const u32x4*)(wrow + c * kBK);
+#pragma unroll
+    for (int tc = 0; tc < TC; ++tc) rw[S][tc] = *(const u32x4*)(wrow + tc * wblock + c * kBK);
   };
   auto sstore = [&](auto set, int buf) {
     constexpr int S = decltype(set)::value;
 #pragma unroll
     for (int r = 0; r < 4; ++r)
       *(u32x4*)(Ps + ((size_t)(buf * kBP + lrow + 32 * r)) * kPitchB + lk8 * 2) = rp[S][r];
-    *(u32x4*)(Cs + ((size_t)(buf * kBC + lrow)) * kPitchB + lk8 * 2) = rw[S];
+#pragma unroll
+    for (int tc = 0; tc < TC; ++tc)
+      *(u32x4*)(Cs + ((size_t)(buf * BC + tc * kBC + lrow)) * kPitchB + lk8 * 2) = rw[S][tc];
   };
 
-  f32x16 acc;
+  f32x16 acc[TC];
 #pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+  for (int tc = 0; tc < TC; ++tc)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[tc][v] = 0.0f;
 
   auto compute = [&](int buf) {
     const unsigned char* Pb = Ps + ((size_t)(buf * kBP + wave * 32 + li)) * kPitchB + lh * 16;
-    const unsigned char* Cb = Cs + ((size_t)(buf * kBC + li)) * kPitchB + lh * 16;
+    const unsigned char* Cb = Cs + ((size_t)(buf * BC + li)) * kPitchB + lh * 16;
 #pragma unroll
     for (int s = 0; s < kBK / 16; ++s) {
       if (kF16) {
-        const f16x8 wf = *(const f16x8*)(Cb + s * 32);
         const f16x8 pf = *(const f16x8*)(Pb + s * 32);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf, pf, acc, 0, 0, 0);
+#pragma unroll
+        for (int tc = 0; tc < TC; ++tc) {
+          const f16x8 wf = *(const f16x8*)(Cb + tc * kBC * kPitchB + s * 32);
+          acc[tc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf, pf, acc[tc], 0, 0, 0);
+        }
       } else {
-        const bf16x8 wf = *(const bf16x8*)(Cb + s * 32);
         const bf16x8 pf = *(const bf16x8*)(Pb + s * 32);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, pf, acc, 0, 0, 0);
+#pragma unroll
+        for (int tc = 0; tc < TC; ++tc) {
+          const bf16x8 wf = *(const bf16x8*)(Cb + tc * kBC * kPitchB + s * 32);
+          acc[tc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, pf, acc[tc], 0, 0, 0);
+        }
       }
     }
   };
@@ -236,14 +255,16 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
   // The bias is fetched before the K loop (after it, its latency would end every tile).
   // Channels of this lane: n0 + 8*q4 + 4*lh .. +3; a tile that reaches past N (a multiple
   // of 4, not of 32) checks each group of four.
-  const bool whole_n = n0 + kBC <= g.N;
-  f32x4 bq[4];
+  const bool whole_n = n0 + BC <= g.N;
+  f32x4 bq[TC][4];
 #pragma unroll
-  for (int q4 = 0; q4 < 4; ++q4) {
-    int ch = n0 + 8 * q4 + 4 * lh;
-    ch = ch < g.N ? ch : g.N - 4;
-    bq[q4] = *(const f32x4*)(g.bias + ch);
-  }
+  for (int tc = 0; tc < TC; ++tc)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      int ch = n0 + tc * kBC + 8 * q4 + 4 * lh;
+      ch = ch < g.N ? ch : g.N - 4;
+      bq[tc][q4] = *(const f32x4*)(g.bias + ch);
+    }
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
   gload(I0{}, 0);
@@ -275,12 +296,14 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
   const int m = m0 + wave * 32 + li;
   if (m >= g.M) return;
 #pragma unroll
+  for (int tc = 0; tc < TC; ++tc)
+#pragma unroll
   for (int q4 = 0; q4 < 4; ++q4) {
-    const int ch = n0 + 8 * q4 + 4 * lh;
+    const int ch = n0 + tc * kBC + 8 * q4 + 4 * lh;
     if (!whole_n && ch >= g.N) continue;  // N is a multiple of 4
     float r[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) r[t] = acc[4 * q4 + t] + bq[q4][t];
+    for (int t = 0; t < 4; ++t) r[t] = acc[tc][4 * q4 + t] + bq[tc][q4][t];
     if (g.resid) {
       if (g.resid_f32) {
         const f32x4 rv = *(const f32x4*)((const float*)g.resid + (size_t)m * g.N + ch);
@@ -394,19 +417,19 @@ __global__ __launch_bounds__(256) void conv3x3_u8_bf16_kernel(
     dst[o / 2] = f32_to_h<kF16>(acc[o]) | (f32_to_h<kF16>(acc[o + 1]) << 16);
 }
 
-template <int TAG>
+template <int TAG, int TC>
 hipError_t launch_tagged(const ConvBf16Args& g, bool f16, hipStream_t st) {
-  const int n_tiles = ((g.M + kBP - 1) / kBP) * ((g.N + kBC - 1) / kBC);
+  const int n_tiles = ((g.M + kBP - 1) / kBP) * ((g.N + kBC * TC - 1) / (kBC * TC));
   const int per_xcd = (n_tiles + 7) / 8;
   const bool simple = g.pad == 0 && g.K == g.Kpad && (g.ks * g.Cin) % kBK == 0;
   if (f16 && simple)
-    conv_bf16_kernel<TAG, true, true><<<per_xcd * 8, 256, 0, st>>>(g);
+    conv_bf16_kernel<TAG, true, true, TC><<<per_xcd * 8, 256, 0, st>>>(g);
   else if (f16)
-    conv_bf16_kernel<TAG, true, false><<<per_xcd * 8, 256, 0, st>>>(g);
+    conv_bf16_kernel<TAG, true, false, TC><<<per_xcd * 8, 256, 0, st>>>(g);
   else if (simple)
-    conv_bf16_kernel<TAG, false, true><<<per_xcd * 8, 256, 0, st>>>(g);
+    conv_bf16_kernel<TAG, false, true, TC><<<per_xcd * 8, 256, 0, st>>>(g);
   else
-    conv_bf16_kernel<TAG, false, false><<<per_xcd * 8, 256, 0, st>>>(g);
+    conv_bf16_kernel<TAG, false, false, TC><<<per_xcd * 8, 256, 0, st>>>(g);
   return hipGetLastError();
 }
 
@@ -482,13 +505,20 @@ hipError_t launch_conv_bf16(const void* in, const uint16_t* wt, const float* bia
   g.stride = stride; g.pad = pad; g.img_elems = (long long)H * W * Cin;
   g.relu_in = relu_in; g.relu_out = relu_out; g.out_f32 = out_f32;
   if (g.M == 0) return hipSuccess;
+  // Two channel blocks per workgroup in grids of several rounds (measured: conv2 of the bf16
+  // configuration 75 -> 71 us at B = 4096; a grid of 1152 such workgroups is slower than 2304
+  // single ones); the results are the same bits either way.
+  const long long tiles2 = (long long)((g.M + kBP - 1) / kBP) * (N / 64);
+  static const int tc_env = getenv("SF_CONV_BF16_TC") ? atoi(getenv("SF_CONV_BF16_TC")) : 0;
+  const bool two = (N % 64) == 0 && (tc_env ? tc_env == 2 : tiles2 >= 2048);
   switch (tag & 15) {
-#define SF_TAG_CASE(T) case T: return launch_tagged<T>(g, f16 != 0, st);
+#define SF_TAG_CASE(T) \
+  case T: return two ? launch_tagged<T, 2>(g, f16 != 0, st) : launch_tagged<T, 1>(g, f16 != 0, st);
     SF_TAG_CASE(0) SF_TAG_CASE(1) SF_TAG_CASE(2) SF_TAG_CASE(3) SF_TAG_CASE(4) SF_TAG_CASE(5)
     SF_TAG_CASE(6) SF_TAG_CASE(7) SF_TAG_CASE(8) SF_TAG_CASE(9) SF_TAG_CASE(10) SF_TAG_CASE(11)
     SF_TAG_CASE(12) SF_TAG_CASE(13) SF_TAG_CASE(14)
 #undef SF_TAG_CASE
-    default: return launch_tagged<15>(g, f16 != 0, st);
+    default: return two ? launch_tagged<15, 2>(g, f16 != 0, st) : launch_tagged<15, 1>(g, f16 != 0, st);
   }
 }
 
