@@ -18,6 +18,8 @@
 // through double-buffered LDS (pitch 144 bytes), global loads one chunk ahead.
 #include <string.h>
 
+#include <type_traits>
+
 #include "sf_internal.h"
 
 namespace sf {
@@ -56,16 +58,22 @@ struct RnnBf16Args {
   int n_env;
 };
 
-// 8 consecutive fp32 -> 8 bf16 (phase 0: the value; 1: hi part; 2: lo part)
+// 8 consecutive fp32 -> 8 bf16 (phase 0: the value; 1: hi part; 2: lo part = bf16(v - hi)),
+// round to nearest even through the packed hardware conversion; both parts are formed and
+// the phase picks whole words (no branches around the conversions)
 __device__ inline u32x4 to_bf16x8(const f32x4& a, const f32x4& b, int phase) {
-  float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-  unsigned h[8];
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  u32x4 o;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    unsigned hi = bf16_rne(v[e]);
-    h[e] = phase == 2 ? bf16_rne(v[e] - bf16_value(hi)) : hi;
+  for (int e = 0; e < 4; ++e) {
+    const f32x2_t p = {v[2 * e], v[2 * e + 1]};
+    const unsigned hi = __builtin_bit_cast(unsigned, __builtin_convertvector(p, bf16x2_t));
+    const f32x2_t r = {v[2 * e] - __uint_as_float(hi << 16), v[2 * e + 1] - __uint_as_float(hi & 0xFFFF0000u)};
+    const unsigned lo = __builtin_bit_cast(unsigned, __builtin_convertvector(r, bf16x2_t));
+    o[e] = phase == 2 ? lo : hi;
   }
-  u32x4 o = {h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
   return o;
 }
 
@@ -125,9 +133,8 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float* src = g.h_in + (size_t)ah[r] * S + kk;
-        const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-        ra[r][0] = areset[r] ? zero : *(const f32x4*)src;
-        ra[r][1] = areset[r] ? zero : *(const f32x4*)(src + 4);
+        ra[r][0] = *(const f32x4*)src;
+        ra[r][1] = *(const f32x4*)(src + 4);
       }
 #pragma unroll
       for (int q = 0; q < NG; ++q)
@@ -136,8 +143,12 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
   };
   auto sstore = [&](int buf) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-      *(u32x4*)(Rs + (buf * kBR + lrow + 32 * r) * kPitch + lk8 * 2) = to_bf16x8(ra[r][0], ra[r][1], rphase);
+    for (int r = 0; r < 4; ++r) {
+      // the reset is applied here, not behind the load (a select there waits for the load)
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      const u32x4 v = to_bf16x8(ra[r][0], ra[r][1], rphase);
+      *(u32x4*)(Rs + (buf * kBR + lrow + 32 * r) * kPitch + lk8 * 2) = (rphase != 0 && areset[r]) ? zero : v;
+    }
 #pragma unroll
     for (int q = 0; q < NG; ++q)
       *(u32x4*)(Ws + (buf * NG * kBJ + q * kBJ + lrow) * kPitch + lk8 * 2) = rw[q];
@@ -149,11 +160,11 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
 
-  auto compute = [&](int c) {
+  auto compute = [&](int c, auto xph) {
     const int buf = c & 1;
     const unsigned char* rb = Rs + (buf * kBR + wave * 32 + li) * kPitch + lh * 16;
     const unsigned char* wb = Ws + (buf * NG * kBJ + li) * kPitch + lh * 16;
-    const bool xphase = c < nxc;
+    constexpr bool xphase = decltype(xph)::value;
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
       const bf16x8 bfrag = __builtin_bit_cast(bf16x8, *(const u32x4*)(rb + ks * 32));
@@ -179,12 +190,22 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
   gload(0);
   sstore(0);
   __syncthreads();
-  for (int c = 0; c < nchunks; ++c) {
-    if (c + 1 < nchunks) gload(c + 1);
-    compute(c);
-    if (c + 1 < nchunks) sstore((c + 1) & 1);
+  // one plain loop per accumulator set (x chunks, then h chunks), no conditions around the
+  // loads; the last chunk (always an h chunk) is peeled off
+  int c = 0;
+  for (; c < nxc; ++c) {
+    gload(c + 1);
+    compute(c, std::true_type{});
+    sstore((c + 1) & 1);
     __syncthreads();
   }
+  for (; c + 1 < nchunks; ++c) {
+    gload(c + 1);
+    compute(c, std::false_type{});
+    sstore((c + 1) & 1);
+    __syncthreads();
+  }
+  compute(c, std::false_type{});
 
   // epilogue: register 4*q4 + u of a tile holds hidden unit j0 + 8*q4 + 4*lh + u of batch
   // row m0 + wave*32 + li
