@@ -5,9 +5,10 @@
 // bf16 configuration are bf16 numbers, the core's input is a bf16 activation (rounded to
 // nearest even while it is staged), and the fp32 state h enters the contraction as the
 // exact sum of two bf16 numbers, h = hi + lo with hi = bf16(h), lo = bf16(h - hi)
-// (relative error below 2^-16): K runs over the input features, then over hi, then over
-// lo, the last two against the same rows of W_hh.  The state itself, the gates and the
-// blend stay fp32.
+// (relative error below 2^-16): K runs over the input features and then, per 64-wide block
+// of h, over its hi part and its lo part, both against the same rows of W_hh (which, like
+// the block of h, are fetched once and reused from registers).  The state itself, the gates
+// and the blend stay fp32.
 //
 // v_mfma_f32_32x32x16_bf16: lane l supplies A[i = l%32][k = 8*(l/32) + e] and
 // B[k = 8*(l/32) + e][j = l%32].  The weights take the A role (i = hidden unit), the batch
@@ -107,41 +108,39 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
     }
   }
   const int n1c = g.I1 / kBK, nxc = I / kBK, nhc = H / kBK;
-  const int nchunks = nxc + 2 * nhc;  // x, then h's hi parts, then its lo parts
 
   f32x4 ra[4][2];
   u32x4 rw[NG];
-  int rphase = 0;
-  auto gload = [&](int c) {
-    if (c < nxc) {
-      rphase = 0;
-      const int kk = c * kBK + lk8;
+  // K runs over the x chunks and then, per 64-wide block of h, over its hi part and its lo
+  // part: the lo chunk reuses the state values and the weight rows that the hi chunk loaded
+  // (they stay in registers), so every block of h and of W_hh is fetched once.
+  auto gload_x = [&](int c) {
+    const int kk = c * kBK + lk8;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float* src = c < n1c ? g.x1 + (size_t)am[r] * g.I1 + kk
-                                   : g.x2 + (size_t)am[r] * g.I2 + (kk - g.I1);
-        ra[r][0] = *(const f32x4*)src;
-        ra[r][1] = *(const f32x4*)(src + 4);
-      }
-#pragma unroll
-      for (int q = 0; q < NG; ++q)
-        rw[q] = *(const u32x4*)(g.w_ih + (size_t)(q * H + j0 + lrow) * I + kk);
-    } else {
-      const int ch = c - nxc;
-      rphase = ch < nhc ? 1 : 2;
-      const int kk = (ch < nhc ? ch : ch - nhc) * kBK + lk8;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float* src = g.h_in + (size_t)ah[r] * S + kk;
-        ra[r][0] = *(const f32x4*)src;
-        ra[r][1] = *(const f32x4*)(src + 4);
-      }
-#pragma unroll
-      for (int q = 0; q < NG; ++q)
-        rw[q] = *(const u32x4*)(g.w_hh + (size_t)(q * H + j0 + lrow) * H + kk);
+    for (int r = 0; r < 4; ++r) {
+      const float* src = c < n1c ? g.x1 + (size_t)am[r] * g.I1 + kk
+                                 : g.x2 + (size_t)am[r] * g.I2 + (kk - g.I1);
+      ra[r][0] = *(const f32x4*)src;
+      ra[r][1] = *(const f32x4*)(src + 4);
     }
+#pragma unroll
+    for (int q = 0; q < NG; ++q)
+      rw[q] = *(const u32x4*)(g.w_ih + (size_t)(q * H + j0 + lrow) * I + kk);
   };
-  auto sstore = [&](int buf) {
+  auto gload_h = [&](int kb) {
+    const int kk = kb * kBK + lk8;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float* src = g.h_in + (size_t)ah[r] * S + kk;
+      ra[r][0] = *(const f32x4*)src;
+      ra[r][1] = *(const f32x4*)(src + 4);
+    }
+#pragma unroll
+    for (int q = 0; q < NG; ++q)
+      rw[q] = *(const u32x4*)(g.w_hh + (size_t)(q * H + j0 + lrow) * H + kk);
+  };
+  // rphase: 0 = x values, 1 = hi parts of h, 2 = lo parts of h
+  auto sstore = [&](int buf, int rphase) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       // the reset is applied here, not behind the load (a select there waits for the load)
@@ -160,8 +159,7 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
 
-  auto compute = [&](int c, auto xph) {
-    const int buf = c & 1;
+  auto compute = [&](int buf, auto xph) {
     const unsigned char* rb = Rs + (buf * kBR + wave * 32 + li) * kPitch + lh * 16;
     const unsigned char* wb = Ws + (buf * NG * kBJ + li) * kPitch + lh * 16;
     constexpr bool xphase = decltype(xph)::value;
@@ -187,25 +185,42 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
     }
   };
 
-  gload(0);
-  sstore(0);
+  // Single register set: loads of the next chunk, MFMAs of this one, conversion and LDS
+  // store of the next, barrier; `cb` counts chunks (LDS buffer = parity).  One plain loop
+  // per accumulator set, no conditions around the loads.
+  using Xp = std::true_type;
+  using Hp = std::false_type;
+  int cb = 0;
+  gload_x(0);
+  sstore(0, 0);
   __syncthreads();
-  // one plain loop per accumulator set (x chunks, then h chunks), no conditions around the
-  // loads; the last chunk (always an h chunk) is peeled off
-  int c = 0;
-  for (; c < nxc; ++c) {
-    gload(c + 1);
-    compute(c, std::true_type{});
-    sstore((c + 1) & 1);
+  for (int c = 0; c + 1 < nxc; ++c, ++cb) {
+    gload_x(c + 1);
+    compute(cb & 1, Xp{});
+    sstore((cb + 1) & 1, 0);
     __syncthreads();
   }
-  for (; c + 1 < nchunks; ++c) {
-    gload(c + 1);
-    compute(c, std::false_type{});
-    sstore((c + 1) & 1);
+  gload_h(0);  // the last x chunk runs while block 0 of h arrives
+  compute(cb & 1, Xp{});
+  sstore((cb + 1) & 1, 1);
+  __syncthreads();
+  ++cb;
+  for (int kb = 0; kb + 1 < nhc; ++kb) {
+    compute(cb & 1, Hp{});      // hi part of block kb
+    sstore((cb + 1) & 1, 2);    // its lo part, from the same registers
     __syncthreads();
+    ++cb;
+    gload_h(kb + 1);
+    compute(cb & 1, Hp{});      // lo part of block kb
+    sstore((cb + 1) & 1, 1);    // hi part of block kb + 1
+    __syncthreads();
+    ++cb;
   }
-  compute(c, std::false_type{});
+  compute(cb & 1, Hp{});
+  sstore((cb + 1) & 1, 2);
+  __syncthreads();
+  ++cb;
+  compute(cb & 1, Hp{});
 
   // epilogue: register 4*q4 + u of a tile holds hidden unit j0 + 8*q4 + 4*lh + u of batch
   // row m0 + wave*32 + li
