@@ -94,7 +94,7 @@ struct ConvBf16Args {
 // for two MFMAs and the pixel tile is fetched once for 64 channels (40 % less L2 -> LDS
 // traffic when N is 64).
 template <int TAG, bool kF16, bool kSimple, int TC>
-__global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
+__global__ __launch_bounds__(256, TC == 1 ? 3 : 2) void conv_bf16_kernel(ConvBf16Args g) {
   constexpr int BC = kBC * TC;  // channels per workgroup
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (kBP + BC) * kPitchB];
   unsigned char* Ps = smem;                        // [2][128][pitch] pixels
@@ -141,27 +141,32 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args g) {
   auto gload = [&](auto set, int c) {
     constexpr int S = decltype(set)::value;
     if (kSimple) {  // chunks are requested in order
+      // (one branch per chunk, not one per row)
+      if (g.in_f32) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const long long e = sbase[r] + ld_off;
-        u32x4 v;
-        if (g.in_f32) {
+        for (int r = 0; r < 4; ++r) {
+          const long long e = sbase[r] + ld_off;
           const f32x4 lo = *(const f32x4*)((const float*)g.in + e);
           const f32x4 hi = *(const f32x4*)((const float*)g.in + e + 4);
+          u32x4 v;
           v[0] = f32_to_h<kF16>(lo[0]) | (f32_to_h<kF16>(lo[1]) << 16);
           v[1] = f32_to_h<kF16>(lo[2]) | (f32_to_h<kF16>(lo[3]) << 16);
           v[2] = f32_to_h<kF16>(hi[0]) | (f32_to_h<kF16>(hi[1]) << 16);
           v[3] = f32_to_h<kF16>(hi[2]) | (f32_to_h<kF16>(hi[3]) << 16);
-        } else {
-          v = *(const u32x4*)((const uint16_t*)g.in + e);
+          rp[S][r] = v;
         }
-        if (g.relu_in) {
-          v[0] = relu_bf16x2(v[0]);
-          v[1] = relu_bf16x2(v[1]);
-          v[2] = relu_bf16x2(v[2]);
-          v[3] = relu_bf16x2(v[3]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) rp[S][r] = *(const u32x4*)((const uint16_t*)g.in + sbase[r] + ld_off);
+      }
+      if (g.relu_in) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          rp[S][r][0] = relu_bf16x2(rp[S][r][0]);
+          rp[S][r][1] = relu_bf16x2(rp[S][r][1]);
+          rp[S][r][2] = relu_bf16x2(rp[S][r][2]);
+          rp[S][r][3] = relu_bf16x2(rp[S][r][3]);
         }
-        rp[S][r] = v;
       }
 #pragma unroll
       for (int tc = 0; tc < TC; ++tc) rw[S][tc] = *(const u32x4*)(wrow + tc * wblock + c * kBK);
