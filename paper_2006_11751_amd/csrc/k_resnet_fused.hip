@@ -361,7 +361,7 @@ struct BlockArgs {
 // on the tile plus a one-pixel halo (zero outside the image, as conv_b's padding wants it)
 // into LDS; conv_b reads it from there and adds bias and the un-rectified x from memory.
 template <int C, int TH, int TW, int NW>
-__global__ __launch_bounds__(64 * NW) void res_block_kernel(BlockArgs g) {
+__global__ __launch_bounds__(64 * NW, C == 32 ? 3 : 1) void res_block_kernel(BlockArgs g) {
   constexpr int NT = 64 * NW;
   constexpr int XH = TH + 4, XW = TW + 4;  // x patch
   constexpr int UH = TH + 2, UW = TW + 2;  // branch tensor
