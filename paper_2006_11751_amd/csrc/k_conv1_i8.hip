@@ -48,17 +48,21 @@ __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_k
     const float* __restrict__ bias, void* __restrict__ out_v, int H, int W, int Ho, int Wo,
     int n_xchunks, long long n_items, int n_waves_total) {
   constexpr int NSTEP = CIN * kK / 4;  // MFMA K steps (32 bytes each)
+  // Digit planes used.  A bf16 configuration's weights carry 8 significant bits, so two
+  // base-128 digits (error <= 2^-15 of the channel's largest weight) are more than its
+  // tolerance asks for, and a third of the MFMAs and of the epilogue goes away.
+  constexpr int ND = OUT_BF16 ? 2 : 3;
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWaves + (threadIdx.x >> 6);
   const int n = lane & 31;
   const int h = lane >> 5;
 
   // digit planes of the filter bank: wd[s][digit] = 16 bytes of this lane's B operand
-  i32x4 wd[NSTEP][3];
+  i32x4 wd[NSTEP][ND];
 #pragma unroll
   for (int s = 0; s < NSTEP; ++s)
 #pragma unroll
-    for (int d = 0; d < 3; ++d)
+    for (int d = 0; d < ND; ++d)
 #pragma unroll
       for (int w = 0; w < 4; ++w) wd[s][d][w] = wpk[((s * 3 + d) * 4 + w) * 64 + lane];
   const float s_n = scale[n], b_n = bias[n];
@@ -165,15 +169,20 @@ __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_k
       a[3] = (int)(cur[s][1].y ^ 0x80808080u);
       s1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, wd[s][0], s1, 0, 0, 0);
       s2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, wd[s][1], s2, 0, 0, 0);
-      s3 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, wd[s][2], s3, 0, 0, 0);
+      if constexpr (ND == 3) s3 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, wd[s][2], s3, 0, 0, 0);
     }
     // epilogue.  D[i][j]: j = n, i = (v%4) + 4h + 8(v/4).  S2*128 + S3 fits int32
     // (|S2|, |S3| <= 192*128*64); its float image is exact to 6e-8 relative.
     float r[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const float lo = (float)(s2[v] * 128 + s3[v]);
-      const float q = fmaf(lo, 0x1.0p-14f, (float)s1[v]);
+      float q;
+      if constexpr (ND == 3) {
+        const float lo = (float)(s2[v] * 128 + s3[v]);
+        q = fmaf(lo, 0x1.0p-14f, (float)s1[v]);
+      } else {
+        q = fmaf((float)s2[v], 0x1.0p-7f, (float)s1[v]);
+      }
       r[v] = fmaxf(fmaf(q, s_n, b_n), 0.0f);
     }
     // no predicated stores (each would become a branch): lanes past the row end write the
