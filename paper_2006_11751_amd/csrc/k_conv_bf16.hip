@@ -514,7 +514,8 @@ hipError_t launch_conv_bf16(const void* in, const uint16_t* wt, const float* bia
   // configuration 75 -> 71 us at B = 4096; a grid of 1152 such workgroups is slower than 2304
   // single ones); the results are the same bits either way.
   const long long tiles2 = (long long)((g.M + kBP - 1) / kBP) * (N / 64);
-  static const int tc_env = getenv("SF_CONV_BF16_TC") ? atoi(getenv("SF_CONV_BF16_TC")) : 0;
+  const char* tc_s = getenv("SF_CONV_BF16_TC");  // 1 or 2 forces the variant (tests, A/B runs)
+  const int tc_env = tc_s ? atoi(tc_s) : 0;
   const bool two = (N % 64) == 0 && (tc_env ? tc_env == 2 : tiles2 >= 2048);
   switch (tag & 15) {
 #define SF_TAG_CASE(T) \

@@ -28,6 +28,7 @@ CASES = [
     ("SF_NO_RNN_PAIRS", "1", STD_SMALL),
     ("SF_NO_BF16_PATH", "1", STD_BF16_SMALL),
     ("SF_NO_RNN_BF16", "1", STD_BF16_SMALL),
+    ("SF_CONV_BF16_TC", "2", STD_BF16_SMALL),
     ("SF_NO_RNN_BF16", "1", BY_NAME["lstm_bf16_mfma"]),
     ("SF_NO_FUSED_RESNET", "1", RESNET_BF16_MID),
     ("SF_NO_PATCH_CONV", "1", RESNET_BF16_SMALL),
@@ -40,7 +41,8 @@ def test_switch(torch_cuda, ref, monkeypatch, var, val, net):
     torch = torch_cuda
     monkeypatch.setenv(var, val)
     pol, w = _make(torch, net)
-    monkeypatch.delenv(var)
+    if var != "SF_CONV_BF16_TC":  # read at every launch, not at create
+        monkeypatch.delenv(var)
     d = pol.device
     B = net["B"]
     obs, state, done = wl.observations(net, 0, B), wl.initial_state(net, B), wl.done_mask(net, 0, B)
