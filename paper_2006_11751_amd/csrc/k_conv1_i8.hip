@@ -190,12 +190,20 @@ __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_k
     uint8_t* obase = (uint8_t*)out_v + out_off + (size_t)(xc * 32) * (kCout * ELT);
     if (n_xchunks > 1) set_store_offsets(xc);
     if (OUT_BF16) {
+      // Neighbouring lanes (channels n, n^1) swap half of their rows: the even lane keeps
+      // tile rows 2k, the odd lane rows 2k+1, each as a (channel n&~1, channel n|1) pair in
+      // one 32-bit word: 8 stores per item instead of 16 (a wave can have 63 memory
+      // instructions outstanding, and 12 loads + 16 stores per item run into that).
+      const bool odd = (n & 1) != 0;
 #pragma unroll
-      for (int v = 0; v < 16; v += 2) {
-        const f32x2 pair = {r[v], r[v + 1]};
+      for (int k = 0; k < 8; ++k) {
+        const float mine = odd ? r[2 * k + 1] : r[2 * k];
+        const float give = odd ? r[2 * k] : r[2 * k + 1];
+        const float got = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(give), 0xB1, 0xF, 0xF, true));
+        const f32x2 pair = {odd ? got : mine, odd ? mine : got};
         const unsigned word = __builtin_bit_cast(unsigned, __builtin_convertvector(pair, bf16x2));
-        *(uint16_t*)(obase + voff[v]) = (uint16_t)word;
-        *(uint16_t*)(obase + voff[v + 1]) = (uint16_t)(word >> 16);
+        const uint32_t off = (odd ? voff[2 * k + 1] : voff[2 * k]) - (odd ? ELT : 0);
+        *(uint32_t*)(obase + off) = word;
       }
     } else {
 #pragma unroll
