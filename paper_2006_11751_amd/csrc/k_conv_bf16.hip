@@ -23,8 +23,6 @@
 
 #include <string.h>
 
-#include <stdlib.h>
-
 #include "sf_internal.h"
 
 namespace sf {
@@ -501,7 +499,7 @@ hipError_t launch_conv_bf16(const void* in, const uint16_t* wt, const float* bia
                             const void* resid, void* out, int B, int H, int W, int Cin, int ks,
                             int stride, int pad, int Ho, int Wo, int N, int Kpad, int relu_in,
                             int relu_out, int in_f32, int resid_f32, int out_f32, int f16,
-                            int tag, hipStream_t st) {
+                            int tc_force, int tag, hipStream_t st) {
   ConvBf16Args g;
   g.in = in; g.Wt = wt; g.bias = bias; g.resid = resid; g.out = out;
   g.in_f32 = in_f32; g.resid_f32 = resid_f32;
@@ -514,9 +512,8 @@ hipError_t launch_conv_bf16(const void* in, const uint16_t* wt, const float* bia
   // configuration 75 -> 71 us at B = 4096; a grid of 1152 such workgroups is slower than 2304
   // single ones); the results are the same bits either way.
   const long long tiles2 = (long long)((g.M + kBP - 1) / kBP) * (N / 64);
-  const char* tc_s = getenv("SF_CONV_BF16_TC");  // 1 or 2 forces the variant (tests, A/B runs)
-  const int tc_env = tc_s ? atoi(tc_s) : 0;
-  const bool two = (N % 64) == 0 && (tc_env ? tc_env == 2 : tiles2 >= 2048);
+  // tc_force 1 or 2 fixes the variant (tests, A/B runs)
+  const bool two = (N % 64) == 0 && (tc_force ? tc_force == 2 : tiles2 >= 2048);
   switch (tag & 15) {
 #define SF_TAG_CASE(T) \
   case T: return two ? launch_tagged<T, 2>(g, f16 != 0, st) : launch_tagged<T, 1>(g, f16 != 0, st);

@@ -243,6 +243,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
   p->cfg = *cfg;
   p->flat = Cf * Hf * Wf;
   p->conv1_waves = getenv("SF_CONV1_WAVES") ? atoi(getenv("SF_CONV1_WAVES")) : 0;
+  p->conv_bf16_tc = getenv("SF_CONV_BF16_TC") ? atoi(getenv("SF_CONV_BF16_TC")) : 0;
 
   // bf16 configurations run the encoder and the FC layer on the bf16 kernels with bf16
   // activations, provided every layer has a shape those kernels take; otherwise the
@@ -890,7 +891,7 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
             SF_LAUNCH(launch_conv_bf16(in, L.wbf, L.bbf, buf(op.resid_buf), buf(op.out_buf), B, L.H,
                                        L.W, L.cin, L.k, L.s, L.pad, L.Ho, L.Wo, L.cout, L.Kpad,
                                        L.relu_in, L.relu_out, L.in_f32, p->stream_f32, L.out_f32,
-                                       p->act_f16, op.conv + 1, st));
+                                       p->act_f16, p->conv_bf16_tc, op.conv + 1, st));
             break;
           case CONV3X3_PATCH:
             SF_LAUNCH(launch_conv3x3_patch(in, L.wbf, L.bbf, buf(op.resid_buf), p->stream_f32,
@@ -932,7 +933,7 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
         if (p->fc_wbf)
           SF_LAUNCH(launch_conv_bf16(buf(op.in_buf), p->fc_wbf, p->fc_bbf, nullptr, p->fc_out, B, 1, 1,
                                      p->flat, 1, 1, 0, 1, 1, c.fc_dim, p->fc_Kpad, 0, 1,
-                                     p->stream_f32, 0, 1, p->act_f16, 0, st));
+                                     p->stream_f32, 0, 1, p->act_f16, p->conv_bf16_tc, 0, st));
         else if (p->fc_wt)
           SF_LAUNCH(launch_gemm_mfma(buf(op.in_buf), p->fc_wt, p->fc_b, p->fc_out, B, 1, 1, p->flat, 1,
                                      1, 1, 1, c.fc_dim, 1, p->fc_tile, 0, st));

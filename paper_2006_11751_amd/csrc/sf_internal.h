@@ -80,6 +80,7 @@ struct Policy {
   float* gru_wih;     // dev [G*H][core input] (canonical) for the MFMA kernel, or null
   float* gru_whh;     // dev [G*H][H]
   int gru_bm;         // rows per workgroup of the MFMA kernel, fixed at create
+  int conv_bf16_tc = 0;     // 16-bit conv kernel: 0 = channel blocks per workgroup by grid size, 1 / 2 forced
   int rnn_plain_loops = 1;  // GRU on the MFMA: the two-plain-loops form where the chunk counts allow it
   uint16_t* rnn_wih_bf;  // dev bf16 [G*H][core input] for the 16-bit MFMA kernel, or null
   uint16_t* rnn_whh_bf;  // dev bf16 [G*H][H]
@@ -165,7 +166,7 @@ hipError_t launch_conv_bf16(const void* in, const uint16_t* wt, const float* bia
                             const void* resid, void* out, int B, int H, int W, int Cin, int ks,
                             int stride, int pad, int Ho, int Wo, int N, int Kpad, int relu_in,
                             int relu_out, int in_f32, int resid_f32, int out_f32, int f16,
-                            int tag, hipStream_t st);
+                            int tc_force, int tag, hipStream_t st);
 hipError_t launch_maxpool_bf16(int B, int C, int H, int W, const void* in, void* out, int out_f32,
                                int f16, hipStream_t st);
 bool conv3x3_u8_bf16_supported(int cout);

@@ -41,8 +41,7 @@ def test_switch(torch_cuda, ref, monkeypatch, var, val, net):
     torch = torch_cuda
     monkeypatch.setenv(var, val)
     pol, w = _make(torch, net)
-    if var != "SF_CONV_BF16_TC":  # read at every launch, not at create
-        monkeypatch.delenv(var)
+    monkeypatch.delenv(var)
     d = pol.device
     B = net["B"]
     obs, state, done = wl.observations(net, 0, B), wl.initial_state(net, B), wl.done_mask(net, 0, B)
