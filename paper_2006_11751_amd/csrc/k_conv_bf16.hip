@@ -509,11 +509,13 @@ hipError_t launch_conv_bf16(const void* in, const uint16_t* wt, const float* bia
   g.relu_in = relu_in; g.relu_out = relu_out; g.out_f32 = out_f32;
   if (g.M == 0) return hipSuccess;
   // Two channel blocks per workgroup in grids of several rounds (measured: conv2 of the bf16
-  // configuration 75 -> 71 us at B = 4096; a grid of 1152 such workgroups is slower than 2304
-  // single ones); the results are the same bits either way.
+  // configuration 75 -> 71 us at B = 4096) and in grids of at most one workgroup per CU, where
+  // the smaller operand traffic counts and no round is lost (FC at B = 4096: 29.4 -> 27.7 us);
+  // in between, a grid of 1152 such workgroups is slower than 2304 single ones.  The results
+  // are the same bits either way.
   const long long tiles2 = (long long)((g.M + kBP - 1) / kBP) * (N / 64);
   // tc_force 1 or 2 fixes the variant (tests, A/B runs)
-  const bool two = (N % 64) == 0 && (tc_force ? tc_force == 2 : tiles2 >= 2048);
+  const bool two = (N % 64) == 0 && (tc_force ? tc_force == 2 : (tiles2 >= 2048 || tiles2 <= 256));
   switch (tag & 15) {
 #define SF_TAG_CASE(T) \
   case T: return two ? launch_tagged<T, 2>(g, f16 != 0, st) : launch_tagged<T, 1>(g, f16 != 0, st);
