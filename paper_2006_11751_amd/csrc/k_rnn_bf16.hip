@@ -3,7 +3,8 @@
 //
 // Same cell arithmetic, reset rule and state layout as the fp32 kernel.  The weights of a
 // bf16 configuration are bf16 numbers, the core's input is a bf16 activation (rounded to
-// nearest even while it is staged), and the fp32 state h enters the contraction as the
+// nearest even while it is staged, or handed over as bf16 by the FC kernel, which rounds the
+// same way: XB16), and the fp32 state h enters the contraction as the
 // exact sum of two bf16 numbers, h = hi + lo with hi = bf16(h), lo = bf16(h - hi)
 // (relative error below 2^-16): K runs over the input features and then, per 64-wide block
 // of h, over its hi part and its lo part, both against the same rows of W_hh (which, like
@@ -45,7 +46,7 @@ __device__ inline unsigned bf16_rne(float f) {
 __device__ inline float bf16_value(unsigned h) { return __uint_as_float(h << 16); }
 
 struct RnnBf16Args {
-  const float* x1;        // [B][I1]
+  const void* x1;         // [B][I1], fp32 or (XB16, I2 == 0) bf16
   const float* x2;        // [B][I2] or null
   const float* h_in;      // state rows of S floats, row index = batch row or ids[row]
   const uint8_t* done;    // [B]
@@ -78,7 +79,7 @@ __device__ inline u32x4 to_bf16x8(const f32x4& a, const f32x4& b, int phase) {
   return o;
 }
 
-template <bool LSTM>
+template <bool LSTM, bool XB16>
 __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
   constexpr int NG = LSTM ? 4 : 3;
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (kBR + NG * kBJ) * kPitch];
@@ -116,12 +117,18 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
   // (they stay in registers), so every block of h and of W_hh is fetched once.
   auto gload_x = [&](int c) {
     const int kk = c * kBK + lk8;
+    if (XB16) {  // eight bf16 values, kept as they are in the first register quad
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const float* src = c < n1c ? g.x1 + (size_t)am[r] * g.I1 + kk
-                                 : g.x2 + (size_t)am[r] * g.I2 + (kk - g.I1);
-      ra[r][0] = *(const f32x4*)src;
-      ra[r][1] = *(const f32x4*)(src + 4);
+      for (int r = 0; r < 4; ++r)
+        ra[r][0] = *(const f32x4*)((const uint16_t*)g.x1 + (size_t)am[r] * g.I1 + kk);
+    } else {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float* src = c < n1c ? (const float*)g.x1 + (size_t)am[r] * g.I1 + kk
+                                   : g.x2 + (size_t)am[r] * g.I2 + (kk - g.I1);
+        ra[r][0] = *(const f32x4*)src;
+        ra[r][1] = *(const f32x4*)(src + 4);
+      }
     }
 #pragma unroll
     for (int q = 0; q < NG; ++q)
@@ -145,7 +152,8 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
     for (int r = 0; r < 4; ++r) {
       // the reset is applied here, not behind the load (a select there waits for the load)
       const u32x4 zero = {0u, 0u, 0u, 0u};
-      const u32x4 v = to_bf16x8(ra[r][0], ra[r][1], rphase);
+      const u32x4 v = (XB16 && rphase == 0) ? __builtin_bit_cast(u32x4, ra[r][0])
+                                            : to_bf16x8(ra[r][0], ra[r][1], rphase);
       *(u32x4*)(Rs + (buf * kBR + lrow + 32 * r) * kPitch + lk8 * 2) = (rphase != 0 && areset[r]) ? zero : v;
     }
 #pragma unroll
@@ -290,20 +298,26 @@ void rnn_bf16_pack(const float* w, size_t n, std::vector<uint16_t>& out) {
   }
 }
 
-hipError_t launch_rnn_bf16(int lstm, int B, int I1, int I2, int H, const float* x1, const float* x2,
-                           const float* h_in, const uint8_t* done, const uint16_t* w_ih,
-                           const uint16_t* w_hh, const float* b_ih, const float* b_hh, float* h_out,
-                           const int32_t* ids, int n_env, hipStream_t st) {
+// x1_bf16: x1 holds bf16 values (only without a second input)
+hipError_t launch_rnn_bf16(int lstm, int B, int I1, int I2, int H, const void* x1, int x1_bf16,
+                           const float* x2, const float* h_in, const uint8_t* done,
+                           const uint16_t* w_ih, const uint16_t* w_hh, const float* b_ih,
+                           const float* b_hh, float* h_out, const int32_t* ids, int n_env,
+                           hipStream_t st) {
   if (B == 0) return hipSuccess;
+  if (x1_bf16 && x2) return hipErrorInvalidValue;
   RnnBf16Args g;
   g.x1 = x1; g.x2 = x2; g.h_in = h_in; g.done = done;
   g.w_ih = w_ih; g.w_hh = w_hh; g.b_ih = b_ih; g.b_hh = b_hh; g.h_out = h_out;
   g.B = B; g.I1 = I1; g.I2 = x2 ? I2 : 0; g.H = H; g.ids = ids; g.n_env = n_env;
   dim3 grid((B + kBR - 1) / kBR, H / kBJ);
-  if (lstm)
-    rnn_bf16_kernel<true><<<grid, 256, 0, st>>>(g);
-  else
-    rnn_bf16_kernel<false><<<grid, 256, 0, st>>>(g);
+  if (lstm) {
+    if (x1_bf16) rnn_bf16_kernel<true, true><<<grid, 256, 0, st>>>(g);
+    else rnn_bf16_kernel<true, false><<<grid, 256, 0, st>>>(g);
+  } else {
+    if (x1_bf16) rnn_bf16_kernel<false, true><<<grid, 256, 0, st>>>(g);
+    else rnn_bf16_kernel<false, false><<<grid, 256, 0, st>>>(g);
+  }
   return hipGetLastError();
 }
 

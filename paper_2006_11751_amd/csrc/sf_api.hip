@@ -559,6 +559,10 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
     p->rnn_wih_bf = bld.upload(t);
     rnn_bf16_pack(w->rnn_w_hh, (size_t)HG * cfg->rnn_dim, t);
     p->rnn_whh_bf = bld.upload(t);
+    // The FC kernel can hand its output over as bf16 (the rounding this kernel would apply
+    // while staging it): half the bytes for every unit tile that re-reads the rows.  Not with a
+    // second input (fp32) and not where the 16-bit activations are fp16.
+    p->fc_out_bf16 = p->fc_wbf && !p->act_f16 && p->meas_out_dim == 0 && !getenv("SF_FC_OUT_F32");
   } else if (getenv("SF_FORCE_GENERIC") || !rnn_mfma_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
     p->gru_wih_t = bld.pack_transposed(w->rnn_w_ih, HG, core_in);
     p->gru_whh_t = bld.pack_transposed(w->rnn_w_hh, HG, cfg->rnn_dim);
@@ -933,7 +937,8 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
         if (p->fc_wbf)
           SF_LAUNCH(launch_conv_bf16(buf(op.in_buf), p->fc_wbf, p->fc_bbf, nullptr, p->fc_out, B, 1, 1,
                                      p->flat, 1, 1, 0, 1, 1, c.fc_dim, p->fc_Kpad, 0, 1,
-                                     p->stream_f32, 0, 1, p->act_f16, p->conv_bf16_tc, 0, st));
+                                     p->stream_f32, 0, p->fc_out_bf16 ? 0 : 1, p->act_f16,
+                                     p->conv_bf16_tc, 0, st));
         else if (p->fc_wt)
           SF_LAUNCH(launch_gemm_mfma(buf(op.in_buf), p->fc_wt, p->fc_b, p->fc_out, B, 1, 1, p->flat, 1,
                                      1, 1, 1, c.fc_dim, 1, p->fc_tile, 0, st));
@@ -959,8 +964,8 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
         const float* x2 = p->n_meas ? p->meas_buf[p->n_meas - 1] : nullptr;
         const int lstm = c.rnn_type == SF_RNN_LSTM;
         if (p->rnn_wih_bf)
-          SF_LAUNCH(launch_rnn_bf16(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out, x2, h_in,
-                                    done, p->rnn_wih_bf, p->rnn_whh_bf, p->gru_bih, p->gru_bhh, h_out,
+          SF_LAUNCH(launch_rnn_bf16(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out,
+                                    p->fc_out_bf16, x2, h_in, done, p->rnn_wih_bf, p->rnn_whh_bf, p->gru_bih, p->gru_bhh, h_out,
                                     ids, n_env, st));
         else if (p->gru_wih)
           SF_LAUNCH(launch_rnn_mfma(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out, x2, h_in,

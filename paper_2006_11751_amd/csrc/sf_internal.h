@@ -80,6 +80,7 @@ struct Policy {
   float* gru_wih;     // dev [G*H][core input] (canonical) for the MFMA kernel, or null
   float* gru_whh;     // dev [G*H][H]
   int gru_bm;         // rows per workgroup of the MFMA kernel, fixed at create
+  int fc_out_bf16 = 0;      // the FC kernel hands bf16 values to the 16-bit recurrent kernel
   int conv_bf16_tc = 0;     // 16-bit conv kernel: 0 = channel blocks per workgroup by grid size, 1 / 2 forced
   int rnn_plain_loops = 1;  // GRU on the MFMA: the two-plain-loops form where the chunk counts allow it
   uint16_t* rnn_wih_bf;  // dev bf16 [G*H][core input] for the 16-bit MFMA kernel, or null
@@ -202,10 +203,11 @@ hipError_t launch_rnn_mfma(int lstm, int B, int I1, int I2, int H, const float* 
 int rnn_mfma_pick_bm(int max_batch, int H);
 bool rnn_bf16_supported(int I1, int I2, int H);
 void rnn_bf16_pack(const float* w, size_t n, std::vector<uint16_t>& out);
-hipError_t launch_rnn_bf16(int lstm, int B, int I1, int I2, int H, const float* x1, const float* x2,
-                           const float* h_in, const uint8_t* done, const uint16_t* w_ih,
-                           const uint16_t* w_hh, const float* b_ih, const float* b_hh, float* h_out,
-                           const int32_t* ids, int n_env, hipStream_t st);
+hipError_t launch_rnn_bf16(int lstm, int B, int I1, int I2, int H, const void* x1, int x1_bf16,
+                           const float* x2, const float* h_in, const uint8_t* done,
+                           const uint16_t* w_ih, const uint16_t* w_hh, const float* b_ih,
+                           const float* b_hh, float* h_out, const int32_t* ids, int n_env,
+                           hipStream_t st);
 bool gemm_mfma_supported(int Cin, int ksize, int pad, int N);
 int gemm_mfma_pick_tile(long long M, int N, int K, int seg_len);
 hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,
