@@ -315,6 +315,13 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
           const bool resnet = p->stream_f32;
           L.in_f32 = resnet && !(relu_in == 0 && resid_buf >= 0);  // conv_b reads the bf16 branch
           L.out_f32 = resnet && resid_buf >= 0;
+          if (cfg->encoder == SF_ENCODER_CONV && !p->act_f16 && !relu_in && resid_buf < 0 &&
+              !getenv("SF_NO_CONV_IMAGE") &&
+              conv_image_bf16_supported(C, k, s, pad, H, W, L.Ho, L.Wo, cout)) {
+            conv_image_bf16_pack(w->conv_w[ti], cout, k, wt);
+            L.wbf = bld.upload(wt);
+            L.impl = CONV_IMAGE_BF16;
+          }
         } else if (cfg->encoder == SF_ENCODER_CONV) {
           std::vector<int> ipk;
           std::vector<float> spk, bpk;
@@ -890,6 +897,10 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
             SF_LAUNCH(launch_gemm_mfma((const float*)in, L.wpk, L.bpk, buf(op.out_buf), B, L.H, L.W,
                                        L.cin, L.k, L.s, L.Ho, L.Wo, L.cout, L.relu_out, L.tile,
                                        op.conv + 1, st));
+            break;
+          case CONV_IMAGE_BF16:
+            SF_LAUNCH(launch_conv_image_bf16(in, L.wbf, L.bbf, buf(op.out_buf), B, L.H, L.W, L.cin,
+                                             L.k, L.s, L.Ho, L.Wo, L.cout, L.relu_out, st));
             break;
           case CONV_BF16:
             SF_LAUNCH(launch_conv_bf16(in, L.wbf, L.bbf, buf(op.resid_buf), buf(op.out_buf), B, L.H,

@@ -40,7 +40,8 @@ enum ConvImpl {
   CONV3X3_PATCH = 6,    // 3x3/s1/p1 on the 16-bit MFMA with an LDS-staged input patch
   CONV3X3_STEM = 7,     // first convolution of the residual encoder on the 16-bit MFMA
   CONV3X3_POOL = 8,     // stage convolution fused with the max-pool behind it
-  RES_BLOCK = 9         // a whole residual block (this layer and the next) in one kernel
+  RES_BLOCK = 9,        // a whole residual block (this layer and the next) in one kernel
+  CONV_IMAGE_BF16 = 10  // 16-bit MFMA with the frame's input image resident in LDS
 };
 
 // One kernel launch of the step, fixed at create time.
@@ -208,6 +209,12 @@ hipError_t launch_rnn_bf16(int lstm, int B, int I1, int I2, int H, const void* x
                            const uint16_t* w_ih, const uint16_t* w_hh, const float* b_ih,
                            const float* b_hh, float* h_out, const int32_t* ids, int n_env,
                            hipStream_t st);
+bool conv_image_bf16_supported(int Cin, int ksize, int stride, int pad, int H, int W, int Ho, int Wo,
+                               int N);
+void conv_image_bf16_pack(const float* w, int cout, int k, std::vector<uint16_t>& wpk);
+hipError_t launch_conv_image_bf16(const void* in, const uint16_t* wpk, const float* bias, void* out,
+                                  int B, int H, int W, int Cin, int ksize, int stride, int Ho,
+                                  int Wo, int N, int relu, hipStream_t st);
 bool gemm_mfma_supported(int Cin, int ksize, int pad, int N);
 int gemm_mfma_pick_tile(long long M, int N, int K, int seg_len);
 hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,

@@ -128,6 +128,23 @@ def _sampled_rows_check(torch, ref, net, n_rows, n_steps=1, full_steps=1):
     pol.close()
 
 
+def test_standard_bf16_several_frames_per_workgroup(torch_cuda, ref):
+    """Configuration 2's network at B=1100, every row: the image-resident conv2 kernel walks
+    two or three frames per workgroup here (512 workgroups), the last round ragged."""
+    torch = torch_cuda
+    net = wl.network(2, B=1100, name="standard_bf16_1100")
+    pol, w = _make(torch, net)
+    obs, h_in, done = wl.observations(net), wl.initial_state(net), wl.done_mask(net)
+    g = _gpu_step(torch, pol, obs, h_in, done, wl.PHILOX_SEED, 2)
+    o = ref.policy_step(net, w, obs, h_in, done, wl.PHILOX_SEED, 2)
+    parity.check_against_oracle(net, g, o, ref, wl.PHILOX_SEED, 2)
+    # prefix property on the same handle (one frame per workgroup below 512 rows)
+    g2 = _gpu_step(torch, pol, obs[:300], h_in[:300], done[:300], wl.PHILOX_SEED, 2)
+    for k in g:
+        assert np.array_equal(g[k][:300], g2[k]), k
+    pol.close()
+
+
 def test_standard_bf16_full_size_sampled_rows(torch_cuda, ref):
     """Configuration 2 (B=4096, bf16 weights/activations)."""
     _sampled_rows_check(torch_cuda, ref, wl.network(2), 200)
