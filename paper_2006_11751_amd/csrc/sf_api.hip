@@ -318,7 +318,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
           if (cfg->encoder == SF_ENCODER_CONV && !p->act_f16 && !relu_in && resid_buf < 0 &&
               !getenv("SF_NO_CONV_IMAGE") &&
               conv_image_bf16_supported(C, k, s, pad, H, W, L.Ho, L.Wo, cout)) {
-            conv_image_bf16_pack(w->conv_w[ti], cout, k, wt);
+            conv_image_bf16_pack(w->conv_w[ti], cout, C, k, wt);
             L.wbf = bld.upload(wt);
             L.impl = CONV_IMAGE_BF16;
           }

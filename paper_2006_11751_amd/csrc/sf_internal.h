@@ -211,7 +211,7 @@ hipError_t launch_rnn_bf16(int lstm, int B, int I1, int I2, int H, const void* x
                            hipStream_t st);
 bool conv_image_bf16_supported(int Cin, int ksize, int stride, int pad, int H, int W, int Ho, int Wo,
                                int N);
-void conv_image_bf16_pack(const float* w, int cout, int k, std::vector<uint16_t>& wpk);
+void conv_image_bf16_pack(const float* w, int cout, int cin, int k, std::vector<uint16_t>& wpk);
 hipError_t launch_conv_image_bf16(const void* in, const uint16_t* wpk, const float* bias, void* out,
                                   int B, int H, int W, int Cin, int ksize, int stride, int Ho,
                                   int Wo, int N, int relu, hipStream_t st);
