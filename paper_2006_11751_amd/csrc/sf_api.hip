@@ -244,6 +244,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
   p->flat = Cf * Hf * Wf;
   p->conv1_waves = getenv("SF_CONV1_WAVES") ? atoi(getenv("SF_CONV1_WAVES")) : 0;
   p->conv_bf16_tc = getenv("SF_CONV_BF16_TC") ? atoi(getenv("SF_CONV_BF16_TC")) : 0;
+  p->conv1_image = getenv("SF_NO_CONV1_IMAGE") ? 0 : 1;
 
   // bf16 configurations run the encoder and the FC layer on the bf16 kernels with bf16
   // activations, provided every layer has a shape those kernels take; otherwise the
@@ -887,7 +888,7 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
         switch (L.impl) {
           case CONV1_U8_I8:
             SF_LAUNCH(launch_conv1_i8(L, B, obs, L.ipk, L.spk, L.bpk, buf(op.out_buf), p->bf16_path,
-                                      p->conv1_waves, st));
+                                      p->conv1_waves, p->conv1_image, st));
             break;
           case CONV1_U8_MFMA:
             SF_LAUNCH(launch_conv1_mfma(L, B, obs, L.wpk, L.bpk, buf(op.out_buf), p->trash,

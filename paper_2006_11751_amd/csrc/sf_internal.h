@@ -81,6 +81,7 @@ struct Policy {
   float* gru_wih;     // dev [G*H][core input] (canonical) for the MFMA kernel, or null
   float* gru_whh;     // dev [G*H][H]
   int gru_bm;         // rows per workgroup of the MFMA kernel, fixed at create
+  int conv1_image = 1;      // first convolution: frame-resident variant where it applies
   int fc_out_bf16 = 0;      // the FC kernel hands bf16 values to the 16-bit recurrent kernel
   int conv_bf16_tc = 0;     // 16-bit conv kernel: 0 = channel blocks per workgroup by grid size, 1 / 2 forced
   int rnn_plain_loops = 1;  // GRU on the MFMA: the two-plain-loops form where the chunk counts allow it
@@ -160,7 +161,7 @@ void conv1_i8_pack(const float* w, const float* bias, int cin, float obs_sub, fl
                    std::vector<int>& wpk, std::vector<float>& scale, std::vector<float>& bpk);
 hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const int* wpk,
                            const float* scale, const float* bpk, void* out, int out_bf16,
-                           int waves_hint, hipStream_t st);
+                           int waves_hint, int image, hipStream_t st);
 bool conv_bf16_supported(int Cin, int N);
 void conv_bf16_pack(const float* w, const float* bias, int cout, int cin, int k, bool f16,
                     std::vector<uint16_t>& wt, std::vector<float>& b, int* Kpad);

@@ -129,10 +129,11 @@ def _sampled_rows_check(torch, ref, net, n_rows, n_steps=1, full_steps=1):
 
 
 def test_standard_bf16_several_frames_per_workgroup(torch_cuda, ref):
-    """Configuration 2's network at B=1100, every row: the image-resident conv2 kernel walks
-    two or three frames per workgroup here (512 workgroups), the last round ragged."""
+    """Configuration 2's network at B=2101, every row: the frame-resident kernels (conv1 from
+    2048 rows on, conv2, conv3) walk several frames or rounds per workgroup here, the last round
+    ragged; the 300-row prefix runs conv1 on the gather kernel and must give the same bits."""
     torch = torch_cuda
-    net = wl.network(2, B=1100, name="standard_bf16_1100")
+    net = wl.network(2, B=2101, name="standard_bf16_2101")
     pol, w = _make(torch, net)
     obs, h_in, done = wl.observations(net), wl.initial_state(net), wl.done_mask(net)
     g = _gpu_step(torch, pol, obs, h_in, done, wl.PHILOX_SEED, 2)
@@ -142,6 +143,25 @@ def test_standard_bf16_several_frames_per_workgroup(torch_cuda, ref):
     g2 = _gpu_step(torch, pol, obs[:300], h_in[:300], done[:300], wl.PHILOX_SEED, 2)
     for k in g:
         assert np.array_equal(g[k][:300], g2[k]), k
+    pol.close()
+
+
+def test_first_convolution_variants_give_the_same_bits(torch_cuda, ref):
+    """fp32 standard network at B=2050: the first convolution runs frame-resident from 2048 rows
+    on and as a gather kernel below; a 700-row prefix must equal the full call bitwise, and
+    sampled rows of the full call must match the oracle."""
+    torch = torch_cuda
+    net = wl.network(1, B=2050, name="standard_2050")
+    pol, w = _make(torch, net)
+    obs, h_in, done = wl.observations(net), wl.initial_state(net), wl.done_mask(net)
+    g = _gpu_step(torch, pol, obs, h_in, done, wl.PHILOX_SEED, 1)
+    g2 = _gpu_step(torch, pol, obs[:700], h_in[:700], done[:700], wl.PHILOX_SEED, 1)
+    for k in g:
+        assert np.array_equal(g[k][:700], g2[k]), k
+    rows = np.array([0, 1, 511, 512, 1023, 1024, 1536, 2047, 2048, 2049])
+    o = ref.policy_step(net, w, obs[rows], h_in[rows], done[rows], wl.PHILOX_SEED, 1)
+    np.testing.assert_allclose(g["h_out"][rows], o["h_out"], rtol=1e-4, atol=1e-5)
+    np.testing.assert_allclose(g["value"][rows], o["value"], rtol=1e-4, atol=1e-5)
     pol.close()
 
 
