@@ -61,10 +61,13 @@ RESNET_BF16_MID = dict(RESNET_BF16_SMALL, name="resnet_bf16_mid", B=3, obs=(3, 5
 # width not a multiple of 4 (byte planes not dword-aligned), channel counts 32 -> 16 -> 32
 RESNET_BF16_MIX = dict(RESNET_BF16_SMALL, name="resnet_bf16_mix", B=4, obs=(3, 30, 42), stages=[32, 16, 32])
 STD_BF16_SMALL = wl.network(2, B=37, name="standard_bf16_small")
+# 76x132 frames: conv2 has 8x15 = 120 output pixels (the eight-tile instantiation of the
+# frame-resident kernel), conv3 3x7 = 21 (more than that kernel takes: tiled kernel)
+STD_BF16_WIDE = dict(STD_BF16_SMALL, name="standard_bf16_wide", B=9, obs=(3, 76, 132))
 
 
 @pytest.mark.parametrize("net", [SMALL_RESNET, ODD_NET, RESNET_BF16_SMALL, RESNET_BF16_MID, RESNET_BF16_MIX,
-                                 STD_BF16_SMALL],
+                                 STD_BF16_SMALL, STD_BF16_WIDE],
                          ids=lambda n: n["name"])
 def test_small_networks_all_elements(torch_cuda, ref, net):
     torch = torch_cuda
