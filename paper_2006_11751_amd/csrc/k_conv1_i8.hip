@@ -455,7 +455,7 @@ hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const 
   // B = 4096 bf16 68.5 -> 58.5 us, B = 2048 fp32 52.8 -> 41.4 us, B = 1024 fp32 22.3 -> 23.8 us);
   // both variants give the same bits, so the choice may depend on the batch of the call.
   if (image && B >= 2048 && n_xchunks == 1 && frame_bytes % 16 == 0 &&
-      frame_bytes <= 7 * 256 * 16 && ((uintptr_t)obs & 15) == 0 && (L.cin == 3 || L.cin == 1)) {
+      frame_bytes <= 7 * 256 * 16 && ((uintptr_t)obs & 15) == 0 && L.cin == 3) {
     // two workgroups per CU, each walking its share of the frames
     const int blocks = B < 512 ? B : 512;
     const size_t lds = (size_t)frame_bytes;
@@ -468,7 +468,7 @@ hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const 
       conv1_u8_i8_image_kernel<C, false><<<blocks, 64 * kWaves, lds, st>>>(                    \
           obs, wpk, scale, bpk, out, B, L.H, L.W, L.Ho, L.Wo);                                 \
   } while (0)
-    if (L.cin == 3) SF_LAUNCH_IMG(3); else SF_LAUNCH_IMG(1);
+    SF_LAUNCH_IMG(3);
 #undef SF_LAUNCH_IMG
     return hipGetLastError();
   }
