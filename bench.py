@@ -20,6 +20,10 @@ MI355X_PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2500.0}
 # x 1.000) KiB, the factors being what the same counters read for a 256 MiB plain copy.
 MEASURED_HBM_KIB = {"standard": {"conv1": 30902 + 67456, "conv2": 76932 + 25088, "conv3": 25710 + 9216,
                                  "fc": 46216 + 2048, "gru": 54646 + 2048, "heads": 2293 + 24},
+                    # profiles/policy_step_bf16_kernel_trace_and_hbm_traffic.md (FETCH_SIZE x 2 + WRITE_SIZE)
+                    "standard_bf16": {"conv1": 2 * 56104 + 134920, "conv2": 2 * 67967 + 50252,
+                                      "conv3": 2 * 25731 + 18432, "fc": 2 * 18550 + 4096,
+                                      "gru": 2 * 18638 + 8426, "heads": 2 * 4219 + 96},
                     # profiles/policy_step_resnet_counters.md (FETCH_SIZE x 2 + WRITE_SIZE)
                     "resnet_bf16": {"stage1.conv_pool": 2 * 110600 + 589820, "stage1.block1": 2 * 295000 + 589820,
                                     "stage1.block2": 2 * 295000 + 589820, "stage2.conv_pool": 2 * 295100 + 294900,
@@ -182,6 +186,14 @@ def main():
                 "avg_launch_ms": round(float(op_ms[i_dom]), 5),
                 "whole_step": whole,
                 "per_kernel": per_op}
+    if kib is not None and op_ms[i_dom] > 0:
+        # the dominant launch against the other roof; it is reported against the one it is nearer to
+        gbps = kib * 1024 / (float(op_ms[i_dom]) * 1e-3) / 1e9
+        if gbps / 8000.0 > roofline["frac"]:
+            roofline.update({"bound": "hbm", "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s",
+                             "frac": round(gbps / 8000.0, 5), "mfma_frac": round(dom_tflops / peak, 5)})
+        else:
+            roofline["hbm_frac"] = round(gbps / 8000.0, 5)
 
     cpu = None
     if not args.no_cpu_baseline:
