@@ -12,7 +12,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("net", [wl.network(1, B=96, name="standard_96"), RESNET_BF16_SMALL,
-                                 wl.network(6, B=64, name="full_64")], ids=lambda n: n["name"])
+                                 wl.network(6, B=64, name="full_64"),
+                                 wl.network(2, B=70, name="standard_bf16_70")], ids=lambda n: n["name"])
 def test_captured_step_replays_bitwise(torch_cuda, net):
     torch = torch_cuda
     pol, _ = _make(torch, net)
