@@ -4,30 +4,62 @@ One "step" = one sf_policy_step over a batch of synthetic observations already
 resident in HBM (the standard configuration: B=1024 frames of 3x72x128 bytes,
 conv encoder, FC-512, GRU-512, one 7-way head + value, fp32).  Prints one JSON
 line: env-frames/s, the roofline of the dominant kernel (live HIP-event timing of
-every launch) and the CPU oracle timed on the host cores on a bounded sample.
+every launch, each launch scored against the peak of the arithmetic it runs on)
+and the CPU oracle timed on the host cores on a bounded sample.
+
+Timing protocol: an uncounted, time-based pre-warm-up (the clocks of an idle GPU
+need a few hundred milliseconds of work to settle), then --warmup counted untimed
+steps, then BLOCKS blocks of exactly --steps steps, each bracketed by a device
+synchronisation; ms_per_step is the median block (min and max beside it).
 """
 import argparse
+import hashlib
 import json
+import os
 import sys
 import time
 
 import numpy as np
 
-MI355X_PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2500.0}
+ROOT = os.path.dirname(os.path.abspath(__file__))
 
-# HBM bytes per launch of the standard workload (B=1024), from the two rocprofv3 --pmc runs
-# recorded in profiles/policy_step_standard_hbm_traffic.md: (FETCH_SIZE x 2.000 + WRITE_SIZE
-# x 1.000) KiB, the factors being what the same counters read for a 256 MiB plain copy.
-MEASURED_HBM_KIB = {"standard": {"conv1": 30902 + 67456, "conv2": 76932 + 25088, "conv3": 25710 + 9216,
-                                 "fc": 46216 + 2048, "gru": 54646 + 2048, "heads": 2293 + 24},
-                    # profiles/policy_step_bf16_kernel_trace_and_hbm_traffic.md (FETCH_SIZE x 2 + WRITE_SIZE)
-                    "standard_bf16": {"conv1": 2 * 56104 + 134920, "conv2": 2 * 67967 + 50252,
-                                      "conv3": 2 * 25731 + 18432, "fc": 2 * 18550 + 4096,
-                                      "gru": 2 * 18638 + 8426, "heads": 2 * 4219 + 96},
-                    # profiles/policy_step_resnet_counters.md (FETCH_SIZE x 2 + WRITE_SIZE)
-                    "resnet_bf16": {"stage1.conv_pool": 2 * 110600 + 589820, "stage1.block1": 2 * 295000 + 589820,
-                                    "stage1.block2": 2 * 295000 + 589820, "stage2.conv_pool": 2 * 295100 + 294900,
-                                    "stage2.block1": 2 * 147800 + 294900, "stage2.block2": 2 * 147800 + 294900}}
+# MI355X dense peaks per arithmetic ("pipe") of a launch, in Tera-operations/s: fp32 MFMA (also
+# the fp32 vector rate), 16-bit MFMA, int8 MFMA.  An int8 digit-plane launch executes 2 or 3
+# integer multiply-adds per algorithmic one; its figure below is algorithmic work over the
+# int8 peak, i.e. a lower bound of how busy the int8 pipe is.
+PEAK_TOPS = {"f32": 157.3, "valu": 157.3, "bf16": 2500.0, "f16": 2500.0, "i8x2": 5000.0, "i8x3": 5000.0}
+HBM_PEAK_GBPS = 8000.0
+BLOCKS = 5
+PREWARM_SECONDS = 0.3
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_table.txt")
+
+
+def source_hash():
+    """Identifies the kernels that run: sha256 over the library's sources."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2006_11751_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    h.update(open(os.path.join(ROOT, "include", "sf_policy.h"), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def load_traffic(workload, B, ops, pipes):
+    """HBM bytes per launch from the tracked table of rocprofv3 counter runs, or None when the
+    table has no entry measured on these sources for this workload, batch and launch sequence."""
+    try:
+        text = "".join(l for l in open(TRAFFIC_TABLE) if not l.startswith("#"))
+        table = json.loads(text)
+    except (OSError, ValueError):
+        return None, "no traffic table"
+    src = source_hash()
+    for e in table:
+        if (e["workload"] == workload and e["B"] == B and e["source_hash"] == src and
+                [o["op"] for o in e["ops"]] == [n for n, _ in ops] and [o["pipe"] for o in e["ops"]] == pipes):
+            return {o["op"]: o for o in e["ops"]}, "profiles/hbm_traffic_table.txt (%s)" % e.get("profile", "")
+    return None, "no table entry for these kernels (sources %s)" % src
 
 
 def measure_pipeline(torch, binding, wl, pol, net, rounds):
@@ -104,11 +136,15 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = the headline one)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay figure")
     ap.add_argument("--pipeline", action="store_true",
                     help="also measure the double-buffered pipeline with host-resident observations")
     ap.add_argument("--loss", action="store_true", help="also time the learner-side loss kernels")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
+    ap.add_argument("--profile-run", action="store_true",
+                    help="for runs under rocprofv3: no pre-warm-up, one block, no per-launch event pass, "
+                         "no graph, no CPU baseline; the last launches of the trace are one whole step")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the step is data-parallel over rows "
@@ -146,57 +182,116 @@ def main():
         assert torch.equal(src, dst)
         del src, dst
 
-    run(args.warmup, 0)
+    profile_run = args.profile_run
+    t_next = 0
+    prewarm_steps = 0
+    if not profile_run:
+        tic = time.perf_counter()
+        while time.perf_counter() - tic < PREWARM_SECONDS:
+            run(20, t_next)
+            torch.cuda.synchronize()
+            t_next += 20
+        prewarm_steps = t_next
+    run(args.warmup, t_next)
+    t_next += args.warmup
     torch.cuda.synchronize()
-    tic = time.perf_counter()
-    run(args.steps, args.warmup)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - tic
-    ms_per_step = 1e3 * elapsed / args.steps
-    fps = B * args.steps / elapsed
+    block_ms = []
+    for _ in range(1 if profile_run else BLOCKS):
+        tic = time.perf_counter()
+        run(args.steps, t_next)
+        torch.cuda.synchronize()
+        block_ms.append(1e3 * (time.perf_counter() - tic) / args.steps)
+        t_next += args.steps
+    ms_per_step = float(np.median(block_ms))
+    fps = B / (ms_per_step * 1e-3)
 
-    # per-launch durations: the same steps again with a HIP event after every launch
     ops = pol.ops()
-    pol.set_op_timing(True)
-    acc = np.zeros(len(ops))
-    n_timed = min(args.steps, 100)
-    for t in range(n_timed):
-        run(1, args.warmup + args.steps + t)
-        acc += np.array(pol.last_op_times_ms())
-    pol.set_op_timing(False)
-    op_ms = acc / n_timed
+    pipes = pol.op_pipes()
     dtype = net["dtype"]
-    peak = MI355X_PEAK_TFLOPS[dtype]
-    i_dom = int(np.argmax(op_ms))
-    per_op = {name: {"ms": round(float(ms), 5),
-                     "tflops": round(fl * B / (ms * 1e-3) / 1e12, 3) if ms > 0 else None}
-              for (name, fl), ms in zip(ops, op_ms)}
-    dom_tflops = ops[i_dom][1] * B / (op_ms[i_dom] * 1e-3) / 1e12
-    whole_tflops = pol.flops_per_row() * B / (ms_per_step * 1e-3) / 1e12
-    kib = MEASURED_HBM_KIB.get(net["name"], {}).get(ops[i_dom][0]) if B == wl.CONFIGS[args.config]["B"] else None
-    kib_all = MEASURED_HBM_KIB.get(net["name"]) if B == wl.CONFIGS[args.config]["B"] else None
-    whole = {"achieved": round(whole_tflops, 3), "frac": round(whole_tflops / peak, 5)}
-    if kib_all and set(kib_all) >= {name for name, _ in ops}:
-        # second roof: measured HBM bytes of all launches of the step over the step's time
-        hbm = sum(kib_all[name] for name, _ in ops) * 1024 / (ms_per_step * 1e-3) / 1e9
-        whole.update({"hbm_GBps": round(hbm, 1), "hbm_frac": round(hbm / 8000.0, 4)})
-    roofline = {"bound": "mfma", "kernel": ops[i_dom][0], "achieved": round(dom_tflops, 3), "peak": peak,
-                "unit": "TFLOP/s", "frac": round(dom_tflops / peak, 5),
-                "traffic": kib * 1024 if kib is not None else None,
-                "avg_launch_ms": round(float(op_ms[i_dom]), 5),
-                "whole_step": whole,
-                "per_kernel": per_op}
-    if kib is not None and op_ms[i_dom] > 0:
-        # the dominant launch against the other roof; it is reported against the one it is nearer to
-        gbps = kib * 1024 / (float(op_ms[i_dom]) * 1e-3) / 1e9
-        if gbps / 8000.0 > roofline["frac"]:
-            roofline.update({"bound": "hbm", "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s",
-                             "frac": round(gbps / 8000.0, 5), "mfma_frac": round(dom_tflops / peak, 5)})
-        else:
-            roofline["hbm_frac"] = round(gbps / 8000.0, 5)
+    roofline = None
+    graph = None
+    if not profile_run:
+        # per-launch durations: the same steps again with a HIP event after every launch, on the
+        # stream the launches go to
+        pol.set_op_timing(True)
+        n_timed = min(args.steps, 100)
+        samples = np.zeros((n_timed, len(ops)))
+        for t in range(n_timed):
+            run(1, t_next + t)
+            samples[t] = pol.last_op_times_ms()
+        t_next += n_timed
+        pol.set_op_timing(False)
+        op_ms = samples.mean(axis=0)
+        i_dom = int(np.argmax(op_ms))
+        traffic, traffic_src = load_traffic(net["name"], B, ops, pipes)
+        per_op = {}
+        for (name, fl), pipe, ms in zip(ops, pipes, op_ms):
+            tops = fl * B / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+            e = {"ms": round(float(ms), 5), "pipe": pipe, "tops": round(tops, 3),
+                 "frac_of_pipe_peak": round(tops / PEAK_TOPS[pipe], 5)}
+            if traffic is not None:
+                byts = 1024.0 * traffic[name]["hbm_kib"]
+                e["hbm_bytes"] = int(byts)
+                e["hbm_frac"] = round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 5) if ms > 0 else None
+            per_op[name] = e
+        dom = per_op[ops[i_dom][0]]
+        whole_tops = pol.flops_per_row() * B / (ms_per_step * 1e-3) / 1e12
+        # the step against a roof of its own: every launch at the peak of its pipe
+        t_roof_ms = sum(fl * B / (PEAK_TOPS[p] * 1e12) * 1e3 for (_, fl), p in zip(ops, pipes))
+        whole = {"algorithmic_tops": round(whole_tops, 3), "ms_at_pipe_peaks": round(t_roof_ms, 5),
+                 "frac": round(t_roof_ms / ms_per_step, 5)}
+        f32 = [(fl, ms) for (_, fl), p, ms in zip(ops, pipes, op_ms) if p == "f32"]
+        if f32:
+            tf = sum(fl for fl, _ in f32) * B / (sum(ms for _, ms in f32) * 1e-3) / 1e12
+            whole["fp32_mfma_launches"] = {"tflops": round(tf, 3), "frac": round(tf / PEAK_TOPS["f32"], 5),
+                                           "ms": round(float(sum(ms for _, ms in f32)), 5)}
+        if traffic is not None:
+            hbm = sum(1024.0 * traffic[name]["hbm_kib"] for name, _ in ops) / (ms_per_step * 1e-3) / 1e9
+            whole.update({"hbm_GBps": round(hbm, 1), "hbm_frac": round(hbm / HBM_PEAK_GBPS, 4)})
+        roofline = {"bound": "mfma", "kernel": ops[i_dom][0], "pipe": dom["pipe"], "achieved": dom["tops"],
+                    "peak": PEAK_TOPS[dom["pipe"]], "unit": "TFLOP/s" if not dom["pipe"].startswith("i8") else "TOP/s",
+                    "frac": dom["frac_of_pipe_peak"],
+                    "traffic": dom.get("hbm_bytes"), "traffic_source": traffic_src,
+                    "avg_launch_ms": dom["ms"], "whole_step": whole, "per_kernel": per_op}
+        if dom.get("hbm_frac") is not None:
+            # the dominant launch against the other roof; it is reported against the one it is nearer to
+            if dom["hbm_frac"] > roofline["frac"]:
+                roofline.update({"bound": "hbm", "achieved": round(dom["hbm_bytes"] / (dom["ms"] * 1e-3) / 1e9, 1),
+                                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": dom["hbm_frac"],
+                                 "mfma_frac": dom["frac_of_pipe_peak"]})
+            else:
+                roofline["hbm_frac"] = dom["hbm_frac"]
+
+        if not args.no_graph:
+            # second, labelled figure: two steps (one ping-pong of the state buffers) recorded
+            # into a HIP graph and replayed; launch overhead and inter-launch gaps shrink
+            side = torch.cuda.Stream(device=dev)
+            with torch.cuda.stream(side):
+                pol.step(obs, h[0], done, wl.PHILOX_SEED, 0, out=out[0], stream=side, meas=meas)
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                s = torch.cuda.current_stream(dev)
+                pol.step(obs, h[0], done, wl.PHILOX_SEED, 0, out=out[0], stream=s, meas=meas)
+                pol.step(obs, h[1], done, wl.PHILOX_SEED, 1, out=out[1], stream=s, meas=meas)
+            reps = max(1, args.steps // 2)
+            for _ in range(5):
+                g.replay()
+            torch.cuda.synchronize()
+            gms = []
+            for _ in range(BLOCKS):
+                tic = time.perf_counter()
+                for _ in range(reps):
+                    g.replay()
+                torch.cuda.synchronize()
+                gms.append(1e3 * (time.perf_counter() - tic) / (2 * reps))
+            gm = float(np.median(gms))
+            graph = {"ms_per_step": round(gm, 5), "value": round(B / (gm * 1e-3), 1), "unit": "env-frames/s",
+                     "note": "the same step replayed from a HIP graph (seed/step arguments frozen); "
+                             "not the headline value"}
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not profile_run:
         from oracle import ref
         n_rows = min(B, 1024)
         o_obs, o_h, o_done = wl.observations(net, B=n_rows), wl.initial_state(net, B=n_rows), wl.done_mask(net, B=n_rows)
@@ -212,6 +307,11 @@ def main():
 
     pipeline = measure_pipeline(torch, binding, wl, pol, net, min(args.steps, 100)) if args.pipeline else None
 
+    conv1 = {"i8x3": "int8 MFMA, 3 fixed-point digit planes (admitted: error-bound ratio %.3f <= 1)",
+             "i8x2": "int8 MFMA, 2 fixed-point digit planes (admitted: error-bound ratio %.3f <= 1)",
+             "f32": "fp32 MFMA (fixed-point bank not admitted: ratio %.3f)"}.get(pipes[0])
+    if conv1:
+        conv1 = conv1 % pol.conv1_fixed_point_ratio(2 if pipes[0] == "i8x2" else 3)
     line = {
         "metric": "policy-step env-frames/sec at B=1024 3x72x128 GRU-512; % MFMA/HBM roofline",
         "value": round(fps, 1), "unit": "env-frames/s", "n_gpus": 1, "steps": args.steps,
@@ -221,9 +321,17 @@ def main():
         "config": {"workload": "%s: B=%d obs u8 %dx%dx%d, %s encoder, FC%d, %s%d, heads %s%s" % (
             net["name"], B, *net["obs"], net["encoder"], net["fc"], net["rnn_type"].upper(), net["rnn"],
             net["heads"], ", %d measurements -> FC%s" % (net["meas_dim"], net["meas_hidden"]) if net["meas_dim"] else ""),
+            "name": net["name"], "B": B, "conv1": conv1 or pipes[0],
+            "launch_pipes": dict(zip((n for n, _ in ops), pipes)),
             "paper_accounting_x4_frameskip_fps": round(4 * fps, 1),
-            "inputs": "device-resident; host-to-device transfer excluded"},
+            "inputs": "device-resident; host-to-device transfer excluded",
+            "timing": "median of %d blocks of %d steps after %d uncounted pre-warm-up steps (>= %.1f s) and %d "
+                      "warm-up steps" % (len(block_ms), args.steps, prewarm_steps, PREWARM_SECONDS, args.warmup),
+            "ms_per_step_min": round(min(block_ms), 5), "ms_per_step_max": round(max(block_ms), 5),
+            "source_hash": source_hash()},
         "roofline": roofline, "cpu_baseline": cpu}
+    if graph is not None:
+        line["graph_replay"] = graph
     if pipeline is not None:
         line["pipeline"] = pipeline
     if args.loss:

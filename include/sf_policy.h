@@ -88,9 +88,19 @@ typedef struct {
   int32_t rnn_dim; /* hidden size H of the recurrent core */
   int32_t n_heads; /* independent categorical heads */
   int32_t head_sizes[SF_MAX_HEADS];
-  int32_t dtype; /* SF_DTYPE_FP32, or SF_DTYPE_BF16: weights and encoder/FC activations
-                    in bf16 with fp32 accumulation; the GRU state, the gate arithmetic,
-                    the heads and the sampler stay fp32 */
+  int32_t dtype; /* SF_DTYPE_FP32, or SF_DTYPE_BF16: every parameter is replaced by the nearest
+                    bf16 value (ties to even) of what the caller passes; encoder and FC
+                    activations are 16-bit with fp32 accumulation; the recurrent state, the
+                    gate arithmetic, the heads and the sampler stay fp32.  The 16-bit
+                    activation type is bf16 in the plain convolution stack and fp16 in the
+                    residual encoder (15 convolutions deep: 8-bit significands do not hold the
+                    2e-2 tolerance there).  Limits of the fp16 case: an encoder or FC weight
+                    beyond +-65280 is rejected at create (SF_ERR_ARG); a weight below 2^-14
+                    in magnitude is held on fp16's subnormal grid (multiples of 2^-24); and
+                    if any activation of a row's encoder exceeds 65504 in magnitude, that
+                    row's outputs are unspecified (possibly finite), the other rows of the
+                    batch being unaffected.  With pixel values normalised to [0, 1] and
+                    weights of variance 1/fan_in the activations are of order 1. */
   float obs_sub, obs_mul; /* normalisation: x = ((float)byte - obs_sub) * obs_mul */
   int32_t rnn_type; /* SF_RNN_GRU, or SF_RNN_LSTM (the core of the paper's benchmark model, App.
                        "Model architectures").  A state row ("state_dim" floats below) is
@@ -104,7 +114,8 @@ typedef struct {
   int32_t meas_hidden[SF_MAX_MEAS_LAYERS];
 } sf_policy_config;
 
-/* HOST pointers to fp32 parameters in canonical layouts; read during create only.
+/* HOST pointers to fp32 parameters in canonical layouts; read during create only.  Every
+ * value must be finite (SF_ERR_ARG otherwise).
  *   conv_w[i]: [cout][cin][k][k], conv_b[i]: [cout].  Residual encoder: per stage
  *              the stage convolution, then each block's two convolutions in order.
  *   fc_w: [fc_dim][flat], flat index = c*(Hf*Wf) + y*Wf + x of the encoder output.
@@ -145,6 +156,34 @@ typedef struct {
  * SF_ERR_ARCH, SF_ERR_OOM, SF_ERR_DEVICE; *out is then NULL. */
 int sf_policy_create(const sf_policy_config* cfg, const sf_policy_weights* weights,
                      int hip_device, sf_policy** out);
+
+/* Arithmetic of the first convolution (paper, App. "Model architectures": the convolutional
+ * encoder reads the pixel observation).  The pixels are bytes, so where the layer has the
+ * benchmark shape (8x8, stride 4, no padding, 32 channels, 1/3/4 input planes) it runs as an
+ * exact integer contraction on the int8 matrix cores against a fixed-point image of the
+ * normalisation-folded filter bank: per output channel one scale and three signed digits of
+ * radix 254 (two in a bf16 configuration), i.e. every tap carries the same absolute error,
+ * at most 2^-24 (2^-16) of the channel's largest tap.  Unlike floating point this loses
+ * relative accuracy on taps much smaller than the largest one.  The library therefore tests
+ * each bank when it packs it (create, and again at every weight update): with
+ *   E_fix = 128 * sum_k |W'[k] - fixed-point image of W'[k]|   (bound for every frame)
+ *   E_ref = sqrt(K) * 2^-24 * 255 * sum_k min(|W'[k]|, median non-zero |W'|)   (fp32;
+ *           2^-9 * 255 * sum_k min(...) in a bf16 configuration)
+ * the digit planes are used only if E_fix <= E_ref in every channel; otherwise an fp32
+ * network runs the layer on the fp32 matrix cores (about three times slower for that
+ * launch) and a bf16 network takes the third digit plane.  The decision depends on the
+ * parameter values only, never on the batch.  sf_policy_op_pipe tells which arithmetic a
+ * launch uses ("i8x3", "i8x2", "f32", "bf16", "f16", "valu"); ..._ratio returns the worst
+ * channel's E_fix / E_ref for 2 or 3 planes (0 if the layer has another shape, -1 for a
+ * null handle). */
+const char* sf_policy_op_pipe(const sf_policy* p, int i); /* static storage; "" if out of range */
+double sf_policy_conv1_fixed_point_ratio(const sf_policy* p, int planes);
+/* The same test on a filter bank alone, on the host (no device is touched): conv_w host
+ * [32][cin][8][8] fp32, cin 1, 3 or 4; dtype SF_DTYPE_FP32 or SF_DTYPE_BF16 (the taps are
+ * first rounded to bf16).  Writes the worst channel's E_fix / E_ref for two and for three
+ * digit planes.  Errors: SF_ERR_ARG. */
+int sf_conv1_fixed_point_test(const float* conv_w, int32_t cin, float obs_mul, int32_t dtype,
+                              double* ratio2, double* ratio3);
 
 /* One step of the policy worker (paper, Sec. 3.1) on B rows, enqueued
  * asynchronously on `hip_stream` (a hipStream_t; NULL = the default stream).
@@ -209,8 +248,15 @@ int sf_policy_step_indexed(sf_policy* p, int32_t B, const uint8_t* obs, const fl
  * parameters, steps enqueued after it the new ones, and no step sees a mixture.  Work on
  * other streams is not ordered against the update.  The first call allocates a page-locked
  * staging area of the size of the packed weights (kept until destroy); a later call first
- * waits for the previous update's copies.  Errors: SF_ERR_ARG (null handle or weight
- * pointer), SF_ERR_OOM (staging area), SF_ERR_DEVICE, SF_ERR_SHAPE (internal mismatch). */
+ * waits for the previous update's copies.  The whole set is packed and checked before the
+ * first copy is enqueued: after an error other than SF_ERR_DEVICE the policy still holds its
+ * previous parameters.  The kernels are those chosen at create (environment switches are not
+ * read again), with one exception: the first convolution's admission test (see
+ * sf_policy_op_pipe) is repeated on the new values, and later steps run the arithmetic it
+ * selects.  A HIP graph captured before the update keeps the kernel it recorded, which then
+ * reads the new bank of its own kind: capture again if the selection changed.
+ * Errors: SF_ERR_ARG (null handle or weight pointer), SF_ERR_OOM (staging area),
+ * SF_ERR_DEVICE, SF_ERR_SHAPE (internal mismatch). */
 int sf_policy_update_weights(sf_policy* p, const sf_policy_weights* weights, void* hip_stream);
 
 /* Floats per recurrent-state row of this policy: rnn_dim (GRU) or 2 * rnn_dim (LSTM). */

@@ -104,7 +104,8 @@ EXPORTS = ("sf_policy_create", "sf_policy_step", "sf_policy_destroy", "sf_last_e
            "sf_policy_op_flops_per_row", "sf_policy_set_op_timing", "sf_policy_last_op_times",
            "sf_copy_bytes", "sf_policy_step_indexed", "sf_pipeline_create", "sf_pipeline_submit",
            "sf_pipeline_wait", "sf_pipeline_destroy", "sf_policy_state_dim",
-           "sf_policy_update_weights", "sf_appo_loss", "sf_appo_loss_workspace_bytes")
+           "sf_policy_update_weights", "sf_appo_loss", "sf_appo_loss_workspace_bytes",
+           "sf_policy_op_pipe", "sf_policy_conv1_fixed_point_ratio", "sf_conv1_fixed_point_test")
 
 _lib = None
 
@@ -154,6 +155,13 @@ def load_library():
         L.sf_policy_op_name.argtypes = [C.c_void_p, C.c_int]
         L.sf_policy_op_flops_per_row.restype = C.c_int64
         L.sf_policy_op_flops_per_row.argtypes = [C.c_void_p, C.c_int]
+        L.sf_policy_op_pipe.restype = C.c_char_p
+        L.sf_policy_op_pipe.argtypes = [C.c_void_p, C.c_int]
+        L.sf_policy_conv1_fixed_point_ratio.restype = C.c_double
+        L.sf_policy_conv1_fixed_point_ratio.argtypes = [C.c_void_p, C.c_int]
+        L.sf_conv1_fixed_point_test.restype = C.c_int
+        L.sf_conv1_fixed_point_test.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int32,
+                                                C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.sf_policy_set_op_timing.restype = C.c_int
         L.sf_policy_set_op_timing.argtypes = [C.c_void_p, C.c_int]
         L.sf_policy_last_op_times.restype = C.c_int
@@ -233,6 +241,18 @@ def make_weights(w):
     for i, (mw, mb) in enumerate(zip(w.get("meas_w", []), w.get("meas_b", []))):
         s.meas_w[i], s.meas_b[i] = fp(mw), fp(mb)
     return s, keep
+
+
+def sf_conv1_fixed_point_test(conv_w, obs_mul, dtype="fp32"):
+    """conv_w: fp32 numpy [32, cin, 8, 8] (host).  Returns (ratio with 2 planes, with 3 planes)."""
+    a = np.ascontiguousarray(conv_w, dtype=np.float32)
+    assert a.shape[0] == 32 and a.shape[2:] == (8, 8)
+    r2, r3 = C.c_double(), C.c_double()
+    rc = load_library().sf_conv1_fixed_point_test(a.ctypes.data, a.shape[1], obs_mul,
+                                                  1 if dtype == "bf16" else 0, C.byref(r2), C.byref(r3))
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+    return r2.value, r3.value
 
 
 def sf_policy_create(cfg, weights, hip_device=0):
@@ -396,6 +416,16 @@ class Policy:
         return [(L.sf_policy_op_name(self.handle, i).decode(),
                  int(L.sf_policy_op_flops_per_row(self.handle, i)))
                 for i in range(L.sf_policy_op_count(self.handle))]
+
+    def op_pipes(self):
+        """The arithmetic of each launch: "i8x3", "i8x2", "f32", "bf16", "f16" or "valu"."""
+        L = load_library()
+        return [L.sf_policy_op_pipe(self.handle, i).decode()
+                for i in range(L.sf_policy_op_count(self.handle))]
+
+    def conv1_fixed_point_ratio(self, planes=3):
+        """Worst channel's error-bound ratio of the first convolution's digit planes (<= 1: admitted)."""
+        return float(load_library().sf_policy_conv1_fixed_point_ratio(self.handle, planes))
 
     def set_op_timing(self, enable):
         rc = load_library().sf_policy_set_op_timing(self.handle, int(bool(enable)))

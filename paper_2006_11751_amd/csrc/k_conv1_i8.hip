@@ -5,14 +5,19 @@
 //
 // The observation is bytes, so the convolution is an integer contraction in the
 // pixels.  Per output channel n the (normalisation-folded) filter W'[.][n] is
-// written in three signed base-128 digits with one scale,
-//   W'[k][n] ~= s_n * (d1[k][n] + d2[k][n] / 128 + d3[k][n] / 16384),   |d| <= 127,
-// (error <= 2^-15 * s_n per weight, i.e. 2.4e-7 of the largest weight of the
-// channel: the size of an fp32 rounding).  With x_s = byte - 128 (one XOR per four
-// pixels) the three sums S_i = sum_k x_s[k] * d_i[k][n] are exact int32 values from
-// v_mfma_i32_32x32x32_i8, which runs at 32x the rate of the fp32 MFMA and takes the
+// written in three signed digits of radix 254 with one scale s_n = max_k |W'[k][n]| / 127,
+//   W'[k][n] ~= s_n * (d1[k][n] + d2[k][n] / 254 + d3[k][n] / 254^2),   |d| <= 127
+// (each remainder lies in [-1/2, 1/2], so 254 is the largest radix whose next digit still
+// fits a signed byte).  This is fixed point, not floating point: every tap of a channel
+// carries the same ABSOLUTE error, at most s_n / (2 * 254^2) = 2^-24 of the channel's
+// largest tap, whatever the tap's own size.  A tap half as large as the largest is held as
+// well as fp32 holds it; a tap 1000 times smaller keeps 14 bits.  Whether that is good
+// enough is decided per filter bank when it is packed (conv1_i8_pack below); a bank that
+// fails the test runs on the fp32 MFMA kernel instead.  With x_s = byte - 128 (one XOR
+// per four pixels) the three sums S_i = sum_k x_s[k] * d_i[k][n] are exact int32 values
+// from v_mfma_i32_32x32x32_i8, which runs at 32x the rate of the fp32 MFMA and takes the
 // loaded frame words as operands without any conversion:
-//   out = relu(s_n * (S1 + S2/128 + S3/16384) + b''_n),
+//   out = relu(s_n * (S1 + S2/254 + S3/254^2) + b''_n),
 //   b''_n = b_n - sub*mul*sum_k W[k][n] + 128 * sum_k W'[k][n]   (exact W').
 //
 // v_mfma_i32_32x32x32_i8: lane l supplies 16 bytes A[i = l%32][k = 16*(l/32) + e] and
@@ -21,6 +26,9 @@
 // 8-byte runs of the frame.  A wave walks a contiguous run of (frame, output row, x chunk)
 // items, three register sets of frame bytes in rotation (loads two items ahead).
 #include <math.h>
+#include <string.h>
+
+#include <algorithm>
 
 #include "sf_internal.h"
 
@@ -42,16 +50,16 @@ struct __attribute__((packed, aligned(4))) U2 {
   uint32_t x, y;
 };
 
-template <int CIN, bool OUT_BF16>
+constexpr float kInvRadix = 1.0f / 254.0f;
+constexpr float kInvRadix2 = 1.0f / 64516.0f;
+
+// ND: digit planes used (2 or 3; the packed bank always holds three).
+template <int CIN, bool OUT_BF16, int ND>
 __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_kernel(
     const uint8_t* __restrict__ obs, const int* __restrict__ wpk, const float* __restrict__ scale,
     const float* __restrict__ bias, void* __restrict__ out_v, int H, int W, int Ho, int Wo,
     int n_xchunks, long long n_items, int n_waves_total) {
   constexpr int NSTEP = CIN * kK / 4;  // MFMA K steps (32 bytes each)
-  // Digit planes used.  A bf16 configuration's weights carry 8 significant bits, so two
-  // base-128 digits (error <= 2^-15 of the channel's largest weight) are more than its
-  // tolerance asks for, and a third of the MFMAs and of the epilogue goes away.
-  constexpr int ND = OUT_BF16 ? 2 : 3;
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWaves + (threadIdx.x >> 6);
   const int n = lane & 31;
@@ -171,17 +179,17 @@ __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_k
       s2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, wd[s][1], s2, 0, 0, 0);
       if constexpr (ND == 3) s3 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, wd[s][2], s3, 0, 0, 0);
     }
-    // epilogue.  D[i][j]: j = n, i = (v%4) + 4h + 8(v/4).  S2*128 + S3 fits int32
-    // (|S2|, |S3| <= 192*128*64); its float image is exact to 6e-8 relative.
+    // epilogue.  D[i][j]: j = n, i = (v%4) + 4h + 8(v/4).  S2*254 + S3 fits int32
+    // (|S2|, |S3| <= 256*128*127 = 4.2e6); its float image is exact to 6e-8 relative.
     float r[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       float q;
       if constexpr (ND == 3) {
-        const float lo = (float)(s2[v] * 128 + s3[v]);
-        q = fmaf(lo, 0x1.0p-14f, (float)s1[v]);
+        const float lo = (float)(s2[v] * 254 + s3[v]);
+        q = fmaf(lo, kInvRadix2, (float)s1[v]);
       } else {
-        q = fmaf((float)s2[v], 0x1.0p-7f, (float)s1[v]);
+        q = fmaf((float)s2[v], kInvRadix, (float)s1[v]);
       }
       r[v] = fmaxf(fmaf(q, s_n, b_n), 0.0f);
     }
@@ -243,12 +251,11 @@ __global__ __launch_bounds__(64 * kWaves, (CIN <= 3 ? 2 : 1)) void conv1_u8_i8_k
 // above (same bits).  One x chunk (Wo <= 32) and 16-byte aligned frames only.
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-template <int CIN, bool OUT_BF16>
+template <int CIN, bool OUT_BF16, int ND>
 __global__ __launch_bounds__(64 * kWaves, 2) void conv1_u8_i8_image_kernel(
     const uint8_t* __restrict__ obs, const int* __restrict__ wpk, const float* __restrict__ scale,
     const float* __restrict__ bias, void* __restrict__ out_v, int B, int H, int W, int Ho, int Wo) {
   constexpr int NSTEP = CIN * kK / 4;
-  constexpr int ND = OUT_BF16 ? 2 : 3;
   constexpr int NV = 7;  // 16-byte pieces per thread: frames up to 7 * 256 * 16 = 28672 bytes
   constexpr int NT = 64 * kWaves;
   extern __shared__ __attribute__((aligned(16))) uint8_t frame_lds[];
@@ -329,10 +336,10 @@ __global__ __launch_bounds__(64 * kWaves, 2) void conv1_u8_i8_image_kernel(
     for (int v = 0; v < 16; ++v) {
       float q;
       if constexpr (ND == 3) {
-        const float lo = (float)(s2[v] * 128 + s3[v]);
-        q = fmaf(lo, 0x1.0p-14f, (float)s1[v]);
+        const float lo = (float)(s2[v] * 254 + s3[v]);
+        q = fmaf(lo, kInvRadix2, (float)s1[v]);
       } else {
-        q = fmaf((float)s2[v], 0x1.0p-7f, (float)s1[v]);
+        q = fmaf((float)s2[v], kInvRadix, (float)s1[v]);
       }
       r[v] = fmaxf(fmaf(q, s_n, b_n), 0.0f);
     }
@@ -387,46 +394,92 @@ bool conv1_i8_supported(const ConvLayer& L) {
          (L.cin == 3 || L.cin == 1 || L.cin == 4) && L.relu_out == 1 && !L.add_residual;
 }
 
-// Digit planes, scales and bias for the kernel above.
+// Digit planes, scales and bias for the kernels above, and the test that decides whether
+// the fixed-point bank may stand in for floating-point weights.
 // wpk[((s*3 + d)*4 + w)*64 + lane]: bytes e = 4w..4w+3 of the lane's operand for K step s
 // and digit d; byte e belongs to group g = 4s + 2*(lane/32) + e/8 = (channel g/8, filter
 // row g%8), filter column e%8, output channel lane%32.
+//
+// The test, per output channel, in fp64 on the packed digits themselves.  The kernel's
+// result differs from the exact one by sum_k x_s[k] * (W'[k] - What[k]) with |x_s| <= 128, so
+//   E_fix = 128 * sum_k |W'[k] - What[k]|
+// bounds its error for every frame.  It is held against the error of the floating-point
+// path the bank replaces, for a full-scale frame, with every tap counted at no more than
+// the channel's median non-zero tap m (so that a few dominant taps cannot buy slack for the
+// many small ones, whose terms are what is left of the output when the dominant taps sit on
+// dark pixels):
+//   fp32 bank, three planes: E_ref = sqrt(K) * 2^-24 * 255 * sum_k min(|W'[k]|, m)
+//                            (random-walk estimate of K roundings of an fp32 accumulation)
+//   bf16 bank, two planes:   E_ref = 2^-9 * 255 * sum_k min(|W'[k]|, m)
+//                            (the rounding to bf16 that the configuration applies to the
+//                            same taps)
+// ratio = max over channels of E_fix / E_ref; the bank is admitted when ratio <= 1.  Gaussian
+// filters give about 0.1 (three planes); a filter with one tap 1000 times the others about 45.
 void conv1_i8_pack(const float* w, const float* bias, int cin, float obs_sub, float obs_mul,
-                   std::vector<int>& wpk, std::vector<float>& scale, std::vector<float>& bpk) {
+                   bool bf16_weights, std::vector<int>& wpk, std::vector<float>& scale,
+                   std::vector<float>& bpk, Conv1I8Info* info) {
   const int K = cin * kK * kK;
   const int nstep = cin * kK / 4;
   wpk.assign((size_t)nstep * 3 * 4 * 64, 0);
   scale.assign(kCout, 1.0f);
   bpk.assign(kCout, 0.0f);
   std::vector<signed char> dig((size_t)kCout * K * 3);
+  std::vector<double> wm(K), mag(K);
+  double worst2 = 0.0, worst3 = 0.0;
+  // a bf16 configuration defines its parameters as the nearest bf16 values (ties to even)
+  auto param = [&](float v) -> double {
+    if (bf16_weights) {
+      uint32_t u;
+      memcpy(&u, &v, 4);
+      if ((u & 0x7F800000u) != 0x7F800000u) u = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
+      memcpy(&v, &u, 4);
+    }
+    return (double)v;
+  };
+  auto tap = [&](int n, int i) -> double { return param(w[(size_t)n * K + i]); };
+  auto clamp_digit = [](double d) { return d > 127 ? 127.0 : (d < -127 ? -127.0 : d); };
   for (int n = 0; n < kCout; ++n) {
     double mx = 0.0, sum_w = 0.0, sum_wm = 0.0;
     for (int i = 0; i < K; ++i) {
-      double wm = (double)obs_mul * (double)w[(size_t)n * K + i];
-      mx = fmax(mx, fabs(wm));
-      sum_w += (double)w[(size_t)n * K + i];
-      sum_wm += wm;
+      const double wi = tap(n, i);
+      wm[i] = (double)obs_mul * wi;
+      mx = fmax(mx, fabs(wm[i]));
+      sum_w += wi;
+      sum_wm += wm[i];
     }
     const float sf = mx > 0.0 ? (float)(mx / 127.0) : 1.0f;  // the kernel multiplies by this fp32 value
     const double s = (double)sf;
+    double res2 = 0.0, res3 = 0.0;
+    int nz = 0;
     for (int i = 0; i < K; ++i) {
-      double q = (double)obs_mul * (double)w[(size_t)n * K + i] / s;
-      double d1 = nearbyint(q);
-      if (d1 > 127) d1 = 127;
-      if (d1 < -127) d1 = -127;
-      double r = (q - d1) * 128.0;
-      double d2 = nearbyint(r);
-      if (d2 > 127) d2 = 127;
-      if (d2 < -127) d2 = -127;
-      double d3 = nearbyint((r - d2) * 128.0);
-      if (d3 > 127) d3 = 127;
-      if (d3 < -127) d3 = -127;
+      const double q = wm[i] / s;
+      const double d1 = clamp_digit(nearbyint(q));
+      const double r = (q - d1) * 254.0;
+      const double d2 = clamp_digit(nearbyint(r));
+      const double d3 = clamp_digit(nearbyint((r - d2) * 254.0));
       dig[((size_t)n * K + i) * 3 + 0] = (signed char)d1;
       dig[((size_t)n * K + i) * 3 + 1] = (signed char)d2;
       dig[((size_t)n * K + i) * 3 + 2] = (signed char)d3;
+      res2 += fabs(wm[i] - s * (d1 + d2 / 254.0));
+      res3 += fabs(wm[i] - s * (d1 + d2 / 254.0 + d3 / 64516.0));
+      if (wm[i] != 0.0) mag[nz++] = fabs(wm[i]);
+    }
+    if (nz > 0) {
+      std::nth_element(mag.begin(), mag.begin() + (nz - 1) / 2, mag.begin() + nz);
+      const double m = mag[(nz - 1) / 2];
+      double l1 = 0.0;
+      for (int i = 0; i < K; ++i) l1 += fmin(fabs(wm[i]), m);
+      const double ref3 = sqrt((double)K) * 0x1.0p-24 * 255.0 * l1;
+      const double ref2 = 0x1.0p-9 * 255.0 * l1;
+      worst3 = fmax(worst3, 128.0 * res3 / ref3);
+      worst2 = fmax(worst2, 128.0 * res2 / ref2);
     }
     scale[n] = sf;
-    bpk[n] = (float)((double)bias[n] - (double)obs_sub * (double)obs_mul * sum_w + 128.0 * sum_wm);
+    bpk[n] = (float)(param(bias[n]) - (double)obs_sub * (double)obs_mul * sum_w + 128.0 * sum_wm);
+  }
+  if (info) {
+    info->ratio2 = worst2;
+    info->ratio3 = worst3;
   }
   for (int s = 0; s < nstep; ++s)
     for (int d = 0; d < 3; ++d)
@@ -447,8 +500,9 @@ void conv1_i8_pack(const float* w, const float* bias, int cin, float obs_sub, fl
 
 hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const int* wpk,
                            const float* scale, const float* bpk, void* out, int out_bf16,
-                           int waves_hint, int image, hipStream_t st) {
+                           int planes, int waves_hint, int image, hipStream_t st) {
   if (B == 0) return hipSuccess;
+  if (planes != 2 && planes != 3) return hipErrorInvalidValue;
   const int n_xchunks = (L.Wo + 31) / 32;
   const int frame_bytes = L.cin * L.H * L.W;
   // The frame-resident variant pays from four frames per workgroup on (measured on MI355X:
@@ -459,16 +513,14 @@ hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const 
     // two workgroups per CU, each walking its share of the frames
     const int blocks = B < 512 ? B : 512;
     const size_t lds = (size_t)frame_bytes;
-#define SF_LAUNCH_IMG(C)                                                                       \
-  do {                                                                                         \
-    if (out_bf16)                                                                              \
-      conv1_u8_i8_image_kernel<C, true><<<blocks, 64 * kWaves, lds, st>>>(                     \
-          obs, wpk, scale, bpk, out, B, L.H, L.W, L.Ho, L.Wo);                                 \
-    else                                                                                       \
-      conv1_u8_i8_image_kernel<C, false><<<blocks, 64 * kWaves, lds, st>>>(                    \
-          obs, wpk, scale, bpk, out, B, L.H, L.W, L.Ho, L.Wo);                                 \
-  } while (0)
-    SF_LAUNCH_IMG(3);
+#define SF_LAUNCH_IMG(BF, ND)                                            \
+  conv1_u8_i8_image_kernel<3, BF, ND><<<blocks, 64 * kWaves, lds, st>>>( \
+      obs, wpk, scale, bpk, out, B, L.H, L.W, L.Ho, L.Wo)
+    if (out_bf16) {
+      if (planes == 2) SF_LAUNCH_IMG(true, 2); else SF_LAUNCH_IMG(true, 3);
+    } else {
+      if (planes == 2) SF_LAUNCH_IMG(false, 2); else SF_LAUNCH_IMG(false, 3);
+    }
 #undef SF_LAUNCH_IMG
     return hipGetLastError();
   }
@@ -477,14 +529,16 @@ hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const 
   if (waves > n_items) waves = n_items;
   const int blocks = (int)((waves + kWaves - 1) / kWaves);
   const int n_waves_total = blocks * kWaves;
-#define SF_LAUNCH_CIN(C)                                                                         \
-  do {                                                                                           \
-    if (out_bf16)                                                                                \
-      conv1_u8_i8_kernel<C, true><<<blocks, 64 * kWaves, 0, st>>>(                               \
-          obs, wpk, scale, bpk, out, L.H, L.W, L.Ho, L.Wo, n_xchunks, n_items, n_waves_total);   \
-    else                                                                                         \
-      conv1_u8_i8_kernel<C, false><<<blocks, 64 * kWaves, 0, st>>>(                              \
-          obs, wpk, scale, bpk, out, L.H, L.W, L.Ho, L.Wo, n_xchunks, n_items, n_waves_total);   \
+#define SF_LAUNCH_K(C, BF, ND)                                      \
+  conv1_u8_i8_kernel<C, BF, ND><<<blocks, 64 * kWaves, 0, st>>>(    \
+      obs, wpk, scale, bpk, out, L.H, L.W, L.Ho, L.Wo, n_xchunks, n_items, n_waves_total)
+#define SF_LAUNCH_CIN(C)                                                      \
+  do {                                                                        \
+    if (out_bf16) {                                                           \
+      if (planes == 2) SF_LAUNCH_K(C, true, 2); else SF_LAUNCH_K(C, true, 3); \
+    } else {                                                                  \
+      if (planes == 2) SF_LAUNCH_K(C, false, 2); else SF_LAUNCH_K(C, false, 3); \
+    }                                                                         \
   } while (0)
   switch (L.cin) {
     case 1: SF_LAUNCH_CIN(1); break;
@@ -493,6 +547,7 @@ hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const 
     default: return hipErrorInvalidValue;
   }
 #undef SF_LAUNCH_CIN
+#undef SF_LAUNCH_K
   return hipGetLastError();
 }
 

@@ -21,6 +21,8 @@
 // tiles are summed through LDS in a fixed order.
 #include <stdlib.h>
 
+#include <mutex>
+
 #include <type_traits>
 
 #include "sf_internal.h"
@@ -299,13 +301,13 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
   size_t red = WK > 1 ? sizeof(float) * WM * WN * TM * TN * 16 * 64 : 0;
   if (red > lds) lds = red;
   auto kern = gemm_mfma_kernel<BM, BN, BK, WM, WN, WK, TAG, PIPE>;
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::once_flag attr_once;  // per instantiation
+  static hipError_t attr_status = hipSuccess;
+  std::call_once(attr_once, [&] {
+    attr_status = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)lds);
+  });
+  if (attr_status != hipSuccess) return attr_status;
   const int n_tiles = ((g.M + BM - 1) / BM) * (g.N / BN);
   const int per_xcd = (n_tiles + 7) / 8;
   kern<<<per_xcd * 8, 64 * WM * WN * WK, lds, st>>>(g);

@@ -1,5 +1,6 @@
 // C ABI of the sf_policy library: validation, weight packing, workspace and the
 // launch sequence of one policy step (see include/sf_policy.h for the contract).
+#include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -33,15 +34,31 @@ float bf16_round(float v) {
 
 // Allocates and fills the device buffers of a policy.  In replay mode (a weight update)
 // nothing is allocated: the k-th request returns the k-th buffer of `target`, whose size
-// must match, and uploads become asynchronous copies on `stream` out of `target`'s
-// page-locked staging area.
+// must match, and an upload only writes the packed values into `target`'s page-locked
+// staging area and notes the copy; flush() enqueues the noted copies once the whole plan has
+// been packed and checked, so that a failure on the way leaves the live weights untouched.
 struct Builder {
   Policy* p;
   bool bf16;
   int status = SF_OK;
   Policy* target = nullptr;  // replay: the live policy whose buffers are refilled
-  hipStream_t stream = nullptr;
   size_t next = 0, stage_off = 0;
+  struct Copy {
+    void* dst;
+    size_t off, bytes;
+  };
+  std::vector<Copy> copies;
+
+  int flush(hipStream_t stream) {
+    for (const Copy& c : copies) {
+      hipError_t e = hipMemcpyAsync(c.dst, target->stage + c.off, c.bytes, hipMemcpyHostToDevice, stream);
+      if (e != hipSuccess) {
+        set_error("weight update: hipMemcpyAsync failed: %s", hipGetErrorString(e));
+        return SF_ERR_DEVICE;
+      }
+    }
+    return SF_OK;
+  }
 
   void* dev_alloc(size_t bytes) {
     if (bytes == 0) bytes = 4;
@@ -72,21 +89,22 @@ struct Builder {
     T* d = (T*)dev_alloc(host.size() * sizeof(T));
     if (!d) return nullptr;
     const size_t n = host.size() * sizeof(T);
-    hipError_t e;
     if (target) {
       const size_t off = (stage_off + 15) & ~(size_t)15;
       if (off + n > target->stage_bytes) {
-        set_error("weight update: staging area too small");
-        status = SF_ERR_SHAPE;
+        if (status == SF_OK) {
+          set_error("weight update: staging area too small");
+          status = SF_ERR_SHAPE;
+        }
         return nullptr;
       }
       memcpy(target->stage + off, host.data(), n);
       stage_off = off + n;
-      e = hipMemcpyAsync(d, target->stage + off, n, hipMemcpyHostToDevice, stream);
-    } else {
-      p->upload_bytes += n + 16;
-      e = hipMemcpy(d, host.data(), n, hipMemcpyHostToDevice);
+      copies.push_back(Copy{d, off, n});
+      return d;
     }
+    p->upload_bytes += n + 16;
+    hipError_t e = hipMemcpy(d, host.data(), n, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
       set_error("hipMemcpy to device failed: %s", hipGetErrorString(e));
       status = SF_ERR_DEVICE;
@@ -218,6 +236,36 @@ int check_config(const sf_policy_config* c, int* Cf, int* Hf, int* Wf) {
   return SF_OK;
 }
 
+bool env_set(const char* name) { return getenv(name) != nullptr; }
+int env_int(const char* name) {
+  const char* v = getenv(name);
+  return v ? atoi(v) : 0;
+}
+
+// The only place the environment is read.
+Switches read_switches() {
+  Switches sw;
+  sw.force_generic = env_set("SF_FORCE_GENERIC");
+  const char* c1 = getenv("SF_CONV1");
+  sw.conv1 = !c1 ? 0 : (!strcmp(c1, "fp32") ? 1 : (!strcmp(c1, "i8") ? 2 : 0));
+  sw.conv1_waves = env_int("SF_CONV1_WAVES");
+  sw.gemm_tile = env_int("SF_GEMM_TILE");
+  sw.fc_tile = env_int("SF_FC_TILE");
+  sw.gru_bm = env_int("SF_GRU_BM");
+  sw.no_rnn_pairs = env_set("SF_NO_RNN_PAIRS");
+  sw.no_bf16_path = env_set("SF_NO_BF16_PATH");
+  sw.no_rnn_bf16 = env_set("SF_NO_RNN_BF16");
+  sw.conv_bf16_tc = env_int("SF_CONV_BF16_TC");
+  sw.no_conv1_image = env_set("SF_NO_CONV1_IMAGE");
+  sw.no_conv_image = env_set("SF_NO_CONV_IMAGE");
+  sw.fc_out_f32 = env_set("SF_FC_OUT_F32");
+  sw.no_patch_conv = env_set("SF_NO_PATCH_CONV");
+  sw.no_fused_resnet = env_set("SF_NO_FUSED_RESNET");
+  sw.act_bf16 = env_set("SF_ACT_BF16");
+  sw.stream_f32 = env_set("SF_STREAM_F32");
+  return sw;
+}
+
 void free_policy(Policy* p) {
   if (!p) return;
   for (void* d : p->allocations) (void)hipFree(d);
@@ -235,22 +283,25 @@ using namespace sf;
 
 namespace {
 
-// Chooses the kernels, packs the weights and sizes the workspace of `p` for `cfg`.  Shared by
-// create (bld allocates) and by a weight update (bld replays into the live policy's buffers;
-// `p` is then a scratch object whose plan and pointers come out identical).
+// Chooses the kernels, packs the weights and sizes the workspace of `p` for `cfg` under the
+// switches in p->sw.  Shared by create (bld allocates) and by a weight update (bld replays into
+// the live policy's buffers; `p` is then a scratch object whose plan and pointers come out
+// identical).  The sequence of buffer requests depends on the description and the switches
+// only, never on the parameter values.
 int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights* w, Builder& bld,
                  int Cf, int Hf, int Wf) {
+  const Switches& sw = p->sw;
   p->cfg = *cfg;
   p->flat = Cf * Hf * Wf;
-  p->conv1_waves = getenv("SF_CONV1_WAVES") ? atoi(getenv("SF_CONV1_WAVES")) : 0;
-  p->conv_bf16_tc = getenv("SF_CONV_BF16_TC") ? atoi(getenv("SF_CONV_BF16_TC")) : 0;
-  p->conv1_image = getenv("SF_NO_CONV1_IMAGE") ? 0 : 1;
+  p->conv1_waves = sw.conv1_waves;
+  p->conv_bf16_tc = sw.conv_bf16_tc;
+  p->conv1_image = sw.no_conv1_image ? 0 : 1;
 
   // bf16 configurations run the encoder and the FC layer on the bf16 kernels with bf16
   // activations, provided every layer has a shape those kernels take; otherwise the
   // fp32 kernels run on the (bf16-rounded) weights.
   p->bf16_path = false;
-  if (cfg->dtype == SF_DTYPE_BF16 && !getenv("SF_FORCE_GENERIC") && !getenv("SF_NO_BF16_PATH")) {
+  if (cfg->dtype == SF_DTYPE_BF16 && !sw.force_generic && !sw.no_bf16_path) {
     bool ok = (p->flat % 8) == 0 && (cfg->fc_dim % 4) == 0;
     if (cfg->encoder == SF_ENCODER_CONV) {
       ConvLayer L0{};
@@ -271,11 +322,11 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
   // The residual encoder is 15 convolutions deep: with 8-bit significands the rounding of
   // the activations alone exceeds the 2e-2 tolerance in the tails, so its 16-bit
   // activations are fp16 (the weights stay bf16 values, exactly representable in fp16).
-  p->act_f16 = p->bf16_path && cfg->encoder == SF_ENCODER_RESNET && !getenv("SF_ACT_BF16");
+  p->act_f16 = p->bf16_path && cfg->encoder == SF_ENCODER_RESNET && !sw.act_bf16;
   // With bf16 activations the residual stream is kept in fp32 so that its rounding does not
   // accumulate over the blocks; with fp16 activations that is not needed.
   p->stream_f32 = p->bf16_path && cfg->encoder == SF_ENCODER_RESNET &&
-                  (!p->act_f16 || getenv("SF_STREAM_F32"));
+                  (!p->act_f16 || sw.stream_f32);
 
   // ---- encoder plan ----
   size_t act_elems = 0;
@@ -292,20 +343,24 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
       L.Wo = (W + 2 * pad - k) / s + 1;
       L.w_khwc_o = nullptr;  // packed below if the shape-agnostic kernel runs this layer
       L.bias = bld.pack_vec(w->conv_b[ti], cout);
+      // the bias as the configuration defines it (rounded to bf16 in a bf16 configuration),
+      // for the packers that keep their own copy
+      std::vector<float> qb(cout);
+      for (int o = 0; o < cout; ++o) qb[o] = bld.q(w->conv_b[ti][o]);
       L.relu_in = relu_in; L.relu_out = relu_out; L.add_residual = resid_buf >= 0;
       L.impl = CONV_GENERIC;
-      const bool allow_mfma = !getenv("SF_FORCE_GENERIC") && !p->bf16_path;
+      const bool allow_mfma = !sw.force_generic && !p->bf16_path;
       if (p->bf16_path) {
         if (in_buf >= 0) {
           std::vector<uint16_t> wt;
           std::vector<float> bb;
-          conv_bf16_pack(w->conv_w[ti], w->conv_b[ti], cout, C, k, p->act_f16, wt, bb, &L.Kpad);
+          conv_bf16_pack(w->conv_w[ti], qb.data(), cout, C, k, p->act_f16, wt, bb, &L.Kpad);
           L.wbf = bld.upload(wt);
           L.bbf = bld.upload(bb);
           L.impl = CONV_BF16;
           if (cfg->encoder == SF_ENCODER_RESNET && conv3x3_patch_supported(C, cout, k, s, pad) &&
-              !getenv("SF_NO_PATCH_CONV")) {
-            conv3x3_patch_pack(w->conv_w[ti], w->conv_b[ti], cout, C, p->act_f16, wt, bb);
+              !sw.no_patch_conv) {
+            conv3x3_patch_pack(w->conv_w[ti], qb.data(), cout, C, p->act_f16, wt, bb);
             L.wbf = bld.upload(wt);
             L.bbf = bld.upload(bb);
             L.impl = CONV3X3_PATCH;
@@ -317,20 +372,27 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
           L.in_f32 = resnet && !(relu_in == 0 && resid_buf >= 0);  // conv_b reads the bf16 branch
           L.out_f32 = resnet && resid_buf >= 0;
           if (cfg->encoder == SF_ENCODER_CONV && !p->act_f16 && !relu_in && resid_buf < 0 &&
-              !getenv("SF_NO_CONV_IMAGE") &&
+              !sw.no_conv_image &&
               conv_image_bf16_supported(C, k, s, pad, H, W, L.Ho, L.Wo, cout)) {
             conv_image_bf16_pack(w->conv_w[ti], cout, C, k, wt);
             L.wbf = bld.upload(wt);
             L.impl = CONV_IMAGE_BF16;
           }
         } else if (cfg->encoder == SF_ENCODER_CONV) {
+          // bf16 parameters carry 8 significant bits: two digit planes as a rule, the third
+          // where the admission test asks for it
           std::vector<int> ipk;
           std::vector<float> spk, bpk;
-          conv1_i8_pack(w->conv_w[ti], w->conv_b[ti], C, cfg->obs_sub, cfg->obs_mul, ipk, spk, bpk);
+          Conv1I8Info info;
+          conv1_i8_pack(w->conv_w[ti], w->conv_b[ti], C, cfg->obs_sub, cfg->obs_mul, true, ipk, spk, bpk,
+                        &info);
           L.ipk = bld.upload(ipk);
           L.spk = bld.upload(spk);
-          L.bpk = bld.upload(bpk);
+          L.bpk8 = bld.upload(bpk);
           L.impl = CONV1_U8_I8;
+          L.planes = (sw.conv1 == 2 || info.ratio2 <= 1.0) ? 2 : 3;
+          p->conv1_ratio2 = info.ratio2;
+          p->conv1_ratio3 = info.ratio3;
         } else {
           std::vector<float> t((size_t)C * 9 * cout);  // [c][p][q][cout]
           for (int o = 0; o < cout; ++o)
@@ -341,10 +403,10 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
                       bld.q(w->conv_w[ti][(((size_t)o * C + c2) * 3 + a) * 3 + b2]);
           L.w_cpqo = bld.upload(t);
           L.impl = CONV3X3_U8_BF16;
-          if (conv3x3_stem_supported(C, cout) && !getenv("SF_NO_PATCH_CONV")) {
+          if (conv3x3_stem_supported(C, cout) && !sw.no_patch_conv) {
             std::vector<uint16_t> wt;
             std::vector<float> bb;
-            conv3x3_stem_pack(w->conv_w[ti], w->conv_b[ti], cout, p->act_f16, wt, bb);
+            conv3x3_stem_pack(w->conv_w[ti], qb.data(), cout, p->act_f16, wt, bb);
             L.wbf = bld.upload(wt);
             L.bbf = bld.upload(bb);
             L.impl = CONV3X3_STEM;
@@ -364,25 +426,31 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
         L.wpk = bld.upload(t);
         L.bpk = L.bias;
         L.impl = CONV_GEMM_MFMA;
-        const char* th = getenv("SF_GEMM_TILE");
-        L.tile = th ? atoi(th) : gemm_mfma_pick_tile((long long)cfg->max_batch * L.Ho * L.Wo, cout,
-                                                         k * k * C, k * C);
+        L.tile = sw.gemm_tile > 0 ? sw.gemm_tile
+                                  : gemm_mfma_pick_tile((long long)cfg->max_batch * L.Ho * L.Wo, cout,
+                                                        k * k * C, k * C);
       }
-      const char* c1 = getenv("SF_CONV1");  // "fp32": the fp32-MFMA variant of the first convolution
-      if (in_buf < 0 && allow_mfma && conv1_i8_supported(L) && !(c1 && !strcmp(c1, "fp32"))) {
+      if (in_buf < 0 && allow_mfma && conv1_i8_supported(L) && conv1_mfma_supported(L)) {
+        // First convolution of an fp32 network: three int8 digit planes of the folded filter
+        // bank where that fixed-point image passes its admission test, the fp32 MFMA kernel
+        // otherwise.  Both banks are packed and uploaded, because the answer depends on the
+        // parameter values and a weight update may change it.
         std::vector<int> ipk;
-        std::vector<float> spk, bpk;
-        conv1_i8_pack(w->conv_w[ti], w->conv_b[ti], C, cfg->obs_sub, cfg->obs_mul, ipk, spk, bpk);
+        std::vector<float> spk, bpk8, wpk, bpk;
+        Conv1I8Info info;
+        conv1_i8_pack(w->conv_w[ti], w->conv_b[ti], C, cfg->obs_sub, cfg->obs_mul, false, ipk, spk, bpk8,
+                      &info);
+        conv1_mfma_pack(w->conv_w[ti], w->conv_b[ti], C, cfg->obs_sub, cfg->obs_mul, wpk, bpk);
         L.ipk = bld.upload(ipk);
         L.spk = bld.upload(spk);
-        L.bpk = bld.upload(bpk);
-        L.impl = CONV1_U8_I8;
-      } else if (in_buf < 0 && allow_mfma && conv1_mfma_supported(L)) {
-        std::vector<float> wpk, bpk;
-        conv1_mfma_pack(w->conv_w[ti], w->conv_b[ti], C, cfg->obs_sub, cfg->obs_mul, wpk, bpk);
+        L.bpk8 = bld.upload(bpk8);
         L.wpk = bld.upload(wpk);
         L.bpk = bld.upload(bpk);
-        L.impl = CONV1_U8_MFMA;
+        L.planes = 3;
+        const bool digits = sw.conv1 == 2 || (sw.conv1 == 0 && info.ratio3 <= 1.0);
+        L.impl = digits ? CONV1_U8_I8 : CONV1_U8_MFMA;
+        p->conv1_ratio2 = info.ratio2;
+        p->conv1_ratio3 = info.ratio3;
       }
       if (L.impl == CONV_GENERIC) L.w_khwc_o = bld.pack_conv(w->conv_w[ti], cout, C, k);
       ++ti;
@@ -412,8 +480,8 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
       int in_buf = -1;
       // With fp16 activations throughout, a stage convolution and its max-pool run as one
       // kernel, and so does each residual block.
-      const bool fuse = p->bf16_path && p->act_f16 && !p->stream_f32 && !getenv("SF_NO_PATCH_CONV") &&
-                        !getenv("SF_NO_FUSED_RESNET");
+      const bool fuse = p->bf16_path && p->act_f16 && !p->stream_f32 && !sw.no_patch_conv &&
+                        !sw.no_fused_resnet;
       for (int s = 0; s < cfg->n_stage; ++s) {
         if (fuse && conv3x3_pool_supported(C, cfg->stage_ch[s], W)) {
           const int Hin = H, Win = W;
@@ -500,12 +568,12 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
     p->fc_b = bld.pack_vec(w->fc_b, cfg->fc_dim);
     p->fc_wt = nullptr;
     p->fc_w_t = nullptr;
-    const bool fc_mfma = !getenv("SF_FORCE_GENERIC") && !p->bf16_path &&
+    const bool fc_mfma = !sw.force_generic && !p->bf16_path &&
                          gemm_mfma_supported(p->flat, 1, 0, cfg->fc_dim);
     if (fc_mfma) {
       p->fc_wt = bld.upload(u);
-      const char* th = getenv("SF_FC_TILE");
-      p->fc_tile = th ? atoi(th) : gemm_mfma_pick_tile(cfg->max_batch, cfg->fc_dim, p->flat, p->flat);
+      p->fc_tile = sw.fc_tile > 0 ? sw.fc_tile
+                                  : gemm_mfma_pick_tile(cfg->max_batch, cfg->fc_dim, p->flat, p->flat);
     } else if (!p->bf16_path) {
       // the shape-agnostic kernel reads the transposed matrix [flat][fc]
       std::vector<float> t((size_t)p->flat * cfg->fc_dim);
@@ -559,7 +627,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
   p->gru_wih_t = p->gru_whh_t = nullptr;
   p->gru_wih = p->gru_whh = nullptr;
   p->rnn_wih_bf = p->rnn_whh_bf = nullptr;
-  if (cfg->dtype == SF_DTYPE_BF16 && !getenv("SF_FORCE_GENERIC") && !getenv("SF_NO_RNN_BF16") &&
+  if (cfg->dtype == SF_DTYPE_BF16 && !sw.force_generic && !sw.no_rnn_bf16 &&
       rnn_bf16_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
     // bf16 configuration: gate GEMMs on the 16-bit MFMA, state split into two bf16 terms
     std::vector<uint16_t> t;
@@ -570,15 +638,15 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
     // The FC kernel can hand its output over as bf16 (the rounding this kernel would apply
     // while staging it): half the bytes for every unit tile that re-reads the rows.  Not with a
     // second input (fp32) and not where the 16-bit activations are fp16.
-    p->fc_out_bf16 = p->fc_wbf && !p->act_f16 && p->meas_out_dim == 0 && !getenv("SF_FC_OUT_F32");
-  } else if (getenv("SF_FORCE_GENERIC") || !rnn_mfma_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
+    p->fc_out_bf16 = p->fc_wbf && !p->act_f16 && p->meas_out_dim == 0 && !sw.fc_out_f32;
+  } else if (sw.force_generic || !rnn_mfma_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
     p->gru_wih_t = bld.pack_transposed(w->rnn_w_ih, HG, core_in);
     p->gru_whh_t = bld.pack_transposed(w->rnn_w_hh, HG, cfg->rnn_dim);
   } else {
     p->gru_wih = bld.pack_vec(w->rnn_w_ih, (size_t)HG * core_in);
     p->gru_whh = bld.pack_vec(w->rnn_w_hh, (size_t)HG * cfg->rnn_dim);
-    p->gru_bm = getenv("SF_GRU_BM") ? atoi(getenv("SF_GRU_BM")) : rnn_mfma_pick_bm(cfg->max_batch, cfg->rnn_dim);
-    p->rnn_plain_loops = getenv("SF_NO_RNN_PAIRS") ? 0 : 1;
+    p->gru_bm = sw.gru_bm > 0 ? sw.gru_bm : rnn_mfma_pick_bm(cfg->max_batch, cfg->rnn_dim);
+    p->rnn_plain_loops = sw.no_rnn_pairs ? 0 : 1;
   }
   p->gru_bih = bld.pack_vec(w->rnn_b_ih, HG);
   p->gru_bhh = bld.pack_vec(w->rnn_b_hh, HG);
@@ -625,6 +693,84 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
   return bld.status;
 }
 
+// First non-finite value of a tensor, or -1.
+long long first_non_finite(const float* v, size_t n) {
+  for (size_t i = 0; i < n; ++i) {
+    uint32_t u;
+    memcpy(&u, &v[i], 4);
+    if ((u & 0x7F800000u) == 0x7F800000u) return (long long)i;
+  }
+  return -1;
+}
+
+// Every parameter must be a finite number; in the residual encoder of a bf16 configuration
+// (16-bit operands in fp16) the encoder and FC weights must also fit fp16's range.
+int check_values(const sf_policy_config* cfg, const sf_policy_weights* w, int flat, const char* fn) {
+  struct Tensor {
+    const char* name;
+    int index;
+    const float* v;
+    size_t n;
+    bool fp16_operand;
+  };
+  std::vector<Tensor> ts;
+  const bool f16 = cfg->dtype == SF_DTYPE_BF16 && cfg->encoder == SF_ENCODER_RESNET;
+  int C = cfg->obs_c, ti = 0;
+  if (cfg->encoder == SF_ENCODER_CONV) {
+    for (int l = 0; l < cfg->n_conv; ++l, ++ti) {
+      const sf_conv& v = cfg->conv[l];
+      ts.push_back({"conv_w", ti, w->conv_w[ti], (size_t)v.cout * C * v.k * v.k, false});
+      ts.push_back({"conv_b", ti, w->conv_b[ti], (size_t)v.cout, false});
+      C = v.cout;
+    }
+  } else {
+    for (int st = 0; st < cfg->n_stage; ++st) {
+      for (int j = 0; j < 1 + 2 * cfg->blocks_per_stage; ++j, ++ti) {
+        const int cin = j == 0 ? C : cfg->stage_ch[st];
+        ts.push_back({"conv_w", ti, w->conv_w[ti], (size_t)cfg->stage_ch[st] * cin * 9, f16});
+        ts.push_back({"conv_b", ti, w->conv_b[ti], (size_t)cfg->stage_ch[st], false});
+      }
+      C = cfg->stage_ch[st];
+    }
+  }
+  const int G = cfg->rnn_type == SF_RNN_LSTM ? 4 : 3;
+  int core_in = cfg->fc_dim, n_prev = cfg->meas_dim;
+  for (int l = 0; cfg->meas_dim > 0 && l < cfg->n_meas_layers; ++l) {
+    ts.push_back({"meas_w", l, w->meas_w[l], (size_t)cfg->meas_hidden[l] * n_prev, false});
+    ts.push_back({"meas_b", l, w->meas_b[l], (size_t)cfg->meas_hidden[l], false});
+    n_prev = cfg->meas_hidden[l];
+  }
+  if (cfg->meas_dim > 0) core_in += n_prev;
+  int sumA = 0;
+  for (int k = 0; k < cfg->n_heads; ++k) sumA += cfg->head_sizes[k];
+  const size_t H = (size_t)cfg->rnn_dim;
+  ts.push_back({"fc_w", 0, w->fc_w, (size_t)cfg->fc_dim * flat, f16});
+  ts.push_back({"fc_b", 0, w->fc_b, (size_t)cfg->fc_dim, false});
+  ts.push_back({"rnn_w_ih", 0, w->rnn_w_ih, G * H * core_in, false});
+  ts.push_back({"rnn_w_hh", 0, w->rnn_w_hh, G * H * H, false});
+  ts.push_back({"rnn_b_ih", 0, w->rnn_b_ih, G * H, false});
+  ts.push_back({"rnn_b_hh", 0, w->rnn_b_hh, G * H, false});
+  ts.push_back({"pi_w", 0, w->pi_w, (size_t)sumA * H, false});
+  ts.push_back({"pi_b", 0, w->pi_b, (size_t)sumA, false});
+  ts.push_back({"v_w", 0, w->v_w, H, false});
+  ts.push_back({"v_b", 0, w->v_b, 1, false});
+  for (const Tensor& t : ts) {
+    const long long bad = first_non_finite(t.v, t.n);
+    if (bad >= 0) {
+      set_error("%s: %s[%d] element %lld is not finite", fn, t.name, t.index, bad);
+      return SF_ERR_ARG;
+    }
+    if (t.fp16_operand)
+      for (size_t i = 0; i < t.n; ++i)
+        if (fabsf(t.v[i]) > 65280.0f) {  // the largest bf16 value that fp16 can hold
+          set_error("%s: %s[%d] element %zu = %g is outside the fp16 range of the residual "
+                    "encoder's 16-bit operands", fn, t.name, t.index, i, (double)t.v[i]);
+          return SF_ERR_ARG;
+        }
+  }
+  return SF_OK;
+}
+
 int check_weights(const sf_policy_config* cfg, const sf_policy_weights* w, const char* fn) {
   int n_tensors = cfg->encoder == SF_ENCODER_CONV ? cfg->n_conv
                                                   : cfg->n_stage * (1 + 2 * cfg->blocks_per_stage);
@@ -669,6 +815,8 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
   // every parameter tensor the description needs must be present
   rc = check_weights(cfg, w, "sf_policy_create");
   if (rc != SF_OK) return rc;
+  rc = check_values(cfg, w, Cf * Hf * Wf, "sf_policy_create");
+  if (rc != SF_OK) return rc;
 
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) != hipSuccess || hip_device < 0 || hip_device >= n_dev) {
@@ -696,6 +844,7 @@ extern "C" int sf_policy_create(const sf_policy_config* cfg, const sf_policy_wei
     return SF_ERR_OOM;
   }
   p->device = hip_device;
+  p->sw = read_switches();
   Builder bld{p, cfg->dtype == SF_DTYPE_BF16};
   bld.status = build_policy(p, cfg, w, bld, Cf, Hf, Wf);
   p->events.resize(p->ops.size() + 1, nullptr);
@@ -727,21 +876,28 @@ extern "C" int sf_policy_update_weights(sf_policy* handle, const sf_policy_weigh
   }
   int rc = check_weights(&p->cfg, w, fn);
   if (rc != SF_OK) return rc;
+  rc = check_values(&p->cfg, w, p->flat, fn);
+  if (rc != SF_OK) return rc;
   if (hipSetDevice(p->device) != hipSuccess) {
     set_error("%s: hipSetDevice(%d) failed", fn, p->device);
     return SF_ERR_DEVICE;
   }
   if (!p->stage) {
-    p->stage_bytes = p->upload_bytes;
-    if (hipHostMalloc((void**)&p->stage, p->stage_bytes, hipHostMallocDefault) != hipSuccess) {
-      p->stage = nullptr;
-      set_error("%s: page-locked staging allocation of %zu bytes failed", fn, p->stage_bytes);
-      return SF_ERR_OOM;
-    }
-    if (hipEventCreateWithFlags(&p->stage_ev, hipEventDisableTiming) != hipSuccess) {
+    // the event first: the staging area is published only together with its event
+    hipEvent_t ev = nullptr;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
       set_error("%s: hipEventCreate failed", fn);
       return SF_ERR_DEVICE;
     }
+    unsigned char* stage = nullptr;
+    if (hipHostMalloc((void**)&stage, p->upload_bytes, hipHostMallocDefault) != hipSuccess) {
+      (void)hipEventDestroy(ev);
+      set_error("%s: page-locked staging allocation of %zu bytes failed", fn, p->upload_bytes);
+      return SF_ERR_OOM;
+    }
+    p->stage_ev = ev;
+    p->stage = stage;
+    p->stage_bytes = p->upload_bytes;
   } else if (hipEventSynchronize(p->stage_ev) != hipSuccess) {  // the previous update's copies
     set_error("%s: waiting for the previous update failed", fn);
     return SF_ERR_DEVICE;
@@ -749,18 +905,49 @@ extern "C" int sf_policy_update_weights(sf_policy* handle, const sf_policy_weigh
   int Cf, Hf, Wf;
   rc = check_config(&p->cfg, &Cf, &Hf, &Wf);
   if (rc != SF_OK) return rc;
-  Policy scratch;  // receives a copy of the plan; owns nothing
+  // Pack the whole plan into the staging area and check it against the live policy before
+  // any copy is enqueued: a failure up to here leaves the live parameters untouched.
+  Policy scratch{};  // receives a copy of the plan; owns nothing (value-initialised: zeros)
   scratch.device = p->device;
+  scratch.sw = p->sw;  // the switches as they were at create, whatever the environment says now
   Builder bld{&scratch, p->cfg.dtype == SF_DTYPE_BF16};
   bld.target = p;
-  bld.stream = reinterpret_cast<hipStream_t>(hip_stream);
   rc = build_policy(&scratch, &p->cfg, w, bld, Cf, Hf, Wf);
-  if (rc == SF_OK && bld.next != p->allocations.size()) {
+  if (rc != SF_OK) return rc;
+  if (bld.next != p->allocations.size()) {
     set_error("%s: the update visited %zu of the policy's %zu buffers", fn, bld.next, p->allocations.size());
-    rc = SF_ERR_SHAPE;
+    return SF_ERR_SHAPE;
   }
-  // recorded also after a failure, so that the next update waits for whatever was enqueued
-  if (hipEventRecord(p->stage_ev, bld.stream) != hipSuccess && rc == SF_OK) {
+  bool same_plan = scratch.convs.size() == p->convs.size() && scratch.ops.size() == p->ops.size() &&
+                   scratch.bf16_path == p->bf16_path && scratch.act_f16 == p->act_f16 &&
+                   scratch.stream_f32 == p->stream_f32 && scratch.fc_tile == p->fc_tile &&
+                   scratch.fc_out_bf16 == p->fc_out_bf16 && (scratch.fc_wt != nullptr) == (p->fc_wt != nullptr) &&
+                   (scratch.fc_wbf != nullptr) == (p->fc_wbf != nullptr) &&
+                   (scratch.gru_wih != nullptr) == (p->gru_wih != nullptr) &&
+                   (scratch.rnn_wih_bf != nullptr) == (p->rnn_wih_bf != nullptr);
+  for (size_t i = 0; same_plan && i < p->convs.size(); ++i) {
+    const ConvLayer &a = scratch.convs[i], &b = p->convs[i];
+    // the first convolution's arithmetic (digit planes or fp32) follows the parameter values
+    const bool conv1_pair = (a.impl == CONV1_U8_I8 || a.impl == CONV1_U8_MFMA) &&
+                            (b.impl == CONV1_U8_I8 || b.impl == CONV1_U8_MFMA) && a.ipk && a.wpk;
+    same_plan = (a.impl == b.impl || conv1_pair) && a.tile == b.tile && a.wpk == b.wpk && a.wbf == b.wbf &&
+                a.ipk == b.ipk && a.w_khwc_o == b.w_khwc_o;
+  }
+  if (!same_plan) {
+    set_error("%s: internal error: the replayed plan differs from the one built at create", fn);
+    return SF_ERR_SHAPE;
+  }
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  rc = bld.flush(stream);
+  if (rc == SF_OK)
+    for (size_t i = 0; i < p->convs.size(); ++i) {
+      p->convs[i].impl = scratch.convs[i].impl;
+      p->convs[i].planes = scratch.convs[i].planes;
+    }
+  p->conv1_ratio2 = scratch.conv1_ratio2;
+  p->conv1_ratio3 = scratch.conv1_ratio3;
+  // recorded also after a failed copy, so that the next update waits for whatever was enqueued
+  if (hipEventRecord(p->stage_ev, stream) != hipSuccess && rc == SF_OK) {
     set_error("%s: hipEventRecord failed", fn);
     rc = SF_ERR_DEVICE;
   }
@@ -887,8 +1074,8 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
         const void* in = op.in_buf < 0 ? (const void*)obs : (const void*)buf(op.in_buf);
         switch (L.impl) {
           case CONV1_U8_I8:
-            SF_LAUNCH(launch_conv1_i8(L, B, obs, L.ipk, L.spk, L.bpk, buf(op.out_buf), p->bf16_path,
-                                      p->conv1_waves, p->conv1_image, st));
+            SF_LAUNCH(launch_conv1_i8(L, B, obs, L.ipk, L.spk, L.bpk8, buf(op.out_buf), p->bf16_path,
+                                      L.planes, p->conv1_waves, p->conv1_image, st));
             break;
           case CONV1_U8_MFMA:
             SF_LAUNCH(launch_conv1_mfma(L, B, obs, L.wpk, L.bpk, buf(op.out_buf), p->trash,
@@ -1022,6 +1209,57 @@ extern "C" int64_t sf_policy_op_flops_per_row(const sf_policy* handle, int i) {
   const Policy* p = reinterpret_cast<const Policy*>(handle);
   if (!p || i < 0 || i >= (int)p->ops.size()) return 0;
   return p->ops[i].flops_per_row;
+}
+
+// The arithmetic of launch i, as selected for the current parameters.
+extern "C" const char* sf_policy_op_pipe(const sf_policy* handle, int i) {
+  const Policy* p = reinterpret_cast<const Policy*>(handle);
+  if (!p || i < 0 || i >= (int)p->ops.size()) return "";
+  const Op& op = p->ops[i];
+  const char* mfma16 = p->act_f16 ? "f16" : "bf16";
+  switch (op.kind) {
+    case OP_CONV: {
+      const ConvLayer& L = p->convs[op.conv];
+      switch (L.impl) {
+        case CONV1_U8_I8: return L.planes == 2 ? "i8x2" : "i8x3";
+        case CONV1_U8_MFMA:
+        case CONV_GEMM_MFMA: return "f32";
+        case CONV_BF16:
+        case CONV3X3_PATCH:
+        case CONV3X3_STEM:
+        case CONV3X3_POOL:
+        case RES_BLOCK:
+        case CONV_IMAGE_BF16: return mfma16;
+        default: return "valu";
+      }
+    }
+    case OP_FC: return p->fc_wbf ? mfma16 : (p->fc_wt ? "f32" : "valu");
+    case OP_GRU: return p->rnn_wih_bf ? "bf16" : (p->gru_wih ? "f32" : "valu");
+    default: return "valu";
+  }
+}
+
+extern "C" double sf_policy_conv1_fixed_point_ratio(const sf_policy* handle, int planes) {
+  const Policy* p = reinterpret_cast<const Policy*>(handle);
+  if (!p) return -1.0;
+  return planes == 2 ? p->conv1_ratio2 : p->conv1_ratio3;
+}
+
+// Host only: the admission test on a filter bank [32][cin][8][8], no device involved.
+extern "C" int sf_conv1_fixed_point_test(const float* conv_w, int32_t cin, float obs_mul, int32_t dtype,
+                                         double* ratio2, double* ratio3) {
+  if (!conv_w || !ratio2 || !ratio3 || (cin != 1 && cin != 3 && cin != 4) ||
+      (dtype != SF_DTYPE_FP32 && dtype != SF_DTYPE_BF16)) {
+    set_error("sf_conv1_fixed_point_test: bad argument");
+    return SF_ERR_ARG;
+  }
+  std::vector<int> ipk;
+  std::vector<float> spk, bpk, zero_bias(32, 0.0f);
+  Conv1I8Info info;
+  conv1_i8_pack(conv_w, zero_bias.data(), cin, 0.0f, obs_mul, dtype == SF_DTYPE_BF16, ipk, spk, bpk, &info);
+  *ratio2 = info.ratio2;
+  *ratio3 = info.ratio3;
+  return SF_OK;
 }
 
 extern "C" int sf_policy_set_op_timing(sf_policy* handle, int enable) {

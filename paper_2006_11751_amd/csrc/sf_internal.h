@@ -27,6 +27,8 @@ struct ConvLayer {
   float* bpk;             // dev, bias as the chosen MFMA kernel wants it (or null)
   int* ipk;               // dev, int8 digit planes of the int8 first-convolution kernel
   float* spk;             // dev, per-channel scales of that kernel
+  float* bpk8;            // dev, bias as that kernel wants it
+  int planes;             // digit planes that kernel uses (2 or 3)
   uint16_t* wbf;          // dev, bf16 [Npad][Kpad] weights of the bf16 kernel
   float* bbf;             // dev, bias padded to Npad
   int Kpad;
@@ -44,6 +46,28 @@ enum ConvImpl {
   CONV_IMAGE_BF16 = 10  // 16-bit MFMA with the frame's input image resident in LDS
 };
 
+// Kernel-selection switches (environment variables, for A/B measurements and for the tests
+// that force a fallback kernel).  Read once, in sf_policy_create; a weight update replays the
+// plan with the values stored in the policy.
+struct Switches {
+  bool force_generic = false;    // SF_FORCE_GENERIC: shape-agnostic kernels everywhere
+  int conv1 = 0;                 // SF_CONV1: 0 = by the admission test of the fixed-point bank,
+                                 // 1 = "fp32" (fp32 MFMA forced), 2 = "i8" (digit planes forced)
+  int conv1_waves = 0;           // SF_CONV1_WAVES
+  int gemm_tile = 0, fc_tile = 0, gru_bm = 0;  // SF_GEMM_TILE, SF_FC_TILE, SF_GRU_BM (0 = default)
+  bool no_rnn_pairs = false;     // SF_NO_RNN_PAIRS
+  bool no_bf16_path = false;     // SF_NO_BF16_PATH
+  bool no_rnn_bf16 = false;      // SF_NO_RNN_BF16
+  int conv_bf16_tc = 0;          // SF_CONV_BF16_TC
+  bool no_conv1_image = false;   // SF_NO_CONV1_IMAGE
+  bool no_conv_image = false;    // SF_NO_CONV_IMAGE
+  bool fc_out_f32 = false;       // SF_FC_OUT_F32
+  bool no_patch_conv = false;    // SF_NO_PATCH_CONV
+  bool no_fused_resnet = false;  // SF_NO_FUSED_RESNET
+  bool act_bf16 = false;         // SF_ACT_BF16
+  bool stream_f32 = false;       // SF_STREAM_F32
+};
+
 // One kernel launch of the step, fixed at create time.
 enum OpKind { OP_CONV, OP_POOL, OP_FC, OP_MEAS, OP_GRU, OP_HEADS };
 struct Op {
@@ -59,6 +83,7 @@ struct Op {
 
 struct Policy {
   sf_policy_config cfg;
+  Switches sw;
   int device;
   int flat;   // encoder output elements per row
   int sumA;   // total logits per row
@@ -81,6 +106,7 @@ struct Policy {
   float* gru_wih;     // dev [G*H][core input] (canonical) for the MFMA kernel, or null
   float* gru_whh;     // dev [G*H][H]
   int gru_bm;         // rows per workgroup of the MFMA kernel, fixed at create
+  double conv1_ratio2 = 0, conv1_ratio3 = 0;  // admission test of the first convolution's digit planes
   int conv1_image = 1;      // first convolution: frame-resident variant where it applies
   int fc_out_bf16 = 0;      // the FC kernel hands bf16 values to the 16-bit recurrent kernel
   int conv_bf16_tc = 0;     // 16-bit conv kernel: 0 = channel blocks per workgroup by grid size, 1 / 2 forced
@@ -157,11 +183,18 @@ hipError_t launch_conv1_mfma(const ConvLayer& L, int B, const uint8_t* obs, cons
                              hipStream_t st);
 
 bool conv1_i8_supported(const ConvLayer& L);
+// Result of the admission test of a fixed-point filter bank: worst channel's ratio of the
+// bank's error bound to that of the floating-point path it replaces, with two and with
+// three digit planes (<= 1: admitted).
+struct Conv1I8Info {
+  double ratio2, ratio3;
+};
 void conv1_i8_pack(const float* w, const float* bias, int cin, float obs_sub, float obs_mul,
-                   std::vector<int>& wpk, std::vector<float>& scale, std::vector<float>& bpk);
+                   bool bf16_weights, std::vector<int>& wpk, std::vector<float>& scale,
+                   std::vector<float>& bpk, Conv1I8Info* info);
 hipError_t launch_conv1_i8(const ConvLayer& L, int B, const uint8_t* obs, const int* wpk,
                            const float* scale, const float* bpk, void* out, int out_bf16,
-                           int waves_hint, int image, hipStream_t st);
+                           int planes, int waves_hint, int image, hipStream_t st);
 bool conv_bf16_supported(int Cin, int N);
 void conv_bf16_pack(const float* w, const float* bias, int cout, int cin, int k, bool f16,
                     std::vector<uint16_t>& wt, std::vector<float>& b, int* Kpad);

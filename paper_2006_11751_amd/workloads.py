@@ -105,16 +105,30 @@ def round_to_bf16(a):
     return bits.astype(np.uint32).view(np.float32).reshape(a.shape)
 
 
-def weights(net, seed=None):
-    """Parameters ~ N(0, variance 1/fan_in), biases too (non-zero on purpose).
+def weights(net, seed=None, dist="normal", rounded=True):
+    """Parameters with variance 1/fan_in, biases too (non-zero on purpose): N(0, 1/fan_in)
+    (the benchmark recipe), or for robustness tests "laplace", "student3" (heavy tails: Student t
+    with 3 degrees of freedom) or "uniform", each scaled to that variance.
     For bf16 configurations every tensor is rounded to bf16 once, so that both
-    the oracle and the library start from identical values."""
+    the oracle and the library start from identical values; rounded=False leaves them
+    as drawn (the caller then rounds the oracle's copy itself)."""
     seed = 1000 + net.get("index", 0) if seed is None else seed
     rng = np.random.default_rng(seed)
 
+    def unit(shape):
+        if dist == "normal":
+            return rng.standard_normal(shape)
+        if dist == "laplace":
+            return rng.laplace(size=shape) / np.sqrt(2.0)
+        if dist == "student3":
+            return rng.standard_t(3, size=shape) / np.sqrt(3.0)
+        if dist == "uniform":
+            return rng.uniform(-1.0, 1.0, size=shape) * np.sqrt(3.0)
+        raise ValueError(dist)
+
     def draw(shape, fan_in):
-        a = (rng.standard_normal(shape) / np.sqrt(fan_in)).astype(np.float32)
-        return round_to_bf16(a) if net["dtype"] == "bf16" else a
+        a = (unit(shape) / np.sqrt(fan_in)).astype(np.float32)
+        return round_to_bf16(a) if net["dtype"] == "bf16" and rounded else a
 
     w = {"conv_w": [], "conv_b": []}
     for co, ci, k in conv_tensor_shapes(net):
@@ -137,6 +151,61 @@ def weights(net, seed=None):
         w["meas_b"].append(draw((m,), n_prev))
         n_prev = m
     return w
+
+
+def round_weights_to_bf16(w):
+    """A copy of a parameter dict with every tensor rounded to bf16 (what a bf16 configuration
+    defines its parameters to be)."""
+    out = {}
+    for k, v in w.items():
+        out[k] = [round_to_bf16(a) for a in v] if isinstance(v, list) else round_to_bf16(v)
+    return out
+
+
+# Filter banks for the first convolution whose taps span a wide dynamic range within a channel,
+# and the frames that expose them: the cases a per-channel fixed-point image of the bank handles
+# worst.  (tap index = (channel, filter row, filter column) of conv_w[0][n])
+CONV1_FAMILIES = ("dominant", "log_uniform", "zero_channel", "tiny_equal", "half_half_40",
+                  "half_half_1000")
+
+
+def conv1_family(net, w, kind, seed=77):
+    """A copy of parameters w whose first filter bank is of the given kind."""
+    rng = np.random.default_rng(seed)
+    w = dict(w)
+    a = np.array(w["conv_w"][0], dtype=np.float32, copy=True)
+    co, ci, k, _ = a.shape
+    std = 1.0 / np.sqrt(ci * k * k)
+    if kind == "dominant":        # one tap 1000 times the typical one, the same tap in every filter
+        a[:, ci - 1, 2, 3] = 1000.0 * std * rng.choice([-1.0, 1.0], size=co)
+    elif kind == "log_uniform":   # magnitudes over four decades
+        a = (10.0 ** rng.uniform(-4.0, 0.0, a.shape) * rng.choice([-1.0, 1.0], a.shape) * 4.0 * std)
+    elif kind == "zero_channel":  # two filters that are zero everywhere
+        a[3] = 0.0
+        a[co - 1] = 0.0
+    elif kind == "tiny_equal":    # every tap the same tiny value
+        a[:] = 1e-6
+    elif kind in ("half_half_40", "half_half_1000"):  # even filter columns 40x (1000x) the odd ones
+        ratio = 40.0 if kind == "half_half_40" else 1000.0
+        a = rng.choice([-1.0, 1.0], a.shape) * std
+        a[..., 0::2] *= ratio
+    else:
+        raise ValueError(kind)
+    w["conv_w"] = [a.astype(np.float32)] + list(w["conv_w"][1:])
+    return w
+
+
+def conv1_family_frames(net, kind, obs):
+    """Frames that put the large taps of the family on dark pixels, i.e. on the byte whose
+    normalised value is nearest zero (stride-4 8x8 filter, no padding: filter column q meets
+    image columns = q mod 4, filter row p image rows = p mod 4)."""
+    obs = obs.copy()
+    dark = int(min(255, max(0, round(net["obs_sub"]))))
+    if kind == "dominant":
+        obs[:, -1, 2::4, 3::4] = dark
+    elif kind in ("half_half_40", "half_half_1000"):
+        obs[:, :, :, 0::2] = dark
+    return obs
 
 
 def observations(net, t=0, B=None, seed=None):

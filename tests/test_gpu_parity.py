@@ -97,12 +97,19 @@ def test_standard_full_batch(torch_cuda, ref):
     pol.close()
 
 
-def _sampled_rows_check(torch, ref, net, n_rows, n_steps=1, full_steps=1):
+def _tile_edge_rows(B, tile):
+    """First and last batch row of every `tile`-row block of a B-row batch."""
+    first = np.arange(0, B, tile)
+    return np.concatenate([first, np.minimum(first + tile - 1, B - 1)])
+
+
+def _sampled_rows_check(torch, ref, net, n_rows, n_steps=1, full_steps=1, extra_rows=()):
     """Full-size batch on the GPU; the oracle computes a sample of rows one by one."""
     pol, w = _make(torch, net)
     B = net["B"]
     rng = np.random.default_rng(99)
-    rows = np.unique(np.concatenate([[0, 1, B - 1, B - 2, B // 2], rng.integers(0, B, n_rows)]))
+    rows = np.unique(np.concatenate([[0, 1, B - 1, B - 2, B // 2], rng.integers(0, B, n_rows),
+                                     np.asarray(extra_rows, dtype=np.int64)]))
     h_gpu = wl.initial_state(net)
     for t in range(n_steps):
         obs, done = wl.observations(net, t), wl.done_mask(net, t)
@@ -174,8 +181,10 @@ def test_standard_bf16_full_size_sampled_rows(torch_cuda, ref):
 
 
 def test_multi_discrete_16_steps(torch_cuda, ref):
-    """Configuration 3 (B=2048, six heads, 16 chained steps), sampled rows."""
-    _sampled_rows_check(torch_cuda, ref, wl.network(3), 120, n_steps=16, full_steps=2)
+    """Configuration 3 (B=2048, six heads, 16 chained steps), sampled rows: 400 random ones and
+    the first and last row of every 64-row block (the row tiles of the GEMM and GRU launches)."""
+    _sampled_rows_check(torch_cuda, ref, wl.network(3), 400, n_steps=16, full_steps=2,
+                        extra_rows=_tile_edge_rows(2048, 64))
 
 
 def test_multi_discrete_small_free_running(torch_cuda, ref):
@@ -195,8 +204,12 @@ def test_multi_discrete_small_free_running(torch_cuda, ref):
 
 
 def test_resnet_bf16_full_size_sampled_rows(torch_cuda, ref):
-    """Configuration 4 (B=8192, residual encoder, bf16)."""
-    _sampled_rows_check(torch_cuda, ref, wl.network(4), 40)
+    """Configuration 4 (B=8192, residual encoder, bf16).  The encoder launches take one
+    workgroup per (frame, tile), so every frame runs the same code; the FC and GRU launches tile
+    the batch in blocks of 128 and 32/64 rows.  Compared: the first and last row of every
+    128-row block, of every eighth 32-row block, and 400 random rows (about 600 in all)."""
+    extra = np.concatenate([_tile_edge_rows(8192, 128), _tile_edge_rows(8192, 32)[::8]])
+    _sampled_rows_check(torch_cuda, ref, wl.network(4), 400, extra_rows=extra)
 
 
 def test_purity_done_reset_and_edges(torch_cuda, ref):
@@ -344,13 +357,16 @@ def _random_net(rng, dtype):
                 p_done=0.3, steps=1, obs_sub=float(rng.choice([0.0, 127.5])), obs_mul=wl.OBS_MUL, index=0)
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(18))
 def test_random_network_shapes(torch_cuda, ref, seed):
-    """Randomly drawn network descriptions, every element against the oracle."""
+    """Randomly drawn network descriptions, every element against the oracle.  Seeds from 12 on
+    draw the parameters from non-Gaussian laws (Laplace, Student t with 3 degrees of freedom,
+    uniform) of the same variance."""
     torch = torch_cuda
     rng = np.random.default_rng(500 + seed)
     net = _random_net(rng, "bf16" if seed % 3 == 2 else "fp32")
-    w = wl.weights(net, seed=600 + seed)
+    dist = "normal" if seed < 12 else ("laplace", "student3", "uniform")[(seed - 12) // 2]
+    w = wl.weights(net, seed=600 + seed, dist=dist)
     from paper_2006_11751_amd import binding
     pol = binding.Policy(net, w)
     B = net["B"]

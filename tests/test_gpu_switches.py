@@ -1,7 +1,9 @@
 """Every kernel-selection switch still gives the oracle's result: the fallback kernels
 (shape-agnostic kernels, fp32 kernels on bf16 weights, per-layer residual-encoder kernels,
 fp32-MFMA core in bf16 configurations, fp32 first convolution) are exercised on small
-networks through the C ABI.  The switches are read when a policy is created.
+networks through the C ABI.  The switches are read when a policy is created, once: a weight
+update on such a policy, made after the variable has been removed, still packs for the kernels
+chosen at create.
 """
 import numpy as np
 import pytest
@@ -23,6 +25,7 @@ CASES = [
     ("SF_FORCE_GENERIC", "1", BY_NAME["full_mfma"]),
     ("SF_FORCE_GENERIC", "1", RESNET_BF16_SMALL),
     ("SF_CONV1", "fp32", STD_SMALL),
+    ("SF_CONV1", "i8", STD_SMALL),
     ("SF_GEMM_TILE", "4", STD_SMALL),
     ("SF_GRU_BM", "64", STD_SMALL),
     ("SF_NO_RNN_PAIRS", "1", STD_SMALL),
@@ -52,5 +55,14 @@ def test_switch(torch_cuda, ref, monkeypatch, var, val, net):
                    5, 3, meas=None if meas is None else torch.from_numpy(meas).to(d))
     torch.cuda.synchronize()
     o = ref.policy_step(net, w, obs, state, done, 5, 3, meas=meas)
+    parity.check_against_oracle(net, _to_np(out), o, ref, 5, 3)
+    # The switches were read at create and are kept in the policy: a weight update made after
+    # the variable is gone must pack for the kernels chosen then, not for the default ones.
+    w2 = wl.weights(net, seed=9090)
+    pol.update_weights(w2)
+    out = pol.step(torch.from_numpy(obs).to(d), torch.from_numpy(state).to(d), torch.from_numpy(done).to(d),
+                   5, 3, meas=None if meas is None else torch.from_numpy(meas).to(d))
+    torch.cuda.synchronize()
+    o = ref.policy_step(net, w2, obs, state, done, 5, 3, meas=meas)
     parity.check_against_oracle(net, _to_np(out), o, ref, 5, 3)
     pol.close()
