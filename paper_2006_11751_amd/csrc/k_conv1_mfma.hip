@@ -10,12 +10,17 @@
 // (the normalisation x = (byte - sub) * mul is folded into it and into the bias
 // when the weights are packed), so the only operand traffic per item is one dword
 // (4 horizontally adjacent bytes) per lane per (channel, filter row).
+// With sub != 0 the A operand is byte - c, c = sub rounded to a byte value, and the
+// bias absorbs the rest: the fp32 sums then stay of the size of the normalised
+// pixels' terms instead of cancelling against a large bias.
 //
 // v_mfma_f32_32x32x2_f32: lane l supplies A[i = l%32][k = l/32] and
 // B[k = l/32][j = l%32]; the K index inside one instruction is therefore the lane
 // half h = l/32.  K is ordered so that for a fixed (channel c, filter row p) the
 // lane half h holds filter columns q = 4h..4h+3, and instruction t of the four
 // consumes column q = 4h + t: exactly byte t of the dword the lane loaded.
+#include <math.h>
+
 #include "sf_internal.h"
 
 namespace sf {
@@ -29,11 +34,11 @@ constexpr int kK = 8;       // filter size
 constexpr int kS = 4;       // stride
 constexpr int kWaves = 4;   // per workgroup
 
-template <int CIN>
+template <int CIN, bool CENTER>
 __global__ __launch_bounds__(64 * kWaves, 2) void conv1_u8_mfma_kernel(
     const uint8_t* __restrict__ obs, const float* __restrict__ wpk, const float* __restrict__ bias,
     float* __restrict__ out, float* __restrict__ trash, int H, int W, int Ho, int Wo,
-    int n_xchunks, long long n_items, int n_waves_total) {
+    int n_xchunks, long long n_items, int n_waves_total, float center) {
   constexpr int NG = CIN * kK;  // (channel, filter row) groups; 4 MFMAs each
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWaves + (threadIdx.x >> 6);
@@ -97,18 +102,22 @@ __global__ __launch_bounds__(64 * kWaves, 2) void conv1_u8_mfma_kernel(
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = bias_n;
     float a_cur[8], a_nxt[8];
+    auto pixel = [&](uint32_t word, int t) -> float {
+      const float v = (float)((word >> (8 * t)) & 0xFFu);
+      return CENTER ? v - center : v;
+    };
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      a_cur[t] = (float)((cur[0] >> (8 * t)) & 0xFFu);
-      a_cur[4 + t] = (float)((cur[1] >> (8 * t)) & 0xFFu);
+      a_cur[t] = pixel(cur[0], t);
+      a_cur[4 + t] = pixel(cur[1], t);
     }
 #pragma unroll
     for (int g = 0; g < NG; g += 2) {
       if (g + 2 < NG) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          a_nxt[t] = (float)((cur[g + 2] >> (8 * t)) & 0xFFu);
-          a_nxt[4 + t] = (float)((cur[g + 3] >> (8 * t)) & 0xFFu);
+          a_nxt[t] = pixel(cur[g + 2], t);
+          a_nxt[4 + t] = pixel(cur[g + 3], t);
         }
       }
 #pragma unroll
@@ -116,7 +125,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void conv1_u8_mfma_kernel(
 #pragma unroll
       for (int t = 0; t < 4; ++t)
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[4 + t], wreg[g + 1][t], acc, 0, 0, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);  // VALU: the conversions
+      __builtin_amdgcn_sched_group_barrier(0x002, CENTER ? 16 : 8, 0);  // VALU: the conversions
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);  // MFMA
 #pragma unroll
       for (int t = 0; t < 8; ++t) a_cur[t] = a_nxt[t];
@@ -151,9 +160,16 @@ bool conv1_mfma_supported(const ConvLayer& L) {
 
 // Packed filter bank for the kernel above, with the normalisation folded in:
 // wpk[((c*8 + p)*4 + t)*64 + lane] = mul * w[n = lane%32][c][p][q = 4*(lane/32) + t],
-// bias'[n] = bias[n] - sub * mul * sum(w[n]).
+// bias'[n] = bias[n] - (sub - center) * mul * sum(w[n]), center = conv1_mfma_center(sub).
+float conv1_mfma_center(float obs_sub) {
+  if (obs_sub == 0.0f) return 0.0f;
+  const float c = nearbyintf(obs_sub);
+  return c < 0.0f ? 0.0f : (c > 255.0f ? 255.0f : c);
+}
+
 void conv1_mfma_pack(const float* w, const float* bias, int cin, float obs_sub, float obs_mul,
                      std::vector<float>& wpk, std::vector<float>& bpk) {
+  const double shift = (double)obs_sub - (double)conv1_mfma_center(obs_sub);
   wpk.assign((size_t)cin * kK * 4 * 64, 0.0f);
   bpk.assign(kCout, 0.0f);
   for (int c = 0; c < cin; ++c)
@@ -165,15 +181,15 @@ void conv1_mfma_pack(const float* w, const float* bias, int cin, float obs_sub, 
               obs_mul * w[(((size_t)n * cin + c) * kK + p) * kK + q];
         }
   for (int n = 0; n < kCout; ++n) {
-    double s = 0.0;
-    for (int i = 0; i < cin * kK * kK; ++i) s += (double)w[(size_t)n * cin * kK * kK + i];
-    bpk[n] = (float)((double)bias[n] - (double)obs_sub * (double)obs_mul * s);
+    double s = 0.0;  // over the fp32 products the kernel multiplies by
+    for (int i = 0; i < cin * kK * kK; ++i) s += (double)(obs_mul * w[(size_t)n * cin * kK * kK + i]);
+    bpk[n] = (float)((double)bias[n] - shift * s);
   }
 }
 
 hipError_t launch_conv1_mfma(const ConvLayer& L, int B, const uint8_t* obs, const float* wpk,
                              const float* bpk, float* out, float* trash, int waves_hint,
-                             hipStream_t st) {
+                             float obs_sub, hipStream_t st) {
   if (B == 0) return hipSuccess;
   const int n_xchunks = (L.Wo + 31) / 32;
   const long long n_items = (long long)B * L.Ho * n_xchunks;
@@ -181,22 +197,23 @@ hipError_t launch_conv1_mfma(const ConvLayer& L, int B, const uint8_t* obs, cons
   if (waves > n_items) waves = n_items;
   const int blocks = (int)((waves + kWaves - 1) / kWaves);
   const int n_waves_total = blocks * kWaves;
+  const float center = conv1_mfma_center(obs_sub);
+#define SF_LAUNCH_CIN(C)                                                                          \
+  do {                                                                                            \
+    if (center != 0.0f)                                                                           \
+      conv1_u8_mfma_kernel<C, true><<<blocks, 64 * kWaves, 0, st>>>(                              \
+          obs, wpk, bpk, out, trash, L.H, L.W, L.Ho, L.Wo, n_xchunks, n_items, n_waves_total, center); \
+    else                                                                                          \
+      conv1_u8_mfma_kernel<C, false><<<blocks, 64 * kWaves, 0, st>>>(                             \
+          obs, wpk, bpk, out, trash, L.H, L.W, L.Ho, L.Wo, n_xchunks, n_items, n_waves_total, center); \
+  } while (0)
   switch (L.cin) {
-    case 1:
-      conv1_u8_mfma_kernel<1><<<blocks, 64 * kWaves, 0, st>>>(obs, wpk, bpk, out, trash, L.H, L.W, L.Ho,
-                                                             L.Wo, n_xchunks, n_items, n_waves_total);
-      break;
-    case 3:
-      conv1_u8_mfma_kernel<3><<<blocks, 64 * kWaves, 0, st>>>(obs, wpk, bpk, out, trash, L.H, L.W, L.Ho,
-                                                             L.Wo, n_xchunks, n_items, n_waves_total);
-      break;
-    case 4:
-      conv1_u8_mfma_kernel<4><<<blocks, 64 * kWaves, 0, st>>>(obs, wpk, bpk, out, trash, L.H, L.W, L.Ho,
-                                                             L.Wo, n_xchunks, n_items, n_waves_total);
-      break;
-    default:
-      return hipErrorInvalidValue;
+    case 1: SF_LAUNCH_CIN(1); break;
+    case 3: SF_LAUNCH_CIN(3); break;
+    case 4: SF_LAUNCH_CIN(4); break;
+    default: return hipErrorInvalidValue;
   }
+#undef SF_LAUNCH_CIN
   return hipGetLastError();
 }
 

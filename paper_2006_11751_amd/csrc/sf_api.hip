@@ -1079,7 +1079,7 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
             break;
           case CONV1_U8_MFMA:
             SF_LAUNCH(launch_conv1_mfma(L, B, obs, L.wpk, L.bpk, buf(op.out_buf), p->trash,
-                                        p->conv1_waves, st));
+                                        p->conv1_waves, c.obs_sub, st));
             break;
           case CONV_GEMM_MFMA:
             SF_LAUNCH(launch_gemm_mfma((const float*)in, L.wpk, L.bpk, buf(op.out_buf), B, L.H, L.W,

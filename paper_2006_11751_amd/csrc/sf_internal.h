@@ -180,7 +180,7 @@ void conv1_mfma_pack(const float* w, const float* bias, int cin, float obs_sub, 
                      std::vector<float>& wpk, std::vector<float>& bpk);
 hipError_t launch_conv1_mfma(const ConvLayer& L, int B, const uint8_t* obs, const float* wpk,
                              const float* bpk, float* out, float* trash, int waves_hint,
-                             hipStream_t st);
+                             float obs_sub, hipStream_t st);
 
 bool conv1_i8_supported(const ConvLayer& L);
 // Result of the admission test of a fixed-point filter bank: worst channel's ratio of the
