@@ -373,6 +373,24 @@ int sf_appo_loss(const sf_loss_config* cfg, const float* logits, const int32_t* 
                  const uint8_t* dones, float* vs, float* adv, float* loss, float* dlogits_opt,
                  float* dvalues_opt, void* workspace, void* hip_stream);
 
+
+/* The same loss for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving or training loops, harnesses that forbid allocation.  The
+ * per-trajectory partial sums (N x 16 bytes) live in an array inside the library's device
+ * image, 256 KiB per GPU for as long as the process runs, so N is limited to
+ * sf_appo_loss_static_max_trajectories() = 16384; a larger N is refused with SF_ERR_SHAPE.  The
+ * call allocates and frees nothing, runs on the current HIP device, and is otherwise
+ * sf_appo_loss (same kernels, same bits).  All calls on one GPU share the one array, which
+ * keeps the last call's contents (every slot a call reads is written by that call first): two
+ * calls that overlap on one GPU, on different streams or from different threads, race; calls
+ * on one stream are safe.  Errors: as sf_appo_loss, plus SF_ERR_SHAPE for N beyond the limit
+ * and SF_ERR_DEVICE if the array's address cannot be obtained. */
+int32_t sf_appo_loss_static_max_trajectories(void);
+int sf_appo_loss_static(const sf_loss_config* cfg, const float* logits, const int32_t* actions,
+                        const float* logp_mu, const float* values, const float* rewards,
+                        const uint8_t* dones, float* vs, float* adv, float* loss, float* dlogits_opt,
+                        float* dvalues_opt, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

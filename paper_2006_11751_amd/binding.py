@@ -105,7 +105,8 @@ EXPORTS = ("sf_policy_create", "sf_policy_step", "sf_policy_destroy", "sf_last_e
            "sf_copy_bytes", "sf_policy_step_indexed", "sf_pipeline_create", "sf_pipeline_submit",
            "sf_pipeline_wait", "sf_pipeline_destroy", "sf_policy_state_dim",
            "sf_policy_update_weights", "sf_appo_loss", "sf_appo_loss_workspace_bytes",
-           "sf_policy_op_pipe", "sf_policy_conv1_fixed_point_ratio", "sf_conv1_fixed_point_test")
+           "sf_policy_op_pipe", "sf_policy_conv1_fixed_point_ratio", "sf_conv1_fixed_point_test",
+           "sf_appo_loss_static", "sf_appo_loss_static_max_trajectories")
 
 _lib = None
 
@@ -142,6 +143,10 @@ def load_library():
         L.sf_appo_loss_workspace_bytes.argtypes = [C.POINTER(SfLossConfig)]
         L.sf_appo_loss.restype = C.c_int
         L.sf_appo_loss.argtypes = [C.POINTER(SfLossConfig)] + [C.c_void_p] * 13
+        L.sf_appo_loss_static.restype = C.c_int
+        L.sf_appo_loss_static.argtypes = [C.POINTER(SfLossConfig)] + [C.c_void_p] * 12
+        L.sf_appo_loss_static_max_trajectories.restype = C.c_int32
+        L.sf_appo_loss_static_max_trajectories.argtypes = []
         L.sf_policy_state_dim.restype = C.c_int32
         L.sf_policy_state_dim.argtypes = [C.c_void_p]
         L.sf_policy_destroy.restype = C.c_int
@@ -344,6 +349,15 @@ def sf_appo_loss(cfg, logits, actions, logp_mu, values, rewards, dones, vs, adv,
     """All buffers are device addresses (ints)."""
     rc = load_library().sf_appo_loss(C.byref(cfg), logits, actions, logp_mu, values, rewards, dones, vs,
                                      adv, loss, dlogits_opt, dvalues_opt, workspace, hip_stream)
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+
+
+def sf_appo_loss_static(cfg, logits, actions, logp_mu, values, rewards, dones, vs, adv, loss, dlogits_opt,
+                        dvalues_opt, hip_stream=None):
+    """sf_appo_loss without a workspace argument (the library's built-in scratch); device addresses."""
+    rc = load_library().sf_appo_loss_static(C.byref(cfg), logits, actions, logp_mu, values, rewards, dones,
+                                            vs, adv, loss, dlogits_opt, dvalues_opt, hip_stream)
     if rc != SF_OK:
         raise SfError(rc, sf_last_error())
 

@@ -19,6 +19,8 @@
 // depend on scheduling.
 #include <math.h>
 
+#include <mutex>
+
 #include "sf_internal.h"
 
 namespace sf {
@@ -214,31 +216,30 @@ extern "C" int64_t sf_appo_loss_workspace_bytes(const sf_loss_config* cfg) {
   return (int64_t)cfg->N * 4 * (int64_t)sizeof(float);
 }
 
-extern "C" int sf_appo_loss(const sf_loss_config* cfg, const float* logits, const int32_t* actions,
-                            const float* logp_mu, const float* values, const float* rewards,
-                            const uint8_t* dones, float* vs, float* adv, float* loss,
-                            float* dlogits_opt, float* dvalues_opt, void* workspace, void* hip_stream) {
-  static const char* fn = "sf_appo_loss";
-  int sumA;
-  int rc = check_loss_config(cfg, fn, &sumA);
-  if (rc != SF_OK) return rc;
+namespace {
+
+// Argument checks and the two launches shared by the entry points; `partials` is device
+// memory for N x 4 floats.
+int run_appo_loss(const char* fn, const sf_loss_config* cfg, int sumA, const float* logits,
+                  const int32_t* actions, const float* logp_mu, const float* values, const float* rewards,
+                  const uint8_t* dones, float* vs, float* adv, float* loss, float* dlogits_opt,
+                  float* dvalues_opt, float* partials, hipStream_t st) {
   if (!logits || !actions || !logp_mu || !values || !rewards || !dones || !vs || !adv || !loss ||
-      !workspace) {
+      !partials) {
     set_error("%s: null buffer", fn);
     return SF_ERR_ARG;
   }
   const void* al[] = {logits, actions, logp_mu, values, rewards, vs, adv, loss, dlogits_opt, dvalues_opt,
-                      workspace};
+                      partials};
   for (const void* q : al)
     if ((reinterpret_cast<uintptr_t>(q) & 3) != 0) {
       set_error("%s: misaligned buffer (4 bytes)", fn);
       return SF_ERR_ARG;
     }
-  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   LossArgs g;
   g.logits = logits; g.actions = actions; g.logp_mu = logp_mu; g.values = values; g.rewards = rewards;
   g.dones = dones; g.vs = vs; g.adv = adv; g.dlogits = dlogits_opt; g.dvalues = dvalues_opt;
-  g.partials = (float*)workspace;
+  g.partials = partials;
   g.T = cfg->T; g.N = cfg->N; g.n_heads = cfg->n_heads; g.sumA = sumA;
   for (int k = 0; k < SF_MAX_HEADS; ++k) g.head_sizes[k] = k < cfg->n_heads ? cfg->head_sizes[k] : 0;
   g.gamma = cfg->gamma; g.rho_bar = cfg->rho_bar; g.c_bar = cfg->c_bar; g.clip = cfg->clip;
@@ -256,4 +257,72 @@ extern "C" int sf_appo_loss(const sf_loss_config* cfg, const float* logits, cons
     return SF_ERR_DEVICE;
   }
   return SF_OK;
+}
+
+// Scratch of the entry point that allocates nothing: the per-trajectory partial sums.  One copy
+// of this array exists on every GPU the library is loaded on, at an address of its own; host
+// code never uses the symbol's name as an address but the pointer that hipGetSymbolAddress
+// returns for the current device, looked up once per device.
+constexpr int kStaticMaxTraj = 16384;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) float scratch[(size_t)kStaticMaxTraj * 4];
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(const char* fn, float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    set_error("%s: no current HIP device (%s)", fn, hipGetErrorString(e));
+    return SF_ERR_DEVICE;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    float* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      set_error("%s: hipGetSymbolAddress failed on device %d: %s", fn, dev, hipGetErrorString(e));
+      return SF_ERR_DEVICE;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SF_OK;
+}
+
+}  // namespace
+
+extern "C" int sf_appo_loss(const sf_loss_config* cfg, const float* logits, const int32_t* actions,
+                            const float* logp_mu, const float* values, const float* rewards,
+                            const uint8_t* dones, float* vs, float* adv, float* loss,
+                            float* dlogits_opt, float* dvalues_opt, void* workspace, void* hip_stream) {
+  static const char* fn = "sf_appo_loss";
+  int sumA;
+  int rc = check_loss_config(cfg, fn, &sumA);
+  if (rc != SF_OK) return rc;
+  return run_appo_loss(fn, cfg, sumA, logits, actions, logp_mu, values, rewards, dones, vs, adv, loss,
+                       dlogits_opt, dvalues_opt, (float*)workspace, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int32_t sf_appo_loss_static_max_trajectories(void) { return kStaticMaxTraj; }
+
+extern "C" int sf_appo_loss_static(const sf_loss_config* cfg, const float* logits, const int32_t* actions,
+                                   const float* logp_mu, const float* values, const float* rewards,
+                                   const uint8_t* dones, float* vs, float* adv, float* loss,
+                                   float* dlogits_opt, float* dvalues_opt, void* hip_stream) {
+  static const char* fn = "sf_appo_loss_static";
+  int sumA;
+  int rc = check_loss_config(cfg, fn, &sumA);
+  if (rc != SF_OK) return rc;
+  if (cfg->N > kStaticMaxTraj) {
+    set_error("%s: N = %d trajectories exceed the built-in scratch (%d); use sf_appo_loss with a workspace",
+              fn, cfg->N, kStaticMaxTraj);
+    return SF_ERR_SHAPE;
+  }
+  float* partials = nullptr;
+  rc = static_scratch(fn, &partials);
+  if (rc != SF_OK) return rc;
+  // every trajectory's wave writes its slot before the reduction reads it: nothing to clear
+  return run_appo_loss(fn, cfg, sumA, logits, actions, logp_mu, values, rewards, dones, vs, adv, loss,
+                       dlogits_opt, dvalues_opt, partials, reinterpret_cast<hipStream_t>(hip_stream));
 }
