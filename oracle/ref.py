@@ -11,7 +11,12 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SO = os.path.join(_HERE, "libsf_oracle.so")
+# SF_ORACLE_SANITIZE=1: a second build with AddressSanitizer and UndefinedBehaviorSanitizer (no
+# OpenMP), for running the CPU tests under the sanitizers:
+#   LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 \
+#       SF_ORACLE_SANITIZE=1 python -m pytest tests -m "not gpu"
+_SANITIZE = os.environ.get("SF_ORACLE_SANITIZE", "") not in ("", "0")
+_SO = os.path.join(_HERE, "libsf_oracle_san.so" if _SANITIZE else "libsf_oracle.so")
 _SRC = os.path.join(_HERE, "sf_oracle.c")
 
 MAX_CONV, MAX_STAGE, MAX_HEADS, MAX_CONV_TENSORS = 4, 4, 16, 20
@@ -25,6 +30,10 @@ def build(force=True):
         return _SO
     cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC",
            "-shared", "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
+    if _SANITIZE:
+        cmd = ["gcc", "-O1", "-g", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+               "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+               "-Wall", "-Wextra", "-Wno-unknown-pragmas", "-o", _SO, _SRC, "-lm"]
     subprocess.run(cmd, check=True)
     return _SO
 

@@ -14,7 +14,16 @@ import numpy as np
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 _CSRC = os.path.join(_PKG, "csrc")
-_SO = os.path.join(_PKG, "libsf_policy.so")
+# SF_POLICY_HOST_SANITIZE=1 selects a second build whose HOST code carries AddressSanitizer and
+# UndefinedBehaviorSanitizer (device code unchanged), for running the CPU tests of the host logic:
+#   python -c "from paper_2006_11751_amd import binding; binding.build_library(host_sanitize=True)"
+#   LD_PRELOAD=$(/opt/rocm/lib/llvm/bin/clang -print-file-name=libclang_rt.asan-x86_64.so) \
+#       ASAN_OPTIONS=detect_leaks=0 SF_POLICY_HOST_SANITIZE=1 \
+#       python -m pytest tests/test_abi.py tests/test_host_conv1_admission.py
+# (the host code is compiled by clang and needs clang's sanitizer runtime; the oracle's own
+# sanitizer build uses gcc's, so the two runs are separate)
+_HOST_SANITIZE = os.environ.get("SF_POLICY_HOST_SANITIZE", "") not in ("", "0")
+_SO = os.path.join(_PKG, "libsf_policy_hostsan.so" if _HOST_SANITIZE else "libsf_policy.so")
 
 SF_ABI_VERSION = 2
 SF_MAX_CONV, SF_MAX_STAGE, SF_MAX_HEADS, SF_MAX_CONV_TENSORS = 4, 4, 16, 20
@@ -31,17 +40,24 @@ def library_path():
     return _SO
 
 
-def build_library(verbose=False):
-    """Compile every .hip source for gfx950 and link libsf_policy.so in-tree."""
+HOST_SANITIZE_FLAGS = ["-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                       "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+
+
+def build_library(verbose=False, host_sanitize=False):
+    """Compile every .hip source for gfx950 and link libsf_policy.so in-tree
+    (host_sanitize: libsf_policy_hostsan.so, sanitizers on the host code only)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     srcs = sorted(glob.glob(os.path.join(_CSRC, "*.hip")))
-    objdir = os.path.join(_PKG, "_build")
+    objdir = os.path.join(_PKG, "_build_hostsan" if host_sanitize else "_build")
     os.makedirs(objdir, exist_ok=True)
     inc = ["-I", os.path.join(_ROOT, "include"), "-I", _CSRC]
+    flags = HIPCC_FLAGS + (HOST_SANITIZE_FLAGS if host_sanitize else [])
+    so = os.path.join(_PKG, "libsf_policy_hostsan.so" if host_sanitize else "libsf_policy.so")
     procs = []
     for s in srcs:
         o = os.path.join(objdir, os.path.basename(s) + ".o")
-        cmd = [hipcc] + HIPCC_FLAGS + inc + ["-c", s, "-o", o]
+        cmd = [hipcc] + flags + inc + ["-c", s, "-o", o]
         if verbose:
             print(" ".join(cmd))
         procs.append((s, o, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
@@ -55,9 +71,12 @@ def build_library(verbose=False):
         if verbose and text.strip():
             print(text)
         objs.append(o)
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", _SO] + objs
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", so] + objs
+    if host_sanitize:
+        cmd += ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                "-Xarch_host", "-shared-libsan"]
     subprocess.run(cmd, check=True)
-    return _SO
+    return so
 
 
 class SfConv(C.Structure):
