@@ -258,6 +258,7 @@ Switches read_switches() {
   sw.conv_bf16_tc = env_int("SF_CONV_BF16_TC");
   sw.no_conv1_image = env_set("SF_NO_CONV1_IMAGE");
   sw.no_conv_image = env_set("SF_NO_CONV_IMAGE");
+  sw.no_conv12_fuse = env_set("SF_NO_CONV12_FUSE");
   sw.fc_out_f32 = env_set("SF_FC_OUT_F32");
   sw.no_patch_conv = env_set("SF_NO_PATCH_CONV");
   sw.no_fused_resnet = env_set("SF_NO_FUSED_RESNET");
@@ -474,6 +475,19 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
         out_buf ^= 1;
       }
       p->enc_buf = in_buf;
+      // bf16 configuration of the benchmark shape: the first two layers as one launch (the first
+      // layer's output stays in LDS); its buffer is kept for the cases that run them separately
+      if (cfg->n_conv >= 2 && !sw.no_conv12_fuse && p->convs[0].impl == CONV1_U8_I8 &&
+          p->convs[1].impl == CONV_IMAGE_BF16 &&
+          conv12_fused_bf16_supported(cfg->obs_c, cfg->obs_h, cfg->obs_w, cfg->conv[0], cfg->conv[1])) {
+        Op& a = p->ops[0];
+        const Op b = p->ops[1];
+        a.name = "conv1+conv2";
+        a.flops_per_row += b.flops_per_row;
+        a.mid_buf = a.out_buf;
+        a.out_buf = b.out_buf;
+        p->ops.erase(p->ops.begin() + 1);
+      }
     } else {
       // buffer roles rotate: x holds the stage state, t and u are scratch
       int x = 0, t = 1, u = 2;
@@ -1074,6 +1088,21 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
         const void* in = op.in_buf < 0 ? (const void*)obs : (const void*)buf(op.in_buf);
         switch (L.impl) {
           case CONV1_U8_I8:
+            if (op.mid_buf >= 0) {
+              // first and second layer: one launch where the fused kernel applies (two digit
+              // planes, 16-byte aligned frames), else the two kernels in sequence (same bits)
+              const ConvLayer& L2 = p->convs[op.conv + 1];
+              if (L.planes == 2 && !misaligned(obs, 16)) {
+                SF_LAUNCH(launch_conv12_fused_bf16(L, L2, B, obs, buf(op.out_buf), st));
+              } else {
+                SF_LAUNCH(launch_conv1_i8(L, B, obs, L.ipk, L.spk, L.bpk8, buf(op.mid_buf), 1, L.planes,
+                                          p->conv1_waves, p->conv1_image, st));
+                SF_LAUNCH(launch_conv_image_bf16(buf(op.mid_buf), L2.wbf, L2.bbf, buf(op.out_buf), B, L2.H,
+                                                 L2.W, L2.cin, L2.k, L2.s, L2.Ho, L2.Wo, L2.cout,
+                                                 L2.relu_out, st));
+              }
+              break;
+            }
             SF_LAUNCH(launch_conv1_i8(L, B, obs, L.ipk, L.spk, L.bpk8, buf(op.out_buf), p->bf16_path,
                                       L.planes, p->conv1_waves, p->conv1_image, st));
             break;
@@ -1221,7 +1250,9 @@ extern "C" const char* sf_policy_op_pipe(const sf_policy* handle, int i) {
     case OP_CONV: {
       const ConvLayer& L = p->convs[op.conv];
       switch (L.impl) {
-        case CONV1_U8_I8: return L.planes == 2 ? "i8x2" : "i8x3";
+        case CONV1_U8_I8:
+          if (op.mid_buf >= 0) return L.planes == 2 ? "i8x2+bf16" : "i8x3+bf16";
+          return L.planes == 2 ? "i8x2" : "i8x3";
         case CONV1_U8_MFMA:
         case CONV_GEMM_MFMA: return "f32";
         case CONV_BF16:

@@ -61,6 +61,7 @@ struct Switches {
   int conv_bf16_tc = 0;          // SF_CONV_BF16_TC
   bool no_conv1_image = false;   // SF_NO_CONV1_IMAGE
   bool no_conv_image = false;    // SF_NO_CONV_IMAGE
+  bool no_conv12_fuse = false;   // SF_NO_CONV12_FUSE
   bool fc_out_f32 = false;       // SF_FC_OUT_F32
   bool no_patch_conv = false;    // SF_NO_PATCH_CONV
   bool no_fused_resnet = false;  // SF_NO_FUSED_RESNET
@@ -79,6 +80,8 @@ struct Op {
   int in_buf, out_buf;    // activation buffer indices; in_buf -1 = the observation
   int resid_buf;          // buffer added to the result, or -1
   int C, H, W;            // OP_POOL: input shape
+  int mid_buf = -1;       // first and second convolution in one launch: buffer for the first
+                          // layer's output when the two have to run separately after all
 };
 
 struct Policy {
@@ -249,6 +252,9 @@ void conv_image_bf16_pack(const float* w, int cout, int cin, int k, std::vector<
 hipError_t launch_conv_image_bf16(const void* in, const uint16_t* wpk, const float* bias, void* out,
                                   int B, int H, int W, int Cin, int ksize, int stride, int Ho,
                                   int Wo, int N, int relu, hipStream_t st);
+bool conv12_fused_bf16_supported(int cin, int H, int W, const sf_conv& c1, const sf_conv& c2);
+hipError_t launch_conv12_fused_bf16(const ConvLayer& L1, const ConvLayer& L2, int B, const uint8_t* obs,
+                                    void* out, hipStream_t st);
 bool gemm_mfma_supported(int Cin, int ksize, int pad, int N);
 int gemm_mfma_pick_tile(long long M, int N, int K, int seg_len);
 hipError_t launch_gemm_mfma(const float* A, const float* Wt, const float* bias, float* out, int B,

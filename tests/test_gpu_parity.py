@@ -412,3 +412,44 @@ def test_maximum_batch_size(torch_cuda, ref):
     parity.check_against_oracle(net, {k: v[rows] for k, v in g.items()}, o, ref, 1, 3, rows=rows)
     assert np.all(np.isfinite(g["h_out"])) and np.all(np.abs(g["h_out"]) <= 1.0 + 1e-6)
     pol.close()
+
+
+def test_fused_first_two_layers_equal_the_separate_kernels(torch_cuda, ref, monkeypatch):
+    """bf16 standard network: the launch that runs the first two convolutions with the first
+    layer's image in LDS gives the bits of the two separate kernels, at a batch that makes its
+    workgroups walk several frames with a ragged last round, on a misaligned observation buffer
+    (which takes the separate kernels), and on a second frame shape (76 x 120: 18 x 29 and
+    8 x 13 pixels after the two layers)."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    for net in (wl.network(2, B=1100, name="standard_bf16_1100"),
+                wl.network(2, B=23, name="standard_bf16_76x120", obs=(3, 76, 120))):
+        w = wl.weights(net)
+        B = net["B"]
+        obs, h_in, done = wl.observations(net), wl.initial_state(net), wl.done_mask(net)
+        fused = binding.Policy(net, w)
+        assert fused.op_pipes()[0] == "i8x2+bf16" and [n for n, _ in fused.ops()][0] == "conv1+conv2"
+        g = _gpu_step(torch, fused, obs, h_in, done, 1, 0)
+        monkeypatch.setenv("SF_NO_CONV12_FUSE", "1")
+        plain = binding.Policy(net, w)
+        monkeypatch.delenv("SF_NO_CONV12_FUSE")
+        assert plain.op_pipes()[:2] == ["i8x2", "bf16"]
+        g2 = _gpu_step(torch, plain, obs, h_in, done, 1, 0)
+        for k in g:
+            assert np.array_equal(g[k], g2[k]), (net["name"], k)
+        # observations at an address that is 4-byte but not 16-byte aligned
+        d = fused.device
+        raw = torch.empty(obs.size + 16, dtype=torch.uint8, device=d)
+        t_obs = raw[4:4 + obs.size].view(obs.shape)
+        t_obs.copy_(torch.from_numpy(obs))
+        assert t_obs.data_ptr() % 16 == 4
+        out = fused.step(t_obs, torch.from_numpy(h_in).to(d), torch.from_numpy(done).to(d), 1, 0)
+        torch.cuda.synchronize()
+        for k in g:
+            assert np.array_equal(g[k], out[k].cpu().numpy()), (net["name"], "misaligned", k)
+        rows = np.arange(0, B, max(1, B // 40))
+        o = ref.policy_step(net, w, obs[rows], h_in[rows], done[rows], 1, 0)
+        parity.assert_close("h_out", g["h_out"][rows], o["h_out"], 2e-2)
+        parity.assert_close("value", g["value"][rows], o["value"], 2e-2)
+        fused.close()
+        plain.close()

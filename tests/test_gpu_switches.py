@@ -34,6 +34,7 @@ CASES = [
     ("SF_CONV_BF16_TC", "2", STD_BF16_SMALL),
     ("SF_FC_OUT_F32", "1", STD_BF16_SMALL),
     ("SF_NO_CONV_IMAGE", "1", STD_BF16_SMALL),
+    ("SF_NO_CONV12_FUSE", "1", STD_BF16_SMALL),
     ("SF_NO_RNN_BF16", "1", BY_NAME["lstm_bf16_mfma"]),
     ("SF_NO_FUSED_RESNET", "1", RESNET_BF16_MID),
     ("SF_NO_PATCH_CONV", "1", RESNET_BF16_SMALL),
