@@ -357,7 +357,7 @@ int sf_pipeline_destroy(sf_pipeline* pl);
  *   values   [T+1][N] fp32, row T = bootstrap value;  rewards [T][N] fp32;  dones [T][N] bytes
  *   vs, adv  [T][N] fp32 out;  loss [4] fp32 out = {L_pi, L_v, L_ent, their sum}
  *   dlogits_opt [T][N][sum(head_sizes)], dvalues_opt [T][N] (d/dV_t of L_v) fp32 out, or NULL
- *   workspace   sf_appo_loss_workspace_bytes(cfg) bytes, owned by the caller
+ *   workspace   sf_appo_loss_workspace_bytes(cfg) bytes (16 N + 16), owned by the caller
  * Asynchronous on hip_stream, allocation-free, and bitwise reproducible (the partial sums
  * are added in a fixed order).  Errors: SF_ERR_ARG (null or misaligned pointer, struct_size),
  * SF_ERR_SHAPE (sizes or hyperparameters out of range), SF_ERR_DEVICE. */

@@ -21,6 +21,15 @@ CASES = [
     ("one_sample", wl.loss_config((2,), 1, 1), 6004),
     ("exact_chunk", wl.loss_config((6,), 64, 5), 6005),
     ("large", wl.loss_config((7,), 32, 2048), 6006),
+    # 133 logits per sample: the tiles do not fit LDS, the kernel that reads memory directly runs
+    ("wide_head_direct_kernel", wl.loss_config((130, 3), 20, 5), 6007),
+    # an even number of logits (padded LDS rows, element-wise tile copies), three chunks of 64
+    # steps, and a last workgroup with 3 of its 4 trajectories
+    ("even_width_staged", wl.loss_config((60, 4), 150, 7), 6008),
+    # 32 lanes per trajectory, eight per workgroup, the last workgroup with 3; 16-byte tile copies
+    ("short_trajectories", wl.loss_config((5, 4), 32, 19), 6010),
+    ("short_trajectories_scalar_copies", wl.loss_config((5, 4), 17, 19), 6011),
+    ("full_action_space_large", wl.loss_config((3, 3, 2, 2, 2, 8, 21), 32, 515), 6009),
 ]
 
 
@@ -104,7 +113,7 @@ def test_loss_error_paths(torch_cuda):
         rc = binding.load_library().sf_appo_loss(cfg, *([None] * 13))
         assert rc == code
     cfg = binding.make_loss_config(hp)
-    assert binding.sf_appo_loss_workspace_bytes(cfg) == 2 * 4 * 4
+    assert binding.sf_appo_loss_workspace_bytes(cfg) == 2 * 4 * 4 + 16   # partial sums + alignment room
     assert binding.load_library().sf_appo_loss(cfg, *([None] * 13)) == binding.SF_ERR_ARG
     cfg.struct_size = 8
     assert binding.load_library().sf_appo_loss(cfg, *([None] * 13)) == binding.SF_ERR_ARG
