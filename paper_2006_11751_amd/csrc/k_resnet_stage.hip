@@ -1,0 +1,322 @@
+// All residual blocks of one stage of the residual encoder in one kernel, with the frame
+// resident in LDS (the encoder follows IMPALA; paper, App. DMLab-30):
+//   for every block:  x <- x + conv_b(relu(conv_a(relu(x)))),  3x3 / stride 1 / pad 1 convolutions,
+// fp16 activations, 16-bit MFMA with fp32 accumulation.
+//
+// Run block by block on pixel tiles, every block reads its input from memory with a two-pixel
+// halo, recomputes a one-pixel halo of the branch tensor and writes its output back: at the
+// first stage's size (16 x 36 x 64 per frame, 8192 frames) that is 2.4 GB of traffic for two
+// blocks and a quarter of the first convolution's work done twice.  Here a workgroup of eight
+// waves owns a frame at a time: the residual stream x stays in registers (16-byte pieces, the
+// thread that loaded a piece keeps it), relu(x) and the branch tensor stay in two LDS images
+// with a ring of zero pixels around them (the convolutions' padding), and the frame crosses
+// the memory bus once in each direction.  Per block:
+//   conv_a: X = relu(x) -> T = relu(conv + bias)        (fp16, rounded as it is written)
+//   conv_b: T -> X = conv + bias                         (fp16)
+//   add:    x <- x + X (packed fp16), X <- relu(x) for the next block
+// The next frame's pieces travel into registers meanwhile, and so does the next convolution's
+// filter bank (two register sets in alternation).
+//
+// v_mfma_f32_32x32x16_f16: lane l supplies A[i = l%32][k = 8*(l/32) + e] and
+// B[k = 8*(l/32) + e][j = l%32]; D[i][j] sits in lane j + 32*((i/4)%2), register
+// (i%4) + 4*(i/8).  A = weights (i = output channel, rows >= C are zero), B = pixels: for filter
+// tap (p, q) the B operand of pixel (y, x) is the 16-byte run of 8 channels at image pixel
+// (y + p - 1, x + q - 1).  Frame width a power of two (64, 32 or 16): a 32-pixel tile is half a
+// row, a row or two rows, and a tile's LDS addresses are a per-lane constant plus a term that
+// is the same for all lanes.
+#include <mutex>
+#include <type_traits>
+
+#include "sf_internal.h"
+
+namespace sf {
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kNW = 8;          // waves per workgroup
+constexpr int kNT = 64 * kNW;
+constexpr int kMaxConvs = 8;    // 2 * blocks per stage
+
+__device__ inline unsigned pk_max0(unsigned w) {
+  return __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(f16x2, w), f16x2{0, 0}));
+}
+__device__ inline unsigned pk_add(unsigned a, unsigned b) {
+  return __builtin_bit_cast(unsigned, __builtin_bit_cast(f16x2, a) + __builtin_bit_cast(f16x2, b));
+}
+__device__ inline unsigned pk_f16(float a, float b) {
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, f16x2));
+}
+__device__ inline u32x4 relu8(u32x4 v) {
+  return u32x4{pk_max0(v[0]), pk_max0(v[1]), pk_max0(v[2]), pk_max0(v[3])};
+}
+
+struct StageArgs {
+  const u32x4* x;              // fp16 [B][H][W][C] as 16-byte pieces
+  u32x4* out;                  // the same shape
+  const u32x4* w[kMaxConvs];   // A operands [9][C/16][64] of conv_a, conv_b of every block
+  const float* bias[kMaxConvs];  // [32] each
+  int B, H, n_convs, relu_out;
+};
+
+// C channels (16 or 32), frame width 1 << LW, PPT 16-byte pieces of a frame per thread.
+template <int C, int LW, int PPT>
+__global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
+  constexpr int W = 1 << LW;
+  constexpr int C8 = C / 8, NS = C / 16;
+  // pixel pitch: 32 bytes for 16 channels (32 neighbouring pixels then cover 1 KB without a
+  // gap); 64 + 16 for 32 channels (a pitch of 64 puts lanes l and l + 16 on the same banks)
+  constexpr int PITCH = C == 16 ? 32 : 80;
+  constexpr int ROW = (W + 2) * PITCH;  // image row pitch in bytes, ring included
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 31, lh = lane >> 5;
+  const int npix = g.H * W;
+  const int pieces = npix * C8;
+  const int n_tiles = (npix + 31) >> 5;
+  // image rows: the frame, the ring, and the rows that the lanes of a partial last tile look at
+  // (zeros, like the ring; those lanes store nothing)
+  const int img_bytes = (((n_tiles << 5) + W - 1) / W + 2) * ROW;
+  unsigned char* X = lds;
+  unsigned char* T = lds + img_bytes;
+
+  // both images start as zeros: the ring is never written again
+  for (int i = tid; i < 2 * img_bytes / 16; i += kNT) ((u32x4*)lds)[i] = u32x4{0u, 0u, 0u, 0u};
+
+  // this thread's pieces: LDS byte offset of piece tid + k * kNT (past the end: piece 0, unused)
+  // (shifts and masks: computed where it is used rather than kept in registers)
+  auto poff = [&](int k) {
+    const int p = tid + k * kNT;
+    const int pc = p < pieces ? p : 0;
+    const int pix = pc / C8, c8 = pc - pix * C8;
+    const int y = pix >> LW, x = pix & (W - 1);
+    return ((y + 1) * (W + 2) + x + 1) * PITCH + c8 * 16;
+  };
+  // this lane's pixel of tile 0 (for W >= 32 a tile lies in one row and the others follow by a
+  // uniform step; for W = 16 a tile is two rows): byte offset of image pixel (y, x) of the
+  // ring-less frame = ring pixel (y, x), i.e. the window origin of tap (0, 0)
+  const int lane_pix = (li >> LW) * (W + 2) + (li & (W - 1));
+  const int lane_base = lane_pix * PITCH + lh * 16;
+
+  u32x4 xs[PPT], nx[PPT];
+  auto load_frame = [&](int b, u32x4 (&dst)[PPT]) {
+    const u32x4* src = g.x + (size_t)b * pieces;
+#pragma unroll
+    for (int k = 0; k < PPT; ++k) {
+      const int p = tid + k * kNT;
+      dst[k] = src[p < pieces ? p : pieces - 1];
+    }
+  };
+  u32x4 wA[9][NS], wB[9][NS];
+  auto load_bank = [&](int k, u32x4 (&dst)[9][NS]) {
+    const u32x4* src = g.w[k];
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+      for (int s = 0; s < NS; ++s) dst[tap][s] = src[(tap * NS + s) * 64 + lane];
+  };
+  // the bias of convolution k in the accumulator layout: register 4*q4 + u holds channel
+  // 8*q4 + 4*lh + u
+  auto bias_acc = [&](int k) {
+    f32x16 a;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const f32x4 bv = *(const f32x4*)(g.bias[k] + 8 * q4 + 4 * lh);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) a[4 * q4 + u] = bv[u];
+    }
+    return a;
+  };
+
+  // One convolution over the frame: the wave's tiles wave, wave + 8, ... two at a time (two
+  // independent MFMA chains), from image `src` into image `dst`.
+  auto conv = [&](const u32x4 (&wreg)[9][NS], const f32x16& init, const unsigned char* src,
+                  unsigned char* dst, bool relu) {
+    auto tile_off = [&](int t) {  // byte offset of the tile's first pixel row / half row
+      if (LW >= 5) return ((t << 5) >> LW) * ROW + ((t << 5) & (W - 1)) * PITCH;
+      return (t * (32 >> LW)) * ROW;
+    };
+    auto run = [&](auto cnt, int t0) {
+      constexpr int N = decltype(cnt)::value;
+      f32x16 acc[N];
+      const unsigned char* base[N];
+#pragma unroll
+      for (int n = 0; n < N; ++n) {
+        acc[n] = init;
+        base[n] = src + lane_base + tile_off(t0 + n * kNW);
+      }
+      // K steps (tap, 16-channel group) in order; the pixel fragment of step k + 2 is requested
+      // right behind the MFMA of step k (two register sets per tile), so that an LDS read has
+      // 2 * N MFMAs to come back in.  (Left alone, the scheduler sinks each read to its use.)
+      // One 16-byte read per MFMA is what bounds this loop: the four SIMDs of a CU share the
+      // LDS, which measured 16 cycles per such read against 32 cycles per MFMA.  (Sharing one
+      // read among a filter row's three taps by moving fragments down one lane with DPP, the
+      // last lane of each 16-lane row fetching its own pixel, was tried: correct, but the moves,
+      // the masked reads and 30 more registers made the kernel 25 % slower.)
+      constexpr int S = 9 * NS;
+      auto frag_off = [&](int k) {
+        const int tap = k / NS, sg = k - tap * NS;
+        return (tap / 3) * ROW + (tap % 3) * PITCH + sg * 32;
+      };
+      u32x4 pf[2][N];
+#pragma unroll
+      for (int n = 0; n < N; ++n) {
+        pf[0][n] = *(const u32x4*)(base[n] + frag_off(0));
+        pf[1][n] = *(const u32x4*)(base[n] + frag_off(1));
+      }
+#pragma unroll
+      for (int k = 0; k < S; ++k) {
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+          acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, wreg[k / NS][k % NS]),
+                                                          __builtin_bit_cast(f16x8, pf[k & 1][n]), acc[n], 0, 0, 0);
+          if (k + 2 < S) pf[k & 1][n] = *(const u32x4*)(base[n] + frag_off(k + 2));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+#pragma unroll
+      for (int n = 0; n < N; ++n) {
+        const int t = t0 + n * kNW;
+        if ((t << 5) + li >= npix) continue;  // (a last tile may be partial)
+        // the lane's pixel in dst: ring pixel (y + 1, x + 1)
+        unsigned char* o = dst + lane_pix * PITCH + tile_off(t) + ROW + PITCH;
+#pragma unroll
+        for (int q4 = 0; q4 < C8; ++q4) {
+          u32x2 ov;
+          ov[0] = pk_f16(acc[n][4 * q4 + 0], acc[n][4 * q4 + 1]);
+          ov[1] = pk_f16(acc[n][4 * q4 + 2], acc[n][4 * q4 + 3]);
+          if (relu) {
+            ov[0] = pk_max0(ov[0]);
+            ov[1] = pk_max0(ov[1]);
+          }
+          *(u32x2*)(o + (8 * q4 + 4 * lh) * 2) = ov;
+        }
+      }
+    };
+    int t = wave;
+    for (; t + kNW < n_tiles; t += 2 * kNW) run(std::integral_constant<int, 2>{}, t);
+    if (t < n_tiles) run(std::integral_constant<int, 1>{}, t);
+  };
+
+  int b = blockIdx.x;
+  load_frame(b, xs);
+  load_bank(0, wA);
+  __syncthreads();  // zeros in place
+  for (; b < g.B; b += gridDim.x) {
+#pragma unroll
+    for (int k = 0; k < PPT; ++k)
+      if (tid + k * kNT < pieces) *(u32x4*)(X + poff(k)) = relu8(xs[k]);
+    __syncthreads();
+    load_frame(b + (int)gridDim.x < g.B ? b + (int)gridDim.x : b, nx);  // (last round: its own again)
+    for (int k = 0; k < g.n_convs; k += 2) {
+      // conv_a of the block: X -> T, ReLU; conv_b's bank arrives meanwhile
+      load_bank(k + 1, wB);
+      conv(wA, bias_acc(k), X, T, true);
+      __syncthreads();
+      // conv_b: T -> X; the next conv_a's bank (the next block's, or the first of the next frame)
+      load_bank(k + 2 < g.n_convs ? k + 2 : 0, wA);
+      conv(wB, bias_acc(k + 1), T, X, false);
+      __syncthreads();
+      // x <- x + branch; X <- relu(x) unless this was the last block
+      const bool more = k + 2 < g.n_convs;
+#pragma unroll
+      for (int kk = 0; kk < PPT; ++kk) {
+        if (tid + kk * kNT < pieces) {
+          const u32x4 u = *(const u32x4*)(X + poff(kk));
+          u32x4 y;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) y[e] = pk_add(xs[kk][e], u[e]);
+          xs[kk] = y;
+          if (more) *(u32x4*)(X + poff(kk)) = relu8(y);
+        }
+      }
+      if (more) __syncthreads();
+    }
+    u32x4* dst = g.out + (size_t)b * pieces;
+#pragma unroll
+    for (int k = 0; k < PPT; ++k)
+      if (tid + k * kNT < pieces) dst[tid + k * kNT] = g.relu_out ? relu8(xs[k]) : xs[k];
+#pragma unroll
+    for (int k = 0; k < PPT; ++k) xs[k] = nx[k];
+  }
+}
+
+size_t stage_lds_bytes(int c, int H, int W) {
+  const int pitch = c == 16 ? 32 : 80;
+  const int n_tiles = (H * W + 31) / 32;
+  const int rows = (n_tiles * 32 + W - 1) / W + 2;  // as in the kernel
+  return 2 * (size_t)rows * (W + 2) * pitch;
+}
+
+template <int C, int LW, int PPT>
+hipError_t launch_stage_t(const StageArgs& g, size_t lds, hipStream_t st) {
+  auto kern = res_stage_kernel<C, LW, PPT>;
+  static std::once_flag once;
+  static hipError_t attr_status = hipSuccess;
+  std::call_once(once, [&] {
+    attr_status = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  });
+  if (attr_status != hipSuccess) return attr_status;
+  // one workgroup per CU, each walking its share of the frames
+  const int blocks = g.B < 256 ? g.B : 256;
+  kern<<<blocks, kNT, lds, st>>>(g);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Shapes: 16 or 32 channels, frame width 16, 32 or 64, both LDS images within 160 KB, at most
+// nine 16-byte pieces of the frame per thread, one to four blocks; and at least one 32-pixel
+// tile per wave (smaller frames leave waves idle: the per-block tile kernels are faster there,
+// measured on the 9 x 16 frames of the benchmark's last stage).
+bool res_stage_supported(int c, int H, int W, int n_blocks) {
+  if ((c != 16 && c != 32) || (W != 16 && W != 32 && W != 64) || H < 1) return false;
+  if ((H * W + 31) / 32 < kNW) return false;
+  if (n_blocks < 1 || 2 * n_blocks > kMaxConvs) return false;
+  if (stage_lds_bytes(c, H, W) > 160 * 1024) return false;
+  const int pieces = H * W * c / 8;
+  return (pieces + kNT - 1) / kNT <= 9;
+}
+
+// x, out: fp16 [B][H][W][c] (may be the same buffer: a workgroup reads a frame before it
+// writes it, and frames are not shared); wpk[k], bias[k]: the stage's block convolutions in
+// order (conv_a, conv_b of block 1, ...), packed as for the patch kernels with fp16 weights.
+hipError_t launch_res_stage(const void* x, void* out, const uint16_t* const* wpk, const float* const* bias,
+                            int n_convs, int B, int H, int W, int c, int relu_out, hipStream_t st) {
+  if ((long long)B * H * W == 0) return hipSuccess;
+  if (!res_stage_supported(c, H, W, n_convs / 2) || (n_convs & 1)) return hipErrorInvalidValue;
+  StageArgs g;
+  g.x = (const u32x4*)x; g.out = (u32x4*)out;
+  for (int k = 0; k < kMaxConvs; ++k) {
+    g.w[k] = (const u32x4*)wpk[k < n_convs ? k : 0];
+    g.bias[k] = bias[k < n_convs ? k : 0];
+  }
+  g.B = B; g.H = H; g.n_convs = n_convs; g.relu_out = relu_out;
+  const size_t lds = stage_lds_bytes(c, H, W);
+  const int ppt = (H * W * c / 8 + kNT - 1) / kNT;
+#define SF_STAGE(C, LW)                                                    \
+  do {                                                                     \
+    if (ppt <= 2) return launch_stage_t<C, LW, 2>(g, lds, st);             \
+    if (ppt <= 5) return launch_stage_t<C, LW, 5>(g, lds, st);             \
+    return launch_stage_t<C, LW, 9>(g, lds, st);                           \
+  } while (0)
+  if (c == 16) {
+    if (W == 64) SF_STAGE(16, 6);
+    if (W == 32) SF_STAGE(16, 5);
+    SF_STAGE(16, 4);
+  }
+  if (W == 64) SF_STAGE(32, 6);
+  if (W == 32) SF_STAGE(32, 5);
+  SF_STAGE(32, 4);
+#undef SF_STAGE
+}
+
+}  // namespace sf

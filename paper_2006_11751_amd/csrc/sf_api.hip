@@ -262,6 +262,7 @@ Switches read_switches() {
   sw.fc_out_f32 = env_set("SF_FC_OUT_F32");
   sw.no_patch_conv = env_set("SF_NO_PATCH_CONV");
   sw.no_fused_resnet = env_set("SF_NO_FUSED_RESNET");
+  sw.no_res_stage = env_set("SF_NO_RES_STAGE");
   sw.act_bf16 = env_set("SF_ACT_BF16");
   sw.stream_f32 = env_set("SF_STREAM_F32");
   return sw;
@@ -518,6 +519,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
           H = (H - 1) / 2 + 1;
           W = (W - 1) / 2 + 1;
         }
+        const size_t first_block_op = p->ops.size();
         for (int b = 0; b < cfg->blocks_per_stage; ++b) {
           bool last = (s == cfg->n_stage - 1) && (b == cfg->blocks_per_stage - 1);
           snprintf(name, sizeof(name), "stage%d.block%d.conv_a", s + 1, b + 1);
@@ -538,6 +540,34 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
           int tmp = x;
           x = u;
           u = tmp;
+        }
+        // all blocks of the stage as one launch with the frame resident in LDS
+        if (fuse && !sw.no_res_stage && cfg->blocks_per_stage >= 1 &&
+            p->ops.size() - first_block_op == (size_t)cfg->blocks_per_stage &&
+            res_stage_supported(cfg->stage_ch[s], H, W, cfg->blocks_per_stage)) {
+          Op merged = p->ops[first_block_op];
+          bool all_blocks = true;
+          int64_t fl = 0;
+          for (size_t i = first_block_op; i < p->ops.size(); ++i) {
+            all_blocks = all_blocks && p->convs[p->ops[i].conv].impl == RES_BLOCK;
+            fl += p->ops[i].flops_per_row;
+          }
+          if (all_blocks) {
+            snprintf(name, sizeof(name), "stage%d.blocks", s + 1);
+            merged.name = name;
+            merged.flops_per_row = fl;
+            merged.n_sub = 2 * cfg->blocks_per_stage;
+            // the stage's output goes to a buffer other than its input
+            if (x == merged.in_buf) {
+              const int tmp = x;
+              x = t;
+              t = tmp;
+            }
+            merged.out_buf = x;
+            p->convs[merged.conv].impl = RES_STAGE;
+            p->ops.resize(first_block_op);
+            p->ops.push_back(merged);
+          }
         }
         in_buf = x;
       }
@@ -1134,6 +1164,17 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
             SF_LAUNCH(launch_conv3x3_pool(in, L.wbf, L.bbf, buf(op.out_buf), B, L.H, L.W, L.cin, L.cout,
                                           c.obs_sub, c.obs_mul, st));
             break;
+          case RES_STAGE: {
+            const uint16_t* wpk[SF_MAX_CONV_TENSORS];
+            const float* bias[SF_MAX_CONV_TENSORS];
+            for (int k = 0; k < op.n_sub; ++k) {
+              wpk[k] = p->convs[op.conv + k].wbf;
+              bias[k] = p->convs[op.conv + k].bbf;
+            }
+            SF_LAUNCH(launch_res_stage(in, buf(op.out_buf), wpk, bias, op.n_sub, B, L.H, L.W, L.cin,
+                                       p->convs[op.conv + op.n_sub - 1].relu_out, st));
+            break;
+          }
           case RES_BLOCK: {
             const ConvLayer& Lb = p->convs[op.conv + 1];
             SF_LAUNCH(launch_res_block(in, L.wbf, L.bbf, Lb.wbf, Lb.bbf, buf(op.out_buf), B, L.H, L.W,
@@ -1260,6 +1301,7 @@ extern "C" const char* sf_policy_op_pipe(const sf_policy* handle, int i) {
         case CONV3X3_STEM:
         case CONV3X3_POOL:
         case RES_BLOCK:
+        case RES_STAGE:
         case CONV_IMAGE_BF16: return mfma16;
         default: return "valu";
       }

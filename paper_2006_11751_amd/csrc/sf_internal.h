@@ -43,6 +43,7 @@ enum ConvImpl {
   CONV3X3_STEM = 7,     // first convolution of the residual encoder on the 16-bit MFMA
   CONV3X3_POOL = 8,     // stage convolution fused with the max-pool behind it
   RES_BLOCK = 9,        // a whole residual block (this layer and the next) in one kernel
+  RES_STAGE = 11,       // all residual blocks of a stage in one kernel, frame resident in LDS
   CONV_IMAGE_BF16 = 10  // 16-bit MFMA with the frame's input image resident in LDS
 };
 
@@ -65,6 +66,7 @@ struct Switches {
   bool fc_out_f32 = false;       // SF_FC_OUT_F32
   bool no_patch_conv = false;    // SF_NO_PATCH_CONV
   bool no_fused_resnet = false;  // SF_NO_FUSED_RESNET
+  bool no_res_stage = false;     // SF_NO_RES_STAGE
   bool act_bf16 = false;         // SF_ACT_BF16
   bool stream_f32 = false;       // SF_STREAM_F32
 };
@@ -80,6 +82,7 @@ struct Op {
   int in_buf, out_buf;    // activation buffer indices; in_buf -1 = the observation
   int resid_buf;          // buffer added to the result, or -1
   int C, H, W;            // OP_POOL: input shape
+  int n_sub = 0;          // RES_STAGE: convolutions covered (2 per block)
   int mid_buf = -1;       // first and second convolution in one launch: buffer for the first
                           // layer's output when the two have to run separately after all
 };
@@ -227,6 +230,9 @@ bool res_block_supported(int c);
 hipError_t launch_res_block(const void* x, const uint16_t* wa, const float* ba, const uint16_t* wb,
                             const float* bb, void* out, int B, int H, int W, int c, int relu_out,
                             hipStream_t st);
+bool res_stage_supported(int c, int H, int W, int n_blocks);
+hipError_t launch_res_stage(const void* x, void* out, const uint16_t* const* wpk, const float* const* bias,
+                            int n_convs, int B, int H, int W, int c, int relu_out, hipStream_t st);
 bool conv3x3_stem_supported(int cin, int cout);
 void conv3x3_stem_pack(const float* w, const float* bias, int cout, bool f16,
                        std::vector<uint16_t>& wpk, std::vector<float>& b32);

@@ -60,6 +60,13 @@ RESNET_BF16_SMALL = dict(name="resnet_bf16_small", B=7, obs=(3, 20, 28), encoder
 RESNET_BF16_MID = dict(RESNET_BF16_SMALL, name="resnet_bf16_mid", B=3, obs=(3, 50, 76))
 # width not a multiple of 4 (byte planes not dword-aligned), channel counts 32 -> 16 -> 32
 RESNET_BF16_MIX = dict(RESNET_BF16_SMALL, name="resnet_bf16_mix", B=4, obs=(3, 30, 42), stages=[32, 16, 32])
+# stage frames of 24 x 64 (16 channels) and 12 x 32 (32 channels): the kernel that runs all blocks
+# of a stage with the frame resident in LDS; more frames than its workgroups (256), so some walk
+# two frames.  (The last stage, 6 x 16, is too small for it and takes the per-block kernels.)
+RESNET_BF16_POW2 = dict(RESNET_BF16_SMALL, name="resnet_bf16_pow2", B=300, obs=(3, 48, 128))
+# 136 x 128 frames: the first two stages are too large for that kernel, the last (17 x 16 pixels:
+# two image rows per MFMA tile, the ninth tile half empty) runs on it
+RESNET_BF16_TALL = dict(RESNET_BF16_SMALL, name="resnet_bf16_tall", B=5, obs=(3, 136, 128))
 STD_BF16_SMALL = wl.network(2, B=37, name="standard_bf16_small")
 # 76x132 frames: conv2 has 8x15 = 120 output pixels (the eight-tile instantiation of the
 # frame-resident kernel), conv3 3x7 = 21 (more than that kernel takes: tiled kernel)
@@ -67,7 +74,7 @@ STD_BF16_WIDE = dict(STD_BF16_SMALL, name="standard_bf16_wide", B=9, obs=(3, 76,
 
 
 @pytest.mark.parametrize("net", [SMALL_RESNET, ODD_NET, RESNET_BF16_SMALL, RESNET_BF16_MID, RESNET_BF16_MIX,
-                                 STD_BF16_SMALL, STD_BF16_WIDE],
+                                 RESNET_BF16_POW2, RESNET_BF16_TALL, STD_BF16_SMALL, STD_BF16_WIDE],
                          ids=lambda n: n["name"])
 def test_small_networks_all_elements(torch_cuda, ref, net):
     torch = torch_cuda
@@ -76,7 +83,7 @@ def test_small_networks_all_elements(torch_cuda, ref, net):
     obs, h_in, done = wl.observations(net, 0, B), wl.initial_state(net, B), wl.done_mask(net, 0, B)
     g = _gpu_step(torch, pol, obs, h_in, done, 7, 11)
     o = ref.policy_step(net, w, obs, h_in, done, 7, 11)
-    parity.check_against_oracle(net, g, o, ref, 7, 11)
+    print(net["name"], [n for n, _ in pol.ops()], parity.check_against_oracle(net, g, o, ref, 7, 11))
     pol.close()
 
 

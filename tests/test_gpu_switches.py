@@ -10,7 +10,7 @@ import pytest
 
 from paper_2006_11751_amd import workloads as wl
 from tests import parity
-from tests.test_gpu_parity import RESNET_BF16_MID, RESNET_BF16_SMALL, _make, _to_np
+from tests.test_gpu_parity import RESNET_BF16_MID, RESNET_BF16_POW2, RESNET_BF16_SMALL, _make, _to_np
 from tests.test_gpu_core import NETS
 
 pytestmark = pytest.mark.gpu
@@ -37,6 +37,7 @@ CASES = [
     ("SF_NO_CONV12_FUSE", "1", STD_BF16_SMALL),
     ("SF_NO_RNN_BF16", "1", BY_NAME["lstm_bf16_mfma"]),
     ("SF_NO_FUSED_RESNET", "1", RESNET_BF16_MID),
+    ("SF_NO_RES_STAGE", "1", dict(RESNET_BF16_POW2, B=9)),
     ("SF_NO_PATCH_CONV", "1", RESNET_BF16_SMALL),
     ("SF_STREAM_F32", "1", RESNET_BF16_SMALL),
 ]
