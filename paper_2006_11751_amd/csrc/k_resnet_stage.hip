@@ -153,9 +153,9 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
         acc[n] = init;
         base[n] = src + lane_base + tile_off(t0 + n * kNW);
       }
-      // K steps (tap, 16-channel group) in order; the pixel fragment of step k + 2 is requested
-      // right behind the MFMA of step k (two register sets per tile), so that an LDS read has
-      // 2 * N MFMAs to come back in.  (Left alone, the scheduler sinks each read to its use.)
+      // K steps (tap, 16-channel group) in order; the pixel fragment of step k + D is requested
+      // right behind the MFMA of step k (D register sets per tile), so that an LDS read has
+      // D * N MFMAs to come back in.  (Left alone, the scheduler sinks each read to its use.)
       // One 16-byte read per MFMA is what bounds this loop: the four SIMDs of a CU share the
       // LDS, which measured 16 cycles per such read against 32 cycles per MFMA.  (Sharing one
       // read among a filter row's three taps by moving fragments down one lane with DPP, the
@@ -166,19 +166,20 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
         const int tap = k / NS, sg = k - tap * NS;
         return (tap / 3) * ROW + (tap % 3) * PITCH + sg * 32;
       };
-      u32x4 pf[2][N];
+      // (D register sets: two, or one where nine pieces per thread leave no room for the second)
+      constexpr int D = PPT >= 9 ? 1 : 2;
+      u32x4 pf[D][N];
 #pragma unroll
-      for (int n = 0; n < N; ++n) {
-        pf[0][n] = *(const u32x4*)(base[n] + frag_off(0));
-        pf[1][n] = *(const u32x4*)(base[n] + frag_off(1));
-      }
+      for (int n = 0; n < N; ++n)
+#pragma unroll
+        for (int d = 0; d < D; ++d) pf[d][n] = *(const u32x4*)(base[n] + frag_off(d));
 #pragma unroll
       for (int k = 0; k < S; ++k) {
 #pragma unroll
         for (int n = 0; n < N; ++n) {
           acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, wreg[k / NS][k % NS]),
-                                                          __builtin_bit_cast(f16x8, pf[k & 1][n]), acc[n], 0, 0, 0);
-          if (k + 2 < S) pf[k & 1][n] = *(const u32x4*)(base[n] + frag_off(k + 2));
+                                                          __builtin_bit_cast(f16x8, pf[k % D][n]), acc[n], 0, 0, 0);
+          if (k + D < S) pf[k % D][n] = *(const u32x4*)(base[n] + frag_off(k + D));
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -201,9 +202,14 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
         }
       }
     };
+    // (32 channels with five or more pieces per thread: two filter banks of 72 registers and
+    // the frame's pieces leave no room for a second tile's accumulators; spills would go to
+    // memory, 260 MB per launch at the benchmark's second stage)
+    constexpr bool kPairs = !(C == 32 && PPT >= 5);
     int t = wave;
-    for (; t + kNW < n_tiles; t += 2 * kNW) run(std::integral_constant<int, 2>{}, t);
-    if (t < n_tiles) run(std::integral_constant<int, 1>{}, t);
+    if (kPairs)
+      for (; t + kNW < n_tiles; t += 2 * kNW) run(std::integral_constant<int, 2>{}, t);
+    for (; t < n_tiles; t += kNW) run(std::integral_constant<int, 1>{}, t);
   };
 
   int b = blockIdx.x;

@@ -73,7 +73,7 @@ def main():
         raise SystemExit("the two runs end in different kernels:\n%s\n%s" % (kf, kw))
     entry = {"workload": a["config"]["name"], "B": a["config"]["B"], "source_hash": a["config"]["source_hash"],
              "profile": args.profile, "fetch_scale": round(sf, 4), "write_scale": round(sw, 4),
-             "ops": [{"op": op, "pipe": pipe, "kernel": k.split("(")[0][:120], "fetch_kib": round(f, 1),
+             "ops": [{"op": op, "pipe": pipe, "kernel": k.replace("(anonymous namespace)::", "").replace("void ", "").split("(")[0][:120], "fetch_kib": round(f, 1),
                       "write_kib": round(wv, 1), "hbm_kib": round(f + wv, 1)}
                      for (op, pipe), k, f, wv in zip(ops, kf, fetch, write)]}
     table = []
