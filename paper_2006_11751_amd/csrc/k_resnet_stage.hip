@@ -72,9 +72,16 @@ template <int C, int LW, int PPT>
 __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
   constexpr int W = 1 << LW;
   constexpr int C8 = C / 8, NS = C / 16;
-  // pixel pitch: 32 bytes for 16 channels (32 neighbouring pixels then cover 1 KB without a
-  // gap); 64 + 16 for 32 channels (a pitch of 64 puts lanes l and l + 16 on the same banks)
+  // Pixel pitch: 64 + 16 bytes for 32 channels, 32 bytes for 16 channels (a pitch of 48 would
+  // not leave room for two images of the benchmark's first stage).  Measured on gfx950 with all
+  // 16 waves of a CU reading: a 16-byte-per-lane read takes 4 cycles when the lanes' addresses
+  // are 16, 48 or 80 bytes apart, 8 at 32 and 16 at 64 (bank conflicts).  At pitch 32 the two
+  // 16-byte halves of a pixel are therefore swapped in every second group of eight pixels (bit
+  // 3 of the pixel's column): reads are back at 4 cycles and the 8-byte accumulator stores take
+  // 8 cycles instead of 16.
   constexpr int PITCH = C == 16 ? 32 : 80;
+  constexpr bool SWZ = C == 16;
+  auto swz = [](int col) { return SWZ ? ((col >> 3) & 1) << 4 : 0; };
   constexpr int ROW = (W + 2) * PITCH;  // image row pitch in bytes, ring included
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -87,9 +94,12 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
   const int img_bytes = (((n_tiles << 5) + W - 1) / W + 2) * ROW;
   unsigned char* X = lds;
   unsigned char* T = lds + img_bytes;
+  float* bias_lds = (float*)(lds + 2 * img_bytes);  // [n_convs][32]: a convolution's first MFMA
+                                                    // must not wait for a load from memory
 
   // both images start as zeros: the ring is never written again
   for (int i = tid; i < 2 * img_bytes / 16; i += kNT) ((u32x4*)lds)[i] = u32x4{0u, 0u, 0u, 0u};
+  for (int i = tid; i < g.n_convs * 32; i += kNT) bias_lds[i] = g.bias[i >> 5][i & 31];
 
   // this thread's pieces: LDS byte offset of piece tid + k * kNT (past the end: piece 0, unused)
   // (shifts and masks: computed where it is used rather than kept in registers)
@@ -98,20 +108,32 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
     const int pc = p < pieces ? p : 0;
     const int pix = pc / C8, c8 = pc - pix * C8;
     const int y = pix >> LW, x = pix & (W - 1);
-    return ((y + 1) * (W + 2) + x + 1) * PITCH + c8 * 16;
+    return ((y + 1) * (W + 2) + x + 1) * PITCH + ((c8 * 16) ^ swz(x + 1));
   };
   // this lane's pixel of tile 0 (for W >= 32 a tile lies in one row and the others follow by a
   // uniform step; for W = 16 a tile is two rows): byte offset of image pixel (y, x) of the
   // ring-less frame = ring pixel (y, x), i.e. the window origin of tap (0, 0)
-  const int lane_pix = (li >> LW) * (W + 2) + (li & (W - 1));
-  const int lane_base = lane_pix * PITCH + lh * 16;
+  const int lane_row = (li >> LW) * ROW, lane_col = li & (W - 1);
+  // fragment of filter column q: ring column lane_col + q (tile columns start at multiples of
+  // 16, so the swizzle bit is that of lane_col + q); accumulator store of channel quad q4:
+  // ring column lane_col + 1
+  int lane_q[3], lane_o[C8];
+#pragma unroll
+  for (int q = 0; q < 3; ++q) lane_q[q] = lane_row + (lane_col + q) * PITCH + ((lh * 16) ^ swz(lane_col + q));
+#pragma unroll
+  for (int q4 = 0; q4 < C8; ++q4)
+    lane_o[q4] = lane_row + ROW + (lane_col + 1) * PITCH + (((q4 * 16) ^ swz(lane_col + 1)) + lh * 8);
 
   u32x4 xs[PPT], nx[PPT];
   auto load_frame = [&](int b, u32x4 (&dst)[PPT]) {
     const u32x4* src = g.x + (size_t)b * pieces;
 #pragma unroll
     for (int k = 0; k < PPT; ++k) {
-      const int p = tid + k * kNT;
+      // (an opaque move keeps the index from being computed ahead of the frame loop, where it
+      // would be spilled: its reload would wait for the previous frame's stores to complete)
+      int p = tid;
+      asm volatile("" : "+v"(p));
+      p += k * kNT;
       dst[k] = src[p < pieces ? p : pieces - 1];
     }
   };
@@ -129,7 +151,7 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
     f32x16 a;
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
-      const f32x4 bv = *(const f32x4*)(g.bias[k] + 8 * q4 + 4 * lh);
+      const f32x4 bv = *(const f32x4*)(bias_lds + 32 * k + 8 * q4 + 4 * lh);
 #pragma unroll
       for (int u = 0; u < 4; ++u) a[4 * q4 + u] = bv[u];
     }
@@ -151,7 +173,7 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
 #pragma unroll
       for (int n = 0; n < N; ++n) {
         acc[n] = init;
-        base[n] = src + lane_base + tile_off(t0 + n * kNW);
+        base[n] = src + tile_off(t0 + n * kNW);
       }
       // K steps (tap, 16-channel group) in order; the pixel fragment of step k + D is requested
       // right behind the MFMA of step k (D register sets per tile), so that an LDS read has
@@ -164,7 +186,7 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
       constexpr int S = 9 * NS;
       auto frag_off = [&](int k) {
         const int tap = k / NS, sg = k - tap * NS;
-        return (tap / 3) * ROW + (tap % 3) * PITCH + sg * 32;
+        return lane_q[tap % 3] + (tap / 3) * ROW + sg * 32;
       };
       // (D register sets: two, or one where nine pieces per thread leave no room for the second)
       constexpr int D = PPT >= 9 ? 1 : 2;
@@ -188,7 +210,7 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
         const int t = t0 + n * kNW;
         if ((t << 5) + li >= npix) continue;  // (a last tile may be partial)
         // the lane's pixel in dst: ring pixel (y + 1, x + 1)
-        unsigned char* o = dst + lane_pix * PITCH + tile_off(t) + ROW + PITCH;
+        unsigned char* o = dst + tile_off(t);
 #pragma unroll
         for (int q4 = 0; q4 < C8; ++q4) {
           u32x2 ov;
@@ -198,7 +220,7 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
             ov[0] = pk_max0(ov[0]);
             ov[1] = pk_max0(ov[1]);
           }
-          *(u32x2*)(o + (8 * q4 + 4 * lh) * 2) = ov;
+          *(u32x2*)(o + lane_o[q4]) = ov;
         }
       }
     };
@@ -231,25 +253,35 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
       load_bank(k + 2 < g.n_convs ? k + 2 : 0, wA);
       conv(wB, bias_acc(k + 1), T, X, false);
       __syncthreads();
-      // x <- x + branch; X <- relu(x) unless this was the last block
+      // x <- x + branch; X <- relu(x) unless this was the last block.  Three pieces at a time:
+      // their reads first, then the arithmetic and the writes (one LDS latency per three pieces).
       const bool more = k + 2 < g.n_convs;
 #pragma unroll
-      for (int kk = 0; kk < PPT; ++kk) {
-        if (tid + kk * kNT < pieces) {
-          const u32x4 u = *(const u32x4*)(X + poff(kk));
-          u32x4 y;
+      for (int k0 = 0; k0 < PPT; k0 += 3) {
+        u32x4 u[3];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) y[e] = pk_add(xs[kk][e], u[e]);
-          xs[kk] = y;
-          if (more) *(u32x4*)(X + poff(kk)) = relu8(y);
-        }
+        for (int j = 0; j < 3; ++j)
+          if (k0 + j < PPT) u[j] = *(const u32x4*)(X + poff(k0 + j));
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+          if (k0 + j < PPT) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) xs[k0 + j][e] = pk_add(xs[k0 + j][e], u[j][e]);
+            if (more && tid + (k0 + j) * kNT < pieces) *(u32x4*)(X + poff(k0 + j)) = relu8(xs[k0 + j]);
+          }
       }
       if (more) __syncthreads();
     }
+    // (the piece index goes through an opaque move: offsets computed ahead of the loop would be
+    // spilled, and a reload between two stores waits for the first store to complete)
     u32x4* dst = g.out + (size_t)b * pieces;
 #pragma unroll
-    for (int k = 0; k < PPT; ++k)
-      if (tid + k * kNT < pieces) dst[tid + k * kNT] = g.relu_out ? relu8(xs[k]) : xs[k];
+    for (int k = 0; k < PPT; ++k) {
+      int p = tid;
+      asm volatile("" : "+v"(p));
+      p += k * kNT;
+      if (p < pieces) dst[p] = g.relu_out ? relu8(xs[k]) : xs[k];
+    }
 #pragma unroll
     for (int k = 0; k < PPT; ++k) xs[k] = nx[k];
   }
@@ -259,7 +291,7 @@ size_t stage_lds_bytes(int c, int H, int W) {
   const int pitch = c == 16 ? 32 : 80;
   const int n_tiles = (H * W + 31) / 32;
   const int rows = (n_tiles * 32 + W - 1) / W + 2;  // as in the kernel
-  return 2 * (size_t)rows * (W + 2) * pitch;
+  return 2 * (size_t)rows * (W + 2) * pitch + kMaxConvs * 32 * sizeof(float);  // + the biases
 }
 
 template <int C, int LW, int PPT>
