@@ -177,6 +177,12 @@ int sf_policy_create(const sf_policy_config* cfg, const sf_policy_weights* weigh
  * channel's E_fix / E_ref for 2 or 3 planes (0 if the layer has another shape, -1 for a
  * null handle). */
 const char* sf_policy_op_pipe(const sf_policy* p, int i); /* static storage; "" if out of range */
+/* The kernel family launch i runs, for tests and benchmarks that must know which code path a
+ * shape took: one of "generic", "conv1_mfma", "gemm_mfma", "conv1_i8", "conv_bf16",
+ * "conv3x3_u8", "conv3x3_patch", "conv3x3_stem", "conv3x3_pool", "stem_pool", "res_block",
+ * "res_stage", "conv_image_bf16", "conv12_fused" for a convolution launch, and "pool", "fc",
+ * "meas", "rnn", "heads" for the others.  Static storage; "" if out of range or null. */
+const char* sf_policy_op_kernel(const sf_policy* p, int i);
 double sf_policy_conv1_fixed_point_ratio(const sf_policy* p, int planes);
 /* The same test on a filter bank alone, on the host (no device is touched): conv_w host
  * [32][cin][8][8] fp32, cin 1, 3 or 4; dtype SF_DTYPE_FP32 or SF_DTYPE_BF16 (the taps are

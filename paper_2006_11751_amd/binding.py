@@ -125,7 +125,7 @@ EXPORTS = ("sf_policy_create", "sf_policy_step", "sf_policy_destroy", "sf_last_e
            "sf_pipeline_wait", "sf_pipeline_destroy", "sf_policy_state_dim",
            "sf_policy_update_weights", "sf_appo_loss", "sf_appo_loss_workspace_bytes",
            "sf_policy_op_pipe", "sf_policy_conv1_fixed_point_ratio", "sf_conv1_fixed_point_test",
-           "sf_appo_loss_static", "sf_appo_loss_static_max_trajectories")
+           "sf_appo_loss_static", "sf_appo_loss_static_max_trajectories", "sf_policy_op_kernel")
 
 _lib = None
 
@@ -181,6 +181,8 @@ def load_library():
         L.sf_policy_op_flops_per_row.argtypes = [C.c_void_p, C.c_int]
         L.sf_policy_op_pipe.restype = C.c_char_p
         L.sf_policy_op_pipe.argtypes = [C.c_void_p, C.c_int]
+        L.sf_policy_op_kernel.restype = C.c_char_p
+        L.sf_policy_op_kernel.argtypes = [C.c_void_p, C.c_int]
         L.sf_policy_conv1_fixed_point_ratio.restype = C.c_double
         L.sf_policy_conv1_fixed_point_ratio.argtypes = [C.c_void_p, C.c_int]
         L.sf_conv1_fixed_point_test.restype = C.c_int
@@ -454,6 +456,12 @@ class Policy:
         """The arithmetic of each launch: "i8x3", "i8x2", "f32", "bf16", "f16" or "valu"."""
         L = load_library()
         return [L.sf_policy_op_pipe(self.handle, i).decode()
+                for i in range(L.sf_policy_op_count(self.handle))]
+
+    def op_kernels(self):
+        """The kernel family of each launch ("stem_pool", "res_stage", "gemm_mfma", ...)."""
+        L = load_library()
+        return [L.sf_policy_op_kernel(self.handle, i).decode()
                 for i in range(L.sf_policy_op_count(self.handle))]
 
     def conv1_fixed_point_ratio(self, planes=3):

@@ -368,6 +368,9 @@ hipError_t launch_conv3x3_patch(const void* in, const uint16_t* wpk, const float
   return hipErrorInvalidValue;
 }
 
+// (for the packers of the other residual-encoder kernels)
+uint16_t conv_weight_bits(float v, bool f16) { return weight_bits(v, f16); }
+
 bool conv3x3_stem_supported(int cin, int cout) { return cin == 3 && (cout == 16 || cout == 32); }
 
 // A operands of the stem kernel: wpk[(p*64 + lane)*8 + e] = w[n][c = e%4][p][q = 2*(lane/32) + e/4]

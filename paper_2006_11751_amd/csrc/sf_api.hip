@@ -263,6 +263,7 @@ Switches read_switches() {
   sw.no_patch_conv = env_set("SF_NO_PATCH_CONV");
   sw.no_fused_resnet = env_set("SF_NO_FUSED_RESNET");
   sw.no_res_stage = env_set("SF_NO_RES_STAGE");
+  sw.no_stem_pool = env_set("SF_NO_STEM_POOL");
   sw.act_bf16 = env_set("SF_ACT_BF16");
   sw.stream_f32 = env_set("SF_STREAM_F32");
   return sw;
@@ -412,6 +413,11 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
             L.wbf = bld.upload(wt);
             L.bbf = bld.upload(bb);
             L.impl = CONV3X3_STEM;
+            if (p->act_f16 && !sw.no_stem_pool && stem_pool_supported(C, cout, H, W)) {
+              std::vector<uint16_t> ws;
+              stem_pool_pack(w->conv_w[ti], true, ws);
+              L.wsp = bld.upload(ws);
+            }
           }
         }
       }
@@ -503,7 +509,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
           snprintf(name, sizeof(name), "stage%d.conv_pool", s + 1);
           // in_buf is the previous stage's x: the pooled result goes to t, which becomes x
           add_conv(name, cfg->stage_ch[s], 3, 1, 1, 0, 0, in_buf, t, -1);
-          p->convs.back().impl = CONV3X3_POOL;
+          p->convs.back().impl = p->convs.back().wsp ? STEM_POOL : CONV3X3_POOL;
           {
             const int tmp = x;
             x = t;
@@ -582,7 +588,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
     if (op.kind == OP_CONV) {
       const ConvLayer& L = p->convs[op.conv];
       size_t elems = (size_t)L.Ho * L.Wo * L.cout;
-      if (L.impl == CONV3X3_POOL) elems = (size_t)((L.Ho - 1) / 2 + 1) * ((L.Wo - 1) / 2 + 1) * L.cout;
+      if (L.impl == CONV3X3_POOL || L.impl == STEM_POOL) elems = (size_t)((L.Ho - 1) / 2 + 1) * ((L.Wo - 1) / 2 + 1) * L.cout;
       bytes = elems * (p->bf16_path && !L.out_f32 ? 2 : 4);
     } else if (op.kind == OP_POOL) {
       bytes = (size_t)((op.H - 1) / 2 + 1) * ((op.W - 1) / 2 + 1) * op.C * (p->bf16_path && !p->stream_f32 ? 2 : 4);
@@ -975,7 +981,7 @@ extern "C" int sf_policy_update_weights(sf_policy* handle, const sf_policy_weigh
     const bool conv1_pair = (a.impl == CONV1_U8_I8 || a.impl == CONV1_U8_MFMA) &&
                             (b.impl == CONV1_U8_I8 || b.impl == CONV1_U8_MFMA) && a.ipk && a.wpk;
     same_plan = (a.impl == b.impl || conv1_pair) && a.tile == b.tile && a.wpk == b.wpk && a.wbf == b.wbf &&
-                a.ipk == b.ipk && a.w_khwc_o == b.w_khwc_o;
+                a.ipk == b.ipk && a.w_khwc_o == b.w_khwc_o && a.wsp == b.wsp;
   }
   if (!same_plan) {
     set_error("%s: internal error: the replayed plan differs from the one built at create", fn);
@@ -1164,6 +1170,9 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
             SF_LAUNCH(launch_conv3x3_pool(in, L.wbf, L.bbf, buf(op.out_buf), B, L.H, L.W, L.cin, L.cout,
                                           c.obs_sub, c.obs_mul, st));
             break;
+          case STEM_POOL:
+            SF_LAUNCH(launch_stem_pool(obs, L.wsp, L.bbf, buf(op.out_buf), B, L.H, L.W, c.obs_sub, c.obs_mul, st));
+            break;
           case RES_STAGE: {
             const uint16_t* wpk[SF_MAX_CONV_TENSORS];
             const float* bias[SF_MAX_CONV_TENSORS];
@@ -1275,6 +1284,37 @@ extern "C" const char* sf_policy_op_name(const sf_policy* handle, int i) {
   return p->ops[i].name.c_str();
 }
 
+extern "C" const char* sf_policy_op_kernel(const sf_policy* handle, int i) {
+  const Policy* p = reinterpret_cast<const Policy*>(handle);
+  if (!p || i < 0 || i >= (int)p->ops.size()) return "";
+  const Op& op = p->ops[i];
+  switch (op.kind) {
+    case OP_CONV:
+      if (op.mid_buf >= 0) return "conv12_fused";
+      switch (p->convs[op.conv].impl) {
+        case CONV1_U8_MFMA: return "conv1_mfma";
+        case CONV_GEMM_MFMA: return "gemm_mfma";
+        case CONV1_U8_I8: return "conv1_i8";
+        case CONV_BF16: return "conv_bf16";
+        case CONV3X3_U8_BF16: return "conv3x3_u8";
+        case CONV3X3_PATCH: return "conv3x3_patch";
+        case CONV3X3_STEM: return "conv3x3_stem";
+        case CONV3X3_POOL: return "conv3x3_pool";
+        case STEM_POOL: return "stem_pool";
+        case RES_BLOCK: return "res_block";
+        case RES_STAGE: return "res_stage";
+        case CONV_IMAGE_BF16: return "conv_image_bf16";
+        default: return "generic";
+      }
+    case OP_POOL: return "pool";
+    case OP_FC: return "fc";
+    case OP_MEAS: return "meas";
+    case OP_GRU: return "rnn";
+    case OP_HEADS: return "heads";
+  }
+  return "";
+}
+
 extern "C" int64_t sf_policy_op_flops_per_row(const sf_policy* handle, int i) {
   const Policy* p = reinterpret_cast<const Policy*>(handle);
   if (!p || i < 0 || i >= (int)p->ops.size()) return 0;
@@ -1300,6 +1340,7 @@ extern "C" const char* sf_policy_op_pipe(const sf_policy* handle, int i) {
         case CONV3X3_PATCH:
         case CONV3X3_STEM:
         case CONV3X3_POOL:
+        case STEM_POOL:
         case RES_BLOCK:
         case RES_STAGE:
         case CONV_IMAGE_BF16: return mfma16;

@@ -34,6 +34,7 @@ struct ConvLayer {
   int Kpad;
   int in_f32, out_f32;    // bf16 kernel: element type of its input / output tensors
   float* w_cpqo;          // dev, fp32 [c][p][q][cout] for the byte-input 3x3 kernel
+  uint16_t* wsp;          // dev, A operands of the register-pooled first convolution (or null)
 };
 enum ConvImpl {
   CONV_GENERIC = 0, CONV1_U8_MFMA = 1, CONV_GEMM_MFMA = 2, CONV1_U8_I8 = 3,
@@ -44,6 +45,7 @@ enum ConvImpl {
   CONV3X3_POOL = 8,     // stage convolution fused with the max-pool behind it
   RES_BLOCK = 9,        // a whole residual block (this layer and the next) in one kernel
   RES_STAGE = 11,       // all residual blocks of a stage in one kernel, frame resident in LDS
+  STEM_POOL = 12,       // first convolution of the residual encoder and its max-pool, pooled in registers
   CONV_IMAGE_BF16 = 10  // 16-bit MFMA with the frame's input image resident in LDS
 };
 
@@ -67,6 +69,7 @@ struct Switches {
   bool no_patch_conv = false;    // SF_NO_PATCH_CONV
   bool no_fused_resnet = false;  // SF_NO_FUSED_RESNET
   bool no_res_stage = false;     // SF_NO_RES_STAGE
+  bool no_stem_pool = false;     // SF_NO_STEM_POOL
   bool act_bf16 = false;         // SF_ACT_BF16
   bool stream_f32 = false;       // SF_STREAM_F32
 };
@@ -233,6 +236,11 @@ hipError_t launch_res_block(const void* x, const uint16_t* wa, const float* ba, 
 bool res_stage_supported(int c, int H, int W, int n_blocks);
 hipError_t launch_res_stage(const void* x, void* out, const uint16_t* const* wpk, const float* const* bias,
                             int n_convs, int B, int H, int W, int c, int relu_out, hipStream_t st);
+uint16_t conv_weight_bits(float v, bool f16);
+bool stem_pool_supported(int cin, int cout, int H, int W);
+void stem_pool_pack(const float* w, bool f16, std::vector<uint16_t>& wpk);
+hipError_t launch_stem_pool(const uint8_t* obs, const uint16_t* wpk, const float* bias, void* out, int B,
+                            int H, int W, float obs_sub, float obs_mul, hipStream_t st);
 bool conv3x3_stem_supported(int cin, int cout);
 void conv3x3_stem_pack(const float* w, const float* bias, int cout, bool f16,
                        std::vector<uint16_t>& wpk, std::vector<float>& b32);

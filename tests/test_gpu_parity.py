@@ -460,3 +460,40 @@ def test_fused_first_two_layers_equal_the_separate_kernels(torch_cuda, ref, monk
         parity.assert_close("value", g["value"][rows], o["value"], 2e-2)
         fused.close()
         plain.close()
+
+
+# frame shapes for the kernel that pools the first convolution in registers: odd height and a
+# last column group with four live lanes; two frames with fewer pooled rows than waves;
+# the benchmark's frame with more frames than workgroups (512), so some walk two
+STEM_POOL_NETS = [dict(RESNET_BF16_SMALL, name="resnet_bf16_37x40", B=6, obs=(3, 37, 40)),
+                  dict(RESNET_BF16_SMALL, name="resnet_bf16_9x12", B=3, obs=(3, 9, 12)),
+                  dict(RESNET_BF16_SMALL, name="resnet_bf16_10x16", B=2, obs=(3, 10, 16)),
+                  dict(RESNET_BF16_SMALL, name="resnet_bf16_72x128", B=600, obs=(3, 72, 128))]
+
+
+@pytest.mark.parametrize("net", STEM_POOL_NETS, ids=lambda n: n["name"])
+def test_first_convolution_pooled_in_registers(torch_cuda, ref, monkeypatch, net):
+    """Residual encoder, fp16 activations: the first convolution and its max-pool as one launch
+    that never stores the full-resolution output against the oracle, and against the kernel that
+    pools out of LDS (same values up to the summation order inside the matrix cores)."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    w = wl.weights(net)
+    B = net["B"]
+    obs, h_in, done = wl.observations(net, 0, B), wl.initial_state(net, B), wl.done_mask(net, 0, B)
+    pol = binding.Policy(net, w)
+    assert pol.op_kernels()[0] == "stem_pool", pol.op_kernels()
+    g = _gpu_step(torch, pol, obs, h_in, done, 7, 11)
+    rows = np.arange(B) if B <= 16 else np.unique(np.concatenate([np.arange(0, B, 23), [B - 1, 511, 512]]))
+    o = ref.policy_step(net, w, obs[rows], h_in[rows], done[rows], 7, 11)
+    parity.assert_close("h_out", g["h_out"][rows], o["h_out"], 2e-2)
+    parity.assert_close("value", g["value"][rows], o["value"], 2e-2)
+    monkeypatch.setenv("SF_NO_STEM_POOL", "1")
+    old = binding.Policy(net, w)
+    monkeypatch.delenv("SF_NO_STEM_POOL")
+    assert old.op_kernels()[0] == "conv3x3_pool", old.op_kernels()
+    g2 = _gpu_step(torch, old, obs, h_in, done, 7, 11)
+    parity.assert_close("h_out vs LDS-pooled kernel", g["h_out"], g2["h_out"], 4e-3)
+    parity.assert_close("value vs LDS-pooled kernel", g["value"], g2["value"], 4e-3)
+    pol.close()
+    old.close()
