@@ -179,7 +179,7 @@ int sf_policy_create(const sf_policy_config* cfg, const sf_policy_weights* weigh
 const char* sf_policy_op_pipe(const sf_policy* p, int i); /* static storage; "" if out of range */
 /* The kernel family launch i runs, for tests and benchmarks that must know which code path a
  * shape took: one of "generic", "conv1_mfma", "gemm_mfma", "conv1_i8", "conv_bf16",
- * "conv3x3_u8", "conv3x3_patch", "conv3x3_stem", "conv3x3_pool", "stem_pool", "res_block",
+ * "conv3x3_u8", "conv3x3_patch", "conv3x3_stem", "conv3x3_pool", "stem_pool", "conv_pool_regs", "res_block",
  * "res_stage", "conv_image_bf16", "conv12_fused" for a convolution launch, and "pool", "fc",
  * "meas", "rnn", "heads" for the others.  Static storage; "" if out of range or null. */
 const char* sf_policy_op_kernel(const sf_policy* p, int i);

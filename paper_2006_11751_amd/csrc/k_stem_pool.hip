@@ -88,9 +88,11 @@ struct StemPoolArgs {
   float obs_sub, obs_mul;
 };
 
-__global__ __launch_bounds__(kNT, 2) void stem_pool_kernel(StemPoolArgs g) {
+// (second launch bound: waves per SIMD; four = two workgroups of eight waves per CU, 128 VGPRs)
+__global__ __launch_bounds__(kNT, 4) void stem_pool_kernel(StemPoolArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char patch[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (scalar: row loops branch uniformly)
   const int j = lane & 15, grp = lane >> 4;
   const size_t plane = (size_t)g.H * g.W;
 
@@ -100,6 +102,11 @@ __global__ __launch_bounds__(kNT, 2) void stem_pool_kernel(StemPoolArgs g) {
   const u32x4 a_lo1 = g.wpk[lane], a_lo2 = g.wpk[64 + lane];
   const u32x4 a_hi1 = g.wpk[128 + lane], a_hi2 = g.wpk[192 + lane];
   const f32x4 bias = *(const f32x4*)(g.bias + 4 * grp);
+  // The parameters have arrived before the first frame is requested (vmcnt(0), other counters
+  // untouched).  Otherwise the compiler, which must assume their loads pending on some path,
+  // drains the load counter ahead of every row loop that uses them, and that wait would catch
+  // the next frame's bytes right after they have been requested.
+  __builtin_amdgcn_s_waitcnt(0x0F70);
 
   // Item i = tid + it * kNT is the four pixels at byte 4*i of each colour plane: image row
   // i / (W/4), columns 4*(i % (W/4)) ..; in LDS, row + 1 and column + 2.
@@ -157,31 +164,50 @@ __global__ __launch_bounds__(kNT, 2) void stem_pool_kernel(StemPoolArgs g) {
       const int colb = (2 * x + 2 * (grp & 1)) * 8;
       const unsigned char* p1 = patch + (grp >> 1) * g.RP + colb;
       const unsigned char* p2 = patch + 2 * g.RP + colb;
-      // horizontal maximum of convolution row r (0 <= r < H) over columns 2x-1 .. 2x+1
-      auto conv_row = [&](int r) {
-        const unsigned char* q1 = p1 + r * g.RP;  // filter row 0 = image row r-1 = LDS row r
+      // pixel operands of convolution row r (0 <= r < H): windows 2x-2.. and 2x.., filter rows
+      // 0-1 (image rows r-1, r = LDS rows r, r+1) and filter row 2
+      auto read_row = [&](int r, u32x4 (&bo)[4]) {
+        const unsigned char* q1 = p1 + r * g.RP;
         const unsigned char* q2 = p2 + r * g.RP;
-        const u32x4 b0a = *(const u32x4*)q1, b0b = *(const u32x4*)q2;
-        const u32x4 b1a = *(const u32x4*)(q1 + 16), b1b = *(const u32x4*)(q2 + 16);
-        f32x4 tlo = mfma(a_lo1, b0a, bias);  // column 2x-1
-        f32x4 thi = mfma(a_hi1, b0a, bias);  // column 2x
-        f32x4 tnx = mfma(a_lo1, b1a, bias);  // column 2x+1
-        tlo = mfma(a_lo2, b0b, tlo);
-        thi = mfma(a_hi2, b0b, thi);
-        tnx = mfma(a_lo2, b1b, tnx);
-        // (column -1 is the pool's padding: the window's own column 0 stands in)
-        f32x4 l;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) l[e] = x == 0 ? thi[e] : tlo[e];
-        return max3_after_mfma(l, thi, tnx);
+        bo[0] = *(const u32x4*)q1;
+        bo[1] = *(const u32x4*)q2;
+        bo[2] = *(const u32x4*)(q1 + 16);
+        bo[3] = *(const u32x4*)(q2 + 16);
       };
+      // horizontal maximum of a convolution row over columns 2x-1 .. 2x+1
+      auto row_max = [&](const u32x4 (&bo)[4]) {
+        f32x4 tlo = mfma(a_lo1, bo[0], bias);  // column 2x-1
+        f32x4 thi = mfma(a_hi1, bo[0], bias);  // column 2x
+        f32x4 tnx = mfma(a_lo1, bo[2], bias);  // column 2x+1
+        tlo = mfma(a_lo2, bo[1], tlo);
+        thi = mfma(a_hi2, bo[1], thi);
+        tnx = mfma(a_lo2, bo[3], tnx);
+        // (column -1 is the pool's padding: the window's own column 0 stands in)
+        if (cg == 0) {  // uniform
+#pragma unroll
+          for (int e = 0; e < 4; ++e) tlo[e] = x == 0 ? thi[e] : tlo[e];
+        }
+        return max3_after_mfma(tlo, thi, tnx);
+      };
+      // The operands of a row are requested one row ahead (two register sets: even rows in be,
+      // odd rows in bo), so that an LDS read has the previous row's MFMAs to complete behind.
+      u32x4 be[4], bo[4];
       f32x4 carry = {ninf, ninf, ninf, ninf};  // row -1 is the pool's padding
-      if (oy0 > 0) carry = conv_row(2 * oy0 - 1);
+      if (oy0 > 0) {
+        read_row(2 * oy0 - 1, bo);
+        read_row(2 * oy0, be);
+        carry = row_max(bo);
+      } else {
+        read_row(0, be);
+      }
       uint16_t* dst = g.out + (((size_t)b * g.Ho + oy0) * g.Wo + x) * 16 + 4 * grp;
       for (int oy = oy0; oy < oy1; ++oy) {
-        const f32x4 h0 = conv_row(2 * oy);
+        const bool odd_row = 2 * oy + 1 < g.H;  // (false: the last pooled row of an odd height)
+        if (odd_row) read_row(2 * oy + 1, bo);
+        const f32x4 h0 = row_max(be);
+        if (oy + 1 < oy1) read_row(2 * oy + 2, be);
         f32x4 h1 = {ninf, ninf, ninf, ninf};
-        if (2 * oy + 1 < g.H) h1 = conv_row(2 * oy + 1);
+        if (odd_row) h1 = row_max(bo);
         f32x4 m;
 #pragma unroll
         for (int e = 0; e < 4; ++e) m[e] = max3(carry[e], h0[e], h1[e]);

@@ -264,6 +264,7 @@ Switches read_switches() {
   sw.no_fused_resnet = env_set("SF_NO_FUSED_RESNET");
   sw.no_res_stage = env_set("SF_NO_RES_STAGE");
   sw.no_stem_pool = env_set("SF_NO_STEM_POOL");
+  sw.no_conv_pool_regs = env_set("SF_NO_CONV_POOL_REGS");
   sw.act_bf16 = env_set("SF_ACT_BF16");
   sw.stream_f32 = env_set("SF_STREAM_F32");
   return sw;
@@ -505,11 +506,13 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
                         !sw.no_fused_resnet;
       for (int s = 0; s < cfg->n_stage; ++s) {
         if (fuse && conv3x3_pool_supported(C, cfg->stage_ch[s], W)) {
-          const int Hin = H, Win = W;
+          const int Hin = H, Win = W, C_in_stage = C;
           snprintf(name, sizeof(name), "stage%d.conv_pool", s + 1);
           // in_buf is the previous stage's x: the pooled result goes to t, which becomes x
           add_conv(name, cfg->stage_ch[s], 3, 1, 1, 0, 0, in_buf, t, -1);
           p->convs.back().impl = p->convs.back().wsp ? STEM_POOL : CONV3X3_POOL;
+          if (in_buf >= 0 && !sw.no_conv_pool_regs && conv_pool_regs_supported(C_in_stage, cfg->stage_ch[s], Hin, Win))
+            p->convs.back().impl = CONV_POOL_REGS;
           {
             const int tmp = x;
             x = t;
@@ -588,7 +591,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
     if (op.kind == OP_CONV) {
       const ConvLayer& L = p->convs[op.conv];
       size_t elems = (size_t)L.Ho * L.Wo * L.cout;
-      if (L.impl == CONV3X3_POOL || L.impl == STEM_POOL) elems = (size_t)((L.Ho - 1) / 2 + 1) * ((L.Wo - 1) / 2 + 1) * L.cout;
+      if (L.impl == CONV3X3_POOL || L.impl == STEM_POOL || L.impl == CONV_POOL_REGS) elems = (size_t)((L.Ho - 1) / 2 + 1) * ((L.Wo - 1) / 2 + 1) * L.cout;
       bytes = elems * (p->bf16_path && !L.out_f32 ? 2 : 4);
     } else if (op.kind == OP_POOL) {
       bytes = (size_t)((op.H - 1) / 2 + 1) * ((op.W - 1) / 2 + 1) * op.C * (p->bf16_path && !p->stream_f32 ? 2 : 4);
@@ -1170,6 +1173,9 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
             SF_LAUNCH(launch_conv3x3_pool(in, L.wbf, L.bbf, buf(op.out_buf), B, L.H, L.W, L.cin, L.cout,
                                           c.obs_sub, c.obs_mul, st));
             break;
+          case CONV_POOL_REGS:
+            SF_LAUNCH(launch_conv_pool_regs(in, L.wbf, L.bbf, buf(op.out_buf), B, L.H, L.W, L.cin, st));
+            break;
           case STEM_POOL:
             SF_LAUNCH(launch_stem_pool(obs, L.wsp, L.bbf, buf(op.out_buf), B, L.H, L.W, c.obs_sub, c.obs_mul, st));
             break;
@@ -1301,6 +1307,7 @@ extern "C" const char* sf_policy_op_kernel(const sf_policy* handle, int i) {
         case CONV3X3_STEM: return "conv3x3_stem";
         case CONV3X3_POOL: return "conv3x3_pool";
         case STEM_POOL: return "stem_pool";
+        case CONV_POOL_REGS: return "conv_pool_regs";
         case RES_BLOCK: return "res_block";
         case RES_STAGE: return "res_stage";
         case CONV_IMAGE_BF16: return "conv_image_bf16";
@@ -1341,6 +1348,7 @@ extern "C" const char* sf_policy_op_pipe(const sf_policy* handle, int i) {
         case CONV3X3_STEM:
         case CONV3X3_POOL:
         case STEM_POOL:
+        case CONV_POOL_REGS:
         case RES_BLOCK:
         case RES_STAGE:
         case CONV_IMAGE_BF16: return mfma16;

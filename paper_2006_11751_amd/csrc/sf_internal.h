@@ -46,6 +46,7 @@ enum ConvImpl {
   RES_BLOCK = 9,        // a whole residual block (this layer and the next) in one kernel
   RES_STAGE = 11,       // all residual blocks of a stage in one kernel, frame resident in LDS
   STEM_POOL = 12,       // first convolution of the residual encoder and its max-pool, pooled in registers
+  CONV_POOL_REGS = 13,  // stage convolution (16 or 32 -> 32 channels) and its max-pool, pooled in registers
   CONV_IMAGE_BF16 = 10  // 16-bit MFMA with the frame's input image resident in LDS
 };
 
@@ -70,6 +71,7 @@ struct Switches {
   bool no_fused_resnet = false;  // SF_NO_FUSED_RESNET
   bool no_res_stage = false;     // SF_NO_RES_STAGE
   bool no_stem_pool = false;     // SF_NO_STEM_POOL
+  bool no_conv_pool_regs = false;  // SF_NO_CONV_POOL_REGS
   bool act_bf16 = false;         // SF_ACT_BF16
   bool stream_f32 = false;       // SF_STREAM_F32
 };
@@ -241,6 +243,9 @@ bool stem_pool_supported(int cin, int cout, int H, int W);
 void stem_pool_pack(const float* w, bool f16, std::vector<uint16_t>& wpk);
 hipError_t launch_stem_pool(const uint8_t* obs, const uint16_t* wpk, const float* bias, void* out, int B,
                             int H, int W, float obs_sub, float obs_mul, hipStream_t st);
+bool conv_pool_regs_supported(int cin, int cout, int H, int W);
+hipError_t launch_conv_pool_regs(const void* in, const uint16_t* wpk, const float* bias32, void* out, int B,
+                                 int H, int W, int cin, hipStream_t st);
 bool conv3x3_stem_supported(int cin, int cout);
 void conv3x3_stem_pack(const float* w, const float* bias, int cout, bool f16,
                        std::vector<uint16_t>& wpk, std::vector<float>& b32);

@@ -497,3 +497,43 @@ def test_first_convolution_pooled_in_registers(torch_cuda, ref, monkeypatch, net
     parity.assert_close("value vs LDS-pooled kernel", g["value"], g2["value"], 4e-3)
     pol.close()
     old.close()
+
+
+# stage inputs for the kernel that pools a stage convolution in registers: 24 x 64 x 16 and
+# 12 x 32 x 32 (one and two frames per workgroup round, more rounds than workgroups);
+# 25 x 38 x 16 (odd height, 19 pooled columns); 19 x 20 and 10 x 10 (two frames per round, five
+# and ten live lanes per frame); 5 x 8 and 3 x 4 (fewer pooled rows than waves); odd batch sizes
+# leave the second frame of the last round empty
+CONV_POOL_REGS_NETS = [(dict(RESNET_BF16_POW2, name="resnet_bf16_pow2_601", B=601), 2),
+                       (dict(RESNET_BF16_MID, B=5), 1),
+                       (dict(RESNET_BF16_SMALL, name="resnet_bf16_37x40", B=7, obs=(3, 37, 40)), 2),
+                       (dict(RESNET_BF16_SMALL, name="resnet_bf16_10x16", B=3, obs=(3, 10, 16)), 2)]
+
+
+@pytest.mark.parametrize("net,n_regs", CONV_POOL_REGS_NETS, ids=lambda v: v["name"] if isinstance(v, dict) else str(v))
+def test_stage_convolution_pooled_in_registers(torch_cuda, ref, monkeypatch, net, n_regs):
+    """Residual encoder, fp16 activations: the second and third stage convolutions with their
+    max-pools as launches that never store the full-resolution output, against the oracle and
+    against the kernels that pool out of LDS (same values up to the summation order inside the
+    matrix cores)."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    w = wl.weights(net)
+    B = net["B"]
+    obs, h_in, done = wl.observations(net, 0, B), wl.initial_state(net, B), wl.done_mask(net, 0, B)
+    pol = binding.Policy(net, w)
+    assert pol.op_kernels().count("conv_pool_regs") == n_regs, pol.op_kernels()
+    g = _gpu_step(torch, pol, obs, h_in, done, 7, 11)
+    rows = np.arange(B) if B <= 16 else np.unique(np.concatenate([np.arange(0, B, 29), [B - 1, B - 2, 255, 256, 511, 512]]))
+    o = ref.policy_step(net, w, obs[rows], h_in[rows], done[rows], 7, 11)
+    parity.assert_close("h_out", g["h_out"][rows], o["h_out"], 2e-2)
+    parity.assert_close("value", g["value"][rows], o["value"], 2e-2)
+    monkeypatch.setenv("SF_NO_CONV_POOL_REGS", "1")
+    old = binding.Policy(net, w)
+    monkeypatch.delenv("SF_NO_CONV_POOL_REGS")
+    assert "conv_pool_regs" not in old.op_kernels(), old.op_kernels()
+    g2 = _gpu_step(torch, old, obs, h_in, done, 7, 11)
+    parity.assert_close("h_out vs LDS-pooled kernels", g["h_out"], g2["h_out"], 4e-3)
+    parity.assert_close("value vs LDS-pooled kernels", g["value"], g2["value"], 4e-3)
+    pol.close()
+    old.close()

@@ -39,6 +39,7 @@ CASES = [
     ("SF_NO_FUSED_RESNET", "1", RESNET_BF16_MID),
     ("SF_NO_RES_STAGE", "1", dict(RESNET_BF16_POW2, B=9)),
     ("SF_NO_STEM_POOL", "1", RESNET_BF16_MID),
+    ("SF_NO_CONV_POOL_REGS", "1", RESNET_BF16_MID),
     ("SF_NO_PATCH_CONV", "1", RESNET_BF16_SMALL),
     ("SF_STREAM_F32", "1", RESNET_BF16_SMALL),
 ]
