@@ -62,7 +62,8 @@ __device__ inline u32x4 relu8(u32x4 v) {
 struct StageArgs {
   const u32x4* x;              // fp16 [B][H][W][C] as 16-byte pieces
   u32x4* out;                  // the same shape
-  const u32x4* w[kMaxConvs];   // A operands [9][C/16][64] of conv_a, conv_b of every block
+  const u32x4* w[kMaxConvs];   // A operands of conv_a, conv_b of every block: [9][C/16][64], or
+                               // [5][64] tap pairs for 16 channels (res_stage_pack16)
   const float* bias[kMaxConvs];  // [32] each
   int B, H, n_convs, relu_out;
 };
@@ -137,11 +138,15 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
       dst[k] = src[p < pieces ? p : pieces - 1];
     }
   };
-  u32x4 wA[9][NS], wB[9][NS];
-  auto load_bank = [&](int k, u32x4 (&dst)[9][NS]) {
+  // A operands of a convolution: nine taps x NS channel groups for the 32x32x16 MFMA; five tap
+  // pairs for the 16x16x32 MFMA that runs the 16-channel stages (see conv16 below)
+  constexpr bool M16 = C == 16;
+  constexpr int NB = M16 ? 5 : 9;
+  u32x4 wA[NB][NS], wB[NB][NS];
+  auto load_bank = [&](int k, u32x4 (&dst)[NB][NS]) {
     const u32x4* src = g.w[k];
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap)
+    for (int tap = 0; tap < NB; ++tap)
 #pragma unroll
       for (int s = 0; s < NS; ++s) dst[tap][s] = src[(tap * NS + s) * 64 + lane];
   };
@@ -160,8 +165,9 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
 
   // One convolution over the frame: the wave's tiles wave, wave + 8, ... two at a time (two
   // independent MFMA chains), from image `src` into image `dst`.
-  auto conv = [&](const u32x4 (&wreg)[9][NS], const f32x16& init, const unsigned char* src,
-                  unsigned char* dst, bool relu) {
+  auto conv32 = [&](const u32x4 (&wreg)[NB][NS], int kconv, const unsigned char* src, unsigned char* dst,
+                    bool relu) {
+    const f32x16 init = bias_acc(kconv);
     auto tile_off = [&](int t) {  // byte offset of the tile's first pixel row / half row
       if (LW >= 5) return ((t << 5) >> LW) * ROW + ((t << 5) & (W - 1)) * PITCH;
       return (t * (32 >> LW)) * ROW;
@@ -228,10 +234,86 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
     // the frame's pieces leave no room for a second tile's accumulators; spills would go to
     // memory, 260 MB per launch at the benchmark's second stage)
     constexpr bool kPairs = !(C == 32 && PPT >= 5);
-    int t = wave;
-    if (kPairs)
-      for (; t + kNW < n_tiles; t += 2 * kNW) run(std::integral_constant<int, 2>{}, t);
-    for (; t < n_tiles; t += kNW) run(std::integral_constant<int, 1>{}, t);
+    if constexpr (!M16) {  // (the tile code is instantiated for 32 channels only)
+      int t = wave;
+      if (kPairs)
+        for (; t + kNW < n_tiles; t += 2 * kNW) run(std::integral_constant<int, 2>{}, t);
+      for (; t < n_tiles; t += kNW) run(std::integral_constant<int, 1>{}, t);
+    }
+  };
+
+  // The same for 16 channels on v_mfma_f32_16x16x32_f16 (a 32x32 tile would compute 16 output
+  // rows of zeros): lane l supplies A[i = l%16][k = 8*(l/16) + e] and B[k][j = l%16]; D[i][j] sits
+  // in lane j + 16*(i/4), register i%4.  A tile is 16 neighbouring pixels of a row; K = 32 is two
+  // filter taps x 16 channels, lane group g = l/16 holding tap g%2 of the pair, channels
+  // 8*(g/2)..: with the two taps side by side in a filter row, the 64 lanes' 16-byte reads are
+  // free of bank conflicts (4 cycles measured; 8 with the channel half in the low bit of g, and 8
+  // for two taps of different rows).  Five MFMAs: taps (0,1), (3,4), (6,7), (2,5), (8, none: zero
+  // weights, the lanes re-read tap 8).
+  const int j16 = lane & 15, g16 = lane >> 4;
+  int lane_m[5], lane_o16;
+  {
+    constexpr int pair[5][2] = {{0, 1}, {3, 4}, {6, 7}, {2, 5}, {8, 8}};
+#pragma unroll
+    for (int m = 0; m < 5; ++m) {
+      const int tap = pair[m][g16 & 1], p = tap / 3, q = tap % 3;
+      lane_m[m] = p * ROW + (j16 + q) * PITCH + (((g16 >> 1) * 16) ^ swz(j16 + q));
+    }
+    // channels 4*g .. 4*g+3 of ring pixel (y + 1, x + 1)
+    lane_o16 = ROW + (j16 + 1) * PITCH + ((((g16 >> 1) * 16) ^ swz(j16 + 1)) + (g16 & 1) * 8);
+  }
+  auto conv16 = [&](const u32x4 (&wreg)[NB][NS], int kconv, const unsigned char* src, unsigned char* dst,
+                    bool relu) {
+    const f32x4 init = *(const f32x4*)(bias_lds + 32 * kconv + 4 * g16);
+    const int n16 = npix >> 4;  // (the width is a multiple of 16: no partial tiles)
+    auto tile_off = [&](int t) { return ((t << 4) >> LW) * ROW + ((t << 4) & (W - 1)) * PITCH; };
+    auto run = [&](auto cnt, int t0) {
+      constexpr int N = decltype(cnt)::value;
+      f32x4 acc[N];
+      const unsigned char* base[N];
+#pragma unroll
+      for (int n = 0; n < N; ++n) {
+        acc[n] = init;
+        base[n] = src + tile_off(t0 + n * kNW);
+      }
+      // the pixel fragment of step k + 2 is requested right behind the MFMA of step k
+      u32x4 pf[2][N];
+#pragma unroll
+      for (int n = 0; n < N; ++n)
+#pragma unroll
+        for (int d = 0; d < 2; ++d) pf[d][n] = *(const u32x4*)(base[n] + lane_m[d]);
+#pragma unroll
+      for (int k = 0; k < 5; ++k) {
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, wreg[k][0]),
+                                                          __builtin_bit_cast(f16x8, pf[k & 1][n]), acc[n], 0, 0, 0);
+          if (k + 2 < 5) pf[k & 1][n] = *(const u32x4*)(base[n] + lane_m[k + 2]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+#pragma unroll
+      for (int n = 0; n < N; ++n) {
+        u32x2 ov;
+        ov[0] = pk_f16(acc[n][0], acc[n][1]);
+        ov[1] = pk_f16(acc[n][2], acc[n][3]);
+        if (relu) {
+          ov[0] = pk_max0(ov[0]);
+          ov[1] = pk_max0(ov[1]);
+        }
+        *(u32x2*)(dst + tile_off(t0 + n * kNW) + lane_o16) = ov;
+      }
+    };
+    if constexpr (M16) {
+      int t = wave;
+      for (; t + 3 * kNW < n16; t += 4 * kNW) run(std::integral_constant<int, 4>{}, t);
+      for (; t < n16; t += kNW) run(std::integral_constant<int, 1>{}, t);
+    }
+  };
+  auto conv = [&](const u32x4 (&wreg)[NB][NS], int kconv, const unsigned char* src, unsigned char* dst,
+                  bool relu) {
+    if constexpr (M16) conv16(wreg, kconv, src, dst, relu);
+    else conv32(wreg, kconv, src, dst, relu);
   };
 
   int b = blockIdx.x;
@@ -247,11 +329,11 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
     for (int k = 0; k < g.n_convs; k += 2) {
       // conv_a of the block: X -> T, ReLU; conv_b's bank arrives meanwhile
       load_bank(k + 1, wB);
-      conv(wA, bias_acc(k), X, T, true);
+      conv(wA, k, X, T, true);
       __syncthreads();
       // conv_b: T -> X; the next conv_a's bank (the next block's, or the first of the next frame)
       load_bank(k + 2 < g.n_convs ? k + 2 : 0, wA);
-      conv(wB, bias_acc(k + 1), T, X, false);
+      conv(wB, k + 1, T, X, false);
       __syncthreads();
       // x <- x + branch; X <- relu(x) unless this was the last block.  Three pieces at a time:
       // their reads first, then the arithmetic and the writes (one LDS latency per three pieces).
@@ -310,6 +392,22 @@ hipError_t launch_stage_t(const StageArgs& g, size_t lds, hipStream_t st) {
 }
 
 }  // namespace
+
+// A operands of a 16 -> 16 channel convolution for the tap-pair MFMAs of the stage kernel:
+// wpk[(m * 64 + lane) * 8 + e] = w[n = lane%16][c = 8*(lane/32) + e][tap], tap = pair m's first
+// (lane/16 even) or second (odd) member; pair 4 has no second member (zeros).
+void res_stage_pack16(const float* w, bool f16, std::vector<uint16_t>& wpk) {
+  static const int pair[5][2] = {{0, 1}, {3, 4}, {6, 7}, {2, 5}, {8, -1}};
+  wpk.assign((size_t)5 * 64 * 8, 0);
+  for (int m = 0; m < 5; ++m)
+    for (int lane = 0; lane < 64; ++lane)
+      for (int e = 0; e < 8; ++e) {
+        const int n = lane & 15, grp = lane >> 4, c = 8 * (grp >> 1) + e, tap = pair[m][grp & 1];
+        if (tap >= 0)
+          wpk[((size_t)m * 64 + lane) * 8 + e] =
+              conv_weight_bits(w[(((size_t)n * 16 + c) * 3 + tap / 3) * 3 + tap % 3], f16);
+      }
+}
 
 // Shapes: 16 or 32 channels, frame width 16, 32 or 64, both LDS images within 160 KB, at most
 // nine 16-byte pieces of the frame per thread, one to four blocks; and at least one 32-pixel

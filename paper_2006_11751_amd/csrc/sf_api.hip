@@ -368,6 +368,12 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
             L.wbf = bld.upload(wt);
             L.bbf = bld.upload(bb);
             L.impl = CONV3X3_PATCH;
+            if (C == 16 && cout == 16 && p->act_f16) {
+              // (block convolutions of a 16-channel stage: the stage kernel's tap-pair layout)
+              std::vector<uint16_t> w16;
+              res_stage_pack16(w->conv_w[ti], true, w16);
+              L.wsp = bld.upload(w16);
+            }
           }
           // Residual encoder: the stream x (pool outputs, block outputs) stays fp32 so that
           // its rounding does not accumulate over the blocks; branch intermediates and
@@ -1183,7 +1189,7 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
             const uint16_t* wpk[SF_MAX_CONV_TENSORS];
             const float* bias[SF_MAX_CONV_TENSORS];
             for (int k = 0; k < op.n_sub; ++k) {
-              wpk[k] = p->convs[op.conv + k].wbf;
+              wpk[k] = L.cin == 16 ? p->convs[op.conv + k].wsp : p->convs[op.conv + k].wbf;
               bias[k] = p->convs[op.conv + k].bbf;
             }
             SF_LAUNCH(launch_res_stage(in, buf(op.out_buf), wpk, bias, op.n_sub, B, L.H, L.W, L.cin,

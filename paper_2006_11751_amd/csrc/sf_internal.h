@@ -34,7 +34,8 @@ struct ConvLayer {
   int Kpad;
   int in_f32, out_f32;    // bf16 kernel: element type of its input / output tensors
   float* w_cpqo;          // dev, fp32 [c][p][q][cout] for the byte-input 3x3 kernel
-  uint16_t* wsp;          // dev, A operands of the register-pooled first convolution (or null)
+  uint16_t* wsp;          // dev, A operands in a second layout: of the register-pooled first convolution,
+                          // or of a 16 -> 16 channel block convolution for the stage kernel (or null)
 };
 enum ConvImpl {
   CONV_GENERIC = 0, CONV1_U8_MFMA = 1, CONV_GEMM_MFMA = 2, CONV1_U8_I8 = 3,
@@ -236,6 +237,7 @@ hipError_t launch_res_block(const void* x, const uint16_t* wa, const float* ba, 
                             const float* bb, void* out, int B, int H, int W, int c, int relu_out,
                             hipStream_t st);
 bool res_stage_supported(int c, int H, int W, int n_blocks);
+void res_stage_pack16(const float* w, bool f16, std::vector<uint16_t>& wpk);
 hipError_t launch_res_stage(const void* x, void* out, const uint16_t* const* wpk, const float* const* bias,
                             int n_convs, int B, int H, int W, int c, int relu_out, hipStream_t st);
 uint16_t conv_weight_bits(float v, bool f16);
