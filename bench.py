@@ -133,11 +133,29 @@ def measure_loss(torch, binding, wl, reps):
             binding.sf_appo_loss(cfg, *ptrs, st)
         torch.cuda.synchronize()
         us = 1e6 * (time.perf_counter() - tic) / reps
+        # the same calls recorded into a HIP graph (eight per graph) and replayed: what a learner
+        # loop that captures its step pays, without the host's cost of enqueueing two launches
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(8):
+                binding.sf_appo_loss(cfg, *ptrs, torch.cuda.current_stream().cuda_stream)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        tic = time.perf_counter()
+        for _ in range(max(1, reps // 8)):
+            graph.replay()
+        torch.cuda.synchronize()
+        gus = 1e6 * (time.perf_counter() - tic) / (8 * max(1, reps // 8))
         M, sumA, nh = hp["T"] * hp["N"], sum(hp["heads"]), len(hp["heads"])
         # logits and actions are read for the forward pass and again for the gradient; the rest once
         nbytes = M * (2 * (4 * sumA + 4 * nh) + 4 * 4 + 1 + 4 * 4 + 4 * sumA)
         res[name] = {"us_per_call": round(us, 2), "samples_per_s": round(M / us * 1e6, 1),
-                     "algorithmic_GBps": round(nbytes / us / 1e3, 2)}
+                     "algorithmic_GBps": round(nbytes / us / 1e3, 2),
+                     "graph_replay_us_per_call": round(gus, 2),
+                     "graph_replay_algorithmic_GBps": round(nbytes / gus / 1e3, 2)}
     return res
 
 
@@ -337,6 +355,7 @@ def main():
             net["heads"], ", %d measurements -> FC%s" % (net["meas_dim"], net["meas_hidden"]) if net["meas_dim"] else ""),
             "name": net["name"], "B": B, "conv1": conv1 or pipes[0],
             "launch_pipes": dict(zip((n for n, _ in ops), pipes)),
+            "launch_kernels": dict(zip((n for n, _ in ops), pol.op_kernels())),
             "paper_accounting_x4_frameskip_fps": round(4 * fps, 1),
             "inputs": "device-resident; host-to-device transfer excluded",
             "timing": "median of %d blocks of %d steps after %d uncounted pre-warm-up steps (>= %.1f s) and %d "

@@ -117,3 +117,77 @@ def test_loss_error_paths(torch_cuda):
     assert binding.load_library().sf_appo_loss(cfg, *([None] * 13)) == binding.SF_ERR_ARG
     cfg.struct_size = 8
     assert binding.load_library().sf_appo_loss(cfg, *([None] * 13)) == binding.SF_ERR_ARG
+
+
+def test_loss_is_independent_of_the_workspace_contents(torch_cuda, ref):
+    """Whatever the workspace held before (zeros, ones, random bytes, the previous call's partial
+    sums), repeated calls on it give the same bits, and the loss terms equal the oracle's
+    (515 trajectories: 129 workgroups, the last with three trajectories)."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    hp = wl.loss_config((3, 3, 2, 2, 2, 8, 21), 32, 515)
+    tr = wl.trajectories(hp, 6020)
+    d = torch.device("cuda", 0)
+    dev = {k: torch.from_numpy(v).to(d) for k, v in tr.items()}
+    out = binding.appo_loss(hp, dev)
+    torch.cuda.synchronize()
+    want = out["loss"].cpu().numpy().copy()
+    o = ref.appo_loss(hp, **tr)
+    scale = np.abs(o["loss"][:3]).max()
+    assert np.all(np.abs(want - o["loss"]) <= RTOL * (np.abs(o["loss"]) + scale)), (want, o["loss"])
+    cfg = binding.make_loss_config(hp)
+    ws = out["workspace"]
+    st = torch.cuda.current_stream().cuda_stream
+    ptrs = [dev[k].data_ptr() for k in ("logits", "actions", "logp_mu", "values", "rewards", "dones")] + \
+           [out[k].data_ptr() for k in ("vs", "adv", "loss", "dlogits", "dvalues", "workspace")]
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    for fill in ("zeros", "ones", "random", "keep", "keep"):
+        if fill == "zeros":
+            ws.zero_()
+        elif fill == "ones":
+            ws.fill_(255)
+        elif fill == "random":
+            ws.copy_(torch.randint(0, 256, (ws.numel(),), dtype=torch.uint8, generator=gen))
+        out["loss"].fill_(float("nan"))
+        binding.sf_appo_loss(cfg, *ptrs, st)
+        torch.cuda.synchronize()
+        assert np.array_equal(out["loss"].cpu().numpy(), want), fill
+
+
+def test_loss_replayed_from_a_graph(torch_cuda, ref):
+    """The entry point that allocates nothing, recorded into a HIP graph once and replayed with the
+    program's own eager calls and synchronisations in between: every replay gives the eager call's
+    bits (two kernel nodes, no memset node: nothing has to start at zero)."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    hp = wl.loss_config((3, 3, 2, 2, 2, 8, 21), 32, 259)
+    tr = wl.trajectories(hp, 6021)
+    d = torch.device("cuda", 0)
+    dev = {k: torch.from_numpy(v).to(d) for k, v in tr.items()}
+    eager = binding.appo_loss(hp, dev)
+    torch.cuda.synchronize()
+    want = {k: eager[k].cpu().numpy().copy() for k in ("vs", "adv", "loss", "dlogits", "dvalues")}
+    cfg = binding.make_loss_config(hp)
+    out = {k: torch.empty_like(eager[k]) for k in want}
+    ptrs = [dev[k].data_ptr() for k in ("logits", "actions", "logp_mu", "values", "rewards", "dones")] + \
+           [out[k].data_ptr() for k in ("vs", "adv", "loss", "dlogits", "dvalues")]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        binding.sf_appo_loss_static(cfg, *ptrs, side.cuda_stream)   # first use on this device, outside the capture
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        binding.sf_appo_loss_static(cfg, *ptrs, torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        for v in out.values():
+            v.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in want:
+            assert np.array_equal(out[k].cpu().numpy(), want[k]), (rep, k)
+        # eager work of the same kind between the replays
+        again = binding.appo_loss(hp, dev)
+        torch.cuda.synchronize()
+        assert np.array_equal(again["loss"].cpu().numpy(), want["loss"])
