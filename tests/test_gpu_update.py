@@ -100,3 +100,42 @@ def test_update_rejects_missing_tensors(torch_cuda):
     assert e.value.code == binding.SF_ERR_ARG
     assert binding.load_library().sf_policy_update_weights(None, None, None) == binding.SF_ERR_ARG
     pol.close()
+
+
+@pytest.mark.parametrize("net", [wl.network(1, B=70, name="standard_small"), RESNET_BF16_SMALL], ids=lambda n: n["name"])
+def test_rejected_update_leaves_the_old_parameters_in_place(torch_cuda, net):
+    """The whole parameter set is packed and checked before the first copy is enqueued: an update
+    whose LAST tensors are bad (a NaN in the value head's bias; for the fp16 encoder a weight beyond
+    the fp16 range in the FC layer) fails with SF_ERR_ARG and the next step still computes the old
+    policy's bits, although every earlier tensor of the update differed from the old one."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    pol, w0 = _make(torch, net)
+    before, _ = _step(torch, pol, net, 0)
+    torch.cuda.synchronize()
+    before = _to_np(before)
+    bad = []
+    w1 = wl.weights(net, seed=777)
+    w1["v_b"] = w1["v_b"].copy()
+    w1["v_b"][0] = np.nan
+    bad.append(w1)
+    if net["dtype"] == "bf16" and net["encoder"] == "resnet":
+        w2 = wl.weights(net, seed=778)
+        w2["fc_w"] = w2["fc_w"].copy()
+        w2["fc_w"][1, 5] = 1.0e5
+        bad.append(w2)
+    for w in bad:
+        with pytest.raises(binding.SfError) as e:
+            pol.update_weights(w)
+        assert e.value.code == binding.SF_ERR_ARG
+        after, _ = _step(torch, pol, net, 0)
+        torch.cuda.synchronize()
+        after = _to_np(after)
+        for k in ("actions", "logp", "value", "h_out", "logits"):
+            assert np.array_equal(after[k], before[k]), k
+    # a good update still goes through afterwards
+    pol.update_weights(wl.weights(net, seed=779))
+    ok, _ = _step(torch, pol, net, 0)
+    torch.cuda.synchronize()
+    assert not np.array_equal(_to_np(ok)["logits"], before["logits"])
+    pol.close()
