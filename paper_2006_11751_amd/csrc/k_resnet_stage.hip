@@ -59,6 +59,16 @@ __device__ inline u32x4 relu8(u32x4 v) {
   return u32x4{pk_max0(v[0]), pk_max0(v[1]), pk_max0(v[2]), pk_max0(v[3])};
 }
 
+// f(integral_constant<int, 0>), f(integral_constant<int, STEP>), ... below END
+template <int STEP, class F, int... I>
+__device__ inline void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I * STEP>{}), ...);
+}
+template <int END, int STEP, class F>
+__device__ inline void static_for(F&& f) {
+  static_for_impl<STEP>(f, std::make_integer_sequence<int, (END + STEP - 1) / STEP>{});
+}
+
 struct StageArgs {
   const u32x4* x;              // fp16 [B][H][W][C] as 16-byte pieces
   u32x4* out;                  // the same shape
@@ -68,8 +78,9 @@ struct StageArgs {
   int B, H, n_convs, relu_out;
 };
 
-// C channels (16 or 32), frame width 1 << LW, PPT 16-byte pieces of a frame per thread.
-template <int C, int LW, int PPT>
+// C channels (16 or 32), frame width 1 << LW, PPT 16-byte pieces of a frame per thread; RES: the
+// filter banks of all (at most four) convolutions stay in registers (16 channels only).
+template <int C, int LW, int PPT, bool RES>
 __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
   constexpr int W = 1 << LW;
   constexpr int C8 = C / 8, NS = C / 16;
@@ -85,7 +96,8 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
   auto swz = [](int col) { return SWZ ? ((col >> 3) & 1) << 4 : 0; };
   constexpr int ROW = (W + 2) * PITCH;  // image row pitch in bytes, ring included
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (scalar: tile loops branch uniformly)
   const int li = lane & 31, lh = lane >> 5;
   const int npix = g.H * W;
   const int pieces = npix * C8;
@@ -306,7 +318,10 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
     };
     if constexpr (M16) {
       int t = wave;
-      for (; t + 3 * kNW < n16; t += 4 * kNW) run(std::integral_constant<int, 4>{}, t);
+      // (four tiles in flight, two where the resident filter banks leave no room for more)
+      if constexpr (!(RES && PPT >= 9))
+        for (; t + 3 * kNW < n16; t += 4 * kNW) run(std::integral_constant<int, 4>{}, t);
+      for (; t + kNW < n16; t += 2 * kNW) run(std::integral_constant<int, 2>{}, t);
       for (; t < n16; t += kNW) run(std::integral_constant<int, 1>{}, t);
     }
   };
@@ -315,6 +330,153 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
     if constexpr (M16) conv16(wreg, kconv, src, dst, relu);
     else conv32(wreg, kconv, src, dst, relu);
   };
+
+  if constexpr (M16) {
+    // 16 channels: the residual stream lives in the accumulator layout of the wave that owns the
+    // tile (lane j + 16*g: channels 4g..4g+3 of pixel j, 8 bytes; tiles wave, wave + 8, ...), so
+    // conv_b's epilogue adds it in registers and writes relu(x) for the next block straight into
+    // X: no separate pass over the frame, one barrier fewer per block.  Same arithmetic as the
+    // piece form: conv_b's result is rounded to fp16, then added to x in fp16.
+    constexpr int RT = 2 * PPT;  // 16-pixel tiles per wave at most
+    const int n16 = npix >> 4;
+    u32x2 xt[RT], nt[RT];
+    auto tile_off16 = [&](int t) { return ((t << 4) >> LW) * ROW + ((t << 4) & (W - 1)) * PITCH; };
+    const int lane_g = j16 * 32 + g16 * 8;  // the lane's 8 bytes within a tile's 512 in memory
+    auto load_tiles = [&](int bb, u32x2 (&dst)[RT]) {
+      const unsigned char* src = (const unsigned char*)g.x + (size_t)bb * pieces * 16;
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+        // (an opaque move keeps the offsets from being computed ahead of the frame loop and spilled)
+        int o = lane_g;
+        asm volatile("" : "+v"(o));
+        const int t = wave + kNW * r;
+        dst[r] = *(const u32x2*)(src + (size_t)(t < n16 ? t : n16 - 1) * 512 + o);
+      }
+    };
+    auto relu2 = [](u32x2 v) { return u32x2{pk_max0(v[0]), pk_max0(v[1])}; };
+    // conv_b of a block: T -> x += conv + bias; X <- relu(x) if another block follows.  The tile
+    // rounds are unrolled (the stream's registers are indexed by the round).
+    auto conv16_b = [&](const u32x4 (&wreg)[NB][NS], int kconv, bool more) {
+      const f32x4 init = *(const f32x4*)(bias_lds + 32 * kconv + 4 * g16);
+      auto run = [&](auto cnt, auto r0c) {
+        constexpr int N = decltype(cnt)::value, R0 = decltype(r0c)::value;
+        f32x4 acc[N];
+        const unsigned char* base[N];
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+          acc[n] = init;
+          base[n] = T + tile_off16(wave + kNW * (R0 + n));
+        }
+        u32x4 pf[2][N];
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+#pragma unroll
+          for (int d = 0; d < 2; ++d) pf[d][n] = *(const u32x4*)(base[n] + lane_m[d]);
+#pragma unroll
+        for (int k = 0; k < 5; ++k) {
+#pragma unroll
+          for (int n = 0; n < N; ++n) {
+            acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, wreg[k][0]),
+                                                            __builtin_bit_cast(f16x8, pf[k & 1][n]), acc[n], 0, 0, 0);
+            if (k + 2 < 5) pf[k & 1][n] = *(const u32x4*)(base[n] + lane_m[k + 2]);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+          if (R0 + n < RT) {  // (constant once unrolled)
+            u32x2& x = xt[R0 + n < RT ? R0 + n : RT - 1];
+            x[0] = pk_add(x[0], pk_f16(acc[n][0], acc[n][1]));
+            x[1] = pk_add(x[1], pk_f16(acc[n][2], acc[n][3]));
+            if (more) *(u32x2*)(X + tile_off16(wave + kNW * (R0 + n)) + lane_o16) = relu2(x);
+          }
+        }
+      };
+      if constexpr (RES && PPT >= 9) {
+        static_for<RT, 2>([&](auto r0c) {
+          constexpr int R0 = decltype(r0c)::value;
+          const int t0 = wave + kNW * R0;
+          if (t0 + kNW < n16 && R0 + 1 < RT) run(std::integral_constant<int, 2>{}, r0c);
+          else if (t0 < n16) run(std::integral_constant<int, 1>{}, r0c);
+        });
+      } else {
+        static_for<RT, 4>([&](auto r0c) {
+          constexpr int R0 = decltype(r0c)::value;
+          const int t0 = wave + kNW * R0;
+          if (t0 + 3 * kNW < n16 && R0 + 3 < RT) {
+            run(std::integral_constant<int, 4>{}, r0c);
+          } else if (t0 < n16) {
+            if (t0 + kNW < n16 && R0 + 1 < RT) {
+              run(std::integral_constant<int, 2>{}, r0c);
+              if (t0 + 2 * kNW < n16 && R0 + 2 < RT) run(std::integral_constant<int, 1>{}, std::integral_constant<int, R0 + 2>{});
+            } else {
+              run(std::integral_constant<int, 1>{}, r0c);
+            }
+          }
+        });
+      }
+    };
+
+    int b = blockIdx.x;
+    load_tiles(b, xt);
+    // Up to two blocks: all four filter banks stay in registers (80), so that the next frame's
+    // tiles are the only loads in flight while a frame is computed.  The load counter completes in
+    // order: a filter bank requested behind the frame's 18 loads per lane would arrive only after
+    // them, and a wait for a bank requested ahead of them is sized by the compiler for the loop's
+    // other trips, where fewer loads follow it, so that it caught 14 of the 18 (14 k of a frame's
+    // 42 k cycles, measured with cycle stamps).
+    constexpr bool resident = RES;
+    u32x4 wk[RES ? 4 : 1][NB][NS];
+    if constexpr (resident) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) load_bank(c < g.n_convs ? c : 0, wk[c]);
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the banks (and the first frame) have arrived
+    } else {
+      load_bank(0, wA);
+    }
+    __syncthreads();  // zeros in place
+    for (; b < g.B; b += gridDim.x) {
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+        const int t = wave + kNW * r;
+        if (t < n16) *(u32x2*)(X + tile_off16(t) + lane_o16) = relu2(xt[r]);
+      }
+      __syncthreads();
+      load_tiles(b + (int)gridDim.x < g.B ? b + (int)gridDim.x : b, nt);  // (last round: its own again)
+      if constexpr (resident) {
+        conv16(wk[0], 0, X, T, true);
+        __syncthreads();
+        conv16_b(wk[1], 1, g.n_convs > 2);
+        __syncthreads();  // X complete for the next block / T free for the next frame
+        if (g.n_convs > 2) {
+          conv16(wk[2], 2, X, T, true);
+          __syncthreads();
+          conv16_b(wk[3], 3, false);
+          __syncthreads();
+        }
+      } else {
+        for (int k = 0; k < g.n_convs; k += 2) {
+          load_bank(k + 1, wB);
+          conv16(wA, k, X, T, true);
+          __syncthreads();
+          load_bank(k + 2 < g.n_convs ? k + 2 : 0, wA);
+          conv16_b(wB, k + 1, k + 2 < g.n_convs);
+          __syncthreads();
+        }
+      }
+      unsigned char* dst = (unsigned char*)g.out + (size_t)b * pieces * 16;
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+        int o = lane_g;
+        asm volatile("" : "+v"(o));
+        const int t = wave + kNW * r;
+        if (t < n16) *(u32x2*)(dst + (size_t)t * 512 + o) = g.relu_out ? relu2(xt[r]) : xt[r];
+      }
+#pragma unroll
+      for (int r = 0; r < RT; ++r) xt[r] = nt[r];
+    }
+    return;
+  }
 
   int b = blockIdx.x;
   load_frame(b, xs);
@@ -376,9 +538,9 @@ size_t stage_lds_bytes(int c, int H, int W) {
   return 2 * (size_t)rows * (W + 2) * pitch + kMaxConvs * 32 * sizeof(float);  // + the biases
 }
 
-template <int C, int LW, int PPT>
-hipError_t launch_stage_t(const StageArgs& g, size_t lds, hipStream_t st) {
-  auto kern = res_stage_kernel<C, LW, PPT>;
+template <int C, int LW, int PPT, bool RES>
+hipError_t launch_stage_r(const StageArgs& g, size_t lds, hipStream_t st) {
+  auto kern = res_stage_kernel<C, LW, PPT, RES>;
   static std::once_flag once;
   static hipError_t attr_status = hipSuccess;
   std::call_once(once, [&] {
@@ -389,6 +551,14 @@ hipError_t launch_stage_t(const StageArgs& g, size_t lds, hipStream_t st) {
   const int blocks = g.B < 256 ? g.B : 256;
   kern<<<blocks, kNT, lds, st>>>(g);
   return hipGetLastError();
+}
+
+template <int C, int LW, int PPT>
+hipError_t launch_stage_t(const StageArgs& g, size_t lds, hipStream_t st) {
+  if constexpr (C == 16) {
+    if (g.n_convs <= 4) return launch_stage_r<C, LW, PPT, true>(g, lds, st);
+  }
+  return launch_stage_r<C, LW, PPT, false>(g, lds, st);
 }
 
 }  // namespace
