@@ -342,10 +342,12 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
     u32x2 xt[RT], nt[RT];
     auto tile_off16 = [&](int t) { return ((t << 4) >> LW) * ROW + ((t << 4) & (W - 1)) * PITCH; };
     const int lane_g = j16 * 32 + g16 * 8;  // the lane's 8 bytes within a tile's 512 in memory
-    auto load_tiles = [&](int bb, u32x2 (&dst)[RT]) {
+    // (part p of `parts`: rounds p, p + parts, ...)
+    auto load_tiles = [&](int bb, u32x2 (&dst)[RT], int part = 0, int parts = 1) {
       const unsigned char* src = (const unsigned char*)g.x + (size_t)bb * pieces * 16;
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
+        if (r % parts != part) continue;
         // (an opaque move keeps the offsets from being computed ahead of the frame loop and spilled)
         int o = lane_g;
         asm volatile("" : "+v"(o));
@@ -442,11 +444,16 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
         if (t < n16) *(u32x2*)(X + tile_off16(t) + lane_o16) = relu2(xt[r]);
       }
       __syncthreads();
-      load_tiles(b + (int)gridDim.x < g.B ? b + (int)gridDim.x : b, nt);  // (last round: its own again)
+      const int bn = b + (int)gridDim.x < g.B ? b + (int)gridDim.x : b;  // (last round: its own again)
       if constexpr (resident) {
+        // the next frame is requested in three parts between the convolutions: the requests of
+        // all workgroups in one burst kept the last waves of a workgroup 10 k cycles at issuing theirs
+        load_tiles(bn, nt, 0, 3);
         conv16(wk[0], 0, X, T, true);
+        load_tiles(bn, nt, 1, 3);
         __syncthreads();
         conv16_b(wk[1], 1, g.n_convs > 2);
+        load_tiles(bn, nt, 2, 3);
         __syncthreads();  // X complete for the next block / T free for the next frame
         if (g.n_convs > 2) {
           conv16(wk[2], 2, X, T, true);
@@ -455,6 +462,7 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
           __syncthreads();
         }
       } else {
+        load_tiles(bn, nt);
         for (int k = 0; k < g.n_convs; k += 2) {
           load_bank(k + 1, wB);
           conv16(wA, k, X, T, true);
