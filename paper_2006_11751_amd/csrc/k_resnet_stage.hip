@@ -76,6 +76,7 @@ struct StageArgs {
                                // [5][64] tap pairs for 16 channels (res_stage_pack16)
   const float* bias[kMaxConvs];  // [32] each
   int B, H, n_convs, relu_out;
+  int F;  // frames stacked into one LDS image (32 channels; 1 otherwise)
 };
 
 // C channels (16 or 32), frame width 1 << LW, PPT 16-byte pieces of a frame per thread; RES: the
@@ -99,8 +100,15 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (scalar: tile loops branch uniformly)
   const int li = lane & 31, lh = lane >> 5;
-  const int npix = g.H * W;
-  const int pieces = npix * C8;
+  // Small frames (the 9 x 16 frames of the benchmark's last stage are 4.5 tiles for 8 waves) are
+  // stacked F to an LDS image, one zero row between two frames: that row is the padding of both,
+  // the convolutions run over the stack as over one tall frame and store nothing into the
+  // separating rows, and the pieces of the F frames (contiguous in memory) skip them.
+  const int frame_pieces = g.H * W * C8;
+  const int HS = g.F * (g.H + 1) - 1;  // rows of the stack
+  const int npix = HS * W;
+  const int pieces = g.F * frame_pieces;  // of a full stack
+  const int n_groups = (g.B + g.F - 1) / g.F;
   const int n_tiles = (npix + 31) >> 5;
   // image rows: the frame, the ring, and the rows that the lanes of a partial last tile look at
   // (zeros, like the ring; those lanes store nothing)
@@ -120,9 +128,13 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
     const int p = tid + k * kNT;
     const int pc = p < pieces ? p : 0;
     const int pix = pc / C8, c8 = pc - pix * C8;
-    const int y = pix >> LW, x = pix & (W - 1);
+    const int ya = pix >> LW, x = pix & (W - 1);
+    // row within the stack: one separating row per frame before it (F <= 4)
+    const int y = ya + (ya >= g.H) + (ya >= 2 * g.H) + (ya >= 3 * g.H);
     return ((y + 1) * (W + 2) + x + 1) * PITCH + ((c8 * 16) ^ swz(x + 1));
   };
+  // pieces of stack b that exist (the last stack may hold fewer frames)
+  auto valid_pieces = [&](int b) { return min(g.F, g.B - b * g.F) * frame_pieces; };
   // this lane's pixel of tile 0 (for W >= 32 a tile lies in one row and the others follow by a
   // uniform step; for W = 16 a tile is two rows): byte offset of image pixel (y, x) of the
   // ring-less frame = ring pixel (y, x), i.e. the window origin of tap (0, 0)
@@ -140,6 +152,7 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
   u32x4 xs[PPT], nx[PPT];
   auto load_frame = [&](int b, u32x4 (&dst)[PPT]) {
     const u32x4* src = g.x + (size_t)b * pieces;
+    const int valid = valid_pieces(b);
 #pragma unroll
     for (int k = 0; k < PPT; ++k) {
       // (an opaque move keeps the index from being computed ahead of the frame loop, where it
@@ -147,7 +160,7 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
       int p = tid;
       asm volatile("" : "+v"(p));
       p += k * kNT;
-      dst[k] = src[p < pieces ? p : pieces - 1];
+      dst[k] = src[p < valid ? p : valid - 1];
     }
   };
   // A operands of a convolution: nine taps x NS channel groups for the 32x32x16 MFMA; five tap
@@ -227,6 +240,10 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
       for (int n = 0; n < N; ++n) {
         const int t = t0 + n * kNW;
         if ((t << 5) + li >= npix) continue;  // (a last tile may be partial)
+        if (g.F > 1) {  // (a row between two stacked frames stays zero)
+          const int ys = ((t << 5) + li) >> LW;
+          if (ys == g.H || ys == 2 * g.H + 1 || ys == 3 * g.H + 2) continue;
+        }
         // the lane's pixel in dst: ring pixel (y + 1, x + 1)
         unsigned char* o = dst + tile_off(t);
 #pragma unroll
@@ -490,12 +507,12 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
   load_frame(b, xs);
   load_bank(0, wA);
   __syncthreads();  // zeros in place
-  for (; b < g.B; b += gridDim.x) {
+  for (; b < n_groups; b += gridDim.x) {
 #pragma unroll
     for (int k = 0; k < PPT; ++k)
       if (tid + k * kNT < pieces) *(u32x4*)(X + poff(k)) = relu8(xs[k]);
     __syncthreads();
-    load_frame(b + (int)gridDim.x < g.B ? b + (int)gridDim.x : b, nx);  // (last round: its own again)
+    load_frame(b + (int)gridDim.x < n_groups ? b + (int)gridDim.x : b, nx);  // (last round: its own again)
     for (int k = 0; k < g.n_convs; k += 2) {
       // conv_a of the block: X -> T, ReLU; conv_b's bank arrives meanwhile
       load_bank(k + 1, wB);
@@ -527,18 +544,20 @@ __global__ __launch_bounds__(kNT, 1) void res_stage_kernel(StageArgs g) {
     // (the piece index goes through an opaque move: offsets computed ahead of the loop would be
     // spilled, and a reload between two stores waits for the first store to complete)
     u32x4* dst = g.out + (size_t)b * pieces;
+    const int valid = valid_pieces(b);
 #pragma unroll
     for (int k = 0; k < PPT; ++k) {
       int p = tid;
       asm volatile("" : "+v"(p));
       p += k * kNT;
-      if (p < pieces) dst[p] = g.relu_out ? relu8(xs[k]) : xs[k];
+      if (p < valid) dst[p] = g.relu_out ? relu8(xs[k]) : xs[k];
     }
 #pragma unroll
     for (int k = 0; k < PPT; ++k) xs[k] = nx[k];
   }
 }
 
+// (H: rows of the stack)
 size_t stage_lds_bytes(int c, int H, int W) {
   const int pitch = c == 16 ? 32 : 80;
   const int n_tiles = (H * W + 31) / 32;
@@ -556,7 +575,8 @@ hipError_t launch_stage_r(const StageArgs& g, size_t lds, hipStream_t st) {
   });
   if (attr_status != hipSuccess) return attr_status;
   // one workgroup per CU, each walking its share of the frames
-  const int blocks = g.B < 256 ? g.B : 256;
+  const int groups = (g.B + g.F - 1) / g.F;
+  const int blocks = groups < 256 ? groups : 256;
   kern<<<blocks, kNT, lds, st>>>(g);
   return hipGetLastError();
 }
@@ -588,16 +608,38 @@ void res_stage_pack16(const float* w, bool f16, std::vector<uint16_t>& wpk) {
 }
 
 // Shapes: 16 or 32 channels, frame width 16, 32 or 64, both LDS images within 160 KB, at most
-// nine 16-byte pieces of the frame per thread, one to four blocks; and at least one 32-pixel
-// tile per wave (smaller frames leave waves idle: the per-block tile kernels are faster there,
-// measured on the 9 x 16 frames of the benchmark's last stage).
+// nine 16-byte pieces per thread, one to four blocks; and at least one 32-pixel tile per wave,
+// for which 32-channel frames smaller than that are stacked two to four to an image.
+namespace {
+// Frames per LDS image: 1 where a frame has a tile for every wave; else (32 channels) the
+// stack of 2 to 4 frames that fills the waves' tile rounds best; 0: not a shape for this kernel.
+int stage_frames(int c, int H, int W) {
+  if ((c != 16 && c != 32) || (W != 16 && W != 32 && W != 64) || H < 1) return 0;
+  auto fits = [&](int F) {
+    const int HS = F * (H + 1) - 1;
+    return stage_lds_bytes(c, HS, W) <= 160 * 1024 && (F * H * W * c / 8 + kNT - 1) / kNT <= 9;
+  };
+  if ((H * W + 31) / 32 >= kNW) return fits(1) ? 1 : 0;
+  if (c != 32) return 0;
+  int best = 0;
+  double best_fill = 0.0;
+  for (int F = 2; F <= 4; ++F) {
+    const int tiles = ((F * (H + 1) - 1) * W + 31) / 32;
+    if (tiles < kNW || !fits(F)) continue;
+    // useful pixels per tile slot of the rounds the waves go through
+    const double fill = (double)F * H * W / (32.0 * kNW * ((tiles + kNW - 1) / kNW));
+    if (fill > best_fill) {
+      best_fill = fill;
+      best = F;
+    }
+  }
+  return best;
+}
+}  // namespace
+
 bool res_stage_supported(int c, int H, int W, int n_blocks) {
-  if ((c != 16 && c != 32) || (W != 16 && W != 32 && W != 64) || H < 1) return false;
-  if ((H * W + 31) / 32 < kNW) return false;
   if (n_blocks < 1 || 2 * n_blocks > kMaxConvs) return false;
-  if (stage_lds_bytes(c, H, W) > 160 * 1024) return false;
-  const int pieces = H * W * c / 8;
-  return (pieces + kNT - 1) / kNT <= 9;
+  return stage_frames(c, H, W) > 0;
 }
 
 // x, out: fp16 [B][H][W][c] (may be the same buffer: a workgroup reads a frame before it
@@ -614,8 +656,9 @@ hipError_t launch_res_stage(const void* x, void* out, const uint16_t* const* wpk
     g.bias[k] = bias[k < n_convs ? k : 0];
   }
   g.B = B; g.H = H; g.n_convs = n_convs; g.relu_out = relu_out;
-  const size_t lds = stage_lds_bytes(c, H, W);
-  const int ppt = (H * W * c / 8 + kNT - 1) / kNT;
+  g.F = stage_frames(c, H, W);
+  const size_t lds = stage_lds_bytes(c, g.F * (H + 1) - 1, W);
+  const int ppt = (g.F * H * W * c / 8 + kNT - 1) / kNT;
 #define SF_STAGE(C, LW)                                                    \
   do {                                                                     \
     if (ppt <= 2) return launch_stage_t<C, LW, 2>(g, lds, st);             \

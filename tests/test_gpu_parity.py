@@ -62,7 +62,8 @@ RESNET_BF16_MID = dict(RESNET_BF16_SMALL, name="resnet_bf16_mid", B=3, obs=(3, 5
 RESNET_BF16_MIX = dict(RESNET_BF16_SMALL, name="resnet_bf16_mix", B=4, obs=(3, 30, 42), stages=[32, 16, 32])
 # stage frames of 24 x 64 (16 channels) and 12 x 32 (32 channels): the kernel that runs all blocks
 # of a stage with the frame resident in LDS; more frames than its workgroups (256), so some walk
-# two frames.  (The last stage, 6 x 16, is too small for it and takes the per-block kernels.)
+# two frames.  (The last stage, 6 x 16, has fewer tiles than that kernel has waves: four frames
+# share an LDS image.)
 RESNET_BF16_POW2 = dict(RESNET_BF16_SMALL, name="resnet_bf16_pow2", B=300, obs=(3, 48, 128))
 # 136 x 128 frames: the first two stages are too large for that kernel, the last (17 x 16 pixels:
 # two image rows per MFMA tile, the ninth tile half empty) runs on it
@@ -535,5 +536,47 @@ def test_stage_convolution_pooled_in_registers(torch_cuda, ref, monkeypatch, net
     g2 = _gpu_step(torch, old, obs, h_in, done, 7, 11)
     parity.assert_close("h_out vs LDS-pooled kernels", g["h_out"], g2["h_out"], 4e-3)
     parity.assert_close("value vs LDS-pooled kernels", g["value"], g2["value"], 4e-3)
+    pol.close()
+    old.close()
+
+
+# last-stage frames (32 channels) with fewer 32-pixel tiles than the stage kernel has waves: the
+# kernel stacks them in its LDS image.  9 x 16 (three to a stack; 7 frames: the last stack holds
+# one), 6 x 16 (four to a stack; 302 frames: more stacks than workgroups would be at 256, the last
+# holds two), 13 x 16 (two to a stack, the last holds one); 5 x 32 and 3 x 16 (second and third
+# stage both stacked by four, the last stack with three).
+STACKED_STAGE_NETS = [(dict(RESNET_BF16_SMALL, name="resnet_bf16_72x128", B=7, obs=(3, 72, 128)), 3),
+                      (dict(RESNET_BF16_SMALL, name="resnet_bf16_48x128", B=302, obs=(3, 48, 128)), 3),
+                      (dict(RESNET_BF16_SMALL, name="resnet_bf16_100x128", B=5, obs=(3, 100, 128)), 2),
+                      (dict(RESNET_BF16_SMALL, name="resnet_bf16_20x128", B=11, obs=(3, 20, 128)), 3)]
+
+
+@pytest.mark.parametrize("net,n_stage", STACKED_STAGE_NETS, ids=lambda v: v["name"] if isinstance(v, dict) else str(v))
+def test_small_stage_frames_stacked_in_lds(torch_cuda, ref, monkeypatch, net, n_stage):
+    """Residual blocks of a stage whose frames are smaller than the stage kernel's eight tiles:
+    several frames share one LDS image, a row of zeros between them.  Against the oracle, and
+    against the per-block kernels (same arithmetic per output up to the summation order inside
+    the matrix cores)."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    w = wl.weights(net)
+    B = net["B"]
+    obs, h_in, done = wl.observations(net, 0, B), wl.initial_state(net, B), wl.done_mask(net, 0, B)
+    pol = binding.Policy(net, w)
+    assert pol.op_kernels().count("res_stage") == n_stage, pol.op_kernels()
+    g = _gpu_step(torch, pol, obs, h_in, done, 7, 11)
+    rows = np.arange(B) if B <= 16 else np.unique(np.concatenate([np.arange(0, B, 23), np.arange(B - 6, B), [255, 256, 257]]))
+    o = ref.policy_step(net, w, obs[rows], h_in[rows], done[rows], 7, 11)
+    parity.assert_close("h_out", g["h_out"][rows], o["h_out"], 1e-2)
+    parity.assert_close("value", g["value"][rows], o["value"], 1e-2)
+    monkeypatch.setenv("SF_NO_RES_STAGE", "1")
+    old = binding.Policy(net, w)
+    monkeypatch.delenv("SF_NO_RES_STAGE")
+    assert "res_stage" not in old.op_kernels(), old.op_kernels()
+    g2 = _gpu_step(torch, old, obs, h_in, done, 7, 11)
+    # (both keep the residual stream in fp16 and round it at different points: each measured about
+    # 1e-3 from the oracle, so twice that from one another)
+    parity.assert_close("h_out vs per-block kernels", g["h_out"], g2["h_out"], 1e-2)
+    parity.assert_close("value vs per-block kernels", g["value"], g2["value"], 1e-2)
     pol.close()
     old.close()
