@@ -29,11 +29,10 @@
  * Pins (tests/test_oracle_*.py): convolution, pooling, linear and GRU against
  * PyTorch's CPU fp64 routines and hand-computed / closed-form cases; the whole
  * step against a PyTorch fp64 composition; softmax and sampler against their
- * invariants and a chi-square test; Philox against an independent big-integer
- * implementation.  PARITY UNPINNED: conformance of ref_philox4x32_10 to the
- * published known-answer vectors of Philox4x32-10 (the vectors are not
- * available here); the ResNet pooling alignment, the normalisation constant and
- * the initialisation variance are conventions of this build, not of the paper.
+ * invariants and a chi-square test; Philox against its published known answers
+ * and an independent big-integer implementation.  PARITY UNPINNED: the ResNet
+ * pooling alignment, the normalisation constant and the initialisation variance
+ * are conventions of this build, not of the paper.
  */
 #ifndef SF_ORACLE_H
 #define SF_ORACLE_H

@@ -1,12 +1,12 @@
 """Pins for the oracle's sampler: Philox structure, bits->uniform exactness,
 Gumbel moments, softmax invariants, distributional correctness, tie rule.
 
-Conformance of Philox4x32-10 to its published known-answer vectors is NOT pinned
-here (the vectors are not available in this environment): what is pinned is the
-round structure, against an independent big-integer implementation written from
-the algorithm's description, and statistical behaviour of the draws.
+Philox4x32-10 is pinned three ways: its published known answers (tests/golden), an
+independent big-integer implementation written from the algorithm's description, and
+the statistical behaviour of the draws.
 """
 import math
+import os
 
 import numpy as np
 import pytest
@@ -54,6 +54,19 @@ def test_philox_matches_bigint_implementation(ref):
         assert list(ref.philox4x32_10(ctr, key)) == philox_py(ctr, key)
     for ctr, key in [((0, 0, 0, 0), (0, 0)), ((MASK,) * 4, (MASK, MASK))]:
         assert list(ref.philox4x32_10(ctr, key)) == philox_py(ctr, key)
+
+
+def test_philox_known_answers(ref):
+    """The published known answers of Philox4x32-10: a wrong round constant, multiplier, round
+    count or word order in the oracle and in the big-integer copy above alike would pass the
+    comparison of the two, but not this."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_known_answers.txt")
+    cases = [[int(w, 16) for w in line.split()] for line in open(path) if line.strip() and not line.startswith("#")]
+    assert len(cases) == 3
+    for words in cases:
+        ctr, key, want = words[:4], words[4:6], words[6:]
+        assert [int(v) for v in ref.philox4x32_10(np.array(ctr, np.uint32), np.array(key, np.uint32))] == want
+        assert philox_py(ctr, key) == want
 
 
 def test_philox_is_invertible(ref):
