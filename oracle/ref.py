@@ -232,6 +232,33 @@ def policy_step_indexed(net, w, obs, h_table, env_ids, done, seed, step, meas=No
     return out
 
 
+def policy_unroll(net, w, obs, h0, done, meas=None):
+    """The learner's forward pass: obs [T,N,C,H,W] u8, h0 [N,state_dim], done [T,N] (meas
+    [T,N,meas_dim]); returns dict(logits [T,N,sumA], value [T,N], h_seq [T,N,state_dim])."""
+    L = lib()
+    rn = make_net(net)
+    rp, keep = make_params(w)
+    T, N = int(obs.shape[0]), int(obs.shape[1])
+    obs = np.ascontiguousarray(obs, dtype=np.uint8)
+    h0 = _f32(h0)
+    done = np.ascontiguousarray(done, dtype=np.uint8)
+    assert done.shape == (T, N) and h0.shape == (N, state_dim(net))
+    sumA, S = int(sum(net["heads"])), state_dim(net)
+    meas_p = None
+    if net.get("meas_dim", 0) > 0:
+        meas = _f32(meas)
+        assert meas.shape == (T, N, net["meas_dim"])
+        meas_p = _p(meas)
+    out = {"logits": np.zeros((T, N, sumA), np.float32), "value": np.zeros((T, N), np.float32),
+           "h_seq": np.zeros((T, N, S), np.float32)}
+    rc = L.ref_policy_unroll(C.byref(rn), C.byref(rp), C.c_int32(T), C.c_int32(N), _p(obs), meas_p, _p(h0),
+                             _p(done), _p(out["logits"]), _p(out["value"]), _p(out["h_seq"]))
+    if rc != 0:
+        raise ValueError("ref_policy_unroll rejected the arguments")
+    del keep
+    return out
+
+
 class RefLossCfg(C.Structure):
     _fields_ = [("T", C.c_int32), ("N", C.c_int32), ("n_heads", C.c_int32),
                 ("head_sizes", C.c_int32 * MAX_HEADS),

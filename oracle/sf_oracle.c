@@ -483,6 +483,33 @@ int ref_policy_step_indexed(const ref_net* net, const ref_params* p, int32_t B, 
   return 0;
 }
 
+/* ---- learner's forward pass over trajectories -------------------------------- */
+
+int ref_policy_unroll(const ref_net* net, const ref_params* p, int32_t T, int32_t N,
+                      const uint8_t* obs, const float* meas, const float* h0, const uint8_t* done,
+                      float* logits, float* value, float* h_seq) {
+  if (check_net(net) || T < 1 || N < 0) return -1;
+  if (net->meas_dim > 0 && N > 0 && !meas) return -1;
+  const size_t Sd = (size_t)ref_state_dim(net);
+  const size_t frame = (size_t)net->obs_c * net->obs_h * net->obs_w;
+  size_t sumA = 0;
+  for (int k = 0; k < net->n_heads; ++k) sumA += (size_t)net->head_sizes[k];
+  /* the step draws actions as well: they are not part of this pass and are dropped */
+  int32_t* actions = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1) * net->n_heads);
+  float* logp = (float*)malloc(sizeof(float) * (size_t)(N > 0 ? N : 1));
+  int rc = 0;
+  for (int32_t t = 0; t < T && rc == 0; ++t) {
+    const size_t r = (size_t)t * N; /* first row of time t */
+    const float* h_prev = t == 0 ? h0 : h_seq + (r - N) * Sd;
+    rc = ref_policy_step(net, p, N, obs + r * frame, meas ? meas + r * net->meas_dim : NULL, h_prev,
+                         done + r, 0, (uint64_t)t, actions, logp, value + r, h_seq + r * Sd,
+                         logits + r * sumA, NULL);
+  }
+  free(actions);
+  free(logp);
+  return rc;
+}
+
 /* ---- learner-side loss ----------------------------------------------------- */
 
 int ref_appo_loss(const ref_loss_cfg* cfg, const float* logits, const int32_t* actions,

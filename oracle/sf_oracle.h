@@ -28,7 +28,8 @@
  *
  * Pins (tests/test_oracle_*.py): convolution, pooling, linear and GRU against
  * PyTorch's CPU fp64 routines and hand-computed / closed-form cases; the whole
- * step against a PyTorch fp64 composition; softmax and sampler against their
+ * step against a PyTorch fp64 composition, the pass over trajectories against
+ * PyTorch's fp64 sequence modules; softmax and sampler against their
  * invariants and a chi-square test; Philox against its published known answers
  * and an independent big-integer implementation.  PARITY UNPINNED: the ResNet
  * pooling alignment, the normalisation constant and the initialisation variance
@@ -214,6 +215,19 @@ int ref_policy_step_indexed(const ref_net* net, const ref_params* p, int32_t B, 
                             const float* meas, float* h_table, int32_t n_env, const int32_t* env_ids,
                             const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions,
                             float* logp, float* value, float* logits_opt, float* margin_opt);
+
+/* The learner's forward pass over trajectories (paper, Sec. 3.1: the learner recomputes the
+ * network's outputs on the collected trajectories of T steps, the recurrent core unrolled
+ * over them; hyperparameter table of App. "VizDoom experiments": rollout T = 32).  Time-major
+ * arrays: obs [T][N][C][H][W]; meas [T][N][meas_dim] or NULL; h0 [N][state_dim], the state
+ * each trajectory started from; done [T][N] (non-zero at (t, n): step t of trajectory n is
+ * the first of a new episode, its incoming state is zero).  It is T applications of the
+ * step in order, trajectory n at time t taking the state that time t - 1 left (h0 at t = 0):
+ *   logits [T][N][sumA]; value [T][N]; h_seq [T][N][state_dim] (row t = state after step t).
+ * No action is drawn.  Returns 0, -1 on a bad description or T < 1. */
+int ref_policy_unroll(const ref_net* net, const ref_params* p, int32_t T, int32_t N,
+                      const uint8_t* obs, const float* meas, const float* h0, const uint8_t* done,
+                      float* logits, float* value, float* h_seq);
 
 /* ---- learner-side loss on a batch of trajectories -------------------------- */
 

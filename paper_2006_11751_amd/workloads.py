@@ -240,6 +240,16 @@ def measurements(net, t=0, B=None, seed=None):
     return rng.standard_normal((B, net["meas_dim"])).astype(np.float32)
 
 
+def trajectory_inputs(net, T, N):
+    """Inputs of the learner's forward pass over N trajectories of T steps, time-major: the
+    per-step draws above stacked.  Returns obs [T,N,C,H,W] u8, h0 [N,state_dim] fp32, done [T,N]
+    u8, meas [T,N,meas_dim] fp32 or None."""
+    obs = np.stack([observations(net, t, N) for t in range(T)])
+    done = np.stack([done_mask(net, t, N) for t in range(T)])
+    meas = np.stack([measurements(net, t, N) for t in range(T)]) if net.get("meas_dim", 0) else None
+    return obs, initial_state(net, N), done, meas
+
+
 PHILOX_SEED = 1
 
 
