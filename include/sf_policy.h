@@ -245,6 +245,31 @@ int sf_policy_step_indexed(sf_policy* p, int32_t B, const uint8_t* obs, const fl
                            uint64_t seed, uint64_t step, int32_t* actions, float* logp,
                            float* value, float* logits_opt, void* hip_stream);
 
+/* The learner's forward pass over N trajectories of T steps (paper, Sec. 3.1: the learner
+ * recomputes the network on the collected trajectories, the recurrent core unrolled over
+ * their T steps; hyperparameter table of App. "VizDoom experiments": rollout T = 32, batch of
+ * 2048 samples = 64 trajectories).  Its outputs are what sf_appo_loss takes as `logits` and
+ * as the first T rows of `values`.  All arrays time-major, on the device:
+ *   obs     dev  [T][N][obs_c][obs_h][obs_w] bytes, 4-byte aligned
+ *   meas    dev  [T][N][meas_dim] fp32 (NULL without that input)
+ *   h0      dev  [N][state_dim] fp32, 16-byte aligned: the state each trajectory started from
+ *   done    dev  [T][N] bytes: non-zero at (t, n) = step t of trajectory n begins an episode,
+ *                its incoming state is zero
+ *   logits  dev  [T][N][sum(head_sizes)] fp32;  value  dev [T][N] fp32
+ *   h_seq   dev  [T][N][state_dim] fp32, 16-byte aligned, must not overlap h0: row t is the
+ *                state after step t (the last row is the state the trajectories end in)
+ * The result is that of T calls of sf_policy_step, time t on rows [t][0..N) with the state
+ * rows time t - 1 wrote, except that no action is drawn.  The launches: the encoder and the
+ * FC layer once on all T * N frames, the core T times on N rows, the heads once on T * N
+ * states; the features pass through the handle's workspace, hence T * N <= max_batch, and
+ * N rows of features and of state must be a multiple of 16 bytes.  Asynchronous on
+ * hip_stream; allocates nothing.  N == 0 does nothing.  Errors: SF_ERR_ARG (null or
+ * misaligned pointer), SF_ERR_BATCH (T < 1, N < 0, T * N > max_batch), SF_ERR_SHAPE (the
+ * 16-byte rule), SF_ERR_ALIAS, SF_ERR_DEVICE. */
+int sf_policy_unroll(sf_policy* p, int32_t T, int32_t N, const uint8_t* obs, const float* meas,
+                     const float* h0, const uint8_t* done, float* logits, float* value,
+                     float* h_seq, void* hip_stream);
+
 /* Replace the policy's parameters by new values of the same shapes (paper, Sec. 3.3: after
  * every learner step the policy workers fetch the new parameters; Sec. 3.4: the fresher
  * the sampling policy, the smaller the policy lag).  `weights` as for sf_policy_create:

@@ -125,7 +125,7 @@ EXPORTS = ("sf_policy_create", "sf_policy_step", "sf_policy_destroy", "sf_last_e
            "sf_pipeline_wait", "sf_pipeline_destroy", "sf_policy_state_dim",
            "sf_policy_update_weights", "sf_appo_loss", "sf_appo_loss_workspace_bytes",
            "sf_policy_op_pipe", "sf_policy_conv1_fixed_point_ratio", "sf_conv1_fixed_point_test",
-           "sf_appo_loss_static", "sf_appo_loss_static_max_trajectories", "sf_policy_op_kernel")
+           "sf_appo_loss_static", "sf_appo_loss_static_max_trajectories", "sf_policy_op_kernel", "sf_policy_unroll")
 
 _lib = None
 
@@ -199,6 +199,8 @@ def load_library():
                                              C.c_int32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.c_void_p]
+        L.sf_policy_unroll.restype = C.c_int
+        L.sf_policy_unroll.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 8
         L.sf_pipeline_create.restype = C.c_int
         L.sf_pipeline_create.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
         L.sf_pipeline_submit.restype = C.c_int
@@ -305,6 +307,13 @@ def sf_policy_step_indexed(handle, B, obs, meas, h_table, n_env, env_ids, done, 
     """Device addresses (ints); h_table [n_env, state_dim] is read and written at rows env_ids."""
     rc = load_library().sf_policy_step_indexed(handle, B, obs, meas, h_table, n_env, env_ids, done,
                                                seed, step, actions, logp, value, logits_opt, hip_stream)
+    if rc != SF_OK:
+        raise SfError(rc, sf_last_error())
+
+
+def sf_policy_unroll(handle, T, N, obs, meas, h0, done, logits, value, h_seq, hip_stream=None):
+    """Device addresses (ints) of time-major arrays; see include/sf_policy.h."""
+    rc = load_library().sf_policy_unroll(handle, T, N, obs, meas, h0, done, logits, value, h_seq, hip_stream)
     if rc != SF_OK:
         raise SfError(rc, sf_last_error())
 
@@ -540,6 +549,30 @@ class Policy:
                                out["value"].data_ptr(),
                                out["logits"].data_ptr() if out.get("logits") is not None else None,
                                s.cuda_stream)
+        return out
+
+    def unroll(self, obs, h0, done, out=None, stream=None, meas=None):
+        """The learner's forward pass: obs u8 [T,N,C,H,W], h0 f32 [N,state_dim], done u8 [T,N],
+        meas f32 [T,N,meas_dim]: contiguous CUDA tensors.  Returns logits [T,N,sumA], value [T,N],
+        h_seq [T,N,state_dim]."""
+        t = self._torch
+        T, N = obs.shape[0], obs.shape[1]
+        assert obs.dtype == t.uint8 and h0.dtype == t.float32 and done.dtype == t.uint8
+        assert obs.is_contiguous() and h0.is_contiguous() and done.is_contiguous()
+        assert tuple(obs.shape[2:]) == tuple(self.net["obs"]) and tuple(done.shape) == (T, N)
+        assert tuple(h0.shape) == (N, self.H)
+        if out is None:
+            f32 = dict(dtype=t.float32, device=self.device)
+            out = {"logits": t.empty((T, N, sum(self.net["heads"])), **f32), "value": t.empty((T, N), **f32),
+                   "h_seq": t.empty((T, N, self.H), **f32)}
+        meas_ptr = None
+        if self.meas_dim:
+            assert meas is not None and meas.dtype == t.float32 and meas.is_contiguous()
+            assert tuple(meas.shape) == (T, N, self.meas_dim)
+            meas_ptr = meas.data_ptr()
+        s = stream if stream is not None else t.cuda.current_stream(self.device)
+        sf_policy_unroll(self.handle, T, N, obs.data_ptr(), meas_ptr, h0.data_ptr(), done.data_ptr(),
+                         out["logits"].data_ptr(), out["value"].data_ptr(), out["h_seq"].data_ptr(), s.cuda_stream)
         return out
 
     def close(self):

@@ -118,6 +118,7 @@ __global__ __launch_bounds__(kWave* kRowsPerBlock) void heads_kernel(
   if (lane == 0) value[b] = lg[sumA];
   if (logits_opt)
     for (int a = lane; a < sumA; a += kWave) logits_opt[(size_t)b * sumA + a] = lg[a];
+  if (!actions) return;  // (the learner's pass wants logits and value only)
 
   // Gumbel perturbation of every logit of every head in one pass over the lanes.
   for (int idx = lane; idx < sumA; idx += kWave) {

@@ -1036,10 +1036,13 @@ namespace {
 // The launch sequence of one step.  h_in / h_out are row-indexed by the batch row, unless
 // ids is given: then row b reads its state from h_in[ids[b]] (a table of n_env rows), and
 // the heads launch copies the new state from h_out[b] to h_table[ids[b]].
+// `parts` selects which launches run: the encoder (everything before the core), the core, the
+// heads.  The core reads its input rows starting at row `feat_row` of the encoder's output.
+enum : unsigned { PART_ENCODER = 1u, PART_CORE = 2u, PART_HEADS = 4u, PART_ALL = 7u };
 int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const float* h_in,
              const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions, float* logp,
              float* value, float* h_out, float* logits_opt, const int32_t* ids, float* h_table,
-             int n_env, hipStream_t st);
+             int n_env, hipStream_t st, unsigned parts = PART_ALL, size_t feat_row = 0);
 
 bool misaligned(const void* q, uintptr_t a) { return (reinterpret_cast<uintptr_t>(q) & (a - 1)) != 0; }
 
@@ -1121,12 +1124,15 @@ namespace {
 int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const float* h_in,
              const uint8_t* done, uint64_t seed, uint64_t step, int32_t* actions, float* logp,
              float* value, float* h_out, float* logits_opt, const int32_t* ids, float* h_table,
-             int n_env, hipStream_t st) {
+             int n_env, hipStream_t st, unsigned parts, size_t feat_row) {
   const sf_policy_config& c = p->cfg;
   auto buf = [&](int i) -> float* { return i < 0 ? nullptr : p->act[i]; };
-  if (p->timing) SF_LAUNCH(hipEventRecord(p->events[0], st));
+  const bool timing = p->timing && parts == PART_ALL;
+  if (timing) SF_LAUNCH(hipEventRecord(p->events[0], st));
   for (size_t i = 0; i < p->ops.size(); ++i) {
     const Op& op = p->ops[i];
+    const unsigned part = op.kind == OP_GRU ? PART_CORE : op.kind == OP_HEADS ? PART_HEADS : PART_ENCODER;
+    if (!(parts & part)) continue;
     switch (op.kind) {
       case OP_CONV: {
         const ConvLayer& L = p->convs[op.conv];
@@ -1251,18 +1257,20 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
         break;
       }
       case OP_GRU: {
-        const float* x2 = p->n_meas ? p->meas_buf[p->n_meas - 1] : nullptr;
+        const float* x2 = p->n_meas ? p->meas_buf[p->n_meas - 1] + feat_row * p->meas_out_dim : nullptr;
+        const float* x1 = (const float*)((const char*)p->fc_out +
+                                         feat_row * c.fc_dim * (p->fc_out_bf16 ? 2 : 4));
         const int lstm = c.rnn_type == SF_RNN_LSTM;
         if (p->rnn_wih_bf)
-          SF_LAUNCH(launch_rnn_bf16(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out,
+          SF_LAUNCH(launch_rnn_bf16(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, x1,
                                     p->fc_out_bf16, x2, h_in, done, p->rnn_wih_bf, p->rnn_whh_bf, p->gru_bih, p->gru_bhh, h_out,
                                     ids, n_env, st));
         else if (p->gru_wih)
-          SF_LAUNCH(launch_rnn_mfma(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out, x2, h_in,
+          SF_LAUNCH(launch_rnn_mfma(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, x1, x2, h_in,
                                     done, p->gru_wih, p->gru_whh, p->gru_bih, p->gru_bhh, h_out,
                                     p->gru_bm, p->rnn_plain_loops, ids, n_env, st));
         else
-          SF_LAUNCH(launch_rnn_generic(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, p->fc_out, x2,
+          SF_LAUNCH(launch_rnn_generic(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, x1, x2,
                                        h_in, done, p->gru_wih_t, p->gru_whh_t, p->gru_bih, p->gru_bhh,
                                        h_out, ids, n_env, st));
         break;
@@ -1273,12 +1281,69 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
                                n_env, p->state_dim, p->max_head, st));
         break;
     }
-    if (p->timing) SF_LAUNCH(hipEventRecord(p->events[i + 1], st));
+    if (timing) SF_LAUNCH(hipEventRecord(p->events[i + 1], st));
   }
   return SF_OK;
 }
 
 }  // namespace
+
+extern "C" int sf_policy_unroll(sf_policy* handle, int32_t T, int32_t N, const uint8_t* obs,
+                                const float* meas, const float* h0, const uint8_t* done,
+                                float* logits, float* value, float* h_seq, void* hip_stream) {
+  Policy* p = reinterpret_cast<Policy*>(handle);
+  if (!p) {
+    set_error("sf_policy_unroll: null handle");
+    return SF_ERR_ARG;
+  }
+  const sf_policy_config& c = p->cfg;
+  if (T < 1 || N < 0 || (int64_t)T * N > c.max_batch) {
+    set_error("sf_policy_unroll: T = %d, N = %d: need T >= 1, N >= 0 and T * N <= max_batch = %d", T, N,
+              c.max_batch);
+    return SF_ERR_BATCH;
+  }
+  if (N == 0) return SF_OK;
+  if (!obs || !h0 || !done || !logits || !value || !h_seq || (c.meas_dim > 0 && !meas)) {
+    set_error("sf_policy_unroll: null buffer");
+    return SF_ERR_ARG;
+  }
+  if (misaligned(obs, 4) || (c.meas_dim > 0 && misaligned(meas, 4)) || misaligned(h0, 16) ||
+      misaligned(h_seq, 16) || misaligned(logits, 4) || misaligned(value, 4)) {
+    set_error("sf_policy_unroll: misaligned buffer (obs, meas, logits, value: 4 bytes; h0, h_seq: 16 bytes)");
+    return SF_ERR_ARG;
+  }
+  // every time step's rows must start where the kernels may use 16-byte accesses
+  const size_t feat_bytes = (size_t)N * c.fc_dim * (p->fc_out_bf16 ? 2 : 4);
+  if (feat_bytes % 16 || ((size_t)N * p->meas_out_dim * 4) % 16 || ((size_t)N * p->state_dim * 4) % 16) {
+    set_error("sf_policy_unroll: N = %d rows of features (%d), measurement features (%d) or state (%d "
+              "floats) are not a multiple of 16 bytes", N, c.fc_dim, p->meas_out_dim, p->state_dim);
+    return SF_ERR_SHAPE;
+  }
+  {
+    const uintptr_t a0 = (uintptr_t)h0, b0 = (uintptr_t)h_seq;
+    if (a0 < b0 + sizeof(float) * (uintptr_t)T * N * p->state_dim && b0 < a0 + sizeof(float) * (uintptr_t)N * p->state_dim) {
+      set_error("sf_policy_unroll: h_seq overlaps h0");
+      return SF_ERR_ALIAS;
+    }
+  }
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const int32_t rows = T * N;
+  // the encoder on all T * N frames at once (their features stay in the handle's workspace) ...
+  int rc = run_step(p, rows, obs, meas, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr,
+                    nullptr, nullptr, 0, st, PART_ENCODER);
+  // ... the core one time step after the other, each reading the state rows the previous wrote ...
+  for (int32_t t = 0; t < T && rc == SF_OK; ++t) {
+    const size_t r = (size_t)t * N;
+    const float* h_prev = t == 0 ? h0 : h_seq + (r - N) * p->state_dim;
+    rc = run_step(p, N, nullptr, nullptr, h_prev, done + r, 0, 0, nullptr, nullptr, nullptr,
+                  h_seq + r * p->state_dim, nullptr, nullptr, nullptr, 0, st, PART_CORE, r);
+  }
+  // ... and the heads on all T * N states at once (no action is drawn)
+  if (rc == SF_OK)
+    rc = run_step(p, rows, nullptr, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, value, h_seq, logits,
+                  nullptr, nullptr, 0, st, PART_HEADS);
+  return rc;
+}
 
 extern "C" int32_t sf_policy_state_dim(const sf_policy* handle) {
   return handle ? reinterpret_cast<const Policy*>(handle)->state_dim : 0;

@@ -1,0 +1,148 @@
+"""GPU parity of the learner's forward pass over trajectories (paper, Sec. 3.1; rollout length
+and batch size of the hyperparameter table, App. "VizDoom experiments") against the oracle,
+through the C ABI: small networks of every kernel family on all elements, the benchmark network at
+the paper's 64 trajectories x 32 steps on sampled trajectories, bit-equality with T single steps,
+the pass feeding the loss kernels, and the error paths.
+"""
+import numpy as np
+import pytest
+
+from paper_2006_11751_amd import workloads as wl
+from tests import parity
+from tests.test_gpu_core import NETS as CORE_NETS
+from tests.test_gpu_parity import ODD_NET, RESNET_BF16_SMALL, SMALL_RESNET, STD_BF16_SMALL, _to_np
+
+pytestmark = pytest.mark.gpu
+
+BY_NAME = {n["name"]: n for n in CORE_NETS}
+# (T, N) chosen so that N rows of features and state are multiples of 16 bytes
+CASES = [
+    (wl.network(0), 4, 8),
+    (ODD_NET, 5, 4),                       # generic kernels, 33 state floats per row
+    (SMALL_RESNET, 3, 4),
+    (STD_BF16_SMALL, 6, 8),                # bf16 features into the 16-bit core
+    (RESNET_BF16_SMALL, 4, 6),
+    (BY_NAME["lstm_mfma"], 7, 5),          # [h | c] state rows
+    (BY_NAME["full_mfma"], 5, 8),          # measurement input, seven heads
+    (BY_NAME["full_lstm_mfma"], 3, 12),
+    (BY_NAME["lstm_bf16_mfma"], 4, 16),
+]
+
+
+def _unroll(torch, pol, obs, h0, done, meas):
+    d = pol.device
+    out = pol.unroll(torch.from_numpy(obs).to(d), torch.from_numpy(h0).to(d), torch.from_numpy(done).to(d),
+                     meas=None if meas is None else torch.from_numpy(meas).to(d))
+    torch.cuda.synchronize()
+    return _to_np(out)
+
+
+@pytest.mark.parametrize("net,T,N", CASES, ids=["%s-%dx%d" % (n["name"], T, N) for n, T, N in CASES])
+def test_unroll_matches_the_oracle_and_the_single_steps(torch_cuda, ref, net, T, N):
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    net = dict(net, p_done=0.25)
+    w = wl.weights(net)
+    obs, h0, done, meas = wl.trajectory_inputs(net, T, N)
+    pol = binding.Policy(net, w, max_batch=T * N)
+    g = _unroll(torch, pol, obs, h0, done, meas)
+    o = ref.policy_unroll(net, w, obs, h0, done, meas=meas)
+    rtol = parity.RTOL[net["dtype"]]
+    stats = {k: parity.assert_close(k, g[k], o[k], rtol) for k in ("h_seq", "logits", "value")}
+    # the same bits as T calls of the step, each on the N rows of its time with the state carried
+    d = pol.device
+    h = torch.from_numpy(h0).to(d)
+    for t in range(T):
+        out = pol.step(torch.from_numpy(obs[t]).to(d), h, torch.from_numpy(done[t]).to(d), 3, t,
+                       meas=None if meas is None else torch.from_numpy(meas[t]).to(d))
+        torch.cuda.synchronize()
+        assert np.array_equal(out["h_out"].cpu().numpy(), g["h_seq"][t]), t
+        assert np.array_equal(out["logits"].cpu().numpy(), g["logits"][t]), t
+        assert np.array_equal(out["value"].cpu().numpy(), g["value"][t]), t
+        h = out["h_out"]
+    print(net["name"], stats)
+    pol.close()
+
+
+def test_benchmark_network_at_the_papers_batch(torch_cuda, ref):
+    """64 trajectories of 32 steps (2048 samples) on the benchmark network: trajectories 0, 31 and 63
+    against the oracle (trajectories are independent), every step of them."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    net = wl.network(1, p_done=0.05)
+    T, N = 32, 64
+    w = wl.weights(net)
+    obs, h0, done, meas = wl.trajectory_inputs(net, T, N)
+    pol = binding.Policy(net, w, max_batch=T * N)
+    g = _unroll(torch, pol, obs, h0, done, meas)
+    sel = np.array([0, 31, 63])
+    o = ref.policy_unroll(net, w, obs[:, sel], h0[sel], done[:, sel])
+    for k in ("h_seq", "logits", "value"):
+        parity.assert_close(k, g[k][:, sel], o[k], 1e-4)
+    assert done[:, sel].any() and not done[:, sel].all()
+    pol.close()
+
+
+def test_unroll_feeds_the_loss(torch_cuda, ref):
+    """Forward pass and loss kernels in sequence on the device against the oracle's pair: the
+    learner's loss values and the gradients with respect to the network's outputs."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    net = dict(BY_NAME["full_mfma"], p_done=0.1)
+    T, N = 16, 8
+    w = wl.weights(net)
+    obs, h0, done, meas = wl.trajectory_inputs(net, T, N)
+    hp = wl.loss_config(tuple(net["heads"]), T, N)
+    tr = wl.trajectories(hp, 6100)      # behaviour actions, log-probabilities, rewards, bootstrap values
+    pol = binding.Policy(net, w, max_batch=T * N)
+    d = pol.device
+    fwd = pol.unroll(torch.from_numpy(obs).to(d), torch.from_numpy(h0).to(d), torch.from_numpy(done).to(d),
+                     meas=torch.from_numpy(meas).to(d))
+    values = torch.cat([fwd["value"], torch.from_numpy(tr["values"][T:]).to(d)])
+    dev = {k: torch.from_numpy(v).to(d) for k, v in tr.items()}
+    # an episode that ends at step t is one whose next step starts a new episode
+    ended = np.concatenate([done[1:], tr["dones"][-1:]])
+    dev.update(logits=fwd["logits"], values=values, dones=torch.from_numpy(ended).to(d))
+    out = binding.appo_loss(hp, dev)
+    torch.cuda.synchronize()
+    of = ref.policy_unroll(net, w, obs, h0, done, meas=meas)
+    ol = ref.appo_loss(hp, logits=of["logits"], actions=tr["actions"], logp_mu=tr["logp_mu"],
+                       values=np.concatenate([of["value"], tr["values"][T:]]), rewards=tr["rewards"], dones=ended)
+    loss = out["loss"].cpu().numpy()
+    scale = np.abs(ol["loss"][:3]).max()
+    assert np.all(np.abs(loss - ol["loss"]) <= 2e-4 * (np.abs(ol["loss"]) + scale)), (loss, ol["loss"])
+    for k in ("vs", "adv", "dvalues"):
+        parity.assert_close(k, out[k].cpu().numpy(), ol[k], 2e-4)
+    pol.close()
+
+
+def test_unroll_error_paths(torch_cuda):
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    net = ODD_NET
+    w = wl.weights(net)
+    pol = binding.Policy(net, w, max_batch=16)
+    d = pol.device
+    L = binding.load_library()
+    T, N = 4, 4
+    obs, h0, done, _ = wl.trajectory_inputs(net, T, N)
+    dev = [torch.from_numpy(a).to(d) for a in (obs, h0, done)]
+    f32 = dict(dtype=torch.float32, device=d)
+    logits, value = torch.empty((T, N, sum(net["heads"])), **f32), torch.empty((T, N), **f32)
+    h_seq = torch.empty((T + 1, N, pol.H), **f32)
+    ptr = lambda x: x.data_ptr()
+    call = lambda T_, N_, h0_, hs_: L.sf_policy_unroll(pol.handle, T_, N_, ptr(dev[0]), None, h0_, ptr(dev[2]),
+                                                       ptr(logits), ptr(value), hs_, None)
+    assert call(T, N, ptr(dev[1]), ptr(h_seq)) == binding.SF_OK
+    assert call(5, 4, ptr(dev[1]), ptr(h_seq)) == binding.SF_ERR_BATCH        # 20 rows > max_batch
+    assert call(0, 4, ptr(dev[1]), ptr(h_seq)) == binding.SF_ERR_BATCH
+    assert call(T, -1, ptr(dev[1]), ptr(h_seq)) == binding.SF_ERR_BATCH
+    assert call(T, 0, None, None) == binding.SF_OK                             # nothing to do
+    assert call(T, N, None, ptr(h_seq)) == binding.SF_ERR_ARG
+    assert call(T, N, ptr(dev[1]) + 4, ptr(h_seq)) == binding.SF_ERR_ARG      # misaligned state
+    assert call(4, 3, ptr(dev[1]), ptr(h_seq)) == binding.SF_ERR_SHAPE        # 3 rows x 33 floats: not 16-byte
+    assert call(T, N, ptr(h_seq) + 4 * N * pol.H, ptr(h_seq)) == binding.SF_ERR_ALIAS   # h0 = row 1 of h_seq
+    assert call(T, N, ptr(h_seq) + 16 * N * pol.H, ptr(h_seq)) == binding.SF_OK       # row T: behind it
+    assert L.sf_policy_unroll(None, T, N, *([None] * 8)) == binding.SF_ERR_ARG
+    torch.cuda.synchronize()
+    pol.close()
