@@ -159,6 +159,49 @@ def measure_loss(torch, binding, wl, reps):
     return res
 
 
+def measure_learner_forward(torch, binding, wl, net, w, reps):
+    """The learner's forward pass on the paper's batch (64 trajectories of 32 steps = 2048 samples):
+    one call of the unrolled pass, and the same work as 32 single steps of 64 rows, for comparison."""
+    T, N = 32, 64
+    pol = binding.Policy(net, w, max_batch=T * N)
+    d = pol.device
+    obs, h0, done, meas = wl.trajectory_inputs(net, T, N)
+    obs, h0, done = (torch.from_numpy(a).to(d) for a in (obs, h0, done))
+    meas = None if meas is None else torch.from_numpy(meas).to(d)
+    out = pol.unroll(obs, h0, done, meas=meas)
+    st = torch.cuda.current_stream().cuda_stream
+    args = (pol.handle, T, N, obs.data_ptr(), None if meas is None else meas.data_ptr(), h0.data_ptr(), done.data_ptr(),
+            out["logits"].data_ptr(), out["value"].data_ptr(), out["h_seq"].data_ptr(), st)
+    for _ in range(5):
+        binding.sf_policy_unroll(*args)
+    torch.cuda.synchronize()
+    tic = time.perf_counter()
+    for _ in range(reps):
+        binding.sf_policy_unroll(*args)
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - tic) / reps
+    step_out = pol.alloc_outputs(N)
+    hs = [h0] + [torch.empty_like(h0) for _ in range(2)]
+
+    def steps():
+        for t in range(T):
+            step_out["h_out"] = hs[1 + t % 2]
+            pol.step(obs[t], hs[0] if t == 0 else hs[1 + (t - 1) % 2], done[t], 1, t, out=step_out,
+                     meas=None if meas is None else meas[t])
+    steps()
+    torch.cuda.synchronize()
+    tic = time.perf_counter()
+    for _ in range(max(1, reps // 4)):
+        steps()
+    torch.cuda.synchronize()
+    ms_steps = 1e3 * (time.perf_counter() - tic) / max(1, reps // 4)
+    flops = pol.flops_per_row() * T * N
+    pol.close()
+    return {"T": T, "N": N, "ms_per_pass": round(ms, 4), "samples_per_s": round(T * N / ms * 1e3, 1),
+            "algorithmic_tflops": round(flops / ms / 1e9, 2), "as_32_single_steps_ms": round(ms_steps, 4),
+            "launches": "encoder and FC once on 2048 frames, the core 32 times on 64 rows, the heads once on 2048 states"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -170,7 +213,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay figure")
     ap.add_argument("--pipeline", action="store_true",
                     help="also measure the double-buffered pipeline with host-resident observations")
-    ap.add_argument("--loss", action="store_true", help="also time the learner-side loss kernels")
+    ap.add_argument("--loss", action="store_true", help="also time the learner-side loss kernels and forward pass")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     ap.add_argument("--profile-run", action="store_true",
@@ -369,6 +412,7 @@ def main():
         line["pipeline"] = pipeline
     if args.loss:
         line["loss_kernels"] = measure_loss(torch, binding, wl, 200)
+        line["learner_forward"] = measure_learner_forward(torch, binding, wl, net, w, 40)
     print(json.dumps(line))
     pol.close()
 

@@ -265,6 +265,7 @@ Switches read_switches() {
   sw.no_res_stage = env_set("SF_NO_RES_STAGE");
   sw.no_stem_pool = env_set("SF_NO_STEM_POOL");
   sw.no_conv_pool_regs = env_set("SF_NO_CONV_POOL_REGS");
+  sw.no_rnn_seq = env_set("SF_NO_RNN_SEQ");
   sw.act_bf16 = env_set("SF_ACT_BF16");
   sw.stream_f32 = env_set("SF_STREAM_F32");
   return sw;
@@ -685,6 +686,7 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
   p->state_dim = (lstm ? 2 : 1) * cfg->rnn_dim;
   p->gru_wih_t = p->gru_whh_t = nullptr;
   p->gru_wih = p->gru_whh = nullptr;
+  p->rnn_seq_w = nullptr;
   p->rnn_wih_bf = p->rnn_whh_bf = nullptr;
   if (cfg->dtype == SF_DTYPE_BF16 && !sw.force_generic && !sw.no_rnn_bf16 &&
       rnn_bf16_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
@@ -706,6 +708,15 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
     p->gru_whh = bld.pack_vec(w->rnn_w_hh, (size_t)HG * cfg->rnn_dim);
     p->gru_bm = sw.gru_bm > 0 ? sw.gru_bm : rnn_mfma_pick_bm(cfg->max_batch, cfg->rnn_dim);
     p->rnn_plain_loops = sw.no_rnn_pairs ? 0 : 1;
+    if (!sw.no_rnn_seq && rnn_seq_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
+      // the same matrices once more, in the operand order of the kernel that runs the core on
+      // the few rows per time step of sf_policy_unroll
+      std::vector<float> qi((size_t)HG * core_in), qh((size_t)HG * cfg->rnn_dim), t;
+      for (size_t i = 0; i < qi.size(); ++i) qi[i] = bld.q(w->rnn_w_ih[i]);
+      for (size_t i = 0; i < qh.size(); ++i) qh[i] = bld.q(w->rnn_w_hh[i]);
+      rnn_seq_pack(qi.data(), qh.data(), core_in, cfg->rnn_dim, lstm ? 1 : 0, t);
+      p->rnn_seq_w = bld.upload(t);
+    }
   }
   p->gru_bih = bld.pack_vec(w->rnn_b_ih, HG);
   p->gru_bhh = bld.pack_vec(w->rnn_b_hh, HG);
@@ -983,6 +994,7 @@ extern "C" int sf_policy_update_weights(sf_policy* handle, const sf_policy_weigh
                    scratch.fc_out_bf16 == p->fc_out_bf16 && (scratch.fc_wt != nullptr) == (p->fc_wt != nullptr) &&
                    (scratch.fc_wbf != nullptr) == (p->fc_wbf != nullptr) &&
                    (scratch.gru_wih != nullptr) == (p->gru_wih != nullptr) &&
+                   scratch.rnn_seq_w == p->rnn_seq_w &&
                    (scratch.rnn_wih_bf != nullptr) == (p->rnn_wih_bf != nullptr);
   for (size_t i = 0; same_plan && i < p->convs.size(); ++i) {
     const ConvLayer &a = scratch.convs[i], &b = p->convs[i];
@@ -1261,7 +1273,11 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
         const float* x1 = (const float*)((const char*)p->fc_out +
                                          feat_row * c.fc_dim * (p->fc_out_bf16 ? 2 : 4));
         const int lstm = c.rnn_type == SF_RNN_LSTM;
-        if (p->rnn_wih_bf)
+        if (parts == PART_CORE && p->rnn_seq_w && !ids)
+          // (one time step of the pass over trajectories: few rows)
+          SF_LAUNCH(launch_rnn_seq(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, x1, x2, h_in, done,
+                                   p->rnn_seq_w, p->gru_bih, p->gru_bhh, h_out, st));
+        else if (p->rnn_wih_bf)
           SF_LAUNCH(launch_rnn_bf16(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, x1,
                                     p->fc_out_bf16, x2, h_in, done, p->rnn_wih_bf, p->rnn_whh_bf, p->gru_bih, p->gru_bhh, h_out,
                                     ids, n_env, st));

@@ -73,6 +73,7 @@ struct Switches {
   bool no_res_stage = false;     // SF_NO_RES_STAGE
   bool no_stem_pool = false;     // SF_NO_STEM_POOL
   bool no_conv_pool_regs = false;  // SF_NO_CONV_POOL_REGS
+  bool no_rnn_seq = false;         // SF_NO_RNN_SEQ
   bool act_bf16 = false;         // SF_ACT_BF16
   bool stream_f32 = false;       // SF_STREAM_F32
 };
@@ -117,6 +118,7 @@ struct Policy {
   float* gru_whh_t;   // dev [H][G*H]
   float* gru_wih;     // dev [G*H][core input] (canonical) for the MFMA kernel, or null
   float* gru_whh;     // dev [G*H][H]
+  float* rnn_seq_w = nullptr;  // dev: both matrices in the operand order of k_rnn_seq.hip, or null
   int gru_bm;         // rows per workgroup of the MFMA kernel, fixed at create
   double conv1_ratio2 = 0, conv1_ratio3 = 0;  // admission test of the first convolution's digit planes
   int conv1_image = 1;      // first convolution: frame-resident variant where it applies
@@ -260,6 +262,12 @@ hipError_t launch_rnn_mfma(int lstm, int B, int I1, int I2, int H, const float* 
                            const float* w_hh, const float* b_ih, const float* b_hh, float* h_out,
                            int bm, int plain_loops, const int32_t* ids, int n_env, hipStream_t st);
 int rnn_mfma_pick_bm(int max_batch, int H);
+// the cell for the few rows per time step of the pass over trajectories (k_rnn_seq.hip)
+bool rnn_seq_supported(int I1, int I2, int H);
+void rnn_seq_pack(const float* w_ih, const float* w_hh, int I, int H, int lstm, std::vector<float>& out);
+hipError_t launch_rnn_seq(int lstm, int B, int I1, int I2, int H, const float* x1, const float* x2,
+                          const float* h_in, const uint8_t* done, const float* wpk, const float* b_ih,
+                          const float* b_hh, float* h_out, hipStream_t st);
 bool rnn_bf16_supported(int I1, int I2, int H);
 void rnn_bf16_pack(const float* w, size_t n, std::vector<uint16_t>& out);
 hipError_t launch_rnn_bf16(int lstm, int B, int I1, int I2, int H, const void* x1, int x1_bf16,

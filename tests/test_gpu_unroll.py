@@ -38,7 +38,7 @@ def _unroll(torch, pol, obs, h0, done, meas):
 
 
 @pytest.mark.parametrize("net,T,N", CASES, ids=["%s-%dx%d" % (n["name"], T, N) for n, T, N in CASES])
-def test_unroll_matches_the_oracle_and_the_single_steps(torch_cuda, ref, net, T, N):
+def test_unroll_matches_the_oracle_and_the_single_steps(torch_cuda, ref, monkeypatch, net, T, N):
     torch = torch_cuda
     from paper_2006_11751_amd import binding
     net = dict(net, p_done=0.25)
@@ -49,7 +49,16 @@ def test_unroll_matches_the_oracle_and_the_single_steps(torch_cuda, ref, net, T,
     o = ref.policy_unroll(net, w, obs, h0, done, meas=meas)
     rtol = parity.RTOL[net["dtype"]]
     stats = {k: parity.assert_close(k, g[k], o[k], rtol) for k in ("h_seq", "logits", "value")}
-    # the same bits as T calls of the step, each on the N rows of its time with the state carried
+    pol.close()
+    # With the step's own core kernel in the loop (fp32 networks otherwise run the core on a
+    # kernel made for few rows, which sums in another order): the same bits as T calls of the
+    # step, each on the N rows of its time with the state carried.
+    monkeypatch.setenv("SF_NO_RNN_SEQ", "1")
+    pol = binding.Policy(net, w, max_batch=T * N)
+    monkeypatch.delenv("SF_NO_RNN_SEQ")
+    g = _unroll(torch, pol, obs, h0, done, meas)
+    for k in ("h_seq", "logits", "value"):
+        parity.assert_close(k, g[k], o[k], rtol)
     d = pol.device
     h = torch.from_numpy(h0).to(d)
     for t in range(T):
