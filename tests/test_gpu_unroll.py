@@ -155,3 +155,24 @@ def test_unroll_error_paths(torch_cuda):
     assert L.sf_policy_unroll(None, T, N, *([None] * 8)) == binding.SF_ERR_ARG
     torch.cuda.synchronize()
     pol.close()
+
+
+def test_unroll_after_a_weight_update(torch_cuda, ref):
+    """The update repacks the few-row core kernel's copy of the recurrent weights too."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    net = dict(BY_NAME["full_lstm_mfma"], p_done=0.2)
+    T, N = 5, 8
+    w = wl.weights(net)
+    obs, h0, done, meas = wl.trajectory_inputs(net, T, N)
+    pol = binding.Policy(net, w, max_batch=T * N)
+    _unroll(torch, pol, obs, h0, done, meas)
+    w2 = wl.weights(net, seed=9191)
+    pol.update_weights(w2)
+    g = _unroll(torch, pol, obs, h0, done, meas)
+    o = ref.policy_unroll(net, w2, obs, h0, done, meas=meas)
+    for k in ("h_seq", "logits", "value"):
+        parity.assert_close(k, g[k], o[k], 1e-4)
+    o1 = ref.policy_unroll(net, w, obs, h0, done, meas=meas)
+    assert parity.violation(g["h_seq"], o1["h_seq"], 1e-4) > 10.0     # (the old weights give something else)
+    pol.close()
