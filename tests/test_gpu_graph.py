@@ -49,3 +49,41 @@ def test_captured_step_replays_bitwise(torch_cuda, net):
         for k in ("actions", "logp", "value", "h_out", "logits"):
             assert torch.equal(out[k], eager[k]), (t, k)
     pol.close()
+
+
+def test_captured_pass_over_trajectories_replays_bitwise(torch_cuda):
+    """The learner's forward pass (1 + T + 1 + the encoder's launches, nothing allocated) recorded
+    once and replayed on fresh trajectories: the eager call's bits every time."""
+    torch = torch_cuda
+    net = wl.network(6, name="full_unrolled", p_done=0.1)
+    T, N = 6, 8
+    pol, _ = _make(torch, net, max_batch=T * N)
+    d = pol.device
+
+    def inputs(shift):
+        obs, h0, done, meas = wl.trajectory_inputs(net, T + shift, N)
+        return [torch.from_numpy(np.ascontiguousarray(a[shift:] if a.shape[0] == T + shift else a)).to(d)
+                for a in (obs, h0, done, meas)]
+
+    obs, h0, done, meas = inputs(0)
+    out = pol.unroll(obs, h0, done, meas=meas)
+    side = torch.cuda.Stream(device=d)
+    side.wait_stream(torch.cuda.current_stream(d))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        pol.unroll(obs, h0, done, out=out, stream=torch.cuda.current_stream(d), meas=meas)
+    for shift in range(1, 4):
+        o2, _, d2, m2 = inputs(shift)
+        eager = pol.unroll(o2, h0, d2, meas=m2)           # eager work between the replays
+        torch.cuda.synchronize()
+        obs.copy_(o2)
+        done.copy_(d2)
+        meas.copy_(m2)
+        for v in out.values():
+            v.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in ("logits", "value", "h_seq"):
+            assert torch.equal(out[k], eager[k]), (shift, k)
+    pol.close()
