@@ -28,6 +28,7 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t uint32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
@@ -41,7 +42,7 @@ __device__ inline float tanh_acc(float a) {
 }
 
 struct SeqArgs {
-  const float* x1;      // [B][I1]
+  const void* x1;       // [B][I1] fp32, or bf16 (XB instantiations; then there is no x2)
   const float* x2;      // [B][I2] or null (I2 = 0)
   const float* h_in;    // [B][S]
   const uint8_t* done;  // [B]
@@ -55,7 +56,7 @@ struct SeqArgs {
 // kChunk: K units (of 8) a wave has in flight per register buffer; the loop below takes two
 // buffers per round, so a wave's share of K is walked in steps of 2 * kChunk units (the launch
 // picks the kChunk that pads that share least).
-template <bool LSTM, int kChunk>
+template <bool LSTM, int kChunk, bool XB>
 __global__ __launch_bounds__(kThreads, 2) void rnn_seq_kernel(SeqArgs g) {
   __shared__ float red[kWaves][16][64];  // 32 KB: the waves' partial tiles, then their sum in [0]
   const int tid = threadIdx.x, lane = tid & 63;
@@ -71,7 +72,8 @@ __global__ __launch_bounds__(kThreads, 2) void rnn_seq_kernel(SeqArgs g) {
   const int li = lane & 31, kk = lane >> 5;
   const int row = min(row0 + li, g.B - 1);
   const bool reset = g.done[row] != 0;
-  const float* xr1 = g.x1 + (size_t)row * g.I1 + 4 * kk;
+  const float* xr1 = (const float*)g.x1 + (size_t)row * g.I1 + 4 * kk;
+  const uint16_t* xb1 = (const uint16_t*)g.x1 + (size_t)row * g.I1 + 4 * kk;
   const float* xr2 = g.x2 ? g.x2 + (size_t)row * g.I2 + 4 * kk : nullptr;
   const float* hr = g.h_in + (size_t)row * S + 4 * kk;
   const f32x4* wp = (const f32x4*)g.wpk + ((size_t)blockIdx.y * n_u) * 64 + lane;
@@ -105,6 +107,19 @@ __global__ __launch_bounds__(kThreads, 2) void rnn_seq_kernel(SeqArgs g) {
   // flight where the paths join.)
   auto load_a = [&](int u) -> f32x4 {
     const int k = u << 3;
+    if (XB) {
+      // bf16 features: both sources are read (addresses clamped into their rows), one is kept
+      const uint32x2 xb = *(const uint32x2*)(xb1 + min(k, g.I1 - 8));
+      f32x4 v = *(const f32x4*)(hr + max(k - I, 0));
+      if (reset) v = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+      if (k < g.I1) {
+        v[0] = __builtin_bit_cast(float, xb[0] << 16);
+        v[1] = __builtin_bit_cast(float, xb[0] & 0xFFFF0000u);
+        v[2] = __builtin_bit_cast(float, xb[1] << 16);
+        v[3] = __builtin_bit_cast(float, xb[1] & 0xFFFF0000u);
+      }
+      return v;
+    }
     const float* ptr = k < g.I1 ? xr1 + k : (k < I ? xr2 + (k - g.I1) : hr + (k - I));
     f32x4 v = *(const f32x4*)ptr;
     if (reset && k >= I) v = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
@@ -212,11 +227,11 @@ void rnn_seq_pack(const float* w_ih, const float* w_hh, int I, int H, int lstm, 
         }
 }
 
-hipError_t launch_rnn_seq(int lstm, int B, int I1, int I2, int H, const float* x1, const float* x2,
+hipError_t launch_rnn_seq(int lstm, int B, int I1, int I2, int H, const void* x1, int x1_bf16, const float* x2,
                           const float* h_in, const uint8_t* done, const float* wpk, const float* b_ih,
                           const float* b_hh, float* h_out, hipStream_t st) {
   if (B == 0) return hipSuccess;
-  if (!rnn_seq_supported(I1, x2 ? I2 : 0, H)) return hipErrorInvalidValue;
+  if (!rnn_seq_supported(I1, x2 ? I2 : 0, H) || (x1_bf16 && x2)) return hipErrorInvalidValue;
   SeqArgs g;
   g.x1 = x1; g.x2 = x2; g.h_in = h_in; g.done = done; g.wpk = wpk; g.b_ih = b_ih; g.b_hh = b_hh;
   g.h_out = h_out; g.B = B; g.I1 = I1; g.I2 = x2 ? I2 : 0; g.H = H;
@@ -231,7 +246,10 @@ hipError_t launch_rnn_seq(int lstm, int B, int I1, int I2, int H, const float* x
     }
   }
   auto go = [&](auto lstm_c, auto ch_c) {
-    rnn_seq_kernel<decltype(lstm_c)::value, decltype(ch_c)::value><<<grid, kThreads, 0, st>>>(g);
+    if (x1_bf16)
+      rnn_seq_kernel<decltype(lstm_c)::value, decltype(ch_c)::value, true><<<grid, kThreads, 0, st>>>(g);
+    else
+      rnn_seq_kernel<decltype(lstm_c)::value, decltype(ch_c)::value, false><<<grid, kThreads, 0, st>>>(g);
   };
   auto pick = [&](auto lstm_c) {
     switch (best) {

@@ -708,15 +708,17 @@ int build_policy(Policy* p, const sf_policy_config* cfg, const sf_policy_weights
     p->gru_whh = bld.pack_vec(w->rnn_w_hh, (size_t)HG * cfg->rnn_dim);
     p->gru_bm = sw.gru_bm > 0 ? sw.gru_bm : rnn_mfma_pick_bm(cfg->max_batch, cfg->rnn_dim);
     p->rnn_plain_loops = sw.no_rnn_pairs ? 0 : 1;
-    if (!sw.no_rnn_seq && rnn_seq_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
-      // the same matrices once more, in the operand order of the kernel that runs the core on
-      // the few rows per time step of sf_policy_unroll
-      std::vector<float> qi((size_t)HG * core_in), qh((size_t)HG * cfg->rnn_dim), t;
-      for (size_t i = 0; i < qi.size(); ++i) qi[i] = bld.q(w->rnn_w_ih[i]);
-      for (size_t i = 0; i < qh.size(); ++i) qh[i] = bld.q(w->rnn_w_hh[i]);
-      rnn_seq_pack(qi.data(), qh.data(), core_in, cfg->rnn_dim, lstm ? 1 : 0, t);
-      p->rnn_seq_w = bld.upload(t);
-    }
+  }
+  if ((p->gru_wih || p->rnn_wih_bf) && !sw.no_rnn_seq &&
+      rnn_seq_supported(cfg->fc_dim, p->meas_out_dim, cfg->rnn_dim)) {
+    // the same matrices once more (fp32 values; in a bf16 configuration the rounded ones), in the
+    // operand order of the kernel that runs the core on the few rows per time step of
+    // sf_policy_unroll
+    std::vector<float> qi((size_t)HG * core_in), qh((size_t)HG * cfg->rnn_dim), t;
+    for (size_t i = 0; i < qi.size(); ++i) qi[i] = bld.q(w->rnn_w_ih[i]);
+    for (size_t i = 0; i < qh.size(); ++i) qh[i] = bld.q(w->rnn_w_hh[i]);
+    rnn_seq_pack(qi.data(), qh.data(), core_in, cfg->rnn_dim, lstm ? 1 : 0, t);
+    p->rnn_seq_w = bld.upload(t);
   }
   p->gru_bih = bld.pack_vec(w->rnn_b_ih, HG);
   p->gru_bhh = bld.pack_vec(w->rnn_b_hh, HG);
@@ -1275,7 +1277,7 @@ int run_step(Policy* p, int32_t B, const uint8_t* obs, const float* meas, const 
         const int lstm = c.rnn_type == SF_RNN_LSTM;
         if (parts == PART_CORE && p->rnn_seq_w && !ids)
           // (one time step of the pass over trajectories: few rows)
-          SF_LAUNCH(launch_rnn_seq(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, x1, x2, h_in, done,
+          SF_LAUNCH(launch_rnn_seq(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, x1, p->fc_out_bf16, x2, h_in, done,
                                    p->rnn_seq_w, p->gru_bih, p->gru_bhh, h_out, st));
         else if (p->rnn_wih_bf)
           SF_LAUNCH(launch_rnn_bf16(lstm, B, c.fc_dim, p->meas_out_dim, c.rnn_dim, x1,

@@ -265,7 +265,7 @@ int rnn_mfma_pick_bm(int max_batch, int H);
 // the cell for the few rows per time step of the pass over trajectories (k_rnn_seq.hip)
 bool rnn_seq_supported(int I1, int I2, int H);
 void rnn_seq_pack(const float* w_ih, const float* w_hh, int I, int H, int lstm, std::vector<float>& out);
-hipError_t launch_rnn_seq(int lstm, int B, int I1, int I2, int H, const float* x1, const float* x2,
+hipError_t launch_rnn_seq(int lstm, int B, int I1, int I2, int H, const void* x1, int x1_bf16, const float* x2,
                           const float* h_in, const uint8_t* done, const float* wpk, const float* b_ih,
                           const float* b_hh, float* h_out, hipStream_t st);
 bool rnn_bf16_supported(int I1, int I2, int H);
