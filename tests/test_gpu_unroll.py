@@ -176,3 +176,25 @@ def test_unroll_after_a_weight_update(torch_cuda, ref):
     o1 = ref.policy_unroll(net, w, obs, h0, done, meas=meas)
     assert parity.violation(g["h_seq"], o1["h_seq"], 1e-4) > 10.0     # (the old weights give something else)
     pol.close()
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_unroll_on_random_network_shapes(torch_cuda, ref, seed):
+    """Randomly drawn plain-stack networks (the generator of the step's random-shape test), GRU or
+    LSTM, T and N drawn too (N a multiple of 4: rows of 40 state floats stay 16-byte aligned)."""
+    torch = torch_cuda
+    from paper_2006_11751_amd import binding
+    from tests.test_gpu_parity import _random_net
+    rng = np.random.default_rng(1500 + seed)
+    net = _random_net(rng, "bf16" if seed % 3 == 2 else "fp32")
+    net = dict(net, rnn_type="lstm" if seed % 2 else "gru", p_done=0.2, meas_dim=0, meas_hidden=[])
+    T, N = int(rng.integers(1, 7)), 4 * int(rng.integers(1, 12))
+    w = wl.weights(net, seed=1600 + seed)
+    obs, h0, done, meas = wl.trajectory_inputs(net, T, N)
+    pol = binding.Policy(net, w, max_batch=T * N + int(rng.integers(0, 9)))
+    g = _unroll(torch, pol, obs, h0, done, meas)
+    o = ref.policy_unroll(net, w, obs, h0, done)
+    rtol = parity.RTOL[net["dtype"]]
+    stats = {k: parity.assert_close(k, g[k], o[k], rtol) for k in ("h_seq", "logits", "value")}
+    print(net["obs"], net["convs"], net["fc"], net["rnn"], net["rnn_type"], net["heads"], net["dtype"], T, N, stats)
+    pol.close()
