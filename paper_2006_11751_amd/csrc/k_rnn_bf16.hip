@@ -38,7 +38,17 @@ constexpr int kPitch = 144;   // LDS row pitch in bytes (128 + 16)
 constexpr int kBR = 128;      // batch rows per workgroup
 constexpr int kBJ = 32;       // hidden units per workgroup
 
-__device__ inline float sigmoid_acc(float a) { return 1.0f / (1.0f + expf(-a)); }
+// The gate functions on the hardware's exp2 and reciprocal (about 1 ulp each; no range
+// reduction, no division sequence, no branches: sixteen state elements per thread pass through
+// here, and with the library routines the epilogue held 40 % of the kernel's instructions).
+// exp2 overflows to +inf and underflows to 0, which the reciprocal maps to 0 and 1: the
+// limits come out exact.  tanh as (1 - e) / (1 + e) with e = exp(-2|a|) <= 1, sign restored.
+__device__ inline float exp_hw(float a) { return __builtin_amdgcn_exp2f(a * 1.44269504088896341f); }
+__device__ inline float sigmoid_acc(float a) { return __builtin_amdgcn_rcpf(1.0f + exp_hw(-a)); }
+__device__ inline float tanh_acc(float a) {
+  const float e = exp_hw(-2.0f * fabsf(a));
+  return copysignf((1.0f - e) * __builtin_amdgcn_rcpf(1.0f + e), a);
+}
 __device__ inline unsigned bf16_rne(float f) {
   const unsigned u = __float_as_uint(f);
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;  // finite inputs
@@ -60,23 +70,23 @@ struct RnnBf16Args {
   int n_env;
 };
 
-// 8 consecutive fp32 -> 8 bf16 (phase 0: the value; 1: hi part; 2: lo part = bf16(v - hi)),
-// round to nearest even through the packed hardware conversion; both parts are formed and
-// the phase picks whole words (no branches around the conversions)
-__device__ inline u32x4 to_bf16x8(const f32x4& a, const f32x4& b, int phase) {
+// 8 consecutive fp32 -> 8 bf16, round to nearest even through the packed hardware conversion:
+// the values themselves (hi), and with SPLIT also what is left of them, lo = bf16(v - hi)
+template <bool SPLIT>
+__device__ inline void to_bf16x8(const f32x4& a, const f32x4& b, u32x4& hi_out, u32x4& lo_out) {
   typedef float f32x2_t __attribute__((ext_vector_type(2)));
   typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
   const float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-  u32x4 o;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const f32x2_t p = {v[2 * e], v[2 * e + 1]};
     const unsigned hi = __builtin_bit_cast(unsigned, __builtin_convertvector(p, bf16x2_t));
-    const f32x2_t r = {v[2 * e] - __uint_as_float(hi << 16), v[2 * e + 1] - __uint_as_float(hi & 0xFFFF0000u)};
-    const unsigned lo = __builtin_bit_cast(unsigned, __builtin_convertvector(r, bf16x2_t));
-    o[e] = phase == 2 ? lo : hi;
+    hi_out[e] = hi;
+    if (SPLIT) {
+      const f32x2_t r = {v[2 * e] - __uint_as_float(hi << 16), v[2 * e + 1] - __uint_as_float(hi & 0xFFFF0000u)};
+      lo_out[e] = __builtin_bit_cast(unsigned, __builtin_convertvector(r, bf16x2_t));
+    }
   }
-  return o;
 }
 
 template <bool LSTM, bool XB16>
@@ -146,14 +156,24 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
     for (int q = 0; q < NG; ++q)
       rw[q] = *(const u32x4*)(g.w_hh + (size_t)(q * H + j0 + lrow) * H + kk);
   };
-  // rphase: 0 = x values, 1 = hi parts of h, 2 = lo parts of h
+  // rphase: 0 = x values, 1 = hi parts of h, 2 = lo parts of h.  A block of h is split once,
+  // when its hi part is stored: the lo words then take the place of the fp32 values in the
+  // registers and phase 2 only stores them.
   auto sstore = [&](int buf, int rphase) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       // the reset is applied here, not behind the load (a select there waits for the load)
       const u32x4 zero = {0u, 0u, 0u, 0u};
-      const u32x4 v = (XB16 && rphase == 0) ? __builtin_bit_cast(u32x4, ra[r][0])
-                                            : to_bf16x8(ra[r][0], ra[r][1], rphase);
+      u32x4 v, lo;
+      if (rphase == 0) {
+        if (XB16) v = __builtin_bit_cast(u32x4, ra[r][0]);
+        else to_bf16x8<false>(ra[r][0], ra[r][1], v, lo);
+      } else if (rphase == 1) {
+        to_bf16x8<true>(ra[r][0], ra[r][1], v, lo);
+        ra[r][0] = __builtin_bit_cast(f32x4, lo);
+      } else {
+        v = __builtin_bit_cast(u32x4, ra[r][0]);
+      }
       *(u32x4*)(Rs + (buf * kBR + lrow + 32 * r) * kPitch + lk8 * 2) = (rphase != 0 && areset[r]) ? zero : v;
     }
 #pragma unroll
@@ -259,10 +279,10 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
       for (int u = 0; u < 4; ++u) {
         const float ig = sigmoid_acc(acc[0][4 * q4 + u] + bi[0][u] + bh[0][u]);
         const float fg = sigmoid_acc(acc[1][4 * q4 + u] + bi[1][u] + bh[1][u]);
-        const float gg = tanhf(acc[2][4 * q4 + u] + bi[2][u] + bh[2][u]);
+        const float gg = tanh_acc(acc[2][4 * q4 + u] + bi[2][u] + bh[2][u]);
         const float og = sigmoid_acc(acc[3][4 * q4 + u] + bi[NG - 1][u] + bh[NG - 1][u]);
         cn[u] = fg * cprev[u] + ig * gg;
-        hn[u] = og * tanhf(cn[u]);
+        hn[u] = og * tanh_acc(cn[u]);
       }
       *(f32x4*)(g.h_out + (size_t)m * S + H + j) = cn;
       *(f32x4*)(g.h_out + (size_t)m * S + j) = hn;
@@ -273,7 +293,7 @@ __global__ __launch_bounds__(256) void rnn_bf16_kernel(RnnBf16Args g) {
       for (int u = 0; u < 4; ++u) {
         const float r = sigmoid_acc(acc[0][4 * q4 + u] + bi[0][u] + bh[0][u]);
         const float z = sigmoid_acc(acc[1][4 * q4 + u] + bi[1][u] + bh[1][u]);
-        const float n = tanhf(acc[2][4 * q4 + u] + bi[2][u] + r * (acc[3][4 * q4 + u] + bh[2][u]));
+        const float n = tanh_acc(acc[2][4 * q4 + u] + bi[2][u] + r * (acc[3][4 * q4 + u] + bh[2][u]));
         hn[u] = (1.0f - z) * n + z * hprev[u];
       }
       *(f32x4*)(g.h_out + (size_t)m * S + j) = hn;
