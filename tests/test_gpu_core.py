@@ -28,6 +28,12 @@ NETS = [
     dict(_BASE, name="gru_bf16_mfma", B=137, fc=128, rnn=64, heads=[9], index=5, dtype="bf16"),
     dict(_BASE, name="full_bf16_mfma", B=137, fc=64, rnn=64, meas_dim=11, meas_hidden=[20, 64], heads=[3, 2], index=6,
          dtype="bf16"),
+    # GRU of a bf16 configuration with 128 and 256 hidden units (several unit tiles per row block;
+    # ragged batches of 137 and 65 rows; bf16 features from the FC kernel, and fp32 ones with a
+    # measurement input)
+    dict(_BASE, name="gru_bf16_wide", B=137, fc=64, rnn=128, heads=[5], index=5, dtype="bf16"),
+    dict(_BASE, name="full_bf16_wide", B=65, fc=128, rnn=256, meas_dim=7, meas_hidden=[64], heads=[4, 2], index=6,
+         dtype="bf16"),
 ]
 
 
