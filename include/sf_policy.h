@@ -30,7 +30,8 @@
  *     synchronise, and keeps no pointer past the completion of the stream work
  *     it enqueues.  The caller owns every buffer passed to sf_policy_step.
  *   - one sf_policy handle must not be stepped from two threads or on two
- *     streams at the same time (its workspace is shared by its calls).
+ *     streams at the same time (its workspace is shared by its calls,
+ *     sf_policy_step_indexed and sf_policy_unroll included).
  */
 #ifndef SF_POLICY_H
 #define SF_POLICY_H
